@@ -1,0 +1,143 @@
+/*
+ * peqa.h -- C-ABI of the MI355X (gfx950) PEQA quantized-linear library.
+ *
+ * PEQA (arXiv 2305.14152, Sec. 3.2) replaces a fully-connected weight
+ * W0 in R^{N x K} by  What = (s0 + ds) . (Q - z0)  with frozen b-bit integer
+ * codes Q (b = 3 or 4), zero-points z0 and scales s0 per output channel
+ * (optionally per group of g input features, Sec. 4.3), and trains only ds.
+ *
+ * Conventions for every call
+ *   - Every tensor argument is a DEVICE pointer owned by the caller, contiguous,
+ *     row-major, 16-byte aligned (PEQA_ERR_ALIGN otherwise); outputs must not
+ *     alias inputs.  Descriptor structs (peqa_layout, peqa_adamw) are HOST pointers.
+ *   - `stream` is a hipStream_t passed opaquely (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise, allocate or free.
+ *   - Arguments are validated on the host before the device is touched, so the
+ *     error paths work on a machine without a GPU.  Return value: peqa_status.
+ *   - bf16 tensors are passed as uint16_t bit patterns.
+ *   - G = number of groups per channel = K / group_size, or 1 when group_size = 0.
+ *     Scale-shaped arrays (s0, ds, d_ds, m, v, z0) are [N, G] row-major.
+ *
+ * Shape limits: N % 128 == 0, K % 128 == 0 (every LLaMA-family linear satisfies
+ * this); group_size is 0 or a multiple of 128 dividing K... see peqa_check_layout.
+ */
+#ifndef PEQA_H
+#define PEQA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PEQA_OK = 0,
+    PEQA_ERR_NULL = 1,      /* a required pointer is NULL                       */
+    PEQA_ERR_SHAPE = 2,     /* N, K or T out of the supported range             */
+    PEQA_ERR_BITS = 3,      /* bits is not 3 or 4                               */
+    PEQA_ERR_GROUP = 4,     /* group_size invalid for this K                    */
+    PEQA_ERR_ALIGN = 5,     /* a device pointer is not 16-byte aligned          */
+    PEQA_ERR_WORKSPACE = 6, /* workspace missing or smaller than required       */
+    PEQA_ERR_DEVICE = 7,    /* the HIP runtime reported a launch error          */
+    PEQA_ERR_PARAM = 8      /* an optimizer or other scalar parameter is invalid */
+} peqa_status;
+
+typedef struct {
+    int32_t n_out;      /* N: output channels = rows of W0 (the paper's n)             */
+    int32_t k_in;       /* K: input features = columns of W0 (the paper's m)           */
+    int32_t bits;       /* b: 3 or 4                                                    */
+    int32_t group_size; /* 0 = one (s, z) per channel; else g with g % 128 == 0, K % g == 0 */
+} peqa_layout;
+
+typedef enum { PEQA_OP_FWD = 0, PEQA_OP_BWD = 1 } peqa_op;
+
+/* Host-only helpers (no device access). */
+peqa_status peqa_check_layout(const peqa_layout *L);
+size_t peqa_packed_words(const peqa_layout *L);   /* N*K*bits/32 uint32 words; 0 if invalid */
+size_t peqa_num_scales(const peqa_layout *L);     /* N*G; 0 if invalid                      */
+/* Bytes of scratch the given call needs for T tokens (0 if invalid). */
+size_t peqa_workspace_bytes(const peqa_layout *L, int32_t T, int32_t op);
+const char *peqa_status_string(int32_t status);
+
+/*
+ * Word and bit (0..31) that hold bit `t` of the code of channel i, feature k in the
+ * packed array.  The paper fixes only the density (exactly b bits per weight,
+ * Table 4); the placement is this library's and is part of its contract:
+ * 8x8 blocks of (channel, feature), block (i/8, k/8) at word (i/8 * K/8 + k/8) * 2b;
+ * inside a block r = i%8, c = k%8 and
+ *   b = 4: word r, bits [4p, 4p+4) with p = c/2 + 4*(c%2);
+ *   b = 3: u = 4*(r/2) + c/2; u < 15: word 2*(u/5) + r%2, bits [16*(c%2) + 3*(u%5), +3);
+ *          u = 15: code bit t is bit 15 + 16*(c%2) of word 2t + r%2.
+ * Host-only.  Returns PEQA_ERR_SHAPE for indices out of range.
+ */
+peqa_status peqa_bit_location(const peqa_layout *L, int32_t i, int32_t k, int32_t t,
+                              size_t *word, int32_t *bit);
+
+/*
+ * Eq. 1, round-to-nearest with a min-max range, then dense packing.
+ * Per channel i and group g:  xmin = min(min w, 0), xmax = max(max w, 0),
+ * s0 = (xmax - xmin) / (2^b - 1), z0 = rint(-xmin / s0),
+ * Q = clamp(rint(w / s0) + z0, 0, 2^b - 1); rint rounds half to even; every step is one
+ * IEEE fp32 operation.  A group whose s0 evaluates to 0 gets s0 = 1, z0 = 0.
+ *   W0      [N, K] fp32, in
+ *   packed  peqa_packed_words() uint32, out
+ *   s0      [N, G] fp32, out;   z0  [N, G] uint8, out
+ */
+peqa_status peqa_quantize(const peqa_layout *L, const float *W0, uint32_t *packed,
+                          float *s0, uint8_t *z0, void *stream);
+
+/*
+ * Eq. 2 forward:  Y[t,i] = sum_k X[t,k] * (s0+ds)[i,g(k)] * (Q[i,k] - z0[i,g(k)]).
+ *   ds may be NULL (= 0).  X [T, K] bf16 in, Y [T, N] bf16 out, T >= 1.
+ *   bf16 operands, fp32 accumulation.  T <= 16 takes the bandwidth-bound
+ *   matrix-vector path of Sec. 3.1 ("Inference Latency").
+ *   workspace: peqa_workspace_bytes(L, T, PEQA_OP_FWD) bytes, contents undefined on return.
+ */
+peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                            const float *ds, const uint8_t *z0, const uint16_t *X, int32_t T,
+                            uint16_t *Y, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of Eq. 2 by the chain rule (only the scales are trained, Sec. 3.2):
+ *   dX[t,k]   = sum_i dY[t,i] * (s0+ds)[i,g(k)] * (Q[i,k] - z0[i,g(k)])
+ *   d_ds[i,g] = sum_t dY[t,i] * sum_{k in g} X[t,k] * (Q[i,k] - z0[i,g])
+ *   dX [T, K] bf16 out, or NULL to skip; d_ds [N, G] fp32 out (overwritten, not
+ *   accumulated), or NULL to skip.  X may be NULL when d_ds is NULL.
+ *   The result is deterministic (fixed reduction order, no atomics).
+ */
+peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                            const float *ds, const uint8_t *z0, const uint16_t *X,
+                            const uint16_t *dY, int32_t T, uint16_t *dX, float *d_ds,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One AdamW step on ds (Appendix A names AdamW with a linearly decaying learning rate;
+ * the schedule is the caller's, who passes the current lr).  step is 1-based.
+ *   m <- b1 m + (1-b1) g;  v <- b2 v + (1-b2) g^2
+ *   ds <- ds - lr * ( (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps) + wd * (s0 + ds) )
+ * ds, m, v [n] fp32 in/out (m, v zero-initialised by the caller); d_ds, s0 [n] fp32 in.
+ */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t step;
+} peqa_adamw;
+
+peqa_status peqa_scale_update(size_t n_scales, float *ds, const float *d_ds, float *m, float *v,
+                              const float *s0, const peqa_adamw *opt, void *stream);
+
+/*
+ * Per-kernel timing for benchmarks.  peqa_trace_begin() makes every kernel the library
+ * launches afterwards be bracketed by HIP events on its stream (it creates the events:
+ * call it outside any region that must not allocate).  peqa_trace_end() synchronises those
+ * events, stops tracing and fills, for up to `max_kernels` distinct kernels, a name
+ * (static string), the number of launches and the summed duration in milliseconds;
+ * it returns the number of distinct kernels seen.  Not thread-safe.
+ */
+peqa_status peqa_trace_begin(int32_t max_launches);
+int32_t peqa_trace_end(int32_t max_kernels, const char **names, int32_t *launches, float *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PEQA_H */

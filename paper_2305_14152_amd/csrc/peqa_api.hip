@@ -1,0 +1,316 @@
+// C-ABI of the PEQA library (include/peqa.h): host-side validation, workspace carving and
+// kernel sequencing.  No device memory is allocated here and nothing synchronises, except
+// the benchmark tracing hooks at the bottom.
+#include "../../include/peqa.h"
+
+#include <math.h>
+#include <string.h>
+
+#include "peqa_kernels.h"
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+inline int groups(const peqa_layout *L) { return L->group_size > 0 ? L->k_in / L->group_size : 1; }
+
+// Contraction index at which the second half of a contraction of length n starts:
+// half of it, rounded down to the step of 64 (n % 128 == 0 makes both halves non-empty).
+inline int split_point(int n) { return (n / 2) / 64 * 64; }
+
+struct Workspace {
+    size_t rs, dys, crow, partial, total;
+};
+
+Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
+{
+    Workspace w{};
+    const size_t N = (size_t)L->n_out, G = (size_t)groups(L);
+    const size_t tiles_t = ((size_t)T + 127) / 128;
+    size_t off = 0;
+    w.rs = off;      off += round256((size_t)T * 2 * sizeof(float));
+    if (op == PEQA_OP_BWD) {
+        w.dys = off;     off += round256((size_t)T * N * sizeof(uint16_t));
+        w.crow = off;    off += round256((size_t)T * sizeof(float));
+        w.partial = off; off += round256(tiles_t * N * G * sizeof(float));
+    }
+    w.total = off;
+    return w;
+}
+
+peqa_status dev_status(hipError_t e) { return e == hipSuccess ? PEQA_OK : PEQA_ERR_DEVICE; }
+
+}  // namespace
+
+extern "C" {
+
+peqa_status peqa_check_layout(const peqa_layout *L)
+{
+    if (!L) return PEQA_ERR_NULL;
+    if (L->bits != 3 && L->bits != 4) return PEQA_ERR_BITS;
+    if (L->n_out <= 0 || L->k_in <= 0) return PEQA_ERR_SHAPE;
+    if (L->n_out % 128 != 0 || L->k_in % 128 != 0) return PEQA_ERR_SHAPE;
+    if ((int64_t)L->n_out * L->k_in > ((int64_t)1 << 40)) return PEQA_ERR_SHAPE;
+    if (L->group_size < 0) return PEQA_ERR_GROUP;
+    if (L->group_size > 0 && (L->group_size % 64 != 0 || L->k_in % L->group_size != 0)) return PEQA_ERR_GROUP;
+    return PEQA_OK;
+}
+
+size_t peqa_packed_words(const peqa_layout *L)
+{
+    if (peqa_check_layout(L) != PEQA_OK) return 0;
+    return (size_t)L->n_out * (size_t)L->k_in * (size_t)L->bits / 32u;
+}
+
+size_t peqa_num_scales(const peqa_layout *L)
+{
+    if (peqa_check_layout(L) != PEQA_OK) return 0;
+    return (size_t)L->n_out * (size_t)groups(L);
+}
+
+size_t peqa_workspace_bytes(const peqa_layout *L, int32_t T, int32_t op)
+{
+    if (peqa_check_layout(L) != PEQA_OK || T < 1) return 0;
+    if (op != PEQA_OP_FWD && op != PEQA_OP_BWD) return 0;
+    return carve(L, T, op).total;
+}
+
+const char *peqa_status_string(int32_t status)
+{
+    switch (status) {
+    case PEQA_OK: return "ok";
+    case PEQA_ERR_NULL: return "required pointer is NULL";
+    case PEQA_ERR_SHAPE: return "unsupported shape";
+    case PEQA_ERR_BITS: return "bits must be 3 or 4";
+    case PEQA_ERR_GROUP: return "invalid group size";
+    case PEQA_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case PEQA_ERR_WORKSPACE: return "workspace missing or too small";
+    case PEQA_ERR_DEVICE: return "HIP runtime error";
+    case PEQA_ERR_PARAM: return "invalid scalar parameter";
+    default: return "unknown status";
+    }
+}
+
+peqa_status peqa_bit_location(const peqa_layout *L, int32_t i, int32_t k, int32_t t, size_t *word, int32_t *bit)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (!word || !bit) return PEQA_ERR_NULL;
+    if (i < 0 || i >= L->n_out || k < 0 || k >= L->k_in || t < 0 || t >= L->bits) return PEQA_ERR_SHAPE;
+    const size_t blk = (size_t)(i >> 3) * (size_t)(L->k_in >> 3) + (size_t)(k >> 3);
+    const int r = i & 7, c = k & 7;
+    if (L->bits == 4) {
+        *word = blk * 8 + r;
+        *bit = 4 * ((c >> 1) + 4 * (c & 1)) + t;
+    } else {
+        const int u = 4 * (r >> 1) + (c >> 1), par = r & 1, half = c & 1;
+        if (u < 15) {
+            *word = blk * 6 + 2 * (u / 5) + par;
+            *bit = 16 * half + 3 * (u % 5) + t;
+        } else {
+            *word = blk * 6 + 2 * t + par;
+            *bit = 15 + 16 * half;
+        }
+    }
+    return PEQA_OK;
+}
+
+peqa_status peqa_quantize(const peqa_layout *L, const float *W0, uint32_t *packed, float *s0, uint8_t *z0,
+                          void *stream)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (!W0 || !packed || !s0 || !z0) return PEQA_ERR_NULL;
+    if (!aligned16(W0) || !aligned16(packed) || !aligned16(s0) || !aligned16(z0)) return PEQA_ERR_ALIGN;
+    return dev_status(peqa::launch_quantize(W0, L->n_out, L->k_in, L->bits, L->group_size, packed, s0, z0,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (!packed || !s0 || !z0 || !X || !Y) return PEQA_ERR_NULL;
+    if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(s0) || !aligned16(z0) || !aligned16(X) || !aligned16(Y) ||
+        (ds && !aligned16(ds)))
+        return PEQA_ERR_ALIGN;
+    const Workspace w = carve(L, T, PEQA_OP_FWD);
+    if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
+    if (L->group_size > 0) return PEQA_ERR_GROUP;   // group-wise contraction: not built yet
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    float *rs = reinterpret_cast<float *>(ws + w.rs);
+    const int N = L->n_out, K = L->k_in, ksplit = split_point(K);
+
+    hipError_t e = peqa::launch_rowsum(X, T, K, ksplit, rs, s);
+    if (e != hipSuccess) return PEQA_ERR_DEVICE;
+    peqa::GemmArgs a{};
+    a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
+    a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
+    a.s0 = s0; a.ds = ds; a.z0 = z0; a.rs = rs; a.out = Y;
+    return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
+}
+
+peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const uint16_t *X, const uint16_t *dY, int32_t T, uint16_t *dX,
+                            float *d_ds, void *workspace, size_t workspace_bytes, void *stream)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (!packed || !s0 || !z0 || !dY) return PEQA_ERR_NULL;
+    if (d_ds && !X) return PEQA_ERR_NULL;
+    if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(s0) || !aligned16(z0) || !aligned16(dY) || (X && !aligned16(X)) ||
+        (ds && !aligned16(ds)) || (dX && !aligned16(dX)) || (d_ds && !aligned16(d_ds)))
+        return PEQA_ERR_ALIGN;
+    const Workspace w = carve(L, T, PEQA_OP_BWD);
+    if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
+    if (L->group_size > 0) return PEQA_ERR_GROUP;   // group-wise contraction: not built yet
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const int N = L->n_out, K = L->k_in;
+    const int tiles_t = (T + 127) / 128;
+
+    if (d_ds) {
+        float *rs = reinterpret_cast<float *>(ws + w.rs);
+        float *partial = reinterpret_cast<float *>(ws + w.partial);
+        const int ksplit = split_point(K);
+        if (peqa::launch_rowsum(X, T, K, ksplit, rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        peqa::GemmArgs a{};
+        a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
+        a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
+        a.z0 = z0; a.rs = rs; a.dY = dY; a.partial = partial;
+        if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    }
+    if (dX) {
+        uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
+        float *crow = reinterpret_cast<float *>(ws + w.crow);
+        if (peqa::launch_scale_dy(dY, s0, ds, z0, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        peqa::GemmArgs a{};
+        a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
+        a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
+        a.crow = crow; a.out = dX;
+        if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    }
+    return PEQA_OK;
+}
+
+peqa_status peqa_scale_update(size_t n_scales, float *ds, const float *d_ds, float *m, float *v, const float *s0,
+                              const peqa_adamw *opt, void *stream)
+{
+    if (!ds || !d_ds || !m || !v || !s0 || !opt) return PEQA_ERR_NULL;
+    if (n_scales == 0 || n_scales > ((size_t)1 << 38)) return PEQA_ERR_SHAPE;
+    if (opt->step < 1 || !(opt->beta1 >= 0.f && opt->beta1 < 1.f) || !(opt->beta2 >= 0.f && opt->beta2 < 1.f) ||
+        !(opt->eps >= 0.f) || !(opt->lr == opt->lr) || !(opt->weight_decay == opt->weight_decay))
+        return PEQA_ERR_PARAM;
+    if (!aligned16(ds) || !aligned16(d_ds) || !aligned16(m) || !aligned16(v) || !aligned16(s0)) return PEQA_ERR_ALIGN;
+    const double c1 = 1.0 - pow((double)opt->beta1, (double)opt->step);
+    const double c2 = 1.0 - pow((double)opt->beta2, (double)opt->step);
+    return dev_status(peqa::launch_adamw(n_scales, ds, d_ds, m, v, s0, opt->lr, opt->beta1, opt->beta2, opt->eps,
+                                         opt->weight_decay, (float)(1.0 / c1), (float)(1.0 / c2),
+                                         static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------
+// Benchmark tracing: HIP events around every launch while enabled.
+// ---------------------------------------------------------------------------------------
+namespace {
+
+struct TraceState {
+    bool on = false;
+    int cap = 0, used = 0;
+    hipEvent_t *ev = nullptr;     // 2 per launch
+    int *kid = nullptr;
+} g_trace;
+
+const char *const kKernelNames[peqa::KID_COUNT] = {
+    "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv"};
+
+void trace_release()
+{
+    for (int i = 0; i < 2 * g_trace.cap; ++i) (void)hipEventDestroy(g_trace.ev[i]);
+    delete[] g_trace.ev;
+    delete[] g_trace.kid;
+    g_trace = TraceState{};
+}
+
+}  // namespace
+
+namespace peqa {
+
+void trace_before(int kernel_id, hipStream_t stream)
+{
+    if (!g_trace.on || g_trace.used >= g_trace.cap) return;
+    g_trace.kid[g_trace.used] = kernel_id;
+    (void)hipEventRecord(g_trace.ev[2 * g_trace.used], stream);
+}
+
+void trace_after(int kernel_id, hipStream_t stream)
+{
+    (void)kernel_id;
+    if (!g_trace.on || g_trace.used >= g_trace.cap) return;
+    (void)hipEventRecord(g_trace.ev[2 * g_trace.used + 1], stream);
+    ++g_trace.used;
+}
+
+}  // namespace peqa
+
+extern "C" {
+
+peqa_status peqa_trace_begin(int32_t max_launches)
+{
+    if (max_launches < 1 || max_launches > (1 << 20)) return PEQA_ERR_PARAM;
+    if (g_trace.ev) trace_release();
+    g_trace.ev = new hipEvent_t[2 * (size_t)max_launches];
+    g_trace.kid = new int[max_launches];
+    g_trace.cap = 0;
+    for (int i = 0; i < 2 * max_launches; ++i) {
+        if (hipEventCreate(&g_trace.ev[i]) != hipSuccess) {
+            g_trace.cap = i / 2;
+            trace_release();
+            return PEQA_ERR_DEVICE;
+        }
+    }
+    g_trace.cap = max_launches;
+    g_trace.used = 0;
+    g_trace.on = true;
+    return PEQA_OK;
+}
+
+int32_t peqa_trace_end(int32_t max_kernels, const char **names, int32_t *launches, float *total_ms)
+{
+    if (!g_trace.ev) return 0;
+    g_trace.on = false;
+    int cnt[peqa::KID_COUNT] = {0};
+    float ms[peqa::KID_COUNT] = {0.f};
+    for (int i = 0; i < g_trace.used; ++i) {
+        float t = 0.f;
+        if (hipEventSynchronize(g_trace.ev[2 * i + 1]) == hipSuccess &&
+            hipEventElapsedTime(&t, g_trace.ev[2 * i], g_trace.ev[2 * i + 1]) == hipSuccess) {
+            cnt[g_trace.kid[i]] += 1;
+            ms[g_trace.kid[i]] += t;
+        }
+    }
+    int out = 0;
+    for (int k = 0; k < peqa::KID_COUNT && out < max_kernels; ++k) {
+        if (cnt[k] == 0) continue;
+        if (names) names[out] = kKernelNames[k];
+        if (launches) launches[out] = cnt[k];
+        if (total_ms) total_ms[out] = ms[k];
+        ++out;
+    }
+    trace_release();
+    return out;
+}
+
+}  // extern "C"

@@ -1,0 +1,147 @@
+// Device-side helpers shared by the gfx950 kernels of the PEQA library:
+// vector types for MFMA operands, bf16 <-> fp32 bit tricks, and the in-register
+// unpacking of packed 3/4-bit codes into bf16 MFMA operand fragments.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace peqa {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Codes are turned into bf16 without any int->float conversion: a b-bit code q placed
+// in mantissa bits 3.. of the bf16 pattern of 16.0 (0x4180) denotes exactly 16 + q.
+// Kernels contract against 16 + Q and take the constant offset (and the zero-point)
+// out afterwards through row sums of the other operand.
+constexpr float kCodeOffset = 16.0f;
+constexpr uint32_t kMagic = 0x41804180u;   // two bf16 16.0
+constexpr uint32_t kMask4 = 0x00780078u;   // 4-bit field at bits 3..6 of each half-word
+constexpr uint32_t kMask3 = 0x00380038u;   // 3-bit field at bits 3..5 of each half-word
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xFFFF0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+}
+
+// (x & mask) | magic in one VALU op.  mask rides the constant bus (SGPR), magic a VGPR.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic)
+{
+    uint32_t d;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(magic));
+    return d;
+}
+
+// Field number f (of width b) of both half-words of v -> pair of bf16 (16 + code).
+template <int BITS>
+__device__ __forceinline__ uint32_t field_pair(uint32_t v, int f, uint32_t magic)
+{
+    constexpr uint32_t mask = BITS == 4 ? kMask4 : kMask3;
+    const int sh = BITS * f - 3;
+    const uint32_t x = sh < 0 ? (v << 3) : (sh == 0 ? v : (v >> sh));
+    return and_or(x, mask, magic);
+}
+
+// The 3-bit cell that lives in the spare top bits (15 and 31) of three words.
+__device__ __forceinline__ uint32_t spare_pair3(uint32_t v0, uint32_t v1, uint32_t v2, uint32_t magic)
+{
+    uint32_t t = and_or(v0 >> 12, 0x00080008u, magic);
+    t = and_or(v1 >> 11, 0x00100010u, t);
+    return and_or(v2 >> 10, 0x00200020u, t);
+}
+
+// ---------------------------------------------------------------------------------
+// One 8x8 block of codes (8 channels x 8 features; 2*BITS words) -> eight operand
+// fragments of 8 bf16 (4 registers) each.
+//
+// unpack_along_features: fragment r = channel r, elements = features 0..7 in order
+//   (the operand of a contraction over input features: forward, scale gradient).
+// unpack_along_channels: fragment c = feature c, elements = channels 0..7 in order
+//   (the operand of a contraction over output channels: dX).
+// Layout of the block's words: see peqa_bit_location() in peqa.h.
+// ---------------------------------------------------------------------------------
+template <int BITS>
+__device__ __forceinline__ void unpack_along_features(const uint32_t *w, u32x4 *frag, uint32_t magic)
+{
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) frag[r][j] = field_pair<4>(w[r], j, magic);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int rho = r / 2, par = r % 2;
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                const int u = 4 * rho + pr;
+                if (u < 15) frag[r][pr] = field_pair<3>(w[2 * (u / 5) + par], u % 5, magic);
+                else frag[r][pr] = spare_pair3(w[par], w[2 + par], w[4 + par], magic);
+            }
+        }
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void unpack_along_channels(const uint32_t *w, u32x4 *frag, uint32_t magic)
+{
+    // Merge the half-words of partner channels (2 rho, 2 rho + 1): after the merge the low
+    // half-word belongs to the even channel and the high half-word to the odd one, which is
+    // the element order of the fragment.
+    if constexpr (BITS == 4) {
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho) {
+            const uint32_t lo = __builtin_amdgcn_perm(w[2 * rho + 1], w[2 * rho], 0x05040100u);
+            const uint32_t hi = __builtin_amdgcn_perm(w[2 * rho + 1], w[2 * rho], 0x07060302u);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                frag[2 * p][rho] = field_pair<4>(lo, p, magic);      // even feature 2p: low half-word
+                frag[2 * p + 1][rho] = field_pair<4>(hi, p, magic);  // odd feature 2p+1: high half-word
+            }
+        }
+    } else {
+        uint32_t lo[3], hi[3];
+#pragma unroll
+        for (int m = 0; m < 3; ++m) {
+            lo[m] = __builtin_amdgcn_perm(w[2 * m + 1], w[2 * m], 0x05040100u);
+            hi[m] = __builtin_amdgcn_perm(w[2 * m + 1], w[2 * m], 0x07060302u);
+        }
+#pragma unroll
+        for (int rho = 0; rho < 4; ++rho) {
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                const int u = 4 * rho + pr;
+                if (u < 15) {
+                    frag[2 * pr][rho] = field_pair<3>(lo[u / 5], u % 5, magic);
+                    frag[2 * pr + 1][rho] = field_pair<3>(hi[u / 5], u % 5, magic);
+                } else {
+                    frag[2 * pr][rho] = spare_pair3(lo[0], lo[1], lo[2], magic);
+                    frag[2 * pr + 1][rho] = spare_pair3(hi[0], hi[1], hi[2], magic);
+                }
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ f32x4 mfma16(const u32x4 &a, const u32x4 &b, const f32x4 &c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+}  // namespace peqa

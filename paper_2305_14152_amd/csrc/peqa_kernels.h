@@ -1,0 +1,56 @@
+// Internal launch interface between the C-ABI layer (peqa_api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace peqa {
+
+enum { MODE_Y = 0, MODE_DDS = 1, MODE_DX = 2 };
+
+// Arguments of the tiled MFMA contraction (peqa_gemm.hip).
+struct GemmArgs {
+    const uint32_t *packed;   // packed codes of the whole layer
+    const uint16_t *A;        // activation operand [T, KC] bf16: X (MODE_Y, MODE_DDS) or scaled dY (MODE_DX)
+    int T;                    // tokens
+    int KC;                   // contraction length: K (MODE_Y/DDS) or N (MODE_DX)
+    int C;                    // output columns:     N (MODE_Y/DDS) or K (MODE_DX)
+    int K;                    // input features of the layer (fixes the block stride of `packed`)
+    int ksplit;               // contraction index where the second half starts (multiple of 64)
+    int tiles_c, tiles_t;     // ceil(C/256), ceil(T/128)
+    const float *s0;          // [N]            (MODE_Y)
+    const float *ds;          // [N] or NULL    (MODE_Y)
+    const uint8_t *z0;        // [N]            (MODE_Y, MODE_DDS)
+    const float *rs;          // [T, 2] sums of X[t, :] over each contraction half (MODE_Y, MODE_DDS)
+    const float *crow;        // [T] sum_i A[t,i] (16 + z_i)                      (MODE_DX)
+    const uint16_t *dY;       // [T, N] bf16    (MODE_DDS)
+    float *partial;           // [tiles_t, N]   (MODE_DDS) per-token-tile column sums
+    uint16_t *out;            // [T, C] bf16    (MODE_Y: Y, MODE_DX: dX)
+};
+
+hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
+
+// peqa_small.hip
+hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream);
+hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0,
+                           int T, int N, uint16_t *dYs, float *crow, hipStream_t stream);
+hipError_t launch_reduce_partials(const float *partial, int ntiles, size_t n, float *out, hipStream_t stream);
+hipError_t launch_adamw(size_t n, float *ds, const float *g, float *m, float *v, const float *s0,
+                        float lr, float b1, float b2, float eps, float wd, float inv_c1, float inv_c2,
+                        hipStream_t stream);
+
+// peqa_quantize.hip
+hipError_t launch_quantize(const float *W0, int N, int K, int bits, int group, uint32_t *packed,
+                           float *s0, uint8_t *z0, hipStream_t stream);
+
+// Tracing hook: every launch goes through these so that peqa_trace_* can time it.
+void trace_before(int kernel_id, hipStream_t stream);
+void trace_after(int kernel_id, hipStream_t stream);
+
+enum {
+    KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_COUNT
+};
+
+}  // namespace peqa

@@ -1,0 +1,145 @@
+// Bandwidth-bound helper kernels around the MFMA contractions: row sums of X, the scaled
+// copy of dY, the fixed-order reduction of scale-gradient partials, and the AdamW step.
+#include "peqa_device.h"
+#include "peqa_kernels.h"
+
+namespace peqa {
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// rs[t, h] = sum of X[t, k] over contraction half h (k < ksplit, k >= ksplit), fp32.
+// One wave per token row; 16-byte loads.
+__global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict__ X, int T, int K, int ksplit,
+                                                      float *__restrict__ rs)
+{
+    const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(X + (size_t)t * K);
+    float s[2] = {0.f, 0.f};
+    const int split8 = ksplit >> 3;
+    for (int k8 = lane; k8 < (K >> 3); k8 += 64) {
+        const u32x4 v = row[k8];
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p += bf16_lo(v[i]) + bf16_hi(v[i]);
+        if (k8 < split8) s[0] += p; else s[1] += p;
+    }
+    s[0] = wave_sum(s[0]);
+    s[1] = wave_sum(s[1]);
+    if (lane == 0) { rs[2 * t] = s[0]; rs[2 * t + 1] = s[1]; }
+}
+
+// dYs[t,i] = bf16(dY[t,i] * (s0+ds)[i]);  crow[t] = sum_i dYs[t,i] * (16 + z0[i])  (per-channel).
+// crow uses the rounded dYs so that it cancels the code offset of the dX contraction exactly.
+__global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ s0,
+                                                        const float *__restrict__ ds, const uint8_t *__restrict__ z0,
+                                                        int N, uint16_t *__restrict__ dYs, float *__restrict__ crow)
+{
+    __shared__ float red[4];
+    const int t = blockIdx.x, tid = threadIdx.x;
+    const u32x4 *src = reinterpret_cast<const u32x4 *>(dY + (size_t)t * N);
+    u32x4 *dst = reinterpret_cast<u32x4 *>(dYs + (size_t)t * N);
+    float acc = 0.f;
+    for (int n8 = tid; n8 < (N >> 3); n8 += 256) {
+        const u32x4 v = src[n8];
+        const f32x4 sa = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8);
+        const f32x4 sb = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8 + 4);
+        float s[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
+        if (ds) {
+            const f32x4 da = *reinterpret_cast<const f32x4 *>(ds + 8 * n8);
+            const f32x4 db = *reinterpret_cast<const f32x4 *>(ds + 8 * n8 + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { s[i] += da[i]; s[4 + i] += db[i]; }
+        }
+        const u32x2 zz = *reinterpret_cast<const u32x2 *>(z0 + 8 * n8);
+        u32x4 o;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t lo = float_to_bf16_bits(bf16_lo(v[p]) * s[2 * p]);
+            const uint32_t hi = float_to_bf16_bits(bf16_hi(v[p]) * s[2 * p + 1]);
+            o[p] = lo | (hi << 16);
+            const float zl = kCodeOffset + (float)((zz[(2 * p) >> 2] >> (8 * ((2 * p) & 3))) & 0xFFu);
+            const float zh = kCodeOffset + (float)((zz[(2 * p + 1) >> 2] >> (8 * ((2 * p + 1) & 3))) & 0xFFu);
+            acc += bf16_bits_to_float(lo) * zl + bf16_bits_to_float(hi) * zh;
+        }
+        dst[n8] = o;
+    }
+    acc = wave_sum(acc);
+    if ((tid & 63) == 0) red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) crow[t] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// out[j] = partial[0][j] + partial[1][j] + ... in that order (deterministic).
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial, int ntiles, size_t n,
+                                                               float *__restrict__ out)
+{
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    float s = 0.f;
+    for (int tt = 0; tt < ntiles; ++tt) s += partial[(size_t)tt * n + j];
+    out[j] = s;
+}
+
+__global__ __launch_bounds__(256) void adamw_kernel(size_t n, float *__restrict__ ds, const float *__restrict__ g,
+                                                     float *__restrict__ m, float *__restrict__ v,
+                                                     const float *__restrict__ s0, float lr, float b1, float b2,
+                                                     float eps, float wd, float inv_c1, float inv_c2)
+{
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float gj = g[j];
+    const float mj = b1 * m[j] + (1.f - b1) * gj;
+    const float vj = b2 * v[j] + (1.f - b2) * gj * gj;
+    m[j] = mj;
+    v[j] = vj;
+    const float d = ds[j];
+    ds[j] = d - lr * ((mj * inv_c1) / (sqrtf(vj * inv_c2) + eps) + wd * (s0[j] + d));
+}
+
+}  // namespace
+
+hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream)
+{
+    trace_before(KID_ROWSUM, stream);
+    hipLaunchKernelGGL(rowsum_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, X, T, K, ksplit, rs);
+    trace_after(KID_ROWSUM, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0, int T, int N,
+                           uint16_t *dYs, float *crow, hipStream_t stream)
+{
+    trace_before(KID_SCALE_DY, stream);
+    hipLaunchKernelGGL(scale_dy_kernel, dim3(T), dim3(256), 0, stream, dY, s0, ds, z0, N, dYs, crow);
+    trace_after(KID_SCALE_DY, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_partials(const float *partial, int ntiles, size_t n, float *out, hipStream_t stream)
+{
+    trace_before(KID_REDUCE, stream);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, partial,
+                       ntiles, n, out);
+    trace_after(KID_REDUCE, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_adamw(size_t n, float *ds, const float *g, float *m, float *v, const float *s0, float lr, float b1,
+                        float b2, float eps, float wd, float inv_c1, float inv_c2, hipStream_t stream)
+{
+    trace_before(KID_ADAMW, stream);
+    hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, n, ds, g, m, v, s0, lr,
+                       b1, b2, eps, wd, inv_c1, inv_c2);
+    trace_after(KID_ADAMW, stream);
+    return hipGetLastError();
+}
+
+}  // namespace peqa

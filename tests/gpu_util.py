@@ -1,0 +1,83 @@
+"""Helpers for the GPU parity tests: move seeded host inputs to the device, call the C-ABI
+through the binding, bring results back as numpy.  No arithmetic of the method here."""
+import numpy as np
+
+
+def _t():
+    import torch
+    return torch
+
+
+def to_dev(a):
+    torch = _t()
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def to_host(t, dtype=None):
+    a = t.cpu().numpy()
+    return a.view(dtype) if dtype is not None else a
+
+
+class GpuLayer:
+    """One PEQA linear resident on the GPU, quantized there by peqa_quantize."""
+
+    def __init__(self, W0, bits, group=0):
+        from paper_2305_14152_amd import peqa
+        torch = _t()
+        self.peqa, self.torch = peqa, torch
+        N, K = W0.shape
+        self.N, self.K, self.bits, self.group = N, K, bits, group
+        self.L = peqa.layout(N, K, bits, group)
+        G = self.L.groups
+        self.G = G
+        self.W0 = to_dev(np.ascontiguousarray(W0, np.float32))
+        self.packed = torch.empty(peqa.packed_words(self.L), dtype=torch.int32, device="cuda")
+        self.s0 = torch.empty((N, G), dtype=torch.float32, device="cuda")
+        self.z0 = torch.empty((N, G), dtype=torch.uint8, device="cuda")
+        peqa.quantize(self.L, self.W0, self.packed, self.s0, self.z0)
+        self._ws = {}
+
+    def workspace(self, T, op):
+        key = (T, op)
+        if key not in self._ws:
+            nbytes = self.peqa.workspace_bytes(self.L, T, op)
+            assert nbytes > 0
+            self._ws[key] = (self.torch.empty(nbytes, dtype=self.torch.uint8, device="cuda"), nbytes)
+        return self._ws[key]
+
+    def host_quant(self):
+        return (to_host(self.packed, np.uint32), to_host(self.s0), to_host(self.z0))
+
+    def fwd(self, X_bits, ds=None):
+        torch, peqa = self.torch, self.peqa
+        X = to_dev(X_bits) if isinstance(X_bits, np.ndarray) else X_bits
+        T = X.shape[0]
+        Y = torch.empty((T, self.N), dtype=torch.int16, device="cuda")
+        dsd = to_dev(np.ascontiguousarray(ds, np.float32)) if isinstance(ds, np.ndarray) else ds
+        ws, nb = self.workspace(T, peqa.PEQA_OP_FWD)
+        peqa.linear_fwd(self.L, self.packed, self.s0, dsd, self.z0, X, T, Y, ws, nb)
+        torch.cuda.synchronize()
+        return Y
+
+    def bwd(self, X_bits, dY_bits, ds=None, want_dX=True, want_dds=True):
+        torch, peqa = self.torch, self.peqa
+        X = to_dev(X_bits) if isinstance(X_bits, np.ndarray) else X_bits
+        dY = to_dev(dY_bits) if isinstance(dY_bits, np.ndarray) else dY_bits
+        T = dY.shape[0]
+        dX = torch.empty((T, self.K), dtype=torch.int16, device="cuda") if want_dX else None
+        dds = torch.empty((self.N, self.G), dtype=torch.float32, device="cuda") if want_dds else None
+        dsd = to_dev(np.ascontiguousarray(ds, np.float32)) if isinstance(ds, np.ndarray) else ds
+        ws, nb = self.workspace(T, peqa.PEQA_OP_BWD)
+        peqa.linear_bwd(self.L, self.packed, self.s0, dsd, self.z0, X, dY, T, dX, dds, ws, nb)
+        torch.cuda.synchronize()
+        return dX, dds
+
+
+def bf16_dev_to_f64(t):
+    from paper_2305_14152_amd import synth
+    return synth.bf16_bits_to_f32(to_host(t).view(np.uint16)).astype(np.float64)

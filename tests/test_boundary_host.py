@@ -1,0 +1,109 @@
+"""Host-side tests of the C-ABI library: it loads, exports every declared symbol, its
+host-only helpers agree with the stated layout, and argument validation returns status
+codes before the device is touched.  No GPU needed."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def peqa():
+    from paper_2305_14152_amd import peqa as p
+    if not os.path.exists(p.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    p.lib()
+    return p
+
+
+def test_library_exports_every_declared_symbol(peqa):
+    header = open(os.path.join(ROOT, "include", "peqa.h")).read()
+    declared = set(re.findall(r"\b(peqa_[a-z_0-9]+)\s*\(", header))
+    assert {"peqa_quantize", "peqa_linear_fwd", "peqa_linear_bwd", "peqa_scale_update"} <= declared
+    L = ctypes.CDLL(peqa.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(peqa.EXPORTS)
+
+
+def test_layout_helpers(peqa):
+    L = peqa.layout(4096, 11008, 4)
+    assert peqa.check_layout(L) == peqa.PEQA_OK
+    assert peqa.packed_words(L) == 4096 * 11008 * 4 // 32
+    assert peqa.num_scales(L) == 4096
+    L3 = peqa.layout(5120, 13824, 3, 128)
+    assert peqa.packed_words(L3) == 5120 * 13824 * 3 // 32
+    assert peqa.num_scales(L3) == 5120 * 108
+    assert peqa.workspace_bytes(L, 2048, peqa.PEQA_OP_FWD) > 0
+    assert peqa.workspace_bytes(L, 2048, peqa.PEQA_OP_BWD) > 2048 * 4096 * 2
+    assert peqa.workspace_bytes(L, 0, peqa.PEQA_OP_FWD) == 0
+    assert peqa.workspace_bytes(L, 8, 7) == 0
+
+
+@pytest.mark.parametrize("args,status", [
+    ((4096, 4096, 5, 0), 3), ((4096, 4096, 2, 0), 3), ((4000, 4096, 4, 0), 2), ((4096, 100, 4, 0), 2),
+    ((0, 4096, 4, 0), 2), ((4096, 4096, 4, 96), 4), ((4096, 4096, 4, -1), 4), ((4096, 4096 + 128, 3, 256), 4),
+])
+def test_bad_layouts_are_rejected(peqa, args, status):
+    L = peqa.layout(*args)
+    assert peqa.check_layout(L) == status
+    assert peqa.packed_words(L) == 0 and peqa.num_scales(L) == 0
+    assert peqa.status_string(status) != "unknown status"
+
+
+@pytest.mark.parametrize("bits", [3, 4])
+def test_bit_location_matches_the_oracles_map(peqa, oracle, bits):
+    """The library's statement of its packing layout against the oracle's independent one."""
+    L = peqa.layout(128, 256, bits)
+    r = np.random.default_rng(bits)
+    pts = [(int(r.integers(128)), int(r.integers(256)), int(r.integers(bits))) for _ in range(500)]
+    pts += [(i, k, t) for i in range(8) for k in range(8) for t in range(bits)]
+    for (i, k, t) in pts:
+        assert peqa.bit_location(L, i, k, t) == oracle.bit_location(256, bits, i, k, t)
+    with pytest.raises(peqa.PeqaError):
+        peqa.bit_location(L, 128, 0, 0)
+
+
+def test_argument_validation_needs_no_device(peqa):
+    L = peqa.layout(256, 256, 4)
+    good, bad = 0x10000, 0x10004            # never dereferenced: validation fails first
+    lib = peqa.lib()
+    byref = ctypes.byref
+    assert lib.peqa_quantize(byref(L), None, good, good, good, None) == peqa.PEQA_ERR_NULL
+    assert lib.peqa_quantize(byref(L), good, bad, good, good, None) == peqa.PEQA_ERR_ALIGN
+    assert lib.peqa_quantize(None, good, good, good, good, None) == peqa.PEQA_ERR_NULL
+    Lbad = peqa.layout(256, 256, 7)
+    assert lib.peqa_quantize(byref(Lbad), good, good, good, good, None) == peqa.PEQA_ERR_BITS
+    f = lib.peqa_linear_fwd
+    assert f(byref(L), good, good, None, good, None, 8, good, good, 1 << 20, None) == peqa.PEQA_ERR_NULL
+    assert f(byref(L), good, good, None, good, good, 0, good, good, 1 << 20, None) == peqa.PEQA_ERR_SHAPE
+    assert f(byref(L), good, good, bad, good, good, 8, good, good, 1 << 20, None) == peqa.PEQA_ERR_ALIGN
+    assert f(byref(L), good, good, None, good, good, 8, good, None, 0, None) == peqa.PEQA_ERR_WORKSPACE
+    assert f(byref(L), good, good, None, good, good, 8, good, good, 16, None) == peqa.PEQA_ERR_WORKSPACE
+    b = lib.peqa_linear_bwd
+    assert b(byref(L), good, good, None, good, good, None, 8, good, good, good, 1 << 30, None) == peqa.PEQA_ERR_NULL
+    assert b(byref(L), good, good, None, good, None, good, 8, None, good, good, 1 << 30, None) == peqa.PEQA_ERR_NULL
+    assert b(byref(L), good, good, None, good, good, good, 8, good, good, good, 64, None) == peqa.PEQA_ERR_WORKSPACE
+    opt = peqa.AdamW(1e-3, 0.9, 0.999, 1e-8, 0.0, 0)
+    u = lib.peqa_scale_update
+    assert u(16, good, good, good, good, good, byref(opt), None) == peqa.PEQA_ERR_PARAM
+    opt.step = 1
+    assert u(16, good, None, good, good, good, byref(opt), None) == peqa.PEQA_ERR_NULL
+    assert u(0, good, good, good, good, good, byref(opt), None) == peqa.PEQA_ERR_SHAPE
+    opt.beta1 = 1.0
+    assert u(16, good, good, good, good, good, byref(opt), None) == peqa.PEQA_ERR_PARAM
+
+
+def test_product_package_does_not_touch_the_oracle():
+    """The product path may not import, read or link anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2305_14152_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "synth.py", f

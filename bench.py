@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the PEQA quantized-linear hot path on one MI355X.
+
+One "step" = one training pass over the seven linears of a LLaMA-7B decoder block
+(4-bit per-channel codes, T = 2048 tokens): forward Y, backward dX, scale gradient d_ds
+and the AdamW scale update, all through the C-ABI library.  Quantization is the method's
+one-time decomposition step and is done (and timed) once before the loop.
+
+Prints ONE JSON line: fwd+bwd TFLOP/s counting 6*T*N*K flops per layer (three dense
+contractions: forward, dX, and the product recomputed for the scale gradient), with
+  roofline     - the dominant kernel against the bf16 MFMA peak, timed with HIP events
+  cpu_baseline - the CPU oracle timed on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="workload index (see synth.CONFIGS)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+class Layer:
+    def __init__(self, torch, peqa, N, K, bits, group, T, seed, w_std, dy_std):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        self.N, self.K, self.T = N, K, T
+        self.L = peqa.layout(N, K, bits, group)
+        G = self.L.groups
+        W0 = torch.randn((N, K), generator=g, device="cuda", dtype=torch.float32) * w_std
+        self.packed = torch.empty(peqa.packed_words(self.L), dtype=torch.int32, device="cuda")
+        self.s0 = torch.empty((N, G), dtype=torch.float32, device="cuda")
+        self.z0 = torch.empty((N, G), dtype=torch.uint8, device="cuda")
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        peqa.quantize(self.L, W0, self.packed, self.s0, self.z0)
+        torch.cuda.synchronize()
+        self.quantize_ms = (time.perf_counter() - t0) * 1e3
+        del W0
+        self.ds = torch.zeros((N, G), dtype=torch.float32, device="cuda")
+        self.m = torch.zeros_like(self.ds)
+        self.v = torch.zeros_like(self.ds)
+        self.dds = torch.empty_like(self.ds)
+        self.X = torch.randn((T, K), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        self.dY = (torch.randn((T, N), generator=g, device="cuda", dtype=torch.float32) * dy_std).to(torch.bfloat16)
+        self.Y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+        self.dX = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+        self.ws_fwd = peqa.workspace_bytes(self.L, T, peqa.PEQA_OP_FWD)
+        self.ws_bwd = peqa.workspace_bytes(self.L, T, peqa.PEQA_OP_BWD)
+
+
+def cpu_baseline(cfg, seconds):
+    """The oracle as it stands, on a bounded sample: the first layer shape of the workload,
+    forward + dX + scale gradient on a few token rows (rows are independent for Y and dX, and the
+    scale gradient is a sum over rows), sized by a short calibration run."""
+    import numpy as np
+    from oracle import peqa_oracle as oracle
+    from paper_2305_14152_amd import synth
+    N, K, _ = cfg["layers"][0]
+    W = synth.normal_f32(1, (N, K), cfg["w_std"])
+    codes, s0, z0 = oracle.quantize(W, cfg["bits"], cfg["group"])
+
+    def run(T):
+        X = synth.normal_bf16(2, (T, K), 1.0)
+        dY = synth.normal_bf16(3, (T, N), cfg["dy_std"])
+        t0 = time.perf_counter()
+        oracle.fwd(codes, s0, None, z0, X, cfg["group"])
+        oracle.bwd(codes, s0, None, z0, X, dY, cfg["group"])
+        return time.perf_counter() - t0
+
+    t1 = run(1)
+    T = int(max(2, min(512, seconds / max(t1, 1e-6))))
+    dt = run(T)
+    flops = 6.0 * T * N * K
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": "layer %dx%d, %d-bit, %d token rows: fwd + dX + scale gradient, %.1f s" % (N, K, cfg["bits"], T, dt),
+            "tokens_per_s_block_extrapolated": None}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no cross-GPU step); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2305_14152_amd import peqa, synth
+    peqa.lib()                                   # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = synth.CONFIGS[args.config]
+    T, bits, group = cfg["T"], cfg["bits"], cfg["group"]
+
+    layers = []
+    li = 0
+    for (N, K, count) in cfg["layers"]:
+        for _ in range(count):
+            layers.append(Layer(torch, peqa, N, K, bits, group, T, synth.seed_for(args.config, li, 0),
+                                cfg["w_std"], cfg["dy_std"]))
+            li += 1
+    ws_bytes = max(max(l.ws_fwd, l.ws_bwd) for l in layers)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    step_no = [0]
+
+    def step():
+        step_no[0] += 1
+        for l in layers:
+            peqa.linear_fwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, T, l.Y, ws, ws_bytes, stream)
+        for l in reversed(layers):
+            peqa.linear_bwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, l.dY, T, l.dX, l.dds, ws, ws_bytes, stream)
+        for l in layers:
+            peqa.scale_update(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0, lr=1e-5, step=step_no[0], stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    flops_step = synth.block_flops(args.config)
+    tflops = flops_step / (dt / args.steps) / 1e12
+
+    # per-kernel durations: the same steps again, every launch bracketed by HIP events
+    launches_per_step = len(layers) * 8
+    peqa.trace_begin(launches_per_step * args.steps + 16)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    trace = peqa.trace_end(16)
+    gemm_flops = {"gemm_y": 0.0, "gemm_dds": 0.0, "gemm_dx": 0.0}
+    for l in layers:
+        for k in gemm_flops:
+            gemm_flops[k] += 2.0 * T * l.N * l.K * args.steps
+    dom = max((k for k in gemm_flops if k in trace), key=lambda k: trace[k][1])
+    dom_launches, dom_ms = trace[dom]
+    achieved = gemm_flops[dom] / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": round(dom_ms * 1e3 / dom_launches, 2), "launches": dom_launches}
+    kernels = {k: {"launches": n, "avg_us": round(ms * 1e3 / n, 2),
+                   "tflops": round(gemm_flops[k] / (ms * 1e-3) / 1e12, 1) if k in gemm_flops else None}
+               for k, (n, ms) in trace.items()}
+
+    out = {
+        "metric": "PEQA quantized-linear fwd+bwd TFLOP/s, LLaMA-7B shapes T=2048" if args.config == 1
+                  else "PEQA quantized-linear fwd+bwd TFLOP/s, %s" % cfg["name"],
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: 7 linears of one decoder block, %d-bit %s, T=%d, fwd + dX + d_ds + AdamW"
+                               % (cfg["name"], bits, "per-channel" if not group else "g%d" % group, T)},
+        "frac_of_bf16_mfma_peak": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+        "tokens_per_s": round(T / (dt / args.steps), 1),
+        "flops_per_step": flops_step,
+        "quantize_ms_total": round(sum(l.quantize_ms for l in layers), 3),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds)
+        out["cpu_baseline"].pop("tokens_per_s_block_extrapolated")
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

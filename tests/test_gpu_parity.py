@@ -142,22 +142,25 @@ def test_scale_update_parity(gpu, oracle):
     ds = (r.standard_normal(n) * 1e-4).astype(np.float32)
     m = np.zeros(n, np.float32); v = np.zeros(n, np.float32)
     d = {k: gpu.to_dev(a) for k, a in dict(s0=s0, ds=ds, m=m, v=v).items()}
-    ref = (ds.astype(np.float64), m.astype(np.float64), v.astype(np.float64))
     # the optimizer constants cross the boundary as fp32: the oracle gets those same values
     lr, b1, b2, eps, wd = (float(np.float32(x)) for x in (1e-3, 0.9, 0.999, 1e-8, 0.01))
     for step in range(1, 4):
         g = (r.standard_normal(n) * 10.0 ** r.uniform(-4, 1, n)).astype(np.float32)
         g[::97] = 0.0
+        # each call is checked on its own: the oracle starts from the state the GPU call starts from
+        before = tuple(gpu.to_host(d[k]).astype(np.float64) for k in ("ds", "m", "v"))
         peqa.scale_update(n, d["ds"], gpu.to_dev(g), d["m"], d["v"], d["s0"], lr=lr, beta1=b1, beta2=b2,
                           eps=eps, weight_decay=wd, step=step)
         torch.cuda.synchronize()
-        ref = oracle.adamw(ref[0], g, ref[1], ref[2], s0, lr, b1, b2, eps, wd, step)
+        ref = oracle.adamw(before[0], g, before[1], before[2], s0, lr, b1, b2, eps, wd, step)
         got = gpu.to_host(d["ds"]).astype(np.float64)
         s_ref = s0.astype(np.float64) + ref[0]
         # compare the parameter itself (s0 + ds): relative 1e-6
         assert np.abs((s0.astype(np.float64) + got) - s_ref).max() <= 1e-6 * np.abs(s_ref).max()
-        np.testing.assert_allclose(gpu.to_host(d["m"]), ref[1], rtol=2e-6, atol=1e-30)
-        np.testing.assert_allclose(gpu.to_host(d["v"]), ref[2], rtol=2e-6, atol=1e-30)
+        # m is a difference of two fp32 terms when the gradient changes sign: bound by their magnitudes
+        m_bound = 1e-6 * (b1 * np.abs(before[1]) + (1 - b1) * np.abs(g)) + 1e-30
+        assert (np.abs(gpu.to_host(d["m"]) - ref[1]) <= m_bound).all()
+        np.testing.assert_allclose(gpu.to_host(d["v"]), ref[2], rtol=1e-6, atol=1e-30)
 
 
 def test_trace_reports_kernels(gpu):

@@ -41,8 +41,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 // (x & mask) | magic in one VALU op.  mask rides the constant bus (SGPR), magic a VGPR.
 __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic)
 {
+    // volatile so that the unpacking stays where the caller interleaves it with matrix instructions
     uint32_t d;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(magic));
+    asm volatile("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(magic));
     return d;
 }
 
@@ -66,82 +67,83 @@ __device__ __forceinline__ uint32_t spare_pair3(uint32_t v0, uint32_t v1, uint32
 
 // ---------------------------------------------------------------------------------
 // One 8x8 block of codes (8 channels x 8 features; 2*BITS words) -> eight operand
-// fragments of 8 bf16 (4 registers) each.
+// fragments of 8 bf16 (4 registers) each, produced one at a time so that callers can
+// spread the unpacking between matrix instructions.
 //
-// unpack_along_features: fragment r = channel r, elements = features 0..7 in order
+// Along features: fragment r = channel r, elements = features 0..7 in order
 //   (the operand of a contraction over input features: forward, scale gradient).
-// unpack_along_channels: fragment c = feature c, elements = channels 0..7 in order
+// Along channels: fragment f = feature f, elements = channels 0..7 in order
 //   (the operand of a contraction over output channels: dX).
 // Layout of the block's words: see peqa_bit_location() in peqa.h.
 // ---------------------------------------------------------------------------------
-template <int BITS>
-__device__ __forceinline__ void unpack_along_features(const uint32_t *w, u32x4 *frag, uint32_t magic)
-{
-    if constexpr (BITS == 4) {
+template <int BITS, bool ALONG_CH>
+struct BlockUnpacker {
+    static constexpr int WPB = 2 * BITS;
+    uint32_t lo[4], hi[4];      // along channels: half-words of partner channels merged
+    uint32_t w[WPB];
+
+    __device__ __forceinline__ void prepare(const uint32_t *words)
+    {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
+        for (int i = 0; i < WPB; ++i) w[i] = words[i];
+        if constexpr (ALONG_CH) {
+            // After the merge the low half-word belongs to the even channel of a partner pair and
+            // the high half-word to the odd one, which is the element order of the fragment.
 #pragma unroll
-            for (int j = 0; j < 4; ++j) frag[r][j] = field_pair<4>(w[r], j, magic);
-        }
-    } else {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int rho = r / 2, par = r % 2;
-#pragma unroll
-            for (int pr = 0; pr < 4; ++pr) {
-                const int u = 4 * rho + pr;
-                if (u < 15) frag[r][pr] = field_pair<3>(w[2 * (u / 5) + par], u % 5, magic);
-                else frag[r][pr] = spare_pair3(w[par], w[2 + par], w[4 + par], magic);
+            for (int m = 0; m < BITS; ++m) {
+                lo[m] = __builtin_amdgcn_perm(w[2 * m + 1], w[2 * m], 0x05040100u);
+                hi[m] = __builtin_amdgcn_perm(w[2 * m + 1], w[2 * m], 0x07060302u);
             }
         }
     }
-}
 
-template <int BITS>
-__device__ __forceinline__ void unpack_along_channels(const uint32_t *w, u32x4 *frag, uint32_t magic)
-{
-    // Merge the half-words of partner channels (2 rho, 2 rho + 1): after the merge the low
-    // half-word belongs to the even channel and the high half-word to the odd one, which is
-    // the element order of the fragment.
-    if constexpr (BITS == 4) {
-#pragma unroll
-        for (int rho = 0; rho < 4; ++rho) {
-            const uint32_t lo = __builtin_amdgcn_perm(w[2 * rho + 1], w[2 * rho], 0x05040100u);
-            const uint32_t hi = __builtin_amdgcn_perm(w[2 * rho + 1], w[2 * rho], 0x07060302u);
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                frag[2 * p][rho] = field_pair<4>(lo, p, magic);      // even feature 2p: low half-word
-                frag[2 * p + 1][rho] = field_pair<4>(hi, p, magic);  // odd feature 2p+1: high half-word
+    // register j (0..3: elements 2j, 2j+1) of fragment i (0..7); i, j known at compile time after unrolling
+    __device__ __forceinline__ uint32_t frag_reg(int i, int j, uint32_t magic) const
+    {
+        if constexpr (!ALONG_CH) {
+            if constexpr (BITS == 4) {
+                return field_pair<4>(w[i], j, magic);
+            } else {
+                const int par = i % 2, u = 4 * (i / 2) + j;
+                if (u < 15) return field_pair<3>(w[2 * (u / 5) + par], u % 5, magic);
+                return spare_pair3(w[par], w[2 + par], w[4 + par], magic);
             }
-        }
-    } else {
-        uint32_t lo[3], hi[3];
-#pragma unroll
-        for (int m = 0; m < 3; ++m) {
-            lo[m] = __builtin_amdgcn_perm(w[2 * m + 1], w[2 * m], 0x05040100u);
-            hi[m] = __builtin_amdgcn_perm(w[2 * m + 1], w[2 * m], 0x07060302u);
-        }
-#pragma unroll
-        for (int rho = 0; rho < 4; ++rho) {
-#pragma unroll
-            for (int pr = 0; pr < 4; ++pr) {
-                const int u = 4 * rho + pr;
-                if (u < 15) {
-                    frag[2 * pr][rho] = field_pair<3>(lo[u / 5], u % 5, magic);
-                    frag[2 * pr + 1][rho] = field_pair<3>(hi[u / 5], u % 5, magic);
-                } else {
-                    frag[2 * pr][rho] = spare_pair3(lo[0], lo[1], lo[2], magic);
-                    frag[2 * pr + 1][rho] = spare_pair3(hi[0], hi[1], hi[2], magic);
-                }
+        } else {
+            const bool odd = i & 1;                 // odd features live in the high half-words
+            const int p = i >> 1;
+            if constexpr (BITS == 4) {
+                return field_pair<4>(odd ? hi[j] : lo[j], p, magic);
+            } else {
+                const int u = 4 * j + p;
+                if (u < 15) return field_pair<3>(odd ? hi[u / 5] : lo[u / 5], u % 5, magic);
+                return odd ? spare_pair3(hi[0], hi[1], hi[2], magic) : spare_pair3(lo[0], lo[1], lo[2], magic);
             }
         }
     }
-}
 
-__device__ __forceinline__ f32x4 mfma16(const u32x4 &a, const u32x4 &b, const f32x4 &c)
+    __device__ __forceinline__ u32x4 frag(int i, uint32_t magic) const
+    {
+        u32x4 f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) f[j] = frag_reg(i, j, magic);
+        return f;
+    }
+};
+
+// D += A * B on one 16x16 tile with a 32-deep contraction.  Issued as inline assembly with the
+// accumulator tied to an AGPR tuple: with the builtin, this compiler keeps rotating part of a
+// 256-register accumulator set through VGPRs on every loop iteration.  The hardware does not
+// interlock a read of the result by a non-matrix instruction: callers must put at least 18 wait
+// states (mfma_result_fence) between the last of these and the first such read.
+__device__ __forceinline__ void mfma16_acc(f32x4 &acc, const u32x4 &a, const u32x4 &b)
 {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
-                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    // volatile: keeps the source order of the matrix instructions among themselves and relative
+    // to the DMA queueing and the result fence (the scalar/vector work around them is still free)
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_result_fence()
+{
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
 }
 
 }  // namespace peqa

@@ -19,6 +19,8 @@
 // (peqa_device.h).  The contraction therefore runs on exact small integers; the offset 16,
 // the zero-point and the scale are applied in the epilogue from row sums of the other
 // operand:   sum_k X (Q - z) = sum_k X (16 + Q) - (16 + z) sum_k X.
+#include <type_traits>
+
 #include "peqa_device.h"
 #include "peqa_kernels.h"
 
@@ -28,9 +30,28 @@ namespace {
 
 constexpr int TILE_T = 128;
 constexpr int TILE_C = 256;
-constexpr int KSTEP = 64;
-constexpr int A_TILE_BYTES = TILE_T * KSTEP * 2;          // 16 KB
-constexpr int LDS_BYTES = 128 * 1024;                      // A stages (64 KB) / epilogue exchange (128 KB)
+constexpr int KSTEP = 32;                                  // contraction depth of one loop iteration
+constexpr int NSTAGE = 4;                                  // LDS ring depth (power of two)
+constexpr int A_HALF_BYTES = TILE_T * KSTEP * 2;           // 8 KB: 128 rows x 32 bf16 of one contraction half
+constexpr int B_WAVE_BYTES = 2048;                         // one packed 8x8 block per lane (32 B / 24 B)
+constexpr int STAGE_BYTES = 2 * A_HALF_BYTES + 4 * B_WAVE_BYTES;   // 24 KB
+constexpr int DMA_PER_ITER = 6;                            // DMA instructions per wave per iteration
+constexpr int LDS_BYTES = 128 * 1024;                      // ring (96 KB) / epilogue exchange (128 KB)
+
+// Global -> LDS DMA of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l.  The source
+// is sbase (uniform) + voff (per lane).  Issued from inline assembly so that the compiler does not
+// serialise the ring with a conservative vmcnt(0); completion is tracked by hand with wait_vmcnt().
+__device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t lds_dst)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; other counters left open
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
 
 template <int BITS, int MODE>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
@@ -39,7 +60,8 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
     constexpr int WPB = 2 * BITS;                          // words per 8x8 block
     constexpr bool ALONG_CH = (MODE == MODE_DX);           // contraction over output channels
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int wn = wave & 1, wk = wave >> 1;
     const int c = lane & 15, q = lane >> 4;
 
@@ -61,88 +83,76 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
     const int col0 = tile_c * TILE_C + wn * 128;           // first output column of this wave
     const bool wave_on = col0 < a.C;
     const int T = a.T, KC = a.KC;
-    const int kbeg = wk ? a.ksplit : 0;
-    const int nsteps0 = a.ksplit / KSTEP, nsteps1 = (KC - a.ksplit) / KSTEP;
-    const int nsteps_mine = wk ? nsteps1 : nsteps0;
-    const int nsteps = nsteps0 > nsteps1 ? nsteps0 : nsteps1;
+    const int khalf = KC >> 1;                             // both waves of a column half take KC/2
+    const int kbeg = wk ? khalf : 0;
+    const int nit = khalf / KSTEP;                         // loop iterations (>= 2: KC % 128 == 0)
     const int kblocks = a.K >> 3;                          // blocks per channel-row of blocks
-
     const uint32_t magic = kMagic;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
-    // ---- activation tile loads: 8 chunks of 16 B per thread per step (4 per contraction half)
-    const int a_row = tid >> 3, a_c8 = tid & 7;
-    const uint16_t *a_src[4];
+    // ---- activation tiles: global -> LDS by DMA, 16 wave-loads of 1 KB per iteration (4 per wave).
+    // Wave-load m = 4 i + wave covers contraction half m / 8, rows 16 (m % 8) .. +16; lane s lands at
+    // byte 16 s of that 1 KB, i.e. row s / 4, chunk position s % 4, and fetches the chunk that the
+    // XOR swizzle assigns to that position.
+    uint32_t a_voff[4];
+    {
+        const int row_l = lane >> 2, pos = lane & 3;
+        const int chunk = pos ^ ((row_l >> 2) & 3);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        int t = t0 + j * 32 + a_row;
-        t = t < T ? t : T - 1;
-        a_src[j] = a.A + (size_t)t * KC + a_c8 * 8;
+        for (int i = 0; i < 4; ++i) {
+            const int m = 4 * i + wave;
+            int row = (m & 7) * 16 + row_l;
+            row = t0 + row < T ? row : T - 1 - t0;
+            a_voff[i] = (uint32_t)row * (uint32_t)KC * 2u + (uint32_t)chunk * 16u;
+        }
     }
-    const int a_lds_off = a_row * 128 + ((a_c8 ^ (a_row & 7)) << 4);
+    const uint8_t *a_base = reinterpret_cast<const uint8_t *>(a.A) + (size_t)t0 * KC * 2;
 
-    // ---- packed weight loads
-    // along features: lane (c, q) owns channel block col0/8 + c and feature blocks 2q, 2q+1 of the step
-    // along channels: lane (c, q) owns feature block col0/8 + c and channel blocks 2q, 2q+1 of the step
-    const uint32_t *b_src;
-    size_t b_step;                                         // words to advance per contraction step
-    size_t b_second;                                       // offset of the lane's second block
+    // ---- packed weights: one 8x8 block per lane per iteration, also by DMA into the wave's own slot
+    // along features: lane (c, q) owns channel block col0/8 + c and feature block 4 it + q
+    // along channels: lane (c, q) owns feature block col0/8 + c and channel block 4 it + q
+    const uint8_t *b_base;
+    size_t b_step;                                         // bytes to advance per iteration
+    uint32_t b_voff, b_voff2 = 0;
+    int b_lane_off;                                        // where this lane's block sits in the wave's LDS slot
     if constexpr (!ALONG_CH) {
-        b_src = a.packed + ((size_t)(col0 / 8 + c) * kblocks + (kbeg >> 3) + 2 * q) * WPB;
-        b_step = (size_t)8 * WPB;
-        b_second = WPB;
+        b_base = reinterpret_cast<const uint8_t *>(a.packed + ((size_t)(col0 / 8) * kblocks + (kbeg >> 3)) * WPB);
+        b_step = (size_t)4 * WPB * 4;
     } else {
-        b_src = a.packed + ((size_t)((kbeg >> 3) + 2 * q) * kblocks + (col0 / 8 + c)) * WPB;
-        b_step = (size_t)8 * kblocks * WPB;
-        b_second = (size_t)kblocks * WPB;
+        b_base = reinterpret_cast<const uint8_t *>(a.packed + ((size_t)(kbeg >> 3) * kblocks + col0 / 8) * WPB);
+        b_step = (size_t)4 * kblocks * WPB * 4;
     }
+    if constexpr (BITS == 4) {
+        // two DMAs of 16 B per lane: the halves of the lane's own 32-byte block
+        b_voff = (uint32_t)(ALONG_CH ? q * kblocks + c : c * kblocks + q) * 32u;
+        b_lane_off = lane * 16;
+    } else {
+        // 24-byte blocks: the wave's 64 blocks form 16 runs of 96 B (along features) or 4 runs of
+        // 384 B (along channels) = 96 chunks of 16 B, fetched as chunk `lane` and chunk `64 + lane`
+        // and laid down in LDS in chunk order.
+        constexpr int RUN = ALONG_CH ? 24 : 6;             // chunks per contiguous run
+        const int x0 = lane, x1 = 64 + (lane & 31);
+        b_voff = (uint32_t)(x0 / RUN) * (uint32_t)kblocks * 24u + (uint32_t)(x0 % RUN) * 16u;
+        b_voff2 = (uint32_t)(x1 / RUN) * (uint32_t)kblocks * 24u + (uint32_t)(x1 % RUN) * 16u;
+        b_lane_off = ALONG_CH ? q * 384 + c * 24 : c * 96 + q * 24;
+    }
+    if (!wave_on) { b_base = reinterpret_cast<const uint8_t *>(a.packed); b_step = 0; b_voff = lane * 32; b_voff2 = lane * 32; }
 
-    u32x4 areg[8];
-    uint32_t breg[2][2 * WPB];
-
-    auto load_a = [&](int ks) {
+    auto issue = [&](int it, int stage) {
+        const uint32_t sb = lds_base + stage * STAGE_BYTES;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int ns = h ? nsteps1 : nsteps0;
-            const int kb = (h ? a.ksplit : 0) + ks * KSTEP;
-            if (ks < ns) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    areg[h * 4 + j] = *reinterpret_cast<const u32x4 *>(a_src[j] + kb);
-            }
+        for (int i = 0; i < 4; ++i) {
+            const int m = 4 * i + wave, h = m >> 3;
+            dma16(a_voff[i], a_base + ((size_t)h * khalf + (size_t)it * KSTEP) * 2, sb + h * A_HALF_BYTES + (m & 7) * 1024);
         }
-    };
-    auto store_a = [&](int ks, int stage) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int ns = h ? nsteps1 : nsteps0;
-            if (ks < ns) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    *reinterpret_cast<u32x4 *>(lds + (h * 2 + stage) * A_TILE_BYTES + j * 32 * 128 + a_lds_off) =
-                        areg[h * 4 + j];
-            }
-        }
-    };
-    auto load_b = [&](int ks, int buf) {
-        if (wave_on && ks < nsteps_mine) {
-            const uint32_t *p = b_src + (size_t)ks * b_step;
-#pragma unroll
-            for (int blk = 0; blk < 2; ++blk) {
-                const uint32_t *pb = p + blk * b_second;
-                if constexpr (BITS == 4) {
-                    const u32x4 v0 = *reinterpret_cast<const u32x4 *>(pb);
-                    const u32x4 v1 = *reinterpret_cast<const u32x4 *>(pb + 4);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) { breg[buf][blk * 8 + i] = v0[i]; breg[buf][blk * 8 + 4 + i] = v1[i]; }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 3; ++i) {
-                        const u32x2 v = *reinterpret_cast<const u32x2 *>(pb + 2 * i);
-                        breg[buf][blk * 6 + 2 * i] = v[0];
-                        breg[buf][blk * 6 + 2 * i + 1] = v[1];
-                    }
-                }
-            }
+        const uint8_t *bp = b_base + (size_t)it * b_step;
+        const uint32_t bb = sb + 2 * A_HALF_BYTES + wave * B_WAVE_BYTES;
+        if constexpr (BITS == 4) {
+            dma16(b_voff, bp, bb);
+            dma16(b_voff, bp + 16, bb + 1024);
+        } else {
+            dma16(b_voff, bp, bb);
+            dma16(b_voff2, bp, bb + 1024);      // lanes 32..63 repeat chunks 64..95 into the unused tail of the slot
         }
     };
 
@@ -152,38 +162,85 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // ---- prologue
-    load_a(0);
-    load_b(0, 0);
-    store_a(0, 0);
-    __syncthreads();
+    // row = 16 rt + c, so (row >> 2) & 3 = (c >> 2) & 3
+    const int a_read_off = wk * A_HALF_BYTES + c * 64 + ((q ^ ((c >> 2) & 3)) << 4);
+    const int b_read_off = 2 * A_HALF_BYTES + wave * B_WAVE_BYTES + b_lane_off;
 
-    const int a_read_base = wk * 2 * A_TILE_BYTES + c * 128;   // row = 16 rt + c; row & 7 = c & 7
-    const int csw = c & 7;
-
-    for (int ks = 0; ks < nsteps; ++ks) {
-        const int stage = ks & 1;
-        load_a(ks + 1);
-        load_b(ks + 1, stage ^ 1);
-        if (wave_on && ks < nsteps_mine) {
+    auto read_b = [&](int stage, uint32_t *bw) {
+        const uint8_t *st = lds + stage * STAGE_BYTES + b_read_off;
+        if constexpr (BITS == 4) {
+            const u32x4 v0 = *reinterpret_cast<const u32x4 *>(st);
+            const u32x4 v1 = *reinterpret_cast<const u32x4 *>(st + 1024);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                u32x4 bfrag[8];
-                if constexpr (!ALONG_CH) unpack_along_features<BITS>(&breg[stage][j * WPB], bfrag, magic);
-                else unpack_along_channels<BITS>(&breg[stage][j * WPB], bfrag, magic);
-                const int chunk = ((2 * q + j) ^ csw) << 4;
+            for (int i = 0; i < 4; ++i) { bw[i] = v0[i]; bw[4 + i] = v1[i]; }
+        } else {
 #pragma unroll
-                for (int rt = 0; rt < 8; ++rt) {
-                    const u32x4 afrag = *reinterpret_cast<const u32x4 *>(
-                        lds + a_read_base + stage * A_TILE_BYTES + rt * 16 * 128 + chunk);
-#pragma unroll
-                    for (int ct = 0; ct < 8; ++ct) acc[rt][ct] = mfma16(afrag, bfrag[ct], acc[rt][ct]);
-                }
+            for (int i = 0; i < 3; ++i) {
+                const u32x2 v = *reinterpret_cast<const u32x2 *>(st + 8 * i);
+                bw[2 * i] = v[0];
+                bw[2 * i + 1] = v[1];
             }
         }
-        store_a(ks + 1, stage ^ 1);
-        __syncthreads();
+    };
+
+    auto read_a = [&](int stage, u32x4 *afrag, int rt) {
+        afrag[rt] = *reinterpret_cast<const u32x4 *>(lds + stage * STAGE_BYTES + a_read_off + rt * 16 * 64);
+    };
+
+    // ---- prologue: queue NSTAGE - 1 stages, wait for the first two, fetch and unpack the operands
+    // of step 0
+    u32x4 bfrag[2][8], afrag[2][8];
+#pragma unroll
+    for (int sidx = 0; sidx < NSTAGE - 1; ++sidx) issue(sidx < nit ? sidx : nit - 1, sidx);
+    wait_vmcnt<DMA_PER_ITER *(NSTAGE - 3)>();
+    __syncthreads();
+    {
+        uint32_t bw[WPB];
+        read_b(0, bw);
+#pragma unroll
+        for (int rt = 0; rt < 8; ++rt) read_a(0, afrag[0], rt);
+        BlockUnpacker<BITS, ALONG_CH> up;
+        up.prepare(bw);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bfrag[0][i] = up.frag(i, magic);
     }
+
+    // ---- main loop.  A step is a 32-deep contraction: 64 MFMAs, one per accumulator.  When step
+    // `it` starts, its operands are already in registers and stages it + 1 (next activations and
+    // packed weights) are complete in LDS.  The step queues the DMA for step it + NSTAGE - 1 (the
+    // tail re-fetches the last tile: harmless, and it keeps the DMA count per step constant so
+    // that a fixed vmcnt tells when a stage has landed) and runs its MFMAs back to back, with the
+    // unpacking of the next step's weights and the LDS reads of the next step's activations
+    // spread between them.  Two steps per loop trip so that the register buffers are static.
+    auto step = [&](int it, auto cur_c) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        const int pre = it + NSTAGE - 1 < nit ? it + NSTAGE - 1 : nit - 1;
+        const int nstage = (it + 1) & (NSTAGE - 1);
+        issue(pre, (it + NSTAGE - 1) & (NSTAGE - 1));
+        uint32_t bw[WPB];
+        read_b(nstage, bw);
+        BlockUnpacker<BITS, ALONG_CH> up;
+#pragma unroll
+        for (int rt = 0; rt < 8; ++rt) {
+            if (rt == 0) up.prepare(bw);
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct) {
+                mfma16_acc(acc[rt][ct], afrag[CUR][rt], bfrag[CUR][ct]);
+                // one register of the next step's fragment rt in the shadow of every other MFMA
+                if (ct & 1) bfrag[NXT][rt][ct >> 1] = up.frag_reg(rt, ct >> 1, magic);
+            }
+            read_a(nstage, afrag[NXT], rt);
+        }
+        wait_vmcnt<DMA_PER_ITER *(NSTAGE - 3)>();
+        __syncthreads();
+    };
+    for (int it = 0; it < nit; it += 2) {                  // nit is even: KC % 128 == 0
+        step(it, std::integral_constant<int, 0>{});
+        step(it + 1, std::integral_constant<int, 1>{});
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    mfma_result_fence();
 
     // ---- epilogues
     if constexpr (MODE == MODE_DDS) {
@@ -236,18 +293,18 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
     } else {
         // sum the two contraction halves: wave wk keeps row tiles [4 wk, 4 wk + 4) and sends the others
         f32x4 *xch = reinterpret_cast<f32x4 *>(lds);           // [4 waves][32 tiles][64 lanes]
-        {
-            f32x4 *mine = xch + (size_t)wave * 32 * 64 + lane;
+        auto finish = [&](auto keep_c) {
+            constexpr int KEEP = decltype(keep_c)::value;      // first row tile this wave keeps
+            constexpr int SEND = 4 - KEEP;
+            {
+                f32x4 *mine = xch + (size_t)wave * 32 * 64 + lane;
 #pragma unroll
-            for (int rtl = 0; rtl < 4; ++rtl)
+                for (int rtl = 0; rtl < 4; ++rtl)
 #pragma unroll
-                for (int ct = 0; ct < 8; ++ct) {
-                    // send the half I do not keep
-                    mine[(rtl * 8 + ct) * 64] = wk ? acc[rtl][ct] : acc[4 + rtl][ct];
-                }
-        }
-        __syncthreads();
-        if (wave_on) {
+                    for (int ct = 0; ct < 8; ++ct) mine[(rtl * 8 + ct) * 64] = acc[SEND + rtl][ct];
+            }
+            __syncthreads();
+            if (!wave_on) return;
             const f32x4 *theirs = xch + (size_t)(wave ^ 2) * 32 * 64 + lane;
             float sc[8], zoff[8];
             if constexpr (MODE == MODE_Y) {
@@ -263,14 +320,10 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
             for (int rtl = 0; rtl < 4; ++rtl) {
                 f32x4 sum[8];
 #pragma unroll
-                for (int ct = 0; ct < 8; ++ct) {
-                    const f32x4 o = theirs[(rtl * 8 + ct) * 64];
-                    const f32x4 m = wk ? acc[4 + rtl][ct] : acc[rtl][ct];
-                    sum[ct] = m + o;
-                }
+                for (int ct = 0; ct < 8; ++ct) sum[ct] = acc[KEEP + rtl][ct] + theirs[(rtl * 8 + ct) * 64];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int t = t0 + (4 * wk + rtl) * 16 + 4 * q + j;
+                    const int t = t0 + (KEEP + rtl) * 16 + 4 * q + j;
                     if (t < T) {
                         float v[8];
                         if constexpr (MODE == MODE_Y) {
@@ -289,7 +342,9 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
                     }
                 }
             }
-        }
+        };
+        if (wk == 0) finish(std::integral_constant<int, 0>{});
+        else finish(std::integral_constant<int, 4>{});
     }
 }
 

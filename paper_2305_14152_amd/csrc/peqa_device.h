@@ -38,31 +38,47 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
 }
 
-// (x & mask) | magic in one VALU op.  mask rides the constant bus (SGPR), magic a VGPR.
+// ((x shifted) & mask) | magic in two VALU ops (one when no shift is needed).  mask rides the
+// constant bus (SGPR), magic a VGPR.  Volatile assembly, shift included, so that the unpacking
+// stays exactly where the caller interleaves it with matrix instructions.
 __device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic)
 {
-    // volatile so that the unpacking stays where the caller interleaves it with matrix instructions
     uint32_t d;
     asm volatile("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(x), "s"(mask), "v"(magic));
     return d;
 }
+__device__ __forceinline__ uint32_t shr_and_or(uint32_t x, uint32_t sh, uint32_t mask, uint32_t magic)
+{
+    uint32_t d;
+    asm volatile("v_lshrrev_b32 %0, %1, %2\n\tv_and_or_b32 %0, %0, %3, %4"
+                 : "=&v"(d) : "n"(sh), "v"(x), "s"(mask), "v"(magic));
+    return d;
+}
+__device__ __forceinline__ uint32_t shl_and_or(uint32_t x, uint32_t sh, uint32_t mask, uint32_t magic)
+{
+    uint32_t d;
+    asm volatile("v_lshlrev_b32 %0, %1, %2\n\tv_and_or_b32 %0, %0, %3, %4"
+                 : "=&v"(d) : "n"(sh), "v"(x), "s"(mask), "v"(magic));
+    return d;
+}
 
-// Field number f (of width b) of both half-words of v -> pair of bf16 (16 + code).
-template <int BITS>
-__device__ __forceinline__ uint32_t field_pair(uint32_t v, int f, uint32_t magic)
+// Field number F (of width b) of both half-words of v -> pair of bf16 (16 + code).
+template <int BITS, int F>
+__device__ __forceinline__ uint32_t field_pair(uint32_t v, uint32_t magic)
 {
     constexpr uint32_t mask = BITS == 4 ? kMask4 : kMask3;
-    const int sh = BITS * f - 3;
-    const uint32_t x = sh < 0 ? (v << 3) : (sh == 0 ? v : (v >> sh));
-    return and_or(x, mask, magic);
+    constexpr int sh = BITS * F - 3;
+    if constexpr (sh < 0) return shl_and_or(v, 3, mask, magic);
+    else if constexpr (sh == 0) return and_or(v, mask, magic);
+    else return shr_and_or(v, sh, mask, magic);
 }
 
 // The 3-bit cell that lives in the spare top bits (15 and 31) of three words.
 __device__ __forceinline__ uint32_t spare_pair3(uint32_t v0, uint32_t v1, uint32_t v2, uint32_t magic)
 {
-    uint32_t t = and_or(v0 >> 12, 0x00080008u, magic);
-    t = and_or(v1 >> 11, 0x00100010u, t);
-    return and_or(v2 >> 10, 0x00200020u, t);
+    uint32_t t = shr_and_or(v0, 12, 0x00080008u, magic);
+    t = shr_and_or(v1, 11, 0x00100010u, t);
+    return shr_and_or(v2, 10, 0x00200020u, t);
 }
 
 // ---------------------------------------------------------------------------------
@@ -97,38 +113,45 @@ struct BlockUnpacker {
         }
     }
 
-    // register j (0..3: elements 2j, 2j+1) of fragment i (0..7); i, j known at compile time after unrolling
-    __device__ __forceinline__ uint32_t frag_reg(int i, int j, uint32_t magic) const
+    // register J (0..3: elements 2J, 2J+1) of fragment I (0..7)
+    template <int I, int J>
+    __device__ __forceinline__ uint32_t frag_reg(uint32_t magic) const
     {
         if constexpr (!ALONG_CH) {
             if constexpr (BITS == 4) {
-                return field_pair<4>(w[i], j, magic);
+                return field_pair<4, J>(w[I], magic);
             } else {
-                const int par = i % 2, u = 4 * (i / 2) + j;
-                if (u < 15) return field_pair<3>(w[2 * (u / 5) + par], u % 5, magic);
-                return spare_pair3(w[par], w[2 + par], w[4 + par], magic);
+                constexpr int par = I % 2, u = 4 * (I / 2) + J;
+                if constexpr (u < 15) return field_pair<3, u % 5>(w[2 * (u / 5) + par], magic);
+                else return spare_pair3(w[par], w[2 + par], w[4 + par], magic);
             }
         } else {
-            const bool odd = i & 1;                 // odd features live in the high half-words
-            const int p = i >> 1;
+            constexpr bool odd = I & 1;             // odd features live in the high half-words
+            constexpr int p = I >> 1;
             if constexpr (BITS == 4) {
-                return field_pair<4>(odd ? hi[j] : lo[j], p, magic);
+                return field_pair<4, p>(odd ? hi[J] : lo[J], magic);
             } else {
-                const int u = 4 * j + p;
-                if (u < 15) return field_pair<3>(odd ? hi[u / 5] : lo[u / 5], u % 5, magic);
-                return odd ? spare_pair3(hi[0], hi[1], hi[2], magic) : spare_pair3(lo[0], lo[1], lo[2], magic);
+                constexpr int u = 4 * J + p;
+                if constexpr (u < 15) return field_pair<3, u % 5>(odd ? hi[u / 5] : lo[u / 5], magic);
+                else return odd ? spare_pair3(hi[0], hi[1], hi[2], magic) : spare_pair3(lo[0], lo[1], lo[2], magic);
             }
         }
     }
 
-    __device__ __forceinline__ u32x4 frag(int i, uint32_t magic) const
+    template <int I>
+    __device__ __forceinline__ u32x4 frag(uint32_t magic) const
     {
         u32x4 f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) f[j] = frag_reg(i, j, magic);
+        f[0] = frag_reg<I, 0>(magic);
+        f[1] = frag_reg<I, 1>(magic);
+        f[2] = frag_reg<I, 2>(magic);
+        f[3] = frag_reg<I, 3>(magic);
         return f;
     }
 };
+
+// s_barrier alone: no implied wait on outstanding LDS or memory operations.
+__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // D += A * B on one 16x16 tile with a 32-deep contraction.  Issued as inline assembly with the
 // accumulator tied to an AGPR tuple: with the builtin, this compiler keeps rotating part of a

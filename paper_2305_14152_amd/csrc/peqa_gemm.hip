@@ -31,12 +31,12 @@ namespace {
 constexpr int TILE_T = 128;
 constexpr int TILE_C = 256;
 constexpr int KSTEP = 32;                                  // contraction depth of one loop iteration
-constexpr int NSTAGE = 4;                                  // LDS ring depth (power of two)
+constexpr int NSTAGE = 6;                                  // LDS ring depth
 constexpr int A_HALF_BYTES = TILE_T * KSTEP * 2;           // 8 KB: 128 rows x 32 bf16 of one contraction half
 constexpr int B_WAVE_BYTES = 2048;                         // one packed 8x8 block per lane (32 B / 24 B)
 constexpr int STAGE_BYTES = 2 * A_HALF_BYTES + 4 * B_WAVE_BYTES;   // 24 KB
 constexpr int DMA_PER_ITER = 6;                            // DMA instructions per wave per iteration
-constexpr int LDS_BYTES = 128 * 1024;                      // ring (96 KB) / epilogue exchange (128 KB)
+constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES > 128 * 1024 ? NSTAGE * STAGE_BYTES : 128 * 1024;   // ring / epilogue exchange (128 KB)
 
 // Global -> LDS DMA of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l.  The source
 // is sbase (uniform) + voff (per lane).  Issued from inline assembly so that the compiler does not
@@ -46,6 +46,20 @@ __device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
 }
+// Activation tiles sit in LDS as rows of 64 B (four 16-byte chunks).  Chunk j of row r is stored at
+// position j ^ a_swizzle(r): with it, the 16-byte reads of 8 (16) consecutive rows at one logical
+// chunk fall into 8 (16) different 16-byte bank groups of a 128 (256) byte LDS line.
+__device__ __forceinline__ int a_swizzle(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt()
 {
@@ -65,19 +79,21 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
     const int wn = wave & 1, wk = wave >> 1;
     const int c = lane & 15, q = lane >> 4;
 
-    // workgroup -> tile.  Consecutive workgroup ids land on different XCDs; giving each XCD a
-    // contiguous run of column tiles keeps a weight slab in one L2.
-    const int tiles_c = a.tiles_c, tiles_t = a.tiles_t;
-    int wg = blockIdx.x;
+    // workgroup -> tile.  Workgroup ids are dealt round-robin to the 8 XCDs and every CU holds one
+    // workgroup, so the 32 ids {x, x + 8, ...} that run together on XCD x are given one patch of
+    // patch_t x (32 / patch_t) neighbouring tiles: they share activation rows and weight columns
+    // through that XCD's L2 instead of each pulling its own from the fabric.
+    int tile_t, tile_c;
     {
-        const int total = tiles_c * tiles_t;
-        const int per_xcd = (total + 7) / 8;
-        const int xcd = wg & 7, idx = wg >> 3;
-        const int remapped = xcd * per_xcd + idx;
-        // only use the remap when it is a bijection of [0, total)
-        if ((total & 7) == 0) wg = remapped;
+        const int wg = blockIdx.x;
+        const int xcd = wg & 7, local = wg >> 3;
+        const int g = (local >> 5) * 8 + xcd;              // patch number
+        const int r = local & 31;                          // position in the patch
+        const int pt = a.patch_t, patches_t = (a.tiles_t + pt - 1) / pt;
+        tile_t = (g % patches_t) * pt + (r % pt);
+        tile_c = (g / patches_t) * (32 / pt) + (r / pt);
     }
-    const int tile_t = wg % tiles_t, tile_c = wg / tiles_t;
+    if (tile_t >= a.tiles_t || tile_c >= a.tiles_c) return;   // padding of a ragged patch (uniform per workgroup)
 
     const int t0 = tile_t * TILE_T;
     const int col0 = tile_c * TILE_C + wn * 128;           // first output column of this wave
@@ -97,7 +113,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
     uint32_t a_voff[4];
     {
         const int row_l = lane >> 2, pos = lane & 3;
-        const int chunk = pos ^ ((row_l >> 2) & 3);
+        const int chunk = pos ^ a_swizzle(row_l);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = 4 * i + wave;
@@ -162,8 +178,8 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // row = 16 rt + c, so (row >> 2) & 3 = (c >> 2) & 3
-    const int a_read_off = wk * A_HALF_BYTES + c * 64 + ((q ^ ((c >> 2) & 3)) << 4);
+    // row = 16 rt + c and the swizzle only looks at row % 16
+    const int a_read_off = wk * A_HALF_BYTES + c * 64 + ((q ^ a_swizzle(c)) << 4);
     const int b_read_off = 2 * A_HALF_BYTES + wave * B_WAVE_BYTES + b_lane_off;
 
     auto read_b = [&](int stage, uint32_t *bw) {
@@ -201,8 +217,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
         for (int rt = 0; rt < 8; ++rt) read_a(0, afrag[0], rt);
         BlockUnpacker<BITS, ALONG_CH> up;
         up.prepare(bw);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) bfrag[0][i] = up.frag(i, magic);
+        static_for<8>([&](auto i) { bfrag[0][i.value] = up.template frag<i.value>(magic); });
     }
 
     // ---- main loop.  A step is a 32-deep contraction: 64 MFMAs, one per accumulator.  When step
@@ -212,27 +227,39 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
     // that a fixed vmcnt tells when a stage has landed) and runs its MFMAs back to back, with the
     // unpacking of the next step's weights and the LDS reads of the next step's activations
     // spread between them.  Two steps per loop trip so that the register buffers are static.
+    int cur = 0;                                           // LDS stage of the current step
     auto step = [&](int it, auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         const int pre = it + NSTAGE - 1 < nit ? it + NSTAGE - 1 : nit - 1;
-        const int nstage = (it + 1) & (NSTAGE - 1);
-        issue(pre, (it + NSTAGE - 1) & (NSTAGE - 1));
+        const int nstage = cur + 1 == NSTAGE ? 0 : cur + 1;       // stage of step it + 1
+        const int pstage = cur == 0 ? NSTAGE - 1 : cur - 1;       // stage of step it - 1 = of step it + NSTAGE - 1
         uint32_t bw[WPB];
         read_b(nstage, bw);
+        read_a(nstage, afrag[NXT], 0);
+#ifndef PEQA_EXP_NO_DMA
+        issue(pre, pstage);
+#endif
         BlockUnpacker<BITS, ALONG_CH> up;
-#pragma unroll
-        for (int rt = 0; rt < 8; ++rt) {
-            if (rt == 0) up.prepare(bw);
-#pragma unroll
-            for (int ct = 0; ct < 8; ++ct) {
+        static_for<8>([&](auto rt_c) {
+            constexpr int rt = rt_c.value;
+            if constexpr (rt == 0) up.prepare(bw);
+            if constexpr (rt < 7) read_a(nstage, afrag[NXT], rt + 1);   // last LDS read one group before the barrier
+            static_for<8>([&](auto ct_c) {
+                constexpr int ct = ct_c.value;
+#ifndef PEQA_EXP_NO_MFMA
                 mfma16_acc(acc[rt][ct], afrag[CUR][rt], bfrag[CUR][ct]);
+#endif
                 // one register of the next step's fragment rt in the shadow of every other MFMA
-                if (ct & 1) bfrag[NXT][rt][ct >> 1] = up.frag_reg(rt, ct >> 1, magic);
-            }
-            read_a(nstage, afrag[NXT], rt);
-        }
+#ifndef PEQA_EXP_NO_UNPACK
+                if constexpr (ct & 1) bfrag[NXT][rt][ct >> 1] = up.template frag_reg<rt, (ct >> 1)>(magic);
+#endif
+            });
+        });
+        // Own DMA for the stage after next has landed; the barrier makes every wave's part visible.
+        // No wait on LDS reads is needed here: what this step read is overwritten two steps later.
         wait_vmcnt<DMA_PER_ITER *(NSTAGE - 3)>();
-        __syncthreads();
+        bare_barrier();
+        cur = nstage;
     };
     for (int it = 0; it < nit; it += 2) {                  // nit is even: KC % 128 == 0
         step(it, std::integral_constant<int, 0>{});
@@ -362,8 +389,10 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    const int total = a.tiles_c * a.tiles_t;
-    hipLaunchKernelGGL((gemm_kernel<BITS, MODE>), dim3(total), dim3(256), LDS_BYTES, stream, a);
+    const int pt = a.patch_t, pc = 32 / pt;
+    const int patches = ((a.tiles_t + pt - 1) / pt) * ((a.tiles_c + pc - 1) / pc);
+    const int grid = ((patches + 7) / 8) * 8 * 32;
+    hipLaunchKernelGGL((gemm_kernel<BITS, MODE>), dim3(grid), dim3(256), LDS_BYTES, stream, a);
     return hipGetLastError();
 }
 
@@ -383,8 +412,10 @@ static hipError_t dispatch(int bits, int mode, const GemmArgs &a, hipStream_t st
     }
 }
 
-hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream)
+hipError_t launch_gemm(int bits, int mode, const GemmArgs &a_in, hipStream_t stream)
 {
+    GemmArgs a = a_in;
+    a.patch_t = a.tiles_t >= 4 ? 4 : (a.tiles_t >= 2 ? 2 : 1);
     const int kid = mode == MODE_Y ? KID_GEMM_Y : (mode == MODE_DDS ? KID_GEMM_DDS : KID_GEMM_DX);
     trace_before(kid, stream);
     const hipError_t e = dispatch(bits, mode, a, stream);

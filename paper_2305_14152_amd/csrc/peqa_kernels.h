@@ -19,6 +19,7 @@ struct GemmArgs {
     int K;                    // input features of the layer (fixes the block stride of `packed`)
     int ksplit;               // contraction index where the second half starts (multiple of 64)
     int tiles_c, tiles_t;     // ceil(C/256), ceil(T/128)
+    int patch_t;              // token tiles per L2 patch (1, 2 or 4; set by launch_gemm)
     const float *s0;          // [N]            (MODE_Y)
     const float *ds;          // [N] or NULL    (MODE_Y)
     const uint8_t *z0;        // [N]            (MODE_Y, MODE_DDS)

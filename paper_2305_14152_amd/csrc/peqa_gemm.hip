@@ -5,18 +5,20 @@
 //                                                   (scale gradient, column-reduced epilogue)
 //   MODE_DX  : dX[t,k]   = sum_i (dY[t,i] s_i) (Q[i,k] - z_i)                (chain rule on Eq. 2)
 //
-// One workgroup = 4 waves = a 128 (tokens) x 256 (output columns) tile.  Waves are laid out
-// 2 (column halves) x 2 (halves of the contraction range): every wave owns a 128 x 128
-// accumulator (8 x 8 MFMA 16x16x32 tiles, 256 fp32 registers) over its half of the
-// contraction, so that a 2048 x 4096 output still fills all 256 CUs with one workgroup each.
-// The two halves are summed through LDS in the epilogue (or, for MODE_DDS, after the
-// column reduction, which is linear).
+// One workgroup = 8 waves = a 128 (tokens) x 256 (output columns) tile.  Waves are laid out
+// 2 (token halves) x 2 (column halves) x 2 (halves of the contraction range): every wave owns a
+// 64 x 128 accumulator (4 x 8 MFMA 16x16x32 tiles, 128 fp32 AGPRs) over its half of the
+// contraction.  Two waves share each SIMD, so that the LDS reads, the unpacking and the scalar
+// bookkeeping of one hide behind the matrix instructions of the other; the contraction split
+// keeps 256 workgroups busy on a 2048 x 4096 output.  The two halves are summed through LDS in
+// the epilogue (or, for MODE_DDS, after the column reduction, which is linear).
 //
-// Operand paths.  The activation operand (X, or the pre-scaled dY) goes global -> LDS ->
-// registers (128 x 64 bf16 tiles, double buffered, 16-byte chunks XOR-swizzled by row).
-// The weight operand never touches LDS: each lane loads the packed 8x8 code blocks it needs
-// straight from global memory and unpacks them in registers into bf16 (16 + Q) fragments
-// (peqa_device.h).  The contraction therefore runs on exact small integers; the offset 16,
+// Operand paths.  Both operands go global -> LDS by DMA (global_load_lds) into a ring of
+// stages, one 32-deep contraction step per stage: the activation operand (X, or the pre-scaled
+// dY) as two 128 x 32 bf16 tiles (16-byte chunks XOR-swizzled by row), the weight operand as
+// the packed 8x8 code blocks themselves, one per lane.  Each lane reads its block back and
+// unpacks it in registers into bf16 (16 + Q) fragments (peqa_device.h): dequantised weights
+// never exist in memory.  The contraction therefore runs on exact small integers; the offset 16,
 // the zero-point and the scale are applied in the epilogue from row sums of the other
 // operand:   sum_k X (Q - z) = sum_k X (16 + Q) - (16 + z) sum_k X.
 #include <type_traits>
@@ -35,7 +37,7 @@ constexpr int NSTAGE = 6;                                  // LDS ring depth
 constexpr int A_HALF_BYTES = TILE_T * KSTEP * 2;           // 8 KB: 128 rows x 32 bf16 of one contraction half
 constexpr int B_WAVE_BYTES = 2048;                         // one packed 8x8 block per lane (32 B / 24 B)
 constexpr int STAGE_BYTES = 2 * A_HALF_BYTES + 4 * B_WAVE_BYTES;   // 24 KB
-constexpr int DMA_PER_ITER = 6;                            // DMA instructions per wave per iteration
+constexpr int DMA_PER_ITER = 3;                            // DMA instructions per wave per iteration
 constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES > 128 * 1024 ? NSTAGE * STAGE_BYTES : 128 * 1024;   // ring / epilogue exchange (128 KB)
 
 // Global -> LDS DMA of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l.  The source
@@ -68,15 +70,18 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 
 template <int BITS, int MODE>
-__global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
+__global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 {
+#ifdef PEQA_EXP_TIMING
+    const uint64_t tk0 = wall_clock64();
+#endif
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int WPB = 2 * BITS;                          // words per 8x8 block
     constexpr bool ALONG_CH = (MODE == MODE_DX);           // contraction over output channels
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
-    const int wn = wave & 1, wk = wave >> 1;
+    const int wt = wave & 1, wn = (wave >> 1) & 1, wk = wave >> 2;   // token half, column half, contraction half
     const int c = lane & 15, q = lane >> 4;
 
     // workgroup -> tile.  Workgroup ids are dealt round-robin to the 8 XCDs and every CU holds one
@@ -106,25 +111,22 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
     const uint32_t magic = kMagic;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
-    // ---- activation tiles: global -> LDS by DMA, 16 wave-loads of 1 KB per iteration (4 per wave).
-    // Wave-load m = 4 i + wave covers contraction half m / 8, rows 16 (m % 8) .. +16; lane s lands at
+    // ---- activation tiles: global -> LDS by DMA, 16 wave-loads of 1 KB per iteration (2 per wave).
+    // Wave-load m = 8 i + wave covers contraction half m / 8, rows 16 (m % 8) .. +16; lane s lands at
     // byte 16 s of that 1 KB, i.e. row s / 4, chunk position s % 4, and fetches the chunk that the
     // XOR swizzle assigns to that position.
-    uint32_t a_voff[4];
+    uint32_t a_voff;
     {
         const int row_l = lane >> 2, pos = lane & 3;
         const int chunk = pos ^ a_swizzle(row_l);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = 4 * i + wave;
-            int row = (m & 7) * 16 + row_l;
-            row = t0 + row < T ? row : T - 1 - t0;
-            a_voff[i] = (uint32_t)row * (uint32_t)KC * 2u + (uint32_t)chunk * 16u;
-        }
+        int row = wave * 16 + row_l;
+        row = t0 + row < T ? row : T - 1 - t0;
+        a_voff = (uint32_t)row * (uint32_t)KC * 2u + (uint32_t)chunk * 16u;
     }
     const uint8_t *a_base = reinterpret_cast<const uint8_t *>(a.A) + (size_t)t0 * KC * 2;
 
-    // ---- packed weights: one 8x8 block per lane per iteration, also by DMA into the wave's own slot
+    // ---- packed weights: one 8x8 block per lane per iteration, also by DMA, into the slot shared by
+    // the two token-half waves of this (column half, contraction half); each of them fetches half of it
     // along features: lane (c, q) owns channel block col0/8 + c and feature block 4 it + q
     // along channels: lane (c, q) owns feature block col0/8 + c and channel block 4 it + q
     const uint8_t *b_base;
@@ -153,35 +155,38 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
         b_lane_off = ALONG_CH ? q * 384 + c * 24 : c * 96 + q * 24;
     }
     if (!wave_on) { b_base = reinterpret_cast<const uint8_t *>(a.packed); b_step = 0; b_voff = lane * 32; b_voff2 = lane * 32; }
+    const int slot = wn + 2 * wk;
+    if constexpr (BITS == 3) { if (wt) b_voff = b_voff2; }
 
-    auto issue = [&](int it, int stage) {
+    // One of the three DMAs of a step: 0, 1 = activation tile (contraction half 0, 1), 2 = packed weights.
+    // 4-bit weights: the two 16-byte halves of every lane's block go to the two token-half waves;
+    // 3-bit: chunks 0..63 and 64..95 of the slot (lanes 32..63 of the second repeat chunks 64..95
+    // into the slot's unused tail).
+    auto issue_one = [&](int which, int it, int stage) {
         const uint32_t sb = lds_base + stage * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int m = 4 * i + wave, h = m >> 3;
-            dma16(a_voff[i], a_base + ((size_t)h * khalf + (size_t)it * KSTEP) * 2, sb + h * A_HALF_BYTES + (m & 7) * 1024);
-        }
-        const uint8_t *bp = b_base + (size_t)it * b_step;
-        const uint32_t bb = sb + 2 * A_HALF_BYTES + wave * B_WAVE_BYTES;
-        if constexpr (BITS == 4) {
-            dma16(b_voff, bp, bb);
-            dma16(b_voff, bp + 16, bb + 1024);
+        if (which < 2) {
+            dma16(a_voff, a_base + (size_t)it * KSTEP * 2 + (which ? (size_t)khalf * 2 : 0),
+                  sb + which * A_HALF_BYTES + wave * 1024);
         } else {
-            dma16(b_voff, bp, bb);
-            dma16(b_voff2, bp, bb + 1024);      // lanes 32..63 repeat chunks 64..95 into the unused tail of the slot
+            const uint8_t *bp = b_base + (size_t)it * b_step + (BITS == 4 ? wt * 16 : 0);
+            dma16(b_voff, bp, sb + 2 * A_HALF_BYTES + slot * B_WAVE_BYTES + wt * 1024);
         }
     };
+    auto issue = [&](int it, int stage) {
+        issue_one(0, it, stage);
+        issue_one(1, it, stage);
+        issue_one(2, it, stage);
+    };
 
-    f32x4 acc[8][8];
+    f32x4 acc[4][8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // row = 16 rt + c and the swizzle only looks at row % 16
-    const int a_read_off = wk * A_HALF_BYTES + c * 64 + ((q ^ a_swizzle(c)) << 4);
-    const int b_read_off = 2 * A_HALF_BYTES + wave * B_WAVE_BYTES + b_lane_off;
-
+    // row = 64 wt + 16 rt + c and the swizzle only looks at row % 16
+    const int a_read_off = wk * A_HALF_BYTES + (64 * wt + c) * 64 + ((q ^ a_swizzle(c)) << 4);
+    const int b_read_off = 2 * A_HALF_BYTES + slot * B_WAVE_BYTES + b_lane_off;
     auto read_b = [&](int stage, uint32_t *bw) {
         const uint8_t *st = lds + stage * STAGE_BYTES + b_read_off;
         if constexpr (BITS == 4) {
@@ -203,71 +208,123 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
         afrag[rt] = *reinterpret_cast<const u32x4 *>(lds + stage * STAGE_BYTES + a_read_off + rt * 16 * 64);
     };
 
-    // ---- prologue: queue NSTAGE - 1 stages, wait for the first two, fetch and unpack the operands
-    // of step 0
-    u32x4 bfrag[2][8], afrag[2][8];
+    // ---- prologue: queue NSTAGE - 1 stages, wait for the first three, fetch the operands of step 0
+    // and the packed weights of step 1
+    u32x4 bfrag[2][8], afrag[4];
+    uint32_t bw[2][WPB];                                   // packed weights of the next step / the one after
 #pragma unroll
     for (int sidx = 0; sidx < NSTAGE - 1; ++sidx) issue(sidx < nit ? sidx : nit - 1, sidx);
-    wait_vmcnt<DMA_PER_ITER *(NSTAGE - 3)>();
+    wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4)>();
     __syncthreads();
     {
-        uint32_t bw[WPB];
-        read_b(0, bw);
+        read_b(0, bw[1]);
+        read_b(1, bw[0]);
 #pragma unroll
-        for (int rt = 0; rt < 8; ++rt) read_a(0, afrag[0], rt);
+        for (int rt = 0; rt < 4; ++rt) read_a(0, afrag, rt);
         BlockUnpacker<BITS, ALONG_CH> up;
-        up.prepare(bw);
+        up.prepare(bw[1]);
         static_for<8>([&](auto i) { bfrag[0][i.value] = up.template frag<i.value>(magic); });
     }
 
-    // ---- main loop.  A step is a 32-deep contraction: 64 MFMAs, one per accumulator.  When step
-    // `it` starts, its operands are already in registers and stages it + 1 (next activations and
-    // packed weights) are complete in LDS.  The step queues the DMA for step it + NSTAGE - 1 (the
-    // tail re-fetches the last tile: harmless, and it keeps the DMA count per step constant so
-    // that a fixed vmcnt tells when a stage has landed) and runs its MFMAs back to back, with the
-    // unpacking of the next step's weights and the LDS reads of the next step's activations
-    // spread between them.  Two steps per loop trip so that the register buffers are static.
+    // ---- main loop.  A step is a 32-deep contraction: 32 MFMAs, one per accumulator.  When step
+    // `it` starts, its fragments and the packed weights of step it + 1 are in registers, and stages
+    // it + 1 and it + 2 are complete in LDS.  The MFMAs run back to back from the first instruction
+    // after the barrier; everything else sits in their shadow, in fixed slots:
+    //   after every MFMA      one register of step it + 1's weight fragments (shift + and_or)
+    //   after MFMA 2          LDS read of the packed weights of step it + 2
+    //   after MFMA 5, 13, 21  one DMA for step it + NSTAGE - 1 (the tail re-fetches the last tile:
+    //                         harmless, and it keeps the DMA count per step constant so that a fixed
+    //                         vmcnt tells when a stage has landed)
+    //   after each 8 MFMAs    the activation fragment just used up is refilled from LDS for step it + 1
+    // Two steps per loop trip so that the register buffers are static.
+#ifdef PEQA_EXP_TIMING
+    const uint64_t tk1 = wall_clock64();
+    const uint64_t cy1 = __builtin_readcyclecounter();
+#endif
     int cur = 0;                                           // LDS stage of the current step
     auto step = [&](int it, auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         const int pre = it + NSTAGE - 1 < nit ? it + NSTAGE - 1 : nit - 1;
         const int nstage = cur + 1 == NSTAGE ? 0 : cur + 1;       // stage of step it + 1
+        const int nnstage = nstage + 1 == NSTAGE ? 0 : nstage + 1; // stage of step it + 2
         const int pstage = cur == 0 ? NSTAGE - 1 : cur - 1;       // stage of step it - 1 = of step it + NSTAGE - 1
-        uint32_t bw[WPB];
-        read_b(nstage, bw);
-        read_a(nstage, afrag[NXT], 0);
-#ifndef PEQA_EXP_NO_DMA
-        issue(pre, pstage);
-#endif
         BlockUnpacker<BITS, ALONG_CH> up;
-        static_for<8>([&](auto rt_c) {
+        up.prepare(bw[CUR]);
+        static_for<4>([&](auto rt_c) {
             constexpr int rt = rt_c.value;
-            if constexpr (rt == 0) up.prepare(bw);
-            if constexpr (rt < 7) read_a(nstage, afrag[NXT], rt + 1);   // last LDS read one group before the barrier
             static_for<8>([&](auto ct_c) {
-                constexpr int ct = ct_c.value;
+                constexpr int ct = ct_c.value, m = 8 * rt + ct;
 #ifndef PEQA_EXP_NO_MFMA
-                mfma16_acc(acc[rt][ct], afrag[CUR][rt], bfrag[CUR][ct]);
+                mfma16_acc(acc[rt][ct], afrag[rt], bfrag[CUR][ct]);
 #endif
-                // one register of the next step's fragment rt in the shadow of every other MFMA
 #ifndef PEQA_EXP_NO_UNPACK
-                if constexpr (ct & 1) bfrag[NXT][rt][ct >> 1] = up.template frag_reg<rt, (ct >> 1)>(magic);
+                bfrag[NXT][2 * rt + (ct >> 2)][ct & 3] = up.template frag_reg<2 * rt + (ct >> 2), (ct & 3)>(magic);
+#endif
+                if constexpr (m == 2) read_b(nnstage, bw[NXT]);
+#ifndef PEQA_EXP_NO_DMA
+                if constexpr (m == 5) issue_one(0, pre, pstage);
+                if constexpr (m == 13) issue_one(1, pre, pstage);
+                if constexpr (m == 21) issue_one(2, pre, pstage);
 #endif
             });
+#ifndef PEQA_EXP_NO_AREAD
+            read_a(nstage, afrag, rt);
+#endif
         });
-        // Own DMA for the stage after next has landed; the barrier makes every wave's part visible.
+        // Own DMA for step it + 3 has landed; the barrier makes every wave's part visible.
         // No wait on LDS reads is needed here: what this step read is overwritten two steps later.
-        wait_vmcnt<DMA_PER_ITER *(NSTAGE - 3)>();
+#ifndef PEQA_EXP_NO_BARRIER
+        wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4)>();
         bare_barrier();
+#endif
         cur = nstage;
     };
     for (int it = 0; it < nit; it += 2) {                  // nit is even: KC % 128 == 0
         step(it, std::integral_constant<int, 0>{});
         step(it + 1, std::integral_constant<int, 1>{});
     }
+    // Epilogue parameters are fetched while the last DMAs drain: per-column scale and zero-point of
+    // this lane's 8 columns, per-row correction terms of the 8 rows this wave finishes (MODE_Y, MODE_DX)
+    float ep_sc[8], ep_zoff[8], ep_row[8];
+    if (wave_on) {
+        if constexpr (MODE != MODE_DX) {
+            const u32x2 zz = *reinterpret_cast<const u32x2 *>(a.z0 + col0 + 8 * c);
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct) ep_zoff[ct] = kCodeOffset + (float)((zz[ct >> 2] >> (8 * (ct & 3))) & 0xFFu);
+        }
+        if constexpr (MODE == MODE_Y) {
+            const f32x4 s_lo = *reinterpret_cast<const f32x4 *>(a.s0 + col0 + 8 * c);
+            const f32x4 s_hi = *reinterpret_cast<const f32x4 *>(a.s0 + col0 + 8 * c + 4);
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) { ep_sc[ct] = s_lo[ct]; ep_sc[4 + ct] = s_hi[ct]; }
+            if (a.ds) {
+                const f32x4 d_lo = *reinterpret_cast<const f32x4 *>(a.ds + col0 + 8 * c);
+                const f32x4 d_hi = *reinterpret_cast<const f32x4 *>(a.ds + col0 + 8 * c + 4);
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct) { ep_sc[ct] += d_lo[ct]; ep_sc[4 + ct] += d_hi[ct]; }
+            }
+        }
+        if constexpr (MODE != MODE_DDS) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                int t = t0 + 64 * wt + (2 * wk + (i >> 2)) * 16 + 4 * q + (i & 3);
+                t = t < T ? t : T - 1;
+                if constexpr (MODE == MODE_Y) {
+                    const u32x2 r2 = *reinterpret_cast<const u32x2 *>(a.rs + 2 * t);
+                    ep_row[i] = __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
+                } else {
+                    ep_row[i] = a.crow[t];
+                }
+            }
+        }
+    }
     wait_vmcnt<0>();
     __syncthreads();
     mfma_result_fence();
+#ifdef PEQA_EXP_TIMING
+    const uint64_t tk2 = wall_clock64();
+    const uint64_t cy2 = __builtin_readcyclecounter();
+#endif
 
     // ---- epilogues
     if constexpr (MODE == MODE_DDS) {
@@ -276,26 +333,18 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) colsum[ct] = 0.f;
         if (wave_on) {
-            float zoff[8];
-            {
-                const uint8_t *zp = a.z0 + col0 + 8 * c;
-                const u32x2 zz = *reinterpret_cast<const u32x2 *>(zp);
 #pragma unroll
-                for (int ct = 0; ct < 8; ++ct)
-                    zoff[ct] = kCodeOffset + (float)((zz[ct >> 2] >> (8 * (ct & 3))) & 0xFFu);
-            }
-#pragma unroll
-            for (int rt = 0; rt < 8; ++rt) {
+            for (int rt = 0; rt < 4; ++rt) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int t = t0 + rt * 16 + 4 * q + j;
+                    const int t = t0 + 64 * wt + rt * 16 + 4 * q + j;
                     if (t < T) {
                         const u32x4 dy = *reinterpret_cast<const u32x4 *>(a.dY + (size_t)t * a.C + col0 + 8 * c);
                         const float r = a.rs[2 * t + wk];
 #pragma unroll
                         for (int ct = 0; ct < 8; ++ct) {
                             const float d = (ct & 1) ? bf16_hi(dy[ct >> 1]) : bf16_lo(dy[ct >> 1]);
-                            colsum[ct] += d * (acc[rt][ct][j] - zoff[ct] * r);
+                            colsum[ct] += d * (acc[rt][ct][j] - ep_zoff[ct] * r);
                         }
                     }
                 }
@@ -306,61 +355,53 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
             colsum[ct] += __shfl_xor(colsum[ct], 16);
             colsum[ct] += __shfl_xor(colsum[ct], 32);
         }
-        float *red = reinterpret_cast<float *>(lds);           // [4 waves][128]
+        float *red = reinterpret_cast<float *>(lds);           // [8 waves][128]
         if (q == 0) {
 #pragma unroll
             for (int ct = 0; ct < 8; ++ct) red[wave * 128 + 8 * c + ct] = colsum[ct];
         }
         __syncthreads();
-        {
+        if (tid < 256) {
             const int w2 = tid >> 7, col = tid & 127;          // column half, column in half
             const int n = tile_c * TILE_C + tid;
-            if (n < a.C) a.partial[(size_t)tile_t * a.C + n] = red[w2 * 128 + col] + red[(2 + w2) * 128 + col];
+            // waves wt + 2 wn + 4 wk of this column half, in a fixed order
+            const float *r0 = red + (2 * w2) * 128 + col;
+            if (n < a.C)
+                a.partial[(size_t)tile_t * a.C + n] = (r0[0] + r0[128]) + (r0[4 * 128] + r0[5 * 128]);
         }
     } else {
-        // sum the two contraction halves: wave wk keeps row tiles [4 wk, 4 wk + 4) and sends the others
-        f32x4 *xch = reinterpret_cast<f32x4 *>(lds);           // [4 waves][32 tiles][64 lanes]
+        // sum the two contraction halves: wave wk keeps row tiles [2 wk, 2 wk + 2) and sends the others
+        f32x4 *xch = reinterpret_cast<f32x4 *>(lds);           // [8 waves][16 tiles][64 lanes]
         auto finish = [&](auto keep_c) {
             constexpr int KEEP = decltype(keep_c)::value;      // first row tile this wave keeps
-            constexpr int SEND = 4 - KEEP;
+            constexpr int SEND = 2 - KEEP;
             {
-                f32x4 *mine = xch + (size_t)wave * 32 * 64 + lane;
+                f32x4 *mine = xch + (size_t)wave * 16 * 64 + lane;
 #pragma unroll
-                for (int rtl = 0; rtl < 4; ++rtl)
+                for (int rtl = 0; rtl < 2; ++rtl)
 #pragma unroll
                     for (int ct = 0; ct < 8; ++ct) mine[(rtl * 8 + ct) * 64] = acc[SEND + rtl][ct];
             }
             __syncthreads();
             if (!wave_on) return;
-            const f32x4 *theirs = xch + (size_t)(wave ^ 2) * 32 * 64 + lane;
-            float sc[8], zoff[8];
-            if constexpr (MODE == MODE_Y) {
-                const float *sp = a.s0 + col0 + 8 * c;
-                const u32x2 zz = *reinterpret_cast<const u32x2 *>(a.z0 + col0 + 8 * c);
+            const f32x4 *theirs = xch + (size_t)(wave ^ 4) * 16 * 64 + lane;
 #pragma unroll
-                for (int ct = 0; ct < 8; ++ct) {
-                    sc[ct] = a.ds ? sp[ct] + a.ds[col0 + 8 * c + ct] : sp[ct];
-                    zoff[ct] = kCodeOffset + (float)((zz[ct >> 2] >> (8 * (ct & 3))) & 0xFFu);
-                }
-            }
-#pragma unroll
-            for (int rtl = 0; rtl < 4; ++rtl) {
+            for (int rtl = 0; rtl < 2; ++rtl) {
                 f32x4 sum[8];
 #pragma unroll
                 for (int ct = 0; ct < 8; ++ct) sum[ct] = acc[KEEP + rtl][ct] + theirs[(rtl * 8 + ct) * 64];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int t = t0 + (KEEP + rtl) * 16 + 4 * q + j;
+                    const int t = t0 + 64 * wt + (KEEP + rtl) * 16 + 4 * q + j;
                     if (t < T) {
                         float v[8];
+                        const float r = ep_row[4 * rtl + j];
                         if constexpr (MODE == MODE_Y) {
-                            const float r = a.rs[2 * t] + a.rs[2 * t + 1];
 #pragma unroll
-                            for (int ct = 0; ct < 8; ++ct) v[ct] = sc[ct] * (sum[ct][j] - zoff[ct] * r);
+                            for (int ct = 0; ct < 8; ++ct) v[ct] = ep_sc[ct] * (sum[ct][j] - ep_zoff[ct] * r);
                         } else {
-                            const float cc = a.crow[t];
 #pragma unroll
-                            for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - cc;
+                            for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - r;
                         }
                         u32x4 o;
 #pragma unroll
@@ -371,8 +412,11 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(GemmArgs a)
             }
         };
         if (wk == 0) finish(std::integral_constant<int, 0>{});
-        else finish(std::integral_constant<int, 4>{});
+        else finish(std::integral_constant<int, 2>{});
     }
+#ifdef PEQA_EXP_TIMING
+    if (tid == 0 && a.dbg) { const uint64_t tk3 = wall_clock64(); uint64_t *d = a.dbg + (size_t)blockIdx.x * 8; d[0] = tk0; d[1] = tk1; d[2] = tk2; d[3] = tk3; d[4] = cy2 - cy1; }
+#endif
 }
 
 }  // namespace
@@ -392,7 +436,7 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
     const int pt = a.patch_t, pc = 32 / pt;
     const int patches = ((a.tiles_t + pt - 1) / pt) * ((a.tiles_c + pc - 1) / pc);
     const int grid = ((patches + 7) / 8) * 8 * 32;
-    hipLaunchKernelGGL((gemm_kernel<BITS, MODE>), dim3(grid), dim3(256), LDS_BYTES, stream, a);
+    hipLaunchKernelGGL((gemm_kernel<BITS, MODE>), dim3(grid), dim3(512), LDS_BYTES, stream, a);
     return hipGetLastError();
 }
 

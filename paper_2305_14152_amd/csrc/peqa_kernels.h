@@ -28,6 +28,9 @@ struct GemmArgs {
     const uint16_t *dY;       // [T, N] bf16    (MODE_DDS)
     float *partial;           // [tiles_t, N]   (MODE_DDS) per-token-tile column sums
     uint16_t *out;            // [T, C] bf16    (MODE_Y: Y, MODE_DX: dX)
+#ifdef PEQA_EXP_TIMING
+    uint64_t *dbg;
+#endif
 };
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);

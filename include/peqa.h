@@ -64,8 +64,11 @@ const char *peqa_status_string(int32_t status);
  * Word and bit (0..31) that hold bit `t` of the code of channel i, feature k in the
  * packed array.  The paper fixes only the density (exactly b bits per weight,
  * Table 4); the placement is this library's and is part of its contract:
- * 8x8 blocks of (channel, feature), block (i/8, k/8) at word (i/8 * K/8 + k/8) * 2b;
- * inside a block r = i%8, c = k%8 and
+ * 8x8 blocks of (channel, feature) of 2b words each, stored tile by tile so that every
+ * kernel streams contiguous memory: a tile is 128 channels x 32 features (16 x 4 blocks,
+ * 256 b bytes), tile (i/128, k/32) has number (i/128) * (K/32) + k/32, and block
+ * (i/8, k/8) is block ((i/8)%16) * 4 + (k/8)%4 of its tile, i.e. it starts at word
+ * (64 * tile + block) * 2b; inside a block r = i%8, c = k%8 and
  *   b = 4: word r, bits [4p, 4p+4) with p = c/2 + 4*(c%2);
  *   b = 3: u = 4*(r/2) + c/2; u < 15: word 2*(u/5) + r%2, bits [16*(c%2) + 3*(u%5), +3);
  *          u = 15: code bit t is bit 15 + 16*(c%2) of word 2t + r%2.

@@ -168,8 +168,14 @@ int oracle_quantize_f64(const float *W0, int N, int K, int bits, int group,
  * library's own, stated here as a closed-form map (i, k, bit) -> (word, bit):
  *
  * The N x K code matrix is cut into 8 x 8 blocks (8 output channels x 8 input
- * features).  Block (ib, kb) = (i/8, k/8) owns 2*b consecutive 32-bit words
- * starting at word (ib * (K/8) + kb) * 2*b.  Inside a block, r = i%8, c = k%8.
+ * features), each owning 2*b consecutive 32-bit words.  Blocks are stored tile
+ * by tile: a tile is 128 channels x 32 features = 16 x 4 blocks; tiles run
+ * along the input features first, then down the channels, and inside a tile
+ * the blocks run along the features first as well.  So block (ib, kb) =
+ * (i/8, k/8) has number
+ *     ((ib/16) * (K/32) + kb/4) * 64 + (ib%16) * 4 + kb%4
+ * and starts at word number * 2*b.  (Packing therefore needs N % 128 == 0 and
+ * K % 32 == 0.)  Inside a block, r = i%8, c = k%8.
  *
  *  b = 4: word r of the block holds channel r; feature c sits in nibble
  *         p = c/2 + 4*(c%2), i.e. bits [4p, 4p+4).  (Even features fill the low
@@ -191,7 +197,9 @@ size_t oracle_packed_words(int N, int K, int bits)
 int oracle_bit_location(int K, int bits, int i, int k, int t,
                         size_t *word, int *bit)
 {
-    const size_t blk = (size_t)(i / 8) * (size_t)(K / 8) + (size_t)(k / 8);
+    const int ib = i / 8, kb = k / 8;
+    const size_t tile = (size_t)(ib / 16) * (size_t)(K / 32) + (size_t)(kb / 4);
+    const size_t blk = tile * 64 + (size_t)((ib % 16) * 4 + kb % 4);
     const int r = i % 8, c = k % 8;
     if (bits == 4) {
         const int p = c / 2 + 4 * (c % 2);
@@ -218,6 +226,7 @@ int oracle_pack(const uint8_t *codes, int N, int K, int bits, uint32_t *words)
 {
     int rc = check_layout(N, K, bits, 0);
     if (rc) return rc;
+    if (N % 128 != 0 || K % 32 != 0) return 2;
     memset(words, 0, oracle_packed_words(N, K, bits) * sizeof(uint32_t));
     for (int i = 0; i < N; ++i)
         for (int k = 0; k < K; ++k) {
@@ -236,6 +245,7 @@ int oracle_unpack(const uint32_t *words, int N, int K, int bits, uint8_t *codes)
 {
     int rc = check_layout(N, K, bits, 0);
     if (rc) return rc;
+    if (N % 128 != 0 || K % 32 != 0) return 2;
     for (int i = 0; i < N; ++i)
         for (int k = 0; k < K; ++k) {
             unsigned q = 0;

@@ -18,6 +18,8 @@ inline int groups(const peqa_layout *L) { return L->group_size > 0 ? L->k_in / L
 // half of it, rounded down to the step of 64 (n % 128 == 0 makes both halves non-empty).
 inline int split_point(int n) { return (n / 2) / 64 * 64; }
 
+constexpr int PEQA_GEMV_MAX_T = 16;   // forward calls with at most this many tokens take the matrix-vector path
+
 struct Workspace {
     size_t rs, dys, crow, partial, total;
 };
@@ -28,6 +30,14 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
     const size_t N = (size_t)L->n_out, G = (size_t)groups(L);
     const size_t tiles_t = ((size_t)T + 127) / 128;
     size_t off = 0;
+    if (op == PEQA_OP_FWD && T <= PEQA_GEMV_MAX_T) {
+        // matrix-vector path: fp32 partials of the feature slices
+        const int chunk = L->group_size > 0 ? L->group_size : 128;
+        const size_t S = (size_t)peqa::gemv_slices(L->n_out, L->k_in, T, chunk, L->group_size > 0);
+        w.partial = off; off += round256(S * (size_t)T * N * sizeof(float));
+        w.total = off;
+        return w;
+    }
     w.rs = off;      off += round256((size_t)T * 2 * sizeof(float));
     if (op == PEQA_OP_BWD) {
         w.dys = off;     off += round256((size_t)T * N * sizeof(uint16_t));
@@ -97,7 +107,8 @@ peqa_status peqa_bit_location(const peqa_layout *L, int32_t i, int32_t k, int32_
     if (st != PEQA_OK) return st;
     if (!word || !bit) return PEQA_ERR_NULL;
     if (i < 0 || i >= L->n_out || k < 0 || k >= L->k_in || t < 0 || t >= L->bits) return PEQA_ERR_SHAPE;
-    const size_t blk = (size_t)(i >> 3) * (size_t)(L->k_in >> 3) + (size_t)(k >> 3);
+    const size_t tile = (size_t)(i >> 7) * (size_t)(L->k_in >> 5) + (size_t)(k >> 5);
+    const size_t blk = tile * 64 + (size_t)(((i >> 3) & 15) * 4 + ((k >> 3) & 3));
     const int r = i & 7, c = k & 7;
     if (L->bits == 4) {
         *word = blk * 8 + r;
@@ -140,12 +151,22 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     const Workspace w = carve(L, T, PEQA_OP_FWD);
     if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
-    if (L->group_size > 0) return PEQA_ERR_GROUP;   // group-wise contraction: not built yet
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    float *rs = reinterpret_cast<float *>(ws + w.rs);
     const int N = L->n_out, K = L->k_in, ksplit = split_point(K);
+    if (T <= PEQA_GEMV_MAX_T) {
+        peqa::GemvArgs g{};
+        g.packed = packed; g.X = X; g.s0 = s0; g.ds = ds; g.z0 = z0; g.Y = Y;
+        g.partial = reinterpret_cast<float *>(ws + w.partial);
+        g.N = N; g.K = K; g.G = groups(L); g.T = T;
+        g.chunk = L->group_size > 0 ? L->group_size : 128;
+        g.grouped = L->group_size > 0;
+        g.S = peqa::gemv_slices(N, K, T, g.chunk, g.grouped);
+        return dev_status(peqa::launch_gemv(L->bits, g, s));
+    }
+    if (L->group_size > 0) return PEQA_ERR_GROUP;   // group-wise training contraction: not built yet
+    float *rs = reinterpret_cast<float *>(ws + w.rs);
 
     hipError_t e = peqa::launch_rowsum(X, T, K, ksplit, rs, s);
     if (e != hipSuccess) return PEQA_ERR_DEVICE;
@@ -237,7 +258,8 @@ struct TraceState {
 } g_trace;
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
-    "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv"};
+    "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
+    "gemv_finish"};
 
 void trace_release()
 {

@@ -153,6 +153,12 @@ struct BlockUnpacker {
 // s_barrier alone: no implied wait on outstanding LDS or memory operations.
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// D = A * B + C on one 16x16 tile with a 32-deep contraction (compiler-scheduled form).
+__device__ __forceinline__ f32x4 mfma16(const u32x4 &a, const u32x4 &b, const f32x4 &c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
 // D += A * B on one 16x16 tile with a 32-deep contraction.  Issued as inline assembly with the
 // accumulator tied to an AGPR tuple: with the builtin, this compiler keeps rotating part of a
 // 256-register accumulator set through VGPRs on every loop iteration.  The hardware does not

@@ -107,7 +107,6 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     const int khalf = KC >> 1;                             // both waves of a column half take KC/2
     const int kbeg = wk ? khalf : 0;
     const int nit = khalf / KSTEP;                         // loop iterations (>= 2: KC % 128 == 0)
-    const int kblocks = a.K >> 3;                          // blocks per channel-row of blocks
     const uint32_t magic = kMagic;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
@@ -129,32 +128,46 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     // the two token-half waves of this (column half, contraction half); each of them fetches half of it
     // along features: lane (c, q) owns channel block col0/8 + c and feature block 4 it + q
     // along channels: lane (c, q) owns feature block col0/8 + c and channel block 4 it + q
+    // Blocks are stored in tiles of 16 channel blocks x 4 feature blocks (TILE bytes), tiles along the
+    // features first.  Along features a step of a wave is exactly one tile; along channels it is a
+    // quarter (4 channel blocks x 4 feature blocks, contiguous) of each of 4 neighbouring tiles.
+    constexpr uint32_t BLK = WPB * 4, TILE = 64 * BLK;
+    const size_t tile_row = (size_t)(a.K >> 5) * TILE;     // bytes per row of tiles
     const uint8_t *b_base;
-    size_t b_step;                                         // bytes to advance per iteration
+    const int m0 = kbeg >> 5;                              // 32-deep contraction step at which this wave starts
     uint32_t b_voff, b_voff2 = 0;
     int b_lane_off;                                        // where this lane's block sits in the wave's LDS slot
-    if constexpr (!ALONG_CH) {
-        b_base = reinterpret_cast<const uint8_t *>(a.packed + ((size_t)(col0 / 8) * kblocks + (kbeg >> 3)) * WPB);
-        b_step = (size_t)4 * WPB * 4;
-    } else {
-        b_base = reinterpret_cast<const uint8_t *>(a.packed + ((size_t)(kbeg >> 3) * kblocks + col0 / 8) * WPB);
-        b_step = (size_t)4 * kblocks * WPB * 4;
-    }
+    if constexpr (!ALONG_CH)
+        b_base = reinterpret_cast<const uint8_t *>(a.packed) + (size_t)(col0 >> 7) * tile_row + (size_t)m0 * TILE;
+    else
+        b_base = reinterpret_cast<const uint8_t *>(a.packed) + (size_t)(col0 >> 5) * TILE;
     if constexpr (BITS == 4) {
         // two DMAs of 16 B per lane: the halves of the lane's own 32-byte block
-        b_voff = (uint32_t)(ALONG_CH ? q * kblocks + c : c * kblocks + q) * 32u;
+        b_voff = ALONG_CH ? (uint32_t)(c >> 2) * TILE + (uint32_t)(q * 4 + (c & 3)) * BLK : (uint32_t)(c * 4 + q) * BLK;
         b_lane_off = lane * 16;
     } else {
-        // 24-byte blocks: the wave's 64 blocks form 16 runs of 96 B (along features) or 4 runs of
-        // 384 B (along channels) = 96 chunks of 16 B, fetched as chunk `lane` and chunk `64 + lane`
-        // and laid down in LDS in chunk order.
-        constexpr int RUN = ALONG_CH ? 24 : 6;             // chunks per contiguous run
+        // 24-byte blocks: the wave's 64 blocks are 1536 contiguous bytes (along features) or 4 runs of
+        // 384 B, one per tile (along channels) = 96 chunks of 16 B, fetched as chunk `lane` and chunk
+        // `64 + lane` and laid down in LDS in chunk order.
         const int x0 = lane, x1 = 64 + (lane & 31);
-        b_voff = (uint32_t)(x0 / RUN) * (uint32_t)kblocks * 24u + (uint32_t)(x0 % RUN) * 16u;
-        b_voff2 = (uint32_t)(x1 / RUN) * (uint32_t)kblocks * 24u + (uint32_t)(x1 % RUN) * 16u;
-        b_lane_off = ALONG_CH ? q * 384 + c * 24 : c * 96 + q * 24;
+        if constexpr (!ALONG_CH) {
+            b_voff = (uint32_t)x0 * 16u;
+            b_voff2 = (uint32_t)x1 * 16u;
+            b_lane_off = (c * 4 + q) * 24;
+        } else {
+            b_voff = (uint32_t)(x0 / 24) * TILE + (uint32_t)(x0 % 24) * 16u;
+            b_voff2 = (uint32_t)(x1 / 24) * TILE + (uint32_t)(x1 % 24) * 16u;
+            b_lane_off = (c >> 2) * 384 + (q * 4 + (c & 3)) * 24;
+        }
     }
-    if (!wave_on) { b_base = reinterpret_cast<const uint8_t *>(a.packed); b_step = 0; b_voff = lane * 32; b_voff2 = lane * 32; }
+    if (!wave_on) { b_voff = lane * 32; b_voff2 = lane * 32; }
+    // packed bytes of contraction step `it` of this wave (a wave without columns re-reads tile 0)
+    auto b_src = [&](int it) -> const uint8_t * {
+        if (!wave_on) return reinterpret_cast<const uint8_t *>(a.packed);
+        if constexpr (!ALONG_CH) return b_base + (size_t)it * TILE;
+        const int m = m0 + it;
+        return b_base + (size_t)(m >> 2) * tile_row + (size_t)(m & 3) * (16 * BLK);
+    };
     const int slot = wn + 2 * wk;
     if constexpr (BITS == 3) { if (wt) b_voff = b_voff2; }
 
@@ -168,7 +181,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
             dma16(a_voff, a_base + (size_t)it * KSTEP * 2 + (which ? (size_t)khalf * 2 : 0),
                   sb + which * A_HALF_BYTES + wave * 1024);
         } else {
-            const uint8_t *bp = b_base + (size_t)it * b_step + (BITS == 4 ? wt * 16 : 0);
+            const uint8_t *bp = b_src(it) + (BITS == 4 ? wt * 16 : 0);
             dma16(b_voff, bp, sb + 2 * A_HALF_BYTES + slot * B_WAVE_BYTES + wt * 1024);
         }
     };

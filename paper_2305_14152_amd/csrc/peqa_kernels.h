@@ -35,6 +35,22 @@ struct GemmArgs {
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
 
+// Arguments of the T <= 16 forward (peqa_gemv.hip).
+struct GemvArgs {
+    const uint32_t *packed;
+    const uint16_t *X;        // [T, K] bf16
+    const float *s0, *ds;     // [N, G]; ds may be NULL
+    const uint8_t *z0;        // [N, G]
+    uint16_t *Y;              // [T, N] bf16
+    float *partial;           // [S, T, N] fp32 (S > 1)
+    int N, K, G, T;
+    int S;                    // feature slices (gemv_slices)
+    int chunk;                // features per chunk: the group size, or 128 for per-channel layers
+    int grouped;              // 1: one (s, z) per chunk; 0: one per channel
+};
+int gemv_slices(int N, int K, int T, int chunk, int grouped);
+hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
+
 // peqa_small.hip
 hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream);
 hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0,
@@ -54,7 +70,7 @@ void trace_after(int kernel_id, hipStream_t stream);
 
 enum {
     KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
-    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_COUNT
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_COUNT
 };
 
 }  // namespace peqa

@@ -3,7 +3,7 @@
 //
 // One workgroup quantizes 8 output channels (one row of blocks).  Pass 1 reduces min/max
 // per (channel, group) and derives s0, z0; pass 2 re-reads the rows (from L2), rounds,
-// and assembles whole packed words in LDS so that they leave in coalesced runs.
+// and assembles whole packed words in LDS so that they leave in runs of 4 blocks (a tile row).
 // HBM-bound: 4 N K bytes in, N K b / 8 bytes out.
 //
 // Every fp32 step below is a single IEEE operation (correctly rounded divide, no
@@ -73,7 +73,8 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
     __syncthreads();
 
     // ---- pass 2: codes and packing, 32 blocks per step
-    const size_t out_row = (size_t)ib * (K / 8) * WPB;
+    // block kb of this row of blocks: tile (ib / 16, kb / 4), block (ib % 16) * 4 + kb % 4 of the tile
+    const size_t out_row = (size_t)(ib / 16) * (K / 32) * 64 + (size_t)(ib % 16) * 4;
     for (int k0 = 0; k0 < K; k0 += CHUNK) {
         const int nb = (K - k0) / 8 < 32 ? (K - k0) / 8 : 32;
         if (j < nb) {
@@ -122,7 +123,8 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
                 word |= (uint32_t)((codes[(6 + par) * 8 + 6] >> m) & 1u) << 15;
                 word |= (uint32_t)((codes[(6 + par) * 8 + 7] >> m) & 1u) << 31;
             }
-            packed[out_row + (size_t)(k0 / 8) * WPB + tid] = word;
+            const int kb = k0 / 8 + tid / WPB;
+            packed[(out_row + (size_t)(kb >> 2) * 64 + (kb & 3)) * WPB + tid % WPB] = word;
         }
         __syncthreads();
     }

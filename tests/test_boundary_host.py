@@ -59,14 +59,14 @@ def test_bad_layouts_are_rejected(peqa, args, status):
 @pytest.mark.parametrize("bits", [3, 4])
 def test_bit_location_matches_the_oracles_map(peqa, oracle, bits):
     """The library's statement of its packing layout against the oracle's independent one."""
-    L = peqa.layout(128, 256, bits)
+    L = peqa.layout(256, 256, bits)
     r = np.random.default_rng(bits)
-    pts = [(int(r.integers(128)), int(r.integers(256)), int(r.integers(bits))) for _ in range(500)]
+    pts = [(int(r.integers(256)), int(r.integers(256)), int(r.integers(bits))) for _ in range(500)]
     pts += [(i, k, t) for i in range(8) for k in range(8) for t in range(bits)]
     for (i, k, t) in pts:
         assert peqa.bit_location(L, i, k, t) == oracle.bit_location(256, bits, i, k, t)
     with pytest.raises(peqa.PeqaError):
-        peqa.bit_location(L, 128, 0, 0)
+        peqa.bit_location(L, 256, 0, 0)
 
 
 def test_argument_validation_needs_no_device(peqa):

@@ -86,6 +86,27 @@ def test_ragged_shapes_parity(gpu, oracle, bits, N, K, T):
     _log("  errors: %.2e %.2e" % e)
 
 
+@pytest.mark.parametrize("bits,N,K,group", [
+    (4, 256, 512, 0), (3, 384, 640, 0), (3, 256, 1024, 128), (4, 512, 768, 64), (3, 640, 1152, 128),
+    (4, 256, 512, 256), (3, 128, 128, 0), (4, 1280, 2048, 128),
+])
+def test_small_batch_forward_parity(gpu, oracle, bits, N, K, group):
+    """The T <= 16 matrix-vector path, per-channel and group-wise, every T from 1 to 16 sampled."""
+    _log("small-batch bits=%d N=%d K=%d g=%d" % (bits, N, K, group))
+    seed = 9000 + bits * 1000 + N + K + group
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, group)
+    ds = synth.normal_f32(seed + 3, s0.shape, 1e-3)
+    for T in (1, 2, 7, 16):
+        X = synth.normal_bf16(seed + 10 + T, (T, K), 1.0)
+        for d in (None, ds):
+            Y = gpu.bf16_dev_to_f64(layer.fwd(X, d))
+            Yref = oracle.fwd(codes, s0, d, z0, X, group)
+            assert Y.shape == Yref.shape
+            assert np.abs(Y - Yref).max() <= Y_TOL * np.abs(Yref).max(), (T, np.abs(Y - Yref).max(), np.abs(Yref).max())
+
+
 def test_quantizer_edge_rows(gpu, oracle):
     """Degenerate, one-sided, tie-laden and outlier rows go through the same decisions."""
     N, K = 128, 256

@@ -186,7 +186,7 @@ def test_table4_model_sizes_fix_dense_b_bit_storage(oracle):
 @pytest.mark.parametrize("bits", [3, 4])
 def test_pack_is_a_dense_bijection(oracle, bits):
     """Every bit of every word is owned by exactly one (i, k, code bit)."""
-    N, K = 16, 24
+    N, K = 256, 96                                 # 2 x 3 tiles of 128 channels x 32 features
     seen = {}
     for i, k, t in itertools.product(range(N), range(K), range(bits)):
         loc = oracle.bit_location(K, bits, i, k, t)
@@ -201,36 +201,51 @@ def test_pack_is_a_dense_bijection(oracle, bits):
 @pytest.mark.parametrize("bits", [3, 4])
 def test_pack_unpack_roundtrip(oracle, bits):
     r = np.random.default_rng(bits)
-    codes = r.integers(0, 2 ** bits, size=(40, 72), dtype=np.uint8)
+    codes = r.integers(0, 2 ** bits, size=(256, 96), dtype=np.uint8)
     words = oracle.pack(codes, bits)
     assert words.dtype == np.uint32 and words.size * 4 * 8 == codes.size * bits
-    assert (oracle.unpack(words, 40, 72, bits) == codes).all()
+    assert (oracle.unpack(words, 256, 96, bits) == codes).all()
     with pytest.raises(ValueError):
-        oracle.pack(np.full((8, 8), 2 ** bits, np.uint8), bits)
+        oracle.pack(np.full((128, 32), 2 ** bits, np.uint8), bits)
+    with pytest.raises(ValueError):                # whole tiles only
+        oracle.pack(np.zeros((64, 32), np.uint8), bits)
 
 
 def test_pack_4bit_hand_computed_words(oracle):
     """Words written out by hand from the stated map: feature c of a channel sits in
     nibble c/2 + 4 (c%2) of that channel's word of the 8x8 block."""
-    codes = np.zeros((8, 8), np.uint8)
-    codes[0] = [0, 1, 2, 3, 4, 5, 6, 7]
-    codes[3] = [15, 14, 13, 12, 11, 10, 9, 8]
+    codes = np.zeros((128, 32), np.uint8)          # one tile; its first block is words 0..7
+    codes[0, :8] = [0, 1, 2, 3, 4, 5, 6, 7]
+    codes[3, :8] = [15, 14, 13, 12, 11, 10, 9, 8]
     codes[7, 5] = 0xA                              # feature 5 -> nibble 6
     w = oracle.pack(codes, 4)
-    assert [hex(x) for x in w] == ["0x75316420", "0x0", "0x0", "0x8ace9bdf", "0x0", "0x0", "0x0",
-                                   "0xa000000"]
-    # block placement: blocks run along the input features first, then down the channels
-    codes = np.zeros((16, 32), np.uint8)
-    codes[9, 17] = 0xF                             # block (1, 2) -> words 48..55; channel 1; nibble 4
+    assert [hex(x) for x in w[:8]] == ["0x75316420", "0x0", "0x0", "0x8ace9bdf", "0x0", "0x0", "0x0",
+                                       "0xa000000"]
+    assert np.count_nonzero(w[8:]) == 0
+    # block placement inside a tile: along the features first (4 blocks), then down the channels
+    codes = np.zeros((128, 32), np.uint8)
+    codes[9, 17] = 0xF                             # block (1, 2) -> number 6, words 48..55; channel 1; nibble 4
     w = oracle.pack(codes, 4)
     assert w[49] == 0x000F0000 and np.count_nonzero(w) == 1
+    # tile placement: tiles of 128 channels x 32 features, along the features first
+    codes = np.zeros((256, 64), np.uint8)
+    codes[137, 49] = 0xF                           # tile (1, 1) -> number 3; block (1, 2) of it -> number 198
+    w = oracle.pack(codes, 4)
+    assert w[198 * 8 + 1] == 0x000F0000 and np.count_nonzero(w) == 1
 
 
 def test_pack_3bit_hand_computed_words(oracle):
-    def lone(i, k, q, N=8, K=8):
-        c = np.zeros((N, K), np.uint8)
+    def first_block(c8):
+        c = np.zeros((128, 32), np.uint8)          # one tile; its first block is words 0..5
+        c[:8, :8] = c8
+        w = oracle.pack(c, 3)
+        assert np.count_nonzero(w[6:]) == 0
+        return [int(x) for x in w[:6]]
+
+    def lone(i, k, q):
+        c = np.zeros((8, 8), np.uint8)
         c[i, k] = q
-        return [int(x) for x in oracle.pack(c, 3)]
+        return first_block(c)
     assert lone(0, 0, 5) == [0x5, 0, 0, 0, 0, 0]
     assert lone(1, 1, 5) == [0, 0x00050000, 0, 0, 0, 0]
     assert lone(2, 4, 7) == [0, 0, 0x38, 0, 0, 0]                 # cell u = 6 -> word 2, field 1
@@ -241,7 +256,7 @@ def test_pack_3bit_hand_computed_words(oracle):
     assert lone(6, 6, 3) == [0x8000, 0, 0x8000, 0, 0, 0]           # 3 = 0b011, even channel, low half
     assert lone(7, 7, 6) == [0, 0, 0, 0x80000000, 0, 0x80000000]   # 6 = 0b110, odd channel, high half
     allsev = np.full((8, 8), 7, np.uint8)
-    assert [int(x) for x in oracle.pack(allsev, 3)] == [0xFFFFFFFF] * 6
+    assert first_block(allsev) == [0xFFFFFFFF] * 6
     # a full even/odd channel pair, features 0..7 carrying codes 0..7, channel pair 0:
     # cells u = 0..3 -> word 0 (even channel) / word 1 (odd), fields 0..3;
     # low half-word holds features 0,2,4,6 -> 0 | 2<<3 | 4<<6 | 6<<9, high half holds 1,3,5,7
@@ -250,12 +265,16 @@ def test_pack_3bit_hand_computed_words(oracle):
     lo = 0 | (2 << 3) | (4 << 6) | (6 << 9)
     hi = 1 | (3 << 3) | (5 << 6) | (7 << 9)
     want = (hi << 16) | lo
-    assert [int(x) for x in oracle.pack(c, 3)] == [want, want, 0, 0, 0, 0]
-    # block placement
-    c = np.zeros((16, 32), np.uint8)
-    c[9, 17] = 7                                   # block (1, 2) -> words 36..41; channel 1, feature 1
+    assert first_block(c) == [want, want, 0, 0, 0, 0]
+    # block and tile placement
+    c = np.zeros((128, 32), np.uint8)
+    c[9, 17] = 7                                   # block (1, 2) -> number 6, words 36..41; channel 1, feature 1
     w = oracle.pack(c, 3)
     assert w[37] == 0x00070000 and np.count_nonzero(w) == 1
+    c = np.zeros((256, 64), np.uint8)
+    c[137, 49] = 7                                 # tile 3, block 6 of it -> number 198
+    w = oracle.pack(c, 3)
+    assert w[198 * 6 + 1] == 0x00070000 and np.count_nonzero(w) == 1
 
 
 # ----------------------------------------------------------------------------

@@ -32,8 +32,8 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
     size_t off = 0;
     if (op == PEQA_OP_FWD && T <= PEQA_GEMV_MAX_T) {
         // matrix-vector path: fp32 partials of the feature slices
-        const int chunk = L->group_size > 0 ? L->group_size : 128;
-        const size_t S = (size_t)peqa::gemv_slices(L->n_out, L->k_in, T, chunk, L->group_size > 0);
+        const int chunk = L->group_size > 0 ? L->group_size : L->k_in;
+        const size_t S = (size_t)peqa::gemv_slices(L->n_out, L->k_in, T, chunk);
         w.partial = off; off += round256(S * (size_t)T * N * sizeof(float));
         w.total = off;
         return w;
@@ -160,9 +160,8 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
         g.packed = packed; g.X = X; g.s0 = s0; g.ds = ds; g.z0 = z0; g.Y = Y;
         g.partial = reinterpret_cast<float *>(ws + w.partial);
         g.N = N; g.K = K; g.G = groups(L); g.T = T;
-        g.chunk = L->group_size > 0 ? L->group_size : 128;
-        g.grouped = L->group_size > 0;
-        g.S = peqa::gemv_slices(N, K, T, g.chunk, g.grouped);
+        g.chunk = L->group_size > 0 ? L->group_size : K;
+        g.S = peqa::gemv_slices(N, K, T, g.chunk);
         return dev_status(peqa::launch_gemv(L->bits, g, s));
     }
     if (L->group_size > 0) return PEQA_ERR_GROUP;   // group-wise training contraction: not built yet

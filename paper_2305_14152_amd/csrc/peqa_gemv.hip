@@ -9,10 +9,12 @@
 // and at the end of every scale group   y += s * (acc - (16 + z) * rowsum)   folds offset, zero-point
 // and scale in fp32.  Per-channel layers are one group spanning the whole slice.
 //
-// Grid: (N / 128 channel tiles) x (S feature slices).  A slice is a run of chunks (a chunk = one
-// scale group, or 128 features); the 4 waves of a workgroup take consecutive quarters of it and are
-// summed through LDS at the end.  S > 1 leaves fp32 partials [S, T, N] in the workspace for
-// gemv_finish_kernel to add up in a fixed order.
+// Grid: (N / 128 channel tiles) x (S feature slices).  The K / 64 rounds of 64 features are dealt
+// evenly to the slices and, inside a slice, to the 4 waves of the workgroup (a wave may start or
+// stop in the middle of a scale group: the fold above is linear in the features, so it is applied
+// to whatever part of a group the wave has seen); the waves are summed through LDS at the end.
+// S > 1 leaves fp32 partials [S, T, N] in the workspace for gemv_finish_kernel to add up in a fixed
+// order.
 //
 // A wave moves its operands in rounds of 64 features (two MFMA steps): the packed blocks of its 16
 // channel-block rows and the matching 128 bytes of each of the 16 token rows, by global -> LDS DMA
@@ -31,7 +33,7 @@ namespace peqa {
 namespace {
 
 constexpr int GV_WAVES = 4;
-constexpr int GV_MAX_PER = 8;        // most chunks per slice of a group-wise layer (bounds the scale tile in LDS)
+constexpr int GV_MAX_PER = 16;       // most scale groups a slice may touch (bounds the scale tile in LDS)
 constexpr int GV_B_BYTES = 4096;     // packed blocks of one round of one wave (4 KB at 4 bits, 3 KB at 3 bits)
 constexpr int GV_ROUND_BYTES = GV_B_BYTES + 2048;   // + 16 token rows x 128 B
 
@@ -53,10 +55,14 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
 {
     // [wave][2 rounds][6 KB]; reused as [wave][column tile][row][lane] fp32 (32 KB) for the final sum
     __shared__ __align__(16) uint8_t stage[GV_WAVES * 2 * GV_ROUND_BYTES];
-    __shared__ __align__(8) ScaleZero sz[128][GV_MAX_PER];       // [channel][chunk of the slice], 8 KB
+    __shared__ __align__(16) ScaleZero sz[GV_MAX_PER][128];      // [group of the slice][channel], 16 KB
     constexpr int WPB = 2 * BITS;
     constexpr int NDMA_B = 2 * 64 * WPB * 4 / 1024;               // 1 KB DMAs for the blocks of a round: 4 / 3
+#ifdef PEQA_EXP_NO_X
+    constexpr int NDMA = NDMA_B;
+#else
     constexpr int NDMA = NDMA_B + 2;                              // + 2 for the token rows
+#endif
     const int tid = threadIdx.x, lane = tid & 63;
 #ifdef PEQA_EXP_GVTIMING
     uint64_t tk[5];
@@ -66,17 +72,14 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
     const int c = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.x * 128;
     const int K = a.K, G = a.G;
-    const int chunk_rounds = a.chunk >> 6;                        // 64-feature rounds per chunk
-    // this workgroup's chunks [cbeg, cend); wave w takes a contiguous quarter of them
-    const int nchunks = K / a.chunk;
-    const int per = (nchunks + a.S - 1) / a.S;
-    const int cbeg = blockIdx.y * per;
-    const int cend = cbeg + per < nchunks ? cbeg + per : nchunks;
-    const int pw = (cend - cbeg + GV_WAVES - 1) / GV_WAVES;
-    const int wc0 = cbeg + wave * pw < cend ? cbeg + wave * pw : cend;
-    const int wc1 = wc0 + pw < cend ? wc0 + pw : cend;
-    const int k0 = wc0 * a.chunk;                                 // first feature of this wave
-    const int nrounds = (wc1 - wc0) * chunk_rounds;               // 64-feature rounds of this wave
+    const int chunk_rounds = a.chunk >> 6;                        // 64-feature rounds per scale group
+    // this workgroup's rounds [rbeg, rend); wave w takes the w-th quarter of them
+    const uint32_t R = (uint32_t)K >> 6;
+    const int rbeg = (int)(blockIdx.y * R / (uint32_t)a.S), rend = (int)((blockIdx.y + 1) * R / (uint32_t)a.S);
+    const int wr0 = rbeg + ((wave * (rend - rbeg)) >> 2);
+    const int nrounds = rbeg + (((wave + 1) * (rend - rbeg)) >> 2) - wr0;
+    const int k0 = wr0 << 6;                                      // first feature of this wave
+    const int g_lo = (uint32_t)rbeg / (uint32_t)chunk_rounds;     // first scale group this workgroup touches
 
     const uint32_t magic = kMagic;
     const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
@@ -109,8 +112,10 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
 #pragma unroll
         for (int i = 0; i < NDMA_B; ++i) gv_dma16(b_voff[i], bsrc, dst + i * 1024);
         const uint8_t *xsrc = xbase + (size_t)r * 128;
+#ifndef PEQA_EXP_NO_X
         gv_dma16(x_voff[0], xsrc, dst + GV_B_BYTES);
         gv_dma16(x_voff[1], xsrc, dst + GV_B_BYTES + 1024);
+#endif
     };
     if (nrounds > 0) issue_round(0);
     if (nrounds > 1) issue_round(1);
@@ -118,32 +123,34 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
     tk[1] = __builtin_amdgcn_s_memrealtime();
 #endif
 
-    // scale / zero-point tile of the slice: [128 channels][chunks], or one column for per-channel
-    // layers.  All its loads are issued together (indices clamped instead of branching, so that
-    // the compiler batches them behind a single wait); that wait also covers the two rounds above,
-    // which every wave needs next anyway.
-    const int cols = a.grouped ? cend - cbeg : 1;
-    {
-        float ts[GV_MAX_PER / 2], td[GV_MAX_PER / 2];
-        uint8_t tz[GV_MAX_PER / 2];
+    // scale / zero-point tile of the slice: [groups touched][128 channels].  All its loads are issued
+    // together (indices clamped instead of branching, so that the compiler batches them behind a
+    // single wait); that wait also covers the two rounds above, which every wave needs next anyway.
+    const int cols = rend > rbeg ? (int)((uint32_t)(rend - 1) / (uint32_t)chunk_rounds) - g_lo + 1 : 1;
+    auto load_tile = [&](auto nb_c) {
+        constexpr int NB = decltype(nb_c)::value;                 // batches of 256 entries
+        float ts[NB], td[NB];
+        uint8_t tz[NB];
+        int ch[NB], jj[NB];
 #pragma unroll
-        for (int i = 0; i < GV_MAX_PER / 2; ++i) {
+        for (int i = 0; i < NB; ++i) {
             const int idx = tid + i * GV_WAVES * 64;
-            const int ch = idx < 128 * cols ? idx / cols : 0, j = idx < 128 * cols ? idx - ch * cols : 0;
-            const size_t si = (size_t)(n0 + ch) * G + (a.grouped ? cbeg + j : 0);
+            const bool on = idx < 128 * cols;
+            ch[i] = on ? (int)((uint32_t)idx / (uint32_t)cols) : 0;
+            jj[i] = on ? idx - ch[i] * cols : 0;
+            const size_t si = (size_t)(n0 + ch[i]) * G + g_lo + jj[i];
             ts[i] = a.s0[si];
             tz[i] = a.z0[si];
             td[i] = a.ds ? a.ds[si] : 0.f;
         }
 #pragma unroll
-        for (int i = 0; i < GV_MAX_PER / 2; ++i) {
-            const int idx = tid + i * GV_WAVES * 64;
-            if (idx < 128 * cols) {
-                const int ch = idx / cols, j = idx - ch * cols;
-                sz[ch][j] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i]};
-            }
-        }
-    }
+        for (int i = 0; i < NB; ++i)
+            if (tid + i * GV_WAVES * 64 < 128 * cols) sz[jj[i]][ch[i]] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i]};
+    };
+    if (cols <= 2) load_tile(std::integral_constant<int, 1>{});
+    else if (cols <= 4) load_tile(std::integral_constant<int, 2>{});
+    else if (cols <= 8) load_tile(std::integral_constant<int, 4>{});
+    else load_tile(std::integral_constant<int, 8>{});
     __syncthreads();
 #ifdef PEQA_EXP_GVTIMING
     tk[2] = __builtin_amdgcn_s_memrealtime();
@@ -153,36 +160,48 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
 #pragma unroll
     for (int ct = 0; ct < 8; ++ct) { y[ct] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 
-    // this lane's block of step 0 within a round (step 1: + 2048 at 4 bits, + 1536 at 3 bits)
+    // this lane's block and activation fragment of step 0 within a round
+    constexpr int STEP_B = BITS == 4 ? 2048 : 1536;               // packed bytes of one step in a round buffer
     const int b_off = BITS == 4 ? lane * 16 : c * 96 + q * 24;
-    const int x_off = GV_B_BYTES + c * 128 + q * 16;              // this lane's activation fragment of step 0
-    auto compute_round = [&](int r, auto buf_c) {
-        constexpr int BUF = decltype(buf_c)::value;
-        // rounds r and (if any) r + 1 are in flight: wait for r only
+    const int x_off = GV_B_BYTES + c * 128 + q * 16;
+    int group_left = chunk_rounds - (int)((uint32_t)wr0 % (uint32_t)chunk_rounds);   // rounds to the end of the scale group
+    int gj = (int)((uint32_t)wr0 / (uint32_t)chunk_rounds) - g_lo;                    // its column of the tile
+
+    // One pass of this loop is one 32-feature MFMA step; it is deliberately a single copy of the
+    // code (a workgroup runs only a few steps, so instruction fetch of an unrolled pipeline would
+    // cost more than it hides).
+    const int nsteps = 2 * nrounds;
+#pragma unroll 1
+    for (int step = 0; step < nsteps; ++step) {
+        const int r = step >> 1, s2 = step & 1;
+        if (s2 == 0) {
+            // rounds r and (if any) r + 1 are in flight: wait for r only
 #ifndef PEQA_EXP_NO_WAIT
-        if (r + 1 < nrounds) gv_wait_vmcnt<NDMA>(); else gv_wait_vmcnt<0>();
+            if (r + 1 < nrounds) gv_wait_vmcnt<NDMA>(); else gv_wait_vmcnt<0>();
 #endif
-        const uint8_t *st = stage + (wave * 2 + BUF) * GV_ROUND_BYTES;
+            asm volatile("" ::: "memory");
+        }
+        const uint8_t *rb = stage + (wave * 2 + (r & 1)) * GV_ROUND_BYTES;
 #ifdef PEQA_EXP_NO_COMPUTE
         if (a.T > 99)
 #endif
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
+        {
+            const uint8_t *sb = rb + s2 * STEP_B + b_off;
             uint32_t bw[WPB];
             if constexpr (BITS == 4) {
-                const u32x4 v0 = *reinterpret_cast<const u32x4 *>(st + b_off + s2 * 2048);
-                const u32x4 v1 = *reinterpret_cast<const u32x4 *>(st + b_off + s2 * 2048 + 1024);
+                const u32x4 v0 = *reinterpret_cast<const u32x4 *>(sb);
+                const u32x4 v1 = *reinterpret_cast<const u32x4 *>(sb + 1024);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) { bw[i] = v0[i]; bw[4 + i] = v1[i]; }
             } else {
 #pragma unroll
                 for (int i = 0; i < 3; ++i) {
-                    const u32x2 v = *reinterpret_cast<const u32x2 *>(st + b_off + s2 * 1536 + 8 * i);
+                    const u32x2 v = *reinterpret_cast<const u32x2 *>(sb + 8 * i);
                     bw[2 * i] = v[0];
                     bw[2 * i + 1] = v[1];
                 }
             }
-            const u32x4 af = *reinterpret_cast<const u32x4 *>(st + x_off + s2 * 64);
+            const u32x4 af = *reinterpret_cast<const u32x4 *>(rb + x_off + s2 * 64);
             BlockUnpacker<BITS, false> up;
             up.prepare(bw);
             u32x4 bf[8];
@@ -194,32 +213,28 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
             for (int ct = 0; ct < 8; ++ct) acc[ct] = mfma16(af, bf[ct], acc[ct]);
             accrs = mfma16(af, ones, accrs);
         }
-        // this buffer is free again (its LDS reads have returned: the MFMAs consumed them): refill it
-        if (r + 2 < nrounds) issue_round(r + 2);
-    };
-    auto flush_if_chunk_end = [&](int r) {
-        if ((r + 1) % chunk_rounds == 0) {
-            // end of a chunk: fold offset, zero-point and scale of its group, restart the sums
-            const int j = a.grouped ? wc0 - cbeg + (r + 1) / chunk_rounds - 1 : 0;
+        if (s2 == 1) {
+            // this buffer is free again (its LDS reads have returned: the MFMAs consumed them): refill it
+            if (r + 2 < nrounds) issue_round(r + 2);
+            if (--group_left == 0 || r + 1 == nrounds) {
+                // end of a scale group, or of this wave's share: fold offset, zero-point and scale
+                // of the group into y, restart the sums
+                const f32x4 *szp = reinterpret_cast<const f32x4 *>(&sz[gj][8 * c]);
 #pragma unroll
-            for (int ct = 0; ct < 8; ++ct) {
-                const ScaleZero v = sz[8 * c + ct][j];
+                for (int h = 0; h < 4; ++h) {
+                    const f32x4 v = szp[h];                       // (s, 16 + z) of channels 8c + 2h, 8c + 2h + 1
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) y[ct][jj] += v.s * (acc[ct][jj] - v.zoff * accrs[jj]);
-                acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    for (int e = 0; e < 2; ++e) {
+                        const int ct = 2 * h + e;
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) y[ct][jj] += v[2 * e] * (acc[ct][jj] - v[2 * e + 1] * accrs[jj]);
+                        acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+                accrs = f32x4{0.f, 0.f, 0.f, 0.f};
+                ++gj;
+                group_left = chunk_rounds;
             }
-            accrs = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-    };
-
-    if (nrounds > 0) compute_round(0, std::integral_constant<int, 0>{});
-    if (nrounds > 0) flush_if_chunk_end(0);
-    for (int r = 1; r < nrounds; r += 2) {
-        compute_round(r, std::integral_constant<int, 1>{});
-        flush_if_chunk_end(r);
-        if (r + 1 < nrounds) {
-            compute_round(r + 1, std::integral_constant<int, 0>{});
-            flush_if_chunk_end(r + 1);
         }
     }
 
@@ -273,20 +288,18 @@ __global__ __launch_bounds__(256) void gemv_finish_kernel(const float *__restric
 
 }  // namespace
 
-int gemv_slices(int N, int K, int T, int chunk, int grouped)
+int gemv_slices(int N, int K, int T, int chunk)
 {
-    // enough workgroups to cover the chip a few times over, every wave at least one chunk,
-    // and partials kept small next to the weight bytes
-    const int tiles = N / 128, nchunks = K / chunk;
-    int S = (512 + tiles - 1) / tiles;
-    const int by_chunks = nchunks / GV_WAVES > 0 ? nchunks / GV_WAVES : 1;
-    if (S > by_chunks) S = by_chunks;
+    // as many slices as keep every workgroup resident at once (2 per compute unit), every wave at
+    // least two rounds long, and the partials small next to the weight bytes
+    const int tiles = N / 128, R = K / 64, chunk_rounds = chunk / 64;
+    int S = 512 / tiles;
+    if (S > R / (2 * GV_WAVES)) S = R / (2 * GV_WAVES);
     const int by_bytes = T > 4 ? 6 : 16;
     if (S > by_bytes) S = by_bytes;
     if (S < 1) S = 1;
-    // the scale tile in LDS holds at most GV_MAX_PER chunks per slice of a group-wise layer
-    const int min_S = grouped ? (nchunks + GV_MAX_PER - 1) / GV_MAX_PER : 1;
-    if (S < min_S) S = min_S;
+    // the scale tile in LDS holds at most GV_MAX_PER groups per slice
+    while (((R + S - 1) / S + chunk_rounds - 1) / chunk_rounds + 1 > GV_MAX_PER) ++S;
     return S;
 }
 

@@ -45,10 +45,9 @@ struct GemvArgs {
     float *partial;           // [S, T, N] fp32 (S > 1)
     int N, K, G, T;
     int S;                    // feature slices (gemv_slices)
-    int chunk;                // features per chunk: the group size, or 128 for per-channel layers
-    int grouped;              // 1: one (s, z) per chunk; 0: one per channel
+    int chunk;                // features per scale group (K for per-channel layers)
 };
-int gemv_slices(int N, int K, int T, int chunk, int grouped);
+int gemv_slices(int N, int K, int T, int chunk);
 hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 
 // peqa_small.hip

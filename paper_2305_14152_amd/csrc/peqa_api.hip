@@ -21,7 +21,7 @@ inline int split_point(int n) { return (n / 2) / 64 * 64; }
 constexpr int PEQA_GEMV_MAX_T = 16;   // forward calls with at most this many tokens take the matrix-vector path
 
 struct Workspace {
-    size_t rs, dys, crow, partial, total;
+    size_t rs, dys, crow, partial, table, total;
 };
 
 Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
@@ -35,6 +35,17 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
         const int chunk = L->group_size > 0 ? L->group_size : L->k_in;
         const size_t S = (size_t)peqa::gemv_slices(L->n_out, L->k_in, T, chunk);
         w.partial = off; off += round256(S * (size_t)T * N * sizeof(float));
+        w.total = off;
+        return w;
+    }
+    if (L->group_size > 0) {
+        // group-wise: (s, b) table for the forward / dX contraction; row sums of X over blocks of
+        // 128 features and per-(token tile, channel, group) partials for the scale gradient
+        w.table = off;   off += round256(N * G * 2 * sizeof(float));
+        if (op == PEQA_OP_BWD) {
+            w.rs = off;      off += round256((size_t)T * (size_t)(L->k_in / 128) * sizeof(float));
+            w.partial = off; off += round256(tiles_t * N * G * sizeof(float));
+        }
         w.total = off;
         return w;
     }
@@ -164,7 +175,17 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
         g.S = peqa::gemv_slices(N, K, T, g.chunk);
         return dev_status(peqa::launch_gemv(L->bits, g, s));
     }
-    if (L->group_size > 0) return PEQA_ERR_GROUP;   // group-wise training contraction: not built yet
+    if (L->group_size > 0) {
+        // the tiled contraction walks scale groups in blocks of 128 features
+        if (L->group_size % 128 != 0) return PEQA_ERR_GROUP;
+        float *sb = reinterpret_cast<float *>(ws + w.table);
+        if (peqa::launch_group_table(s0, ds, z0, N, groups(L), sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        peqa::GemmArgs a{};
+        a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
+        a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
+        a.N = N; a.gsz = L->group_size; a.G = groups(L); a.sb = sb; a.out = Y;
+        return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
+    }
     float *rs = reinterpret_cast<float *>(ws + w.rs);
 
     hipError_t e = peqa::launch_rowsum(X, T, K, ksplit, rs, s);
@@ -194,12 +215,40 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
     const Workspace w = carve(L, T, PEQA_OP_BWD);
     if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
-    if (L->group_size > 0) return PEQA_ERR_GROUP;   // group-wise contraction: not built yet
+    // the tiled contractions walk scale groups in blocks of 128 features
+    if (L->group_size > 0 && L->group_size % 128 != 0) return PEQA_ERR_GROUP;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const int N = L->n_out, K = L->k_in;
     const int tiles_t = (T + 127) / 128;
+
+    if (L->group_size > 0) {
+        const int G = groups(L);
+        if (d_ds) {
+            float *rsb = reinterpret_cast<float *>(ws + w.rs);
+            float *partial = reinterpret_cast<float *>(ws + w.partial);
+            if (peqa::launch_rowsum_blocks(X, T, K, rsb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            peqa::GemmArgs a{};
+            a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
+            a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
+            a.N = N; a.gsz = L->group_size; a.G = G;
+            a.z0 = z0; a.rs = rsb; a.dY = dY; a.partial = partial;
+            if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N * G, d_ds, s) != hipSuccess)
+                return PEQA_ERR_DEVICE;
+        }
+        if (dX) {
+            float *sb = reinterpret_cast<float *>(ws + w.table);
+            if (peqa::launch_group_table(s0, ds, z0, N, G, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            peqa::GemmArgs a{};
+            a.packed = packed; a.A = dY; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
+            a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
+            a.N = N; a.gsz = L->group_size; a.G = G; a.sb = sb; a.out = dX;
+            if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        }
+        return PEQA_OK;
+    }
 
     if (d_ds) {
         float *rs = reinterpret_cast<float *>(ws + w.rs);
@@ -258,7 +307,7 @@ struct TraceState {
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
-    "gemv_finish"};
+    "gemv_finish", "group_table"};
 
 void trace_release()
 {

@@ -38,6 +38,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
 }
 
+// A pair of bf16 (16 + code), scaled and shifted in fp32 and rounded once (to nearest even) back to a
+// bf16 pair:  lo -> s_lo * lo + b_lo,  hi -> s_hi * hi + b_hi.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t scale_pair(uint32_t pair, float s_lo, float b_lo, float s_hi, float b_hi)
+{
+    f32x2 v;
+    v[0] = __builtin_fmaf(__uint_as_float(pair << 16), s_lo, b_lo);
+    v[1] = __builtin_fmaf(__uint_as_float(pair & 0xFFFF0000u), s_hi, b_hi);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // ((x shifted) & mask) | magic in two VALU ops (one when no shift is needed).  mask rides the
 // constant bus (SGPR), magic a VGPR.  Volatile assembly, shift included, so that the unpacking
 // stays exactly where the caller interleaves it with matrix instructions.

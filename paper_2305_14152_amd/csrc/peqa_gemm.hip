@@ -21,6 +21,15 @@
 // never exist in memory.  The contraction therefore runs on exact small integers; the offset 16,
 // the zero-point and the scale are applied in the epilogue from row sums of the other
 // operand:   sum_k X (Q - z) = sum_k X (16 + Q) - (16 + z) sum_k X.
+//
+// Group-wise scales (Sec. 4.3, group size a multiple of 128) use the GROUPED instantiations:
+//   MODE_Y, MODE_DX : the scale cannot leave the contraction, so every weight enters the MFMA as
+//                     bf16( s[i,g] (Q[i,k] - z[i,g]) ), formed in fp32 from a per-group table of
+//                     (s, -s (16 + z)) that rides through LDS next to the operand ring; the
+//                     epilogue is a plain store and the activation operand is X / dY itself.
+//   MODE_DDS        : one workgroup contracts one pair of scale groups (blockIdx.y), each
+//                     contraction half one group, and the column-reduced epilogue writes one
+//                     partial per (token tile, channel, group).
 #include <type_traits>
 
 #include "peqa_device.h"
@@ -39,6 +48,7 @@ constexpr int B_WAVE_BYTES = 2048;                         // one packed 8x8 blo
 constexpr int STAGE_BYTES = 2 * A_HALF_BYTES + 4 * B_WAVE_BYTES;   // 24 KB
 constexpr int DMA_PER_ITER = 3;                            // DMA instructions per wave per iteration
 constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES > 128 * 1024 ? NSTAGE * STAGE_BYTES : 128 * 1024;   // ring / epilogue exchange (128 KB)
+constexpr int TBL_BYTES = 4 * 2 * 1024;                    // grouped MODE_Y / MODE_DX: 2 x 1 KB of (s, b) per (column half, contraction half)
 
 // Global -> LDS DMA of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l.  The source
 // is sbase (uniform) + voff (per lane).  Issued from inline assembly so that the compiler does not
@@ -69,7 +79,7 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
-template <int BITS, int MODE>
+template <int BITS, int MODE, bool GROUPED>
 __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 {
 #ifdef PEQA_EXP_TIMING
@@ -78,6 +88,8 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int WPB = 2 * BITS;                          // words per 8x8 block
     constexpr bool ALONG_CH = (MODE == MODE_DX);           // contraction over output channels
+    constexpr bool SCALED = GROUPED && MODE != MODE_DDS;   // weights enter the MFMA already scaled
+    constexpr bool PAIRED = GROUPED && MODE == MODE_DDS;   // one scale group per contraction half
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
@@ -104,9 +116,24 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     const int col0 = tile_c * TILE_C + wn * 128;           // first output column of this wave
     const bool wave_on = col0 < a.C;
     const int T = a.T, KC = a.KC;
-    const int khalf = KC >> 1;                             // both waves of a column half take KC/2
-    const int kbeg = wk ? khalf : 0;
-    const int nit = khalf / KSTEP;                         // loop iterations (>= 2: KC % 128 == 0)
+    // contraction ranges of the two halves: [kh0, kh0 + 32 nit) and [kh1, kh1 + 32 nit)
+    int kh0, kh1, nit, grp = 0;
+    bool half_on = true;
+    if constexpr (PAIRED) {
+        // groups 2 y and 2 y + 1; with an odd number of groups the last workgroup's second half
+        // re-reads its first group and drops the result
+        const int g1 = 2 * (int)blockIdx.y + 1;
+        kh0 = 2 * (int)blockIdx.y * a.gsz;
+        kh1 = (g1 < a.G ? g1 : g1 - 1) * a.gsz;
+        nit = a.gsz / KSTEP;                               // >= 4: the group size is a multiple of 128
+        grp = 2 * (int)blockIdx.y + wk;
+        half_on = grp < a.G;
+    } else {
+        kh0 = 0;
+        kh1 = KC >> 1;                                     // both waves of a column half take KC/2
+        nit = kh1 / KSTEP;                                 // loop iterations (>= 2: KC % 128 == 0)
+    }
+    const int kbeg = wk ? kh1 : kh0;
     const uint32_t magic = kMagic;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
@@ -178,7 +205,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     auto issue_one = [&](int which, int it, int stage) {
         const uint32_t sb = lds_base + stage * STAGE_BYTES;
         if (which < 2) {
-            dma16(a_voff, a_base + (size_t)it * KSTEP * 2 + (which ? (size_t)khalf * 2 : 0),
+            dma16(a_voff, a_base + (size_t)it * KSTEP * 2 + (size_t)(which ? kh1 : kh0) * 2,
                   sb + which * A_HALF_BYTES + wave * 1024);
         } else {
             const uint8_t *bp = b_src(it) + (BITS == 4 ? wt * 16 : 0);
@@ -189,6 +216,42 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         issue_one(0, it, stage);
         issue_one(1, it, stage);
         issue_one(2, it, stage);
+    };
+
+    // ---- grouped MODE_Y / MODE_DX: (s, b = -s (16 + z)) of 128 channels of one scale group, 1 KB,
+    // fetched by the first token-half wave of every (column half, contraction half) one block of four
+    // steps ahead, into a double buffer behind the ring.  Block B covers contraction steps m with
+    // m / 4 == B (m counted from the start of the layer's contraction range):
+    //   along features: the wave's 128 channels, group of features 128 B .. 128 B + 127
+    //   along channels: channels 128 B .. 128 B + 127, group of the wave's 128 features
+    const uint32_t tbl_lds = lds_base + NSTAGE * STAGE_BYTES + slot * 2048;
+    auto issue_table = [&](int B) {
+        const int last = (KC >> 7) - 1;
+        B = B < last ? B : last;
+        const size_t g = ALONG_CH ? (size_t)(col0 / a.gsz) : (size_t)((B << 7) / a.gsz);
+        const size_t ch = ALONG_CH ? (size_t)B << 7 : (size_t)col0;
+        const uint8_t *src = reinterpret_cast<const uint8_t *>(a.sb) + (wave_on ? (g * a.N + ch) * 8 : 0);
+        dma16(lane * 16, src, tbl_lds + (B & 1) * 1024);
+    };
+    float sc[8], bo[8];                                    // scale and offset of this lane's 8 block channels
+    auto read_table = [&](int m) {
+        // entries of contraction step m: along features 8 c .. 8 c + 7 of block m / 4,
+        // along channels 32 (m % 4) + 8 q .. + 7
+        const uint8_t *tp = lds + NSTAGE * STAGE_BYTES + slot * 2048 + ((m >> 2) & 1) * 1024 +
+                            (ALONG_CH ? (m & 3) * 256 + q * 64 : c * 64);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(tp + 16 * h);
+            sc[2 * h] = v[0]; bo[2 * h] = v[1]; sc[2 * h + 1] = v[2]; bo[2 * h + 1] = v[3];
+        }
+    };
+    // register J of fragment I of the next step: plain (16 + Q) pairs, or scaled weights
+    auto next_frag_reg = [&](const BlockUnpacker<BITS, ALONG_CH> &up, auto i_c, auto j_c) -> uint32_t {
+        constexpr int I = decltype(i_c)::value, J = decltype(j_c)::value;
+        const uint32_t pr = up.template frag_reg<I, J>(magic);
+        if constexpr (!SCALED) return pr;
+        else if constexpr (!ALONG_CH) return scale_pair(pr, sc[I], bo[I], sc[I], bo[I]);
+        else return scale_pair(pr, sc[2 * J], bo[2 * J], sc[2 * J + 1], bo[2 * J + 1]);
     };
 
     f32x4 acc[4][8];
@@ -225,6 +288,9 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     // and the packed weights of step 1
     u32x4 bfrag[2][8], afrag[4];
     uint32_t bw[2][WPB];                                   // packed weights of the next step / the one after
+    if constexpr (SCALED) {
+        if (wt == 0) { issue_table(m0 >> 2); issue_table((m0 >> 2) + 1); }
+    }
 #pragma unroll
     for (int sidx = 0; sidx < NSTAGE - 1; ++sidx) issue(sidx < nit ? sidx : nit - 1, sidx);
     wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4)>();
@@ -234,9 +300,12 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         read_b(1, bw[0]);
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt) read_a(0, afrag, rt);
+        if constexpr (SCALED) read_table(m0);
         BlockUnpacker<BITS, ALONG_CH> up;
         up.prepare(bw[1]);
-        static_for<8>([&](auto i) { bfrag[0][i.value] = up.template frag<i.value>(magic); });
+        static_for<8>([&](auto i) {
+            static_for<4>([&](auto j) { bfrag[0][i.value][j.value] = next_frag_reg(up, i, j); });
+        });
     }
 
     // ---- main loop.  A step is a 32-deep contraction: 32 MFMAs, one per accumulator.  When step
@@ -261,6 +330,14 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         const int nstage = cur + 1 == NSTAGE ? 0 : cur + 1;       // stage of step it + 1
         const int nnstage = nstage + 1 == NSTAGE ? 0 : nstage + 1; // stage of step it + 2
         const int pstage = cur == 0 ? NSTAGE - 1 : cur - 1;       // stage of step it - 1 = of step it + NSTAGE - 1
+        if constexpr (SCALED) {
+            // the fragments built in this step belong to contraction step m = m0 + it + 1
+            const int m = m0 + it + 1;
+            if (ALONG_CH || (m & 3) == 0) read_table(m);
+            // its block's table has been read by both token-half waves once they pass this step's
+            // barrier; the other buffer (block m / 4 - 1) is free: fetch block m / 4 + 1 into it
+            if ((m & 3) == 1 && wt == 0) issue_table((m >> 2) + 1);
+        }
         BlockUnpacker<BITS, ALONG_CH> up;
         up.prepare(bw[CUR]);
         static_for<4>([&](auto rt_c) {
@@ -271,7 +348,8 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                 mfma16_acc(acc[rt][ct], afrag[rt], bfrag[CUR][ct]);
 #endif
 #ifndef PEQA_EXP_NO_UNPACK
-                bfrag[NXT][2 * rt + (ct >> 2)][ct & 3] = up.template frag_reg<2 * rt + (ct >> 2), (ct & 3)>(magic);
+                bfrag[NXT][2 * rt + (ct >> 2)][ct & 3] =
+                    next_frag_reg(up, std::integral_constant<int, 2 * rt + (ct >> 2)>{}, std::integral_constant<int, (ct & 3)>{});
 #endif
                 if constexpr (m == 2) read_b(nnstage, bw[NXT]);
 #ifndef PEQA_EXP_NO_DMA
@@ -299,8 +377,12 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     // Epilogue parameters are fetched while the last DMAs drain: per-column scale and zero-point of
     // this lane's 8 columns, per-row correction terms of the 8 rows this wave finishes (MODE_Y, MODE_DX)
     float ep_sc[8], ep_zoff[8], ep_row[8];
-    if (wave_on) {
-        if constexpr (MODE != MODE_DX) {
+    if (wave_on && !SCALED) {
+        if constexpr (PAIRED) {
+            const int g = half_on ? grp : a.G - 1;
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct) ep_zoff[ct] = kCodeOffset + (float)a.z0[(size_t)(col0 + 8 * c + ct) * a.G + g];
+        } else if constexpr (MODE != MODE_DX) {
             const u32x2 zz = *reinterpret_cast<const u32x2 *>(a.z0 + col0 + 8 * c);
 #pragma unroll
             for (int ct = 0; ct < 8; ++ct) ep_zoff[ct] = kCodeOffset + (float)((zz[ct >> 2] >> (8 * (ct & 3))) & 0xFFu);
@@ -353,7 +435,15 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                     const int t = t0 + 64 * wt + rt * 16 + 4 * q + j;
                     if (t < T) {
                         const u32x4 dy = *reinterpret_cast<const u32x4 *>(a.dY + (size_t)t * a.C + col0 + 8 * c);
-                        const float r = a.rs[2 * t + wk];
+                        float r;
+                        if constexpr (PAIRED) {
+                            // row sum of X over this half's group: its gsz / 128 blocks of 128 features
+                            const float *rb = a.rs + (size_t)t * (a.K >> 7) + (kbeg >> 7);
+                            r = 0.f;
+                            for (int b = 0; b < (a.gsz >> 7); ++b) r += rb[b];
+                        } else {
+                            r = a.rs[2 * t + wk];
+                        }
 #pragma unroll
                         for (int ct = 0; ct < 8; ++ct) {
                             const float d = (ct & 1) ? bf16_hi(dy[ct >> 1]) : bf16_lo(dy[ct >> 1]);
@@ -379,8 +469,18 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
             const int n = tile_c * TILE_C + tid;
             // waves wt + 2 wn + 4 wk of this column half, in a fixed order
             const float *r0 = red + (2 * w2) * 128 + col;
-            if (n < a.C)
-                a.partial[(size_t)tile_t * a.C + n] = (r0[0] + r0[128]) + (r0[4 * 128] + r0[5 * 128]);
+            if constexpr (PAIRED) {
+                // the two contraction halves are two scale groups: one partial each
+                const int g0 = 2 * (int)blockIdx.y;
+                if (n < a.C) {
+                    float *dst = a.partial + ((size_t)tile_t * a.C + n) * a.G + g0;
+                    dst[0] = r0[0] + r0[128];
+                    if (g0 + 1 < a.G) dst[1] = r0[4 * 128] + r0[5 * 128];
+                }
+            } else {
+                if (n < a.C)
+                    a.partial[(size_t)tile_t * a.C + n] = (r0[0] + r0[128]) + (r0[4 * 128] + r0[5 * 128]);
+            }
         }
     } else {
         // sum the two contraction halves: wave wk keeps row tiles [2 wk, 2 wk + 2) and sends the others
@@ -409,7 +509,10 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                     if (t < T) {
                         float v[8];
                         const float r = ep_row[4 * rtl + j];
-                        if constexpr (MODE == MODE_Y) {
+                        if constexpr (SCALED) {
+#pragma unroll
+                            for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j];
+                        } else if constexpr (MODE == MODE_Y) {
 #pragma unroll
                             for (int ct = 0; ct < 8; ++ct) v[ct] = ep_sc[ct] * (sum[ct][j] - ep_zoff[ct] * r);
                         } else {
@@ -434,39 +537,43 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 
 }  // namespace
 
-int gemm_lds_bytes() { return LDS_BYTES; }
+int gemm_lds_bytes() { return LDS_BYTES + TBL_BYTES; }
 
-template <int BITS, int MODE>
+template <int BITS, int MODE, bool GROUPED>
 static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
 {
+    constexpr int lds_bytes = LDS_BYTES + (GROUPED && MODE != MODE_DDS ? TBL_BYTES : 0);
     static bool attr_done = false;                          // per instantiation
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MODE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MODE, GROUPED>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
     const int pt = a.patch_t, pc = 32 / pt;
     const int patches = ((a.tiles_t + pt - 1) / pt) * ((a.tiles_c + pc - 1) / pc);
     const int grid = ((patches + 7) / 8) * 8 * 32;
-    hipLaunchKernelGGL((gemm_kernel<BITS, MODE>), dim3(grid), dim3(512), LDS_BYTES, stream, a);
+    // grouped scale gradient: one pair of scale groups per workgroup along y
+    const int gy = GROUPED && MODE == MODE_DDS ? (a.G + 1) / 2 : 1;
+    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED>), dim3(grid, gy), dim3(512), lds_bytes, stream, a);
     return hipGetLastError();
+}
+
+template <int BITS, bool GROUPED>
+static hipError_t dispatch_mode(int mode, const GemmArgs &a, hipStream_t stream)
+{
+    switch (mode) {
+    case MODE_Y: return launch_one<BITS, MODE_Y, GROUPED>(a, stream);
+    case MODE_DDS: return launch_one<BITS, MODE_DDS, GROUPED>(a, stream);
+    default: return launch_one<BITS, MODE_DX, GROUPED>(a, stream);
+    }
 }
 
 static hipError_t dispatch(int bits, int mode, const GemmArgs &a, hipStream_t stream)
 {
-    if (bits == 4) {
-        switch (mode) {
-        case MODE_Y: return launch_one<4, MODE_Y>(a, stream);
-        case MODE_DDS: return launch_one<4, MODE_DDS>(a, stream);
-        default: return launch_one<4, MODE_DX>(a, stream);
-        }
-    }
-    switch (mode) {
-    case MODE_Y: return launch_one<3, MODE_Y>(a, stream);
-    case MODE_DDS: return launch_one<3, MODE_DDS>(a, stream);
-    default: return launch_one<3, MODE_DX>(a, stream);
-    }
+    const bool grouped = a.gsz > 0;
+    if (bits == 4) return grouped ? dispatch_mode<4, true>(mode, a, stream) : dispatch_mode<4, false>(mode, a, stream);
+    return grouped ? dispatch_mode<3, true>(mode, a, stream) : dispatch_mode<3, false>(mode, a, stream);
 }
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a_in, hipStream_t stream)

@@ -28,6 +28,12 @@ struct GemmArgs {
     const uint16_t *dY;       // [T, N] bf16    (MODE_DDS)
     float *partial;           // [tiles_t, N]   (MODE_DDS) per-token-tile column sums
     uint16_t *out;            // [T, C] bf16    (MODE_Y: Y, MODE_DX: dX)
+    // group-wise layers (gsz > 0; a multiple of 128):
+    int N;                    // output channels of the layer
+    int gsz, G;               // group size and groups per channel
+    const float *sb;          // [G, N, 2] (s0 + ds, -(s0 + ds)(16 + z0))  (MODE_Y, MODE_DX)
+                              // rs is then [T, K/128]: sums of X over blocks of 128 features (MODE_DDS),
+                              // partial is [tiles_t, N, G] and z0 is [N, G]
 #ifdef PEQA_EXP_TIMING
     uint64_t *dbg;
 #endif
@@ -54,6 +60,9 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream);
 hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0,
                            int T, int N, uint16_t *dYs, float *crow, hipStream_t stream);
+hipError_t launch_rowsum_blocks(const uint16_t *X, int T, int K, float *rsb, hipStream_t stream);
+hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, int N, int G, float *sb,
+                              hipStream_t stream);
 hipError_t launch_reduce_partials(const float *partial, int ntiles, size_t n, float *out, hipStream_t stream);
 hipError_t launch_adamw(size_t n, float *ds, const float *g, float *m, float *v, const float *s0,
                         float lr, float b1, float b2, float eps, float wd, float inv_c1, float inv_c2,
@@ -69,7 +78,7 @@ void trace_after(int kernel_id, hipStream_t stream);
 
 enum {
     KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
-    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_COUNT
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_COUNT
 };
 
 }  // namespace peqa

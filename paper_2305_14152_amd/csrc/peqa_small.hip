@@ -36,6 +36,40 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
     if (lane == 0) { rs[2 * t] = s[0]; rs[2 * t + 1] = s[1]; }
 }
 
+// rsb[t, j] = sum of X[t, k] over the j-th block of 128 features, fp32 (group-wise scale gradient:
+// a scale group is a run of such blocks).  One wave per token row, 16 lanes per block.
+__global__ __launch_bounds__(256) void rowsum_blocks_kernel(const uint16_t *__restrict__ X, int T, int K,
+                                                             float *__restrict__ rsb)
+{
+    const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const u32x4 *row = reinterpret_cast<const u32x4 *>(X + (size_t)t * K);
+    for (int k8 = lane; k8 < (K >> 3); k8 += 64) {        // K % 128 == 0: whole 16-lane segments
+        const u32x4 v = row[k8];
+        float p = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p += bf16_lo(v[i]) + bf16_hi(v[i]);
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) p += __shfl_xor(p, o);
+        if ((lane & 15) == 0) rsb[(size_t)t * (K >> 7) + (k8 >> 4)] = p;
+    }
+}
+
+// sb[g, n] = (s, -s (16 + z)) with s = (s0 + ds)[n, g], z = z0[n, g]: the per-group table from which the
+// grouped contractions scale their weights.
+__global__ __launch_bounds__(256) void group_table_kernel(const float *__restrict__ s0, const float *__restrict__ ds,
+                                                           const uint8_t *__restrict__ z0, int N, int G,
+                                                           float *__restrict__ sb)
+{
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;   // = n * G + g
+    if (j >= (size_t)N * G) return;
+    const size_t n = j / G, g = j - n * G;
+    const float s = ds ? s0[j] + ds[j] : s0[j];
+    float *o = sb + (g * N + n) * 2;
+    o[0] = s;
+    o[1] = -s * (kCodeOffset + (float)z0[j]);
+}
+
 // dYs[t,i] = bf16(dY[t,i] * (s0+ds)[i]);  crow[t] = sum_i dYs[t,i] * (16 + z0[i])  (per-channel).
 // crow uses the rounded dYs so that it cancels the code offset of the dX contraction exactly.
 __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ s0,
@@ -111,6 +145,24 @@ hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs,
     trace_before(KID_ROWSUM, stream);
     hipLaunchKernelGGL(rowsum_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, X, T, K, ksplit, rs);
     trace_after(KID_ROWSUM, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_rowsum_blocks(const uint16_t *X, int T, int K, float *rsb, hipStream_t stream)
+{
+    trace_before(KID_ROWSUM, stream);
+    hipLaunchKernelGGL(rowsum_blocks_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, X, T, K, rsb);
+    trace_after(KID_ROWSUM, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, int N, int G, float *sb,
+                              hipStream_t stream)
+{
+    trace_before(KID_GROUP_TABLE, stream);
+    const size_t n = (size_t)N * G;
+    hipLaunchKernelGGL(group_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, ds, z0, N, G, sb);
+    trace_after(KID_GROUP_TABLE, stream);
     return hipGetLastError();
 }
 

@@ -86,6 +86,30 @@ def test_ragged_shapes_parity(gpu, oracle, bits, N, K, T):
     _log("  errors: %.2e %.2e" % e)
 
 
+@pytest.mark.parametrize("bits,N,K,T,group", [
+    (3, 256, 512, 200, 128),    # 4 groups, ragged token tail
+    (4, 256, 512, 64, 256),     # 2 groups, one per contraction half
+    (3, 384, 384, 129, 128),    # odd number of groups; contraction halves start in mid-block
+    (4, 384, 640, 300, 128),    # 5 groups, empty second column half
+    (4, 640, 1024, 33, 512),
+    (3, 1280, 2560, 150, 128),  # several column tiles, 20 groups
+])
+def test_groupwise_training_parity(gpu, oracle, bits, N, K, T, group):
+    """Group-wise scales (Sec. 4.3) through the tiled contractions: forward, dX and the
+    per-(channel, group) scale gradient."""
+    _log("group-wise bits=%d N=%d K=%d T=%d g=%d" % (bits, N, K, T, group))
+    seed = 11000 + bits * 1000 + N + K + T + group
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dY = synth.normal_bf16(seed + 2, (T, N), 1.0)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, group)
+    ds = synth.normal_f32(seed + 3, s0.shape, 1e-3)
+    e = _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, ds, group)
+    _log("  errors: %.2e %.2e" % e)
+    _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, None, group)
+
+
 @pytest.mark.parametrize("bits,N,K,group", [
     (4, 256, 512, 0), (3, 384, 640, 0), (3, 256, 1024, 128), (4, 512, 768, 64), (3, 640, 1152, 128),
     (4, 256, 512, 256), (3, 128, 128, 0), (4, 1280, 2048, 128),

@@ -10,6 +10,8 @@ Prints ONE JSON line: fwd+bwd TFLOP/s counting 6*T*N*K flops per layer (three de
 contractions: forward, dX, and the product recomputed for the scale gradient), with
   roofline     - the dominant kernel against the bf16 MFMA peak, timed with HIP events
   cpu_baseline - the CPU oracle timed on a bounded sample of the same workload
+  small_batch  - the deployment forward (T = 1 and 16) of the same block against the HBM peak,
+                 rotating through more than 256 MB of distinct weights so that every read is from HBM
 """
 import argparse
 import json
@@ -31,6 +33,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=1, help="workload index (see synth.CONFIGS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-small-batch", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three 256 MiB device copies, a kernel of known traffic against which "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
 
@@ -64,6 +70,54 @@ class Layer:
         self.ws_bwd = peqa.workspace_bytes(self.L, T, peqa.PEQA_OP_BWD)
 
 
+def small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream, reps=20):
+    """Forward of the block at T = 1 and T = 16 through the matrix-vector path.  Algorithmic bytes per
+    layer: packed codes + s0, ds (fp32) and z0 (uint8) per scale + X and Y (bf16)."""
+    bits = cfg["bits"]
+    block_packed = sum(l.packed.numel() * 4 for l in layers)
+    nsets = max(2, -(-(300 << 20) // block_packed))            # > 256 MB of distinct weight bytes
+    g = torch.Generator(device="cuda")
+    g.manual_seed(12345)
+    sets = [[l.packed for l in layers]]
+    for _ in range(nsets - 1):
+        sets.append([torch.randint(-2 ** 31, 2 ** 31 - 1, (l.packed.numel(),), generator=g, device="cuda",
+                                   dtype=torch.int32) for l in layers])
+    out = {"weight_sets": nsets, "hbm_peak_GBs": HBM_PEAK_GBS}
+    for T in (1, 16):
+        need = max(peqa.workspace_bytes(l.L, T, peqa.PEQA_OP_FWD) for l in layers)
+        assert need <= ws_bytes
+        bytes_block = sum(l.N * l.K * bits / 8 + l.N * l.L.groups * 9 + 2 * T * (l.K + l.N) for l in layers)
+
+        def run():
+            for packed_set in sets:
+                for l, pk in zip(layers, packed_set):
+                    peqa.linear_fwd(l.L, pk, l.s0, l.ds, l.z0, l.X, T, l.Y, ws, ws_bytes, stream)
+
+        for _ in range(3):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run()
+        torch.cuda.synchronize()
+        wall_us = (time.perf_counter() - t0) / (reps * nsets) * 1e6
+        peqa.trace_begin(2 * len(layers) * nsets * reps + 16)
+        for _ in range(reps):
+            run()
+        torch.cuda.synchronize()
+        tr = peqa.trace_end(16)
+        kern_us = sum(ms for (_, ms) in tr.values()) * 1e3 / (reps * nsets)
+        main_us = tr["gemv"][1] * 1e3 / (reps * nsets)
+        out["T%d" % T] = {
+            "bytes_per_block": int(bytes_block),
+            "block_us_wall": round(wall_us, 2), "block_us_kernels": round(kern_us, 2),
+            "block_us_gemv_kernel": round(main_us, 2),
+            "GBs_wall": round(bytes_block / wall_us / 1e3, 1), "GBs_kernels": round(bytes_block / kern_us / 1e3, 1),
+            "frac_of_hbm_peak_kernels": round(bytes_block / kern_us / 1e3 / HBM_PEAK_GBS, 4),
+        }
+    return out
+
+
 def cpu_baseline(cfg, seconds):
     """The oracle as it stands, on a bounded sample: the first layer shape of the workload,
     forward + dX + scale gradient on a few token rows (rows are independent for Y and dX, and the
@@ -83,8 +137,12 @@ def cpu_baseline(cfg, seconds):
         oracle.bwd(codes, s0, None, z0, X, dY, cfg["group"])
         return time.perf_counter() - t0
 
-    t1 = run(1)
-    T = int(max(2, min(512, seconds / max(t1, 1e-6))))
+    # cost model t(T) = a + b T from two short runs (the oracle's second scale-gradient route has a
+    # T-independent part), then one run sized to the time budget
+    t8, t24 = run(8), run(24)
+    b = max((t24 - t8) / 16.0, 1e-9)
+    a = max(t8 - 8.0 * b, 0.0)
+    T = int(max(32, min(cfg["T"], (seconds - a) / b)))
     dt = run(T)
     flops = 6.0 * T * N * K
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
@@ -126,6 +184,14 @@ def main():
         for l in layers:
             peqa.scale_update(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0, lr=1e-5, step=step_no[0], stream=stream)
 
+    if args.pmc_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -150,14 +216,23 @@ def main():
         for k in gemm_flops:
             gemm_flops[k] += 2.0 * T * l.N * l.K * args.steps
     dom = max((k for k in gemm_flops if k in trace), key=lambda k: trace[k][1])
+    # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc summary (default workload only)
+    traffic = None
+    pmc_file = os.path.join(ROOT, "profiles", "gemm_llama7b_4bit_pc_hbm_traffic.txt")
+    if args.config == 1 and os.path.exists(pmc_file):
+        for line in open(pmc_file):
+            if line.startswith("traffic_bytes_per_launch %s = " % dom):
+                traffic = int(line.split("=")[1])
     dom_launches, dom_ms = trace[dom]
     achieved = gemm_flops[dom] / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
                 "avg_launch_us": round(dom_ms * 1e3 / dom_launches, 2), "launches": dom_launches}
     kernels = {k: {"launches": n, "avg_us": round(ms * 1e3 / n, 2),
                    "tflops": round(gemm_flops[k] / (ms * 1e-3) / 1e12, 1) if k in gemm_flops else None}
                for k, (n, ms) in trace.items()}
+
+    small = small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream) if not args.no_small_batch else None
 
     out = {
         "metric": "PEQA quantized-linear fwd+bwd TFLOP/s, LLaMA-7B shapes T=2048" if args.config == 1
@@ -174,6 +249,8 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if small is not None:
+        out["small_batch"] = small
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds)
         out["cpu_baseline"].pop("tokens_per_s_block_extrapolated")

@@ -4,7 +4,7 @@
  * PEQA (arXiv 2305.14152, Sec. 3.2) replaces a fully-connected weight
  * W0 in R^{N x K} by  What = (s0 + ds) . (Q - z0)  with frozen b-bit integer
  * codes Q (b = 3 or 4), zero-points z0 and scales s0 per output channel
- * (optionally per group of g input features, Sec. 4.3), and trains only ds.
+ * (optionally per group of g input features, Sec. 4.2 and Table 5), and trains only ds.
  *
  * Conventions for every call
  *   - Every tensor argument is a DEVICE pointer owned by the caller, contiguous,
@@ -19,7 +19,9 @@
  *     Scale-shaped arrays (s0, ds, d_ds, m, v, z0) are [N, G] row-major.
  *
  * Shape limits: N % 128 == 0, K % 128 == 0 (every LLaMA-family linear satisfies
- * this); group_size is 0 or a multiple of 128 dividing K... see peqa_check_layout.
+ * this).  group_size is 0 or a multiple of 64 that divides K: peqa_quantize and the
+ * small-batch forward (T <= 16) take any such g; the training contractions (forward with
+ * T > 16 and peqa_linear_bwd) need g % 128 == 0 and return PEQA_ERR_GROUP otherwise.
  */
 #ifndef PEQA_H
 #define PEQA_H
@@ -47,7 +49,7 @@ typedef struct {
     int32_t n_out;      /* N: output channels = rows of W0 (the paper's n)             */
     int32_t k_in;       /* K: input features = columns of W0 (the paper's m)           */
     int32_t bits;       /* b: 3 or 4                                                    */
-    int32_t group_size; /* 0 = one (s, z) per channel; else g with g % 128 == 0, K % g == 0 */
+    int32_t group_size; /* 0 = one (s, z) per channel; else g with g % 64 == 0, K % g == 0   */
 } peqa_layout;
 
 typedef enum { PEQA_OP_FWD = 0, PEQA_OP_BWD = 1 } peqa_op;
@@ -95,6 +97,10 @@ peqa_status peqa_quantize(const peqa_layout *L, const float *W0, uint32_t *packe
  *   ds may be NULL (= 0).  X [T, K] bf16 in, Y [T, N] bf16 out, T >= 1.
  *   bf16 operands, fp32 accumulation.  T <= 16 takes the bandwidth-bound
  *   matrix-vector path of Sec. 3.1 ("Inference Latency").
+ *   Per-channel layers and the T <= 16 path contract over the exact integer codes and
+ *   apply scale and zero-point in fp32 afterwards; group-wise layers with T > 16 (and
+ *   their dX) form every weight (s0+ds)(Q - z0) in fp32 and round it once to bf16 before
+ *   the contraction.
  *   workspace: peqa_workspace_bytes(L, T, PEQA_OP_FWD) bytes, contents undefined on return.
  */
 peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const float *s0,

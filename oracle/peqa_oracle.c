@@ -18,7 +18,7 @@
  * Notation (paper Sec. 3.2): W0 in R^{N x K} (paper's n x m), b bits,
  * codes Q in {0..2^b-1}, zero-point z0, scale s0, frozen integer matrix
  * Wbar = Q - z0, trainable ds, effective scale s = s0 + ds.
- * Group-wise variant (paper Sec. 4.3 "Group-wise Quantization"): one (s, z)
+ * Group-wise variant (paper Sec. 4.2, paragraph "Group-wise Quantization", Table 5): one (s, z)
  * per output channel per contiguous group of g input features; g = 0 means
  * one group spanning all K (per-channel).
  */

@@ -95,7 +95,7 @@ def test_ragged_shapes_parity(gpu, oracle, bits, N, K, T):
     (3, 1280, 2560, 150, 128),  # several column tiles, 20 groups
 ])
 def test_groupwise_training_parity(gpu, oracle, bits, N, K, T, group):
-    """Group-wise scales (Sec. 4.3) through the tiled contractions: forward, dX and the
+    """Group-wise scales (Sec. 4.2, Table 5) through the tiled contractions: forward, dX and the
     per-(channel, group) scale gradient."""
     _log("group-wise bits=%d N=%d K=%d T=%d g=%d" % (bits, N, K, T, group))
     seed = 11000 + bits * 1000 + N + K + T + group

@@ -1,0 +1,84 @@
+"""GPU parity at the full sizes of the benchmark workloads (the launch configuration bench.py
+times): every distinct layer shape of configs 1-4 through the C-ABI, quantized codes and packed
+words compared in full, Y / dX / d_ds on sampled rows and channels that the oracle computes one
+by one (rows of Y and dX are independent; d_ds of a channel needs only that channel's codes)."""
+import numpy as np
+import pytest
+
+from paper_2305_14152_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 2e-2
+G_TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2305_14152_amd import peqa
+    peqa.lib()
+    import gpu_util
+    return gpu_util
+
+
+def _sample(n, edges, rng, count):
+    """Indices at the ends, around tile boundaries, and random ones."""
+    picks = {0, n - 1}
+    for e in edges:
+        for d in (-1, 0):
+            if 0 <= e + d < n:
+                picks.add(e + d)
+    picks.update(int(v) for v in rng.integers(0, n, size=count))
+    return np.array(sorted(picks))
+
+
+CASES = [(cfg, li) for cfg in (1, 2, 3, 4) for li in range(3)]
+
+
+@pytest.mark.parametrize("cfg,li", CASES)
+def test_full_size_layer(gpu, oracle, cfg, li):
+    c = synth.CONFIGS[cfg]
+    N, K, _ = c["layers"][li]
+    bits, group, T = c["bits"], c["group"], c["T"]
+    print("full size cfg=%d layer=%d N=%d K=%d T=%d bits=%d g=%d" % (cfg, li, N, K, T, bits, group), flush=True)
+    rng = np.random.default_rng(1000 * cfg + li)
+    W = synth.weights(cfg, li)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = oracle.quantize(W, bits, group)
+    packed, gs0, gz0 = layer.host_quant()
+    assert (gz0 == z0).all()
+    assert (gs0.view(np.uint32) == s0.view(np.uint32)).all()
+    assert (packed == oracle.pack(codes, bits)).all()
+    del W
+    layer.W0 = None
+
+    X = synth.activations(cfg, li)
+    dY = synth.output_grads(cfg, li)
+    ds = synth.normal_f32(77 + cfg, s0.shape, 1e-3 * float(np.mean(s0)))
+    ts = _sample(T, (128, 1024), rng, 3)
+    ns = _sample(N, (128, 256, N // 2), rng, 8)
+    ks = None
+
+    # forward: sampled rows x sampled channels
+    Y = gpu.bf16_dev_to_f64(layer.fwd(X, ds))
+    Yref = oracle.fwd(codes[ns], s0[ns], ds[ns], z0[ns], X[ts], group)
+    assert np.abs(Y[np.ix_(ts, ns)] - Yref).max() <= Y_TOL * np.abs(Yref).max()
+
+    # backward: whole rows of dX for the sampled tokens, d_ds of the sampled channels
+    dX, dds = layer.bwd(X, dY, ds)
+    dXref, _, _ = oracle.bwd(codes, s0, ds, z0, X[ts], dY[ts], group)
+    got = gpu.bf16_dev_to_f64(dX)[ts]
+    assert np.abs(got - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    _, gref, _ = oracle.bwd(codes[ns], s0[ns], ds[ns], z0[ns], X, np.ascontiguousarray(dY[:, ns]), group)
+    g = gpu.to_host(dds).astype(np.float64)[ns]
+    assert np.linalg.norm(g - gref) <= G_TOL * np.linalg.norm(gref)
+
+    if cfg == 4:
+        # deployment forward of the same layer: T = 1 and T = 16, every channel
+        for Ts in (1, 16):
+            Xs = np.ascontiguousarray(X[:Ts])
+            Ys = gpu.bf16_dev_to_f64(layer.fwd(Xs, ds))
+            Ysref = oracle.fwd(codes, s0, ds, z0, Xs, group)
+            assert np.abs(Ys - Ysref).max() <= Y_TOL * np.abs(Ysref).max()

@@ -61,6 +61,37 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
 
 peqa_status dev_status(hipError_t e) { return e == hipSuccess ? PEQA_OK : PEQA_ERR_DEVICE; }
 
+bool trace_active();
+
+// The two halves of the backward (scale gradient; dX) are independent.  When both are wanted, the
+// scale-gradient chain runs on a second stream of the library's own, forked from and joined back
+// into the caller's stream with events: its small kernels and the ragged last round of workgroups
+// of either contraction then overlap with the other chain.  One stream and two events per device,
+// created at the first such call (default priority); if that fails, or while kernels are being
+// traced one by one, everything stays on the caller's stream.
+struct Side {
+    bool tried = false, ok = false;
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+constexpr int kMaxDevices = 64;
+Side g_side[kMaxDevices];
+
+Side *side_stream()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    Side &sd = g_side[dev];
+    if (!sd.tried) {
+        sd.tried = true;
+        sd.ok = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&sd.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&sd.join, hipEventDisableTiming) == hipSuccess;
+        if (!sd.ok) (void)hipGetLastError();
+    }
+    return sd.ok ? &sd : nullptr;
+}
+
 }  // namespace
 
 extern "C" {
@@ -250,17 +281,24 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
         return PEQA_OK;
     }
 
+    Side *side = (d_ds && dX && !trace_active()) ? side_stream() : nullptr;
+    if (side) {
+        if (hipEventRecord(side->fork, s) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+            return PEQA_ERR_DEVICE;
+    }
     if (d_ds) {
+        hipStream_t sg = side ? side->stream : s;
         float *rs = reinterpret_cast<float *>(ws + w.rs);
         float *partial = reinterpret_cast<float *>(ws + w.partial);
         const int ksplit = split_point(K);
-        if (peqa::launch_rowsum(X, T, K, ksplit, rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_rowsum(X, T, K, ksplit, rs, sg) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
         a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
         a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
         a.z0 = z0; a.rs = rs; a.dY = dY; a.partial = partial;
-        if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
-        if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, sg) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, sg) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (side && hipEventRecord(side->join, side->stream) != hipSuccess) return PEQA_ERR_DEVICE;
     }
     if (dX) {
         uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
@@ -272,6 +310,7 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
         a.crow = crow; a.out = dX;
         if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
+    if (side && hipStreamWaitEvent(s, side->join, 0) != hipSuccess) return PEQA_ERR_DEVICE;
     return PEQA_OK;
 }
 
@@ -308,6 +347,10 @@ struct TraceState {
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
     "gemv_finish", "group_table"};
+
+}  // namespace
+namespace {
+bool trace_active() { return g_trace.on; }
 
 void trace_release()
 {

@@ -225,9 +225,6 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
     a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
     a.s0 = s0; a.ds = ds; a.z0 = z0; a.rs = rs; a.out = Y;
-#ifdef PEQA_EXP_TIMING
-    a.dbg = reinterpret_cast<uint64_t *>(ws + 4096 * 64);   // experiment only: needs an oversized workspace
-#endif
     return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
 }
 

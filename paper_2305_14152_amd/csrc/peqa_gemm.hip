@@ -82,9 +82,6 @@ __device__ __forceinline__ void wait_vmcnt()
 template <int BITS, int MODE, bool GROUPED>
 __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 {
-#ifdef PEQA_EXP_TIMING
-    const uint64_t tk0 = wall_clock64();
-#endif
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int WPB = 2 * BITS;                          // words per 8x8 block
     constexpr bool ALONG_CH = (MODE == MODE_DX);           // contraction over output channels
@@ -319,10 +316,6 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     //                         vmcnt tells when a stage has landed)
     //   after each 8 MFMAs    the activation fragment just used up is refilled from LDS for step it + 1
     // Two steps per loop trip so that the register buffers are static.
-#ifdef PEQA_EXP_TIMING
-    const uint64_t tk1 = wall_clock64();
-    const uint64_t cy1 = __builtin_readcyclecounter();
-#endif
     int cur = 0;                                           // LDS stage of the current step
     auto step = [&](int it, auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
@@ -344,30 +337,20 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
             constexpr int rt = rt_c.value;
             static_for<8>([&](auto ct_c) {
                 constexpr int ct = ct_c.value, m = 8 * rt + ct;
-#ifndef PEQA_EXP_NO_MFMA
                 mfma16_acc(acc[rt][ct], afrag[rt], bfrag[CUR][ct]);
-#endif
-#ifndef PEQA_EXP_NO_UNPACK
                 bfrag[NXT][2 * rt + (ct >> 2)][ct & 3] =
                     next_frag_reg(up, std::integral_constant<int, 2 * rt + (ct >> 2)>{}, std::integral_constant<int, (ct & 3)>{});
-#endif
                 if constexpr (m == 2) read_b(nnstage, bw[NXT]);
-#ifndef PEQA_EXP_NO_DMA
                 if constexpr (m == 5) issue_one(0, pre, pstage);
                 if constexpr (m == 13) issue_one(1, pre, pstage);
                 if constexpr (m == 21) issue_one(2, pre, pstage);
-#endif
             });
-#ifndef PEQA_EXP_NO_AREAD
             read_a(nstage, afrag, rt);
-#endif
         });
         // Own DMA for step it + 3 has landed; the barrier makes every wave's part visible.
         // No wait on LDS reads is needed here: what this step read is overwritten two steps later.
-#ifndef PEQA_EXP_NO_BARRIER
         wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4)>();
         bare_barrier();
-#endif
         cur = nstage;
     };
     for (int it = 0; it < nit; it += 2) {                  // nit is even: KC % 128 == 0
@@ -416,10 +399,6 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     wait_vmcnt<0>();
     __syncthreads();
     mfma_result_fence();
-#ifdef PEQA_EXP_TIMING
-    const uint64_t tk2 = wall_clock64();
-    const uint64_t cy2 = __builtin_readcyclecounter();
-#endif
 
     // ---- epilogues
     if constexpr (MODE == MODE_DDS) {
@@ -530,9 +509,6 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         if (wk == 0) finish(std::integral_constant<int, 0>{});
         else finish(std::integral_constant<int, 2>{});
     }
-#ifdef PEQA_EXP_TIMING
-    if (tid == 0 && a.dbg) { const uint64_t tk3 = wall_clock64(); uint64_t *d = a.dbg + (size_t)blockIdx.x * 8; d[0] = tk0; d[1] = tk1; d[2] = tk2; d[3] = tk3; d[4] = cy2 - cy1; }
-#endif
 }
 
 }  // namespace

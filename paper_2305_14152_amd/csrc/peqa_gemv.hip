@@ -58,16 +58,8 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
     __shared__ __align__(16) ScaleZero sz[GV_MAX_PER][128];      // [group of the slice][channel], 16 KB
     constexpr int WPB = 2 * BITS;
     constexpr int NDMA_B = 2 * 64 * WPB * 4 / 1024;               // 1 KB DMAs for the blocks of a round: 4 / 3
-#ifdef PEQA_EXP_NO_X
-    constexpr int NDMA = NDMA_B;
-#else
     constexpr int NDMA = NDMA_B + 2;                              // + 2 for the token rows
-#endif
     const int tid = threadIdx.x, lane = tid & 63;
-#ifdef PEQA_EXP_GVTIMING
-    uint64_t tk[5];
-    tk[0] = __builtin_amdgcn_s_memrealtime();
-#endif
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, q = lane >> 4;
     const int n0 = blockIdx.x * 128;
@@ -112,16 +104,11 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
 #pragma unroll
         for (int i = 0; i < NDMA_B; ++i) gv_dma16(b_voff[i], bsrc, dst + i * 1024);
         const uint8_t *xsrc = xbase + (size_t)r * 128;
-#ifndef PEQA_EXP_NO_X
         gv_dma16(x_voff[0], xsrc, dst + GV_B_BYTES);
         gv_dma16(x_voff[1], xsrc, dst + GV_B_BYTES + 1024);
-#endif
     };
     if (nrounds > 0) issue_round(0);
     if (nrounds > 1) issue_round(1);
-#ifdef PEQA_EXP_GVTIMING
-    tk[1] = __builtin_amdgcn_s_memrealtime();
-#endif
 
     // scale / zero-point tile of the slice: [groups touched][128 channels].  All its loads are issued
     // together (indices clamped instead of branching, so that the compiler batches them behind a
@@ -152,9 +139,6 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
     else if (cols <= 8) load_tile(std::integral_constant<int, 4>{});
     else load_tile(std::integral_constant<int, 8>{});
     __syncthreads();
-#ifdef PEQA_EXP_GVTIMING
-    tk[2] = __builtin_amdgcn_s_memrealtime();
-#endif
 
     f32x4 y[8], acc[8], accrs = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -176,15 +160,10 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
         const int r = step >> 1, s2 = step & 1;
         if (s2 == 0) {
             // rounds r and (if any) r + 1 are in flight: wait for r only
-#ifndef PEQA_EXP_NO_WAIT
             if (r + 1 < nrounds) gv_wait_vmcnt<NDMA>(); else gv_wait_vmcnt<0>();
-#endif
             asm volatile("" ::: "memory");
         }
         const uint8_t *rb = stage + (wave * 2 + (r & 1)) * GV_ROUND_BYTES;
-#ifdef PEQA_EXP_NO_COMPUTE
-        if (a.T > 99)
-#endif
         {
             const uint8_t *sb = rb + s2 * STEP_B + b_off;
             uint32_t bw[WPB];
@@ -238,10 +217,6 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
         }
     }
 
-#ifdef PEQA_EXP_GVTIMING
-    asm volatile("" :: "v"(y[0][0]), "v"(y[7][3]));
-    tk[3] = __builtin_amdgcn_s_memrealtime();
-#endif
     // ---- sum the waves, then write Y (S = 1) or this slice's partial
     __syncthreads();                                              // everyone is done with the stage buffers
     float *red = reinterpret_cast<float *>(stage);                // [wave][column tile][row in lane][lane], 32 KB
@@ -266,13 +241,6 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
             }
         }
     }
-#ifdef PEQA_EXP_GVTIMING
-    tk[4] = __builtin_amdgcn_s_memrealtime();
-    if (tid == 0) {
-        uint64_t *d = reinterpret_cast<uint64_t *>(a.partial + (size_t)a.S * a.T * a.N) + (size_t)(blockIdx.y * gridDim.x + blockIdx.x) * 8;
-        for (int i = 0; i < 5; ++i) d[i] = tk[i];
-    }
-#endif
 }
 
 // Y[t,n] = bf16( partial[0][t,n] + partial[1][t,n] + ... ), fixed order.

@@ -34,9 +34,6 @@ struct GemmArgs {
     const float *sb;          // [G, N, 2] (s0 + ds, -(s0 + ds)(16 + z0))  (MODE_Y, MODE_DX)
                               // rs is then [T, K/128]: sums of X over blocks of 128 features (MODE_DDS),
                               // partial is [tiles_t, N, G] and z0 is [N, G]
-#ifdef PEQA_EXP_TIMING
-    uint64_t *dbg;
-#endif
 };
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);

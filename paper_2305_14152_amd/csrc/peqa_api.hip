@@ -13,6 +13,8 @@ namespace {
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
 inline int groups(const peqa_layout *L) { return L->group_size > 0 ? L->k_in / L->group_size : 1; }
+// A single group per channel is the per-channel layer, and takes its kernels.
+inline bool grouped(const peqa_layout *L) { return groups(L) > 1; }
 
 // Contraction index at which the second half of a contraction of length n starts:
 // half of it, rounded down to the step of 64 (n % 128 == 0 makes both halves non-empty).
@@ -38,12 +40,12 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
         w.total = off;
         return w;
     }
-    if (L->group_size > 0) {
-        // group-wise: (s, b) table for the forward / dX contraction; row sums of X over blocks of
-        // 128 features and per-(token tile, channel, group) partials for the scale gradient
+    if (grouped(L)) {
+        // group-wise: (s, b) table for the forward / dX contraction; row sums of X over every scale
+        // group and per-(token tile, channel, group) partials for the scale gradient
         w.table = off;   off += round256(N * G * 2 * sizeof(float));
         if (op == PEQA_OP_BWD) {
-            w.rs = off;      off += round256((size_t)T * (size_t)(L->k_in / 128) * sizeof(float));
+            w.rs = off;      off += round256((size_t)T * G * sizeof(float));
             w.partial = off; off += round256(tiles_t * N * G * sizeof(float));
         }
         w.total = off;
@@ -206,7 +208,7 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
         g.S = peqa::gemv_slices(N, K, T, g.chunk);
         return dev_status(peqa::launch_gemv(L->bits, g, s));
     }
-    if (L->group_size > 0) {
+    if (grouped(L)) {
         // the tiled contraction walks scale groups in blocks of 128 features
         if (L->group_size % 128 != 0) return PEQA_ERR_GROUP;
         float *sb = reinterpret_cast<float *>(ws + w.table);
@@ -244,19 +246,19 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
     if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
     // the tiled contractions walk scale groups in blocks of 128 features
-    if (L->group_size > 0 && L->group_size % 128 != 0) return PEQA_ERR_GROUP;
+    if (grouped(L) && L->group_size % 128 != 0) return PEQA_ERR_GROUP;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const int N = L->n_out, K = L->k_in;
     const int tiles_t = (T + 127) / 128;
 
-    if (L->group_size > 0) {
+    if (grouped(L)) {
         const int G = groups(L);
         if (d_ds) {
             float *rsb = reinterpret_cast<float *>(ws + w.rs);
             float *partial = reinterpret_cast<float *>(ws + w.partial);
-            if (peqa::launch_rowsum_blocks(X, T, K, rsb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (peqa::launch_rowsum_groups(X, T, K, L->group_size, rsb, s) != hipSuccess) return PEQA_ERR_DEVICE;
             peqa::GemmArgs a{};
             a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
             a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;

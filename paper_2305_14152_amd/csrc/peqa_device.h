@@ -182,6 +182,16 @@ __device__ __forceinline__ void mfma16_acc(f32x4 &acc, const u32x4 &a, const u32
     // to the DMA queueing and the result fence (the scalar/vector work around them is still free)
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
+// An accumulator tile copied from its AGPRs to VGPRs at this point of the program (volatile: the
+// compiler would otherwise gather every such copy of a kernel at one place).
+__device__ __forceinline__ f32x4 read_acc(const f32x4 &acc)
+{
+    f32x4 v;
+    asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\tv_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
+                 : "=v"(v[0]), "=v"(v[1]), "=v"(v[2]), "=v"(v[3])
+                 : "a"(acc[0]), "a"(acc[1]), "a"(acc[2]), "a"(acc[3]));
+    return v;
+}
 __device__ __forceinline__ void mfma_result_fence()
 {
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");

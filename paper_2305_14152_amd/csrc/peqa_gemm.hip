@@ -230,25 +230,40 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         const uint8_t *src = reinterpret_cast<const uint8_t *>(a.sb) + (wave_on ? (g * a.N + ch) * 8 : 0);
         dma16(lane * 16, src, tbl_lds + (B & 1) * 1024);
     };
-    float sc[8], bo[8];                                    // scale and offset of this lane's 8 block channels
+    // Entries of contraction step m for this lane's 8 block channels: along features 8 c .. 8 c + 7 of
+    // block m / 4, along channels 32 (m % 4) + 8 q .. + 7.  Along channels every fragment needs all
+    // eight (element e of a fragment is channel e): they are read into registers once per step.
+    // Along features fragment I needs only entry I: it is read when the fragment's first register is
+    // built, which keeps 14 registers free.
+    float sc[8], bo[8];
+    const uint8_t *tbl_row = nullptr;
     auto read_table = [&](int m) {
-        // entries of contraction step m: along features 8 c .. 8 c + 7 of block m / 4,
-        // along channels 32 (m % 4) + 8 q .. + 7
-        const uint8_t *tp = lds + NSTAGE * STAGE_BYTES + slot * 2048 + ((m >> 2) & 1) * 1024 +
-                            (ALONG_CH ? (m & 3) * 256 + q * 64 : c * 64);
+        tbl_row = lds + NSTAGE * STAGE_BYTES + slot * 2048 + ((m >> 2) & 1) * 1024 +
+                  (ALONG_CH ? (m & 3) * 256 + q * 64 : c * 64);
+        if constexpr (ALONG_CH) {
 #pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const f32x4 v = *reinterpret_cast<const f32x4 *>(tp + 16 * h);
-            sc[2 * h] = v[0]; bo[2 * h] = v[1]; sc[2 * h + 1] = v[2]; bo[2 * h + 1] = v[3];
+            for (int h = 0; h < 4; ++h) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(tbl_row + 16 * h);
+                sc[2 * h] = v[0]; bo[2 * h] = v[1]; sc[2 * h + 1] = v[2]; bo[2 * h + 1] = v[3];
+            }
         }
     };
     // register J of fragment I of the next step: plain (16 + Q) pairs, or scaled weights
     auto next_frag_reg = [&](const BlockUnpacker<BITS, ALONG_CH> &up, auto i_c, auto j_c) -> uint32_t {
         constexpr int I = decltype(i_c)::value, J = decltype(j_c)::value;
         const uint32_t pr = up.template frag_reg<I, J>(magic);
-        if constexpr (!SCALED) return pr;
-        else if constexpr (!ALONG_CH) return scale_pair(pr, sc[I], bo[I], sc[I], bo[I]);
-        else return scale_pair(pr, sc[2 * J], bo[2 * J], sc[2 * J + 1], bo[2 * J + 1]);
+        if constexpr (!SCALED) {
+            return pr;
+        } else if constexpr (!ALONG_CH) {
+            if constexpr (J == 0) {
+                const f32x2 v = *reinterpret_cast<const f32x2 *>(tbl_row + 8 * I);
+                sc[0] = v[0];
+                bo[0] = v[1];
+            }
+            return scale_pair(pr, sc[0], bo[0], sc[0], bo[0]);
+        } else {
+            return scale_pair(pr, sc[2 * J], bo[2 * J], sc[2 * J + 1], bo[2 * J + 1]);
+        }
     };
 
     f32x4 acc[4][8];
@@ -326,7 +341,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         if constexpr (SCALED) {
             // the fragments built in this step belong to contraction step m = m0 + it + 1
             const int m = m0 + it + 1;
-            if (ALONG_CH || (m & 3) == 0) read_table(m);
+            read_table(m);
             // its block's table has been read by both token-half waves once they pass this step's
             // barrier; the other buffer (block m / 4 - 1) is free: fetch block m / 4 + 1 into it
             if ((m & 3) == 1 && wt == 0) issue_table((m >> 2) + 1);
@@ -407,30 +422,42 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) colsum[ct] = 0.f;
         if (wave_on) {
-#pragma unroll
-            for (int rt = 0; rt < 4; ++rt) {
+            // This lane's 16 rows are t0 + 64 wt + 16 rt + 4 q + j.  Rows past T are clamped for the
+            // loads and masked in the sum, so that all loads are unconditional: dY and the row sums
+            // four rows at a time, the next four in flight while these are used.
+            auto row_of = [&](int rt, int j) { return t0 + 64 * wt + rt * 16 + 4 * q + j; };
+            u32x4 dyv[2][4];
+            float rsv[2][4];
+            auto load_rows = [&](auto rt_c, u32x4 *dst, float *rdst) {
+                constexpr int rt = decltype(rt_c)::value;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const int t = t0 + 64 * wt + rt * 16 + 4 * q + j;
-                    if (t < T) {
-                        const u32x4 dy = *reinterpret_cast<const u32x4 *>(a.dY + (size_t)t * a.C + col0 + 8 * c);
-                        float r;
-                        if constexpr (PAIRED) {
-                            // row sum of X over this half's group: its gsz / 128 blocks of 128 features
-                            const float *rb = a.rs + (size_t)t * (a.K >> 7) + (kbeg >> 7);
-                            r = 0.f;
-                            for (int b = 0; b < (a.gsz >> 7); ++b) r += rb[b];
-                        } else {
-                            r = a.rs[2 * t + wk];
-                        }
+                    const int t = row_of(rt, j), tc = t < T ? t : T - 1;
+                    dst[j] = *reinterpret_cast<const u32x4 *>(a.dY + (size_t)tc * a.C + col0 + 8 * c);
+                    // row sum of X over this contraction half, or over this half's scale group
+                    if constexpr (PAIRED) rdst[j] = a.rs[(size_t)tc * a.G + (half_on ? grp : a.G - 1)];
+                    else rdst[j] = a.rs[2 * tc + wk];
+                }
+            };
+            load_rows(std::integral_constant<int, 0>{}, dyv[0], rsv[0]);
+            static_for<4>([&](auto rt_c) {
+                constexpr int rt = rt_c.value;
+                if constexpr (rt + 1 < 4) load_rows(std::integral_constant<int, rt + 1>{}, dyv[(rt + 1) & 1], rsv[(rt + 1) & 1]);
+                float dm[4];                                   // rows past T contribute nothing
 #pragma unroll
-                        for (int ct = 0; ct < 8; ++ct) {
-                            const float d = (ct & 1) ? bf16_hi(dy[ct >> 1]) : bf16_lo(dy[ct >> 1]);
-                            colsum[ct] += d * (acc[rt][ct][j] - ep_zoff[ct] * r);
-                        }
+                for (int j = 0; j < 4; ++j) dm[j] = row_of(rt, j) < T ? 1.f : 0.f;
+#pragma unroll
+                for (int ct = 0; ct < 8; ++ct) {
+                    // one accumulator tile at a time leaves its AGPRs
+                    const f32x4 av = read_acc(acc[rt][ct]);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t w = dyv[rt & 1][j][ct >> 1];
+                        const float d = ((ct & 1) ? bf16_hi(w) : bf16_lo(w)) * dm[j];
+                        colsum[ct] += d * (av[j] - ep_zoff[ct] * rsv[rt & 1][j]);
                     }
                 }
-            }
+            });
         }
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) {

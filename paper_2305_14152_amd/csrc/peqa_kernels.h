@@ -32,7 +32,7 @@ struct GemmArgs {
     int N;                    // output channels of the layer
     int gsz, G;               // group size and groups per channel
     const float *sb;          // [G, N, 2] (s0 + ds, -(s0 + ds)(16 + z0))  (MODE_Y, MODE_DX)
-                              // rs is then [T, K/128]: sums of X over blocks of 128 features (MODE_DDS),
+                              // rs is then [T, G]: sums of X over every scale group (MODE_DDS),
                               // partial is [tiles_t, N, G] and z0 is [N, G]
 };
 
@@ -57,7 +57,7 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream);
 hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0,
                            int T, int N, uint16_t *dYs, float *crow, hipStream_t stream);
-hipError_t launch_rowsum_blocks(const uint16_t *X, int T, int K, float *rsb, hipStream_t stream);
+hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float *rsg, hipStream_t stream);
 hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, int N, int G, float *sb,
                               hipStream_t stream);
 hipError_t launch_reduce_partials(const float *partial, int ntiles, size_t n, float *out, hipStream_t stream);

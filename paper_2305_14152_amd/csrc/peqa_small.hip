@@ -36,22 +36,36 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
     if (lane == 0) { rs[2 * t] = s[0]; rs[2 * t + 1] = s[1]; }
 }
 
-// rsb[t, j] = sum of X[t, k] over the j-th block of 128 features, fp32 (group-wise scale gradient:
-// a scale group is a run of such blocks).  One wave per token row, 16 lanes per block.
-__global__ __launch_bounds__(256) void rowsum_blocks_kernel(const uint16_t *__restrict__ X, int T, int K,
-                                                             float *__restrict__ rsb)
+// rsg[t, g] = sum of X[t, k] over scale group g (gsz features, a multiple of 128), fp32.
+// One wave per token row: 16 lanes sum each block of 128 features, the block sums meet in LDS,
+// and every group adds its gsz / 128 blocks in order.
+__global__ __launch_bounds__(256) void rowsum_groups_kernel(const uint16_t *__restrict__ X, int T, int K, int gsz,
+                                                             float *__restrict__ rsg)
 {
-    const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= T) return;
-    const u32x4 *row = reinterpret_cast<const u32x4 *>(X + (size_t)t * K);
-    for (int k8 = lane; k8 < (K >> 3); k8 += 64) {        // K % 128 == 0: whole 16-lane segments
-        const u32x4 v = row[k8];
-        float p = 0.f;
+    extern __shared__ float blocksum[];                    // [4 waves][K / 128]
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, t = blockIdx.x * 4 + w;
+    const int nblocks = K >> 7;
+    float *mine = blocksum + w * nblocks;
+    if (t < T) {
+        const u32x4 *row = reinterpret_cast<const u32x4 *>(X + (size_t)t * K);
+        for (int k8 = lane; k8 < (K >> 3); k8 += 64) {    // K % 128 == 0: whole 16-lane segments
+            const u32x4 v = row[k8];
+            float p = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p += bf16_lo(v[i]) + bf16_hi(v[i]);
+            for (int i = 0; i < 4; ++i) p += bf16_lo(v[i]) + bf16_hi(v[i]);
 #pragma unroll
-        for (int o = 8; o >= 1; o >>= 1) p += __shfl_xor(p, o);
-        if ((lane & 15) == 0) rsb[(size_t)t * (K >> 7) + (k8 >> 4)] = p;
+            for (int o = 8; o >= 1; o >>= 1) p += __shfl_xor(p, o);
+            if ((lane & 15) == 0) mine[k8 >> 4] = p;
+        }
+    }
+    __syncthreads();
+    if (t < T) {
+        const int per = gsz >> 7, G = K / gsz;
+        for (int g = lane; g < G; g += 64) {
+            float r = 0.f;
+            for (int b = 0; b < per; ++b) r += mine[g * per + b];
+            rsg[(size_t)t * G + g] = r;
+        }
     }
 }
 
@@ -148,10 +162,11 @@ hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs,
     return hipGetLastError();
 }
 
-hipError_t launch_rowsum_blocks(const uint16_t *X, int T, int K, float *rsb, hipStream_t stream)
+hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float *rsg, hipStream_t stream)
 {
     trace_before(KID_ROWSUM, stream);
-    hipLaunchKernelGGL(rowsum_blocks_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, X, T, K, rsb);
+    hipLaunchKernelGGL(rowsum_groups_kernel, dim3((T + 3) / 4), dim3(256), (size_t)4 * (K >> 7) * sizeof(float), stream,
+                       X, T, K, gsz, rsg);
     trace_after(KID_ROWSUM, stream);
     return hipGetLastError();
 }

@@ -93,6 +93,8 @@ def test_ragged_shapes_parity(gpu, oracle, bits, N, K, T):
     (4, 384, 640, 300, 128),    # 5 groups, empty second column half
     (4, 640, 1024, 33, 512),
     (3, 1280, 2560, 150, 128),  # several column tiles, 20 groups
+    (4, 256, 1152, 70, 128),    # 9 groups: the first contraction half idles through the last one
+    (3, 256, 384, 40, 384),     # a single group: the per-channel kernels
 ])
 def test_groupwise_training_parity(gpu, oracle, bits, N, K, T, group):
     """Group-wise scales (Sec. 4.2, Table 5) through the tiled contractions: forward, dX and the

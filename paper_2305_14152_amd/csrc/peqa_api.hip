@@ -4,6 +4,7 @@
 #include "../../include/peqa.h"
 
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "peqa_kernels.h"
@@ -81,6 +82,10 @@ Side g_side[kMaxDevices];
 
 Side *side_stream()
 {
+    // PEQA_SERIAL_BWD=1 in the environment keeps the whole backward on the caller's stream (profiling
+    // kernels one at a time)
+    static const bool serial = [] { const char *e = getenv("PEQA_SERIAL_BWD"); return e && e[0] == '1'; }();
+    if (serial) return nullptr;
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
     Side &sd = g_side[dev];

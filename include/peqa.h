@@ -25,9 +25,7 @@
  *     Scale-shaped arrays (s0, ds, d_ds, m, v, z0) are [N, G] row-major.
  *
  * Shape limits: N % 128 == 0, K % 128 == 0 (every LLaMA-family linear satisfies
- * this).  group_size is 0 or a multiple of 64 that divides K: peqa_quantize and the
- * small-batch forward (T <= 16) take any such g; the training contractions (forward with
- * T > 16 and peqa_linear_bwd) need g % 128 == 0 and return PEQA_ERR_GROUP otherwise.
+ * this).  group_size is 0 or a multiple of 64 that divides K.
  */
 #ifndef PEQA_H
 #define PEQA_H

@@ -214,8 +214,6 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
         return dev_status(peqa::launch_gemv(L->bits, g, s));
     }
     if (grouped(L)) {
-        // the tiled contraction walks scale groups in blocks of 128 features
-        if (L->group_size % 128 != 0) return PEQA_ERR_GROUP;
         float *sb = reinterpret_cast<float *>(ws + w.table);
         if (peqa::launch_group_table(s0, ds, z0, N, groups(L), sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
@@ -250,8 +248,6 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
     const Workspace w = carve(L, T, PEQA_OP_BWD);
     if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
-    // the tiled contractions walk scale groups in blocks of 128 features
-    if (grouped(L) && L->group_size % 128 != 0) return PEQA_ERR_GROUP;
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint8_t *ws = static_cast<uint8_t *>(workspace);

@@ -48,7 +48,8 @@ constexpr int B_WAVE_BYTES = 2048;                         // one packed 8x8 blo
 constexpr int STAGE_BYTES = 2 * A_HALF_BYTES + 4 * B_WAVE_BYTES;   // 24 KB
 constexpr int DMA_PER_ITER = 3;                            // DMA instructions per wave per iteration
 constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES > 128 * 1024 ? NSTAGE * STAGE_BYTES : 128 * 1024;   // ring / epilogue exchange (128 KB)
-constexpr int TBL_BYTES = 4 * 2 * 1024;                    // grouped MODE_Y / MODE_DX: 2 x 1 KB of (s, b) per (column half, contraction half)
+constexpr int TBL_BYTES = 4 * 2 * 1024;                    // grouped MODE_Y / MODE_DX: 2 x 1 KB of (s, b) per (column half, contraction half);
+                                                           // twice that for MODE_DX when groups end inside a 128-feature run
 
 // Global -> LDS DMA of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l.  The source
 // is sbase (uniform) + voff (per lane).  Issued from inline assembly so that the compiler does not
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         const int g1 = 2 * (int)blockIdx.y + 1;
         kh0 = 2 * (int)blockIdx.y * a.gsz;
         kh1 = (g1 < a.G ? g1 : g1 - 1) * a.gsz;
-        nit = a.gsz / KSTEP;                               // >= 4: the group size is a multiple of 128
+        nit = a.gsz / KSTEP;                               // >= 2 and even: the group size is a multiple of 64
         grp = 2 * (int)blockIdx.y + wk;
         half_on = grp < a.G;
     } else {
@@ -216,20 +217,29 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     };
 
     // ---- grouped MODE_Y / MODE_DX: (s, b = -s (16 + z)) of 128 channels of one scale group, 1 KB,
-    // fetched by the first token-half wave of every (column half, contraction half) one block of four
-    // steps ahead, into a double buffer behind the ring.  Block B covers contraction steps m with
-    // m / 4 == B (m counted from the start of the layer's contraction range):
-    //   along features: the wave's 128 channels, group of features 128 B .. 128 B + 127
-    //   along channels: channels 128 B .. 128 B + 127, group of the wave's 128 features
-    const uint32_t tbl_lds = lds_base + NSTAGE * STAGE_BYTES + slot * 2048;
+    // fetched by DMA one block of steps ahead into a double buffer behind the ring, by the first
+    // token-half wave of every (column half, contraction half).  Steps m are counted from the start
+    // of the layer's contraction range.
+    //   along features: block B = steps m with m >> bshift == B, i.e. 128 features -- or 64 when the
+    //                   group size is not a multiple of 128 (`fine`); the wave's 128 channels, group
+    //                   of those features
+    //   along channels: block B = steps 4 B .. 4 B + 3 = channels 128 B .. 128 B + 127, group of the
+    //                   wave's feature columns; when `fine`, columns 0..63 and 64..127 of the wave may
+    //                   lie in two groups: two chunks per block, the second fetched by the second
+    //                   token-half wave, and lanes pick theirs by column half
+    const bool fine = SCALED && (a.gsz & 127) != 0;
+    const int bshift = (!ALONG_CH && fine) ? 1 : 2;
+    const uint32_t tbuf = (ALONG_CH && fine) ? 2048 : 1024;    // bytes per buffer
+    const uint32_t tbl_off = NSTAGE * STAGE_BYTES + slot * 2 * tbuf;
     auto issue_table = [&](int B) {
-        const int last = (KC >> 7) - 1;
+        const int last = (KC >> (5 + bshift)) - 1;
         B = B < last ? B : last;
-        const size_t g = ALONG_CH ? (size_t)(col0 / a.gsz) : (size_t)((B << 7) / a.gsz);
+        const size_t g = ALONG_CH ? (size_t)((col0 + (fine ? 64 * wt : 0)) / a.gsz) : (size_t)((B << (5 + bshift)) / a.gsz);
         const size_t ch = ALONG_CH ? (size_t)B << 7 : (size_t)col0;
         const uint8_t *src = reinterpret_cast<const uint8_t *>(a.sb) + (wave_on ? (g * a.N + ch) * 8 : 0);
-        dma16(lane * 16, src, tbl_lds + (B & 1) * 1024);
+        dma16(lane * 16, src, lds_base + tbl_off + (B & 1) * tbuf + ((ALONG_CH && fine) ? wt * 1024 : 0));
     };
+    const bool table_wave = wt == 0 || (ALONG_CH && fine);
     // Entries of contraction step m for this lane's 8 block channels: along features 8 c .. 8 c + 7 of
     // block m / 4, along channels 32 (m % 4) + 8 q .. + 7.  Along channels every fragment needs all
     // eight (element e of a fragment is channel e): they are read into registers once per step.
@@ -238,8 +248,8 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     float sc[8], bo[8];
     const uint8_t *tbl_row = nullptr;
     auto read_table = [&](int m) {
-        tbl_row = lds + NSTAGE * STAGE_BYTES + slot * 2048 + ((m >> 2) & 1) * 1024 +
-                  (ALONG_CH ? (m & 3) * 256 + q * 64 : c * 64);
+        tbl_row = lds + tbl_off + ((m >> bshift) & 1) * tbuf +
+                  (ALONG_CH ? (fine ? (c >> 3) * 1024 : 0) + (m & 3) * 256 + q * 64 : c * 64);
         if constexpr (ALONG_CH) {
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
@@ -301,7 +311,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     u32x4 bfrag[2][8], afrag[4];
     uint32_t bw[2][WPB];                                   // packed weights of the next step / the one after
     if constexpr (SCALED) {
-        if (wt == 0) { issue_table(m0 >> 2); issue_table((m0 >> 2) + 1); }
+        if (table_wave) { issue_table(m0 >> bshift); issue_table((m0 >> bshift) + 1); }
     }
 #pragma unroll
     for (int sidx = 0; sidx < NSTAGE - 1; ++sidx) issue(sidx < nit ? sidx : nit - 1, sidx);
@@ -342,9 +352,11 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
             // the fragments built in this step belong to contraction step m = m0 + it + 1
             const int m = m0 + it + 1;
             read_table(m);
-            // its block's table has been read by both token-half waves once they pass this step's
-            // barrier; the other buffer (block m / 4 - 1) is free: fetch block m / 4 + 1 into it
-            if ((m & 3) == 1 && wt == 0) issue_table((m >> 2) + 1);
+            // The buffer of the block before m's was last read in the previous step: fetch the block
+            // after m's into it.  With blocks of four steps this is done at the block's second step
+            // (three steps of lead); with blocks of two, at its first (two steps: the DMA is complete
+            // after the next step's wait and visible after its barrier, just in time).
+            if ((m & ((1 << bshift) - 1)) == (bshift == 2 ? 1 : 0) && table_wave) issue_table((m >> bshift) + 1);
         }
         BlockUnpacker<BITS, ALONG_CH> up;
         up.prepare(bw[CUR]);
@@ -540,18 +552,23 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 
 }  // namespace
 
-int gemm_lds_bytes() { return LDS_BYTES + TBL_BYTES; }
+int gemm_lds_bytes() { return LDS_BYTES + 2 * TBL_BYTES; }
 
 template <int BITS, int MODE, bool GROUPED>
 static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
 {
-    constexpr int lds_bytes = LDS_BYTES + (GROUPED && MODE != MODE_DDS ? TBL_BYTES : 0);
-    static bool attr_done = false;                          // per instantiation
-    if (!attr_done) {
+    // dynamic LDS: the ring, plus the scale tables of the grouped forward / dX (twice as large for dX
+    // when groups end inside a 128-feature run)
+    const int lds_bytes = LDS_BYTES + (GROUPED && MODE != MODE_DDS ? (MODE == MODE_DX && (a.gsz & 127) ? 2 : 1) * TBL_BYTES : 0);
+    // the limit is a per-device attribute of every instantiation; raised to what a launch needs
+    static int attr_bytes[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (attr_bytes[dev] < lds_bytes) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MODE, GROUPED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        attr_bytes[dev] = lds_bytes;
     }
     const int pt = a.patch_t, pc = 32 / pt;
     const int patches = ((a.tiles_t + pt - 1) / pt) * ((a.tiles_c + pc - 1) / pc);

@@ -36,31 +36,31 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
     if (lane == 0) { rs[2 * t] = s[0]; rs[2 * t + 1] = s[1]; }
 }
 
-// rsg[t, g] = sum of X[t, k] over scale group g (gsz features, a multiple of 128), fp32.
-// One wave per token row: 16 lanes sum each block of 128 features, the block sums meet in LDS,
-// and every group adds its gsz / 128 blocks in order.
+// rsg[t, g] = sum of X[t, k] over scale group g (gsz features, a multiple of 64), fp32.
+// One wave per token row: 8 lanes sum each run of 64 features, the run sums meet in LDS,
+// and every group adds its gsz / 64 runs in order.
 __global__ __launch_bounds__(256) void rowsum_groups_kernel(const uint16_t *__restrict__ X, int T, int K, int gsz,
                                                              float *__restrict__ rsg)
 {
-    extern __shared__ float blocksum[];                    // [4 waves][K / 128]
+    extern __shared__ float runsum[];                      // [4 waves][K / 64]
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, t = blockIdx.x * 4 + w;
-    const int nblocks = K >> 7;
-    float *mine = blocksum + w * nblocks;
+    const int nruns = K >> 6;
+    float *mine = runsum + w * nruns;
     if (t < T) {
         const u32x4 *row = reinterpret_cast<const u32x4 *>(X + (size_t)t * K);
-        for (int k8 = lane; k8 < (K >> 3); k8 += 64) {    // K % 128 == 0: whole 16-lane segments
+        for (int k8 = lane; k8 < (K >> 3); k8 += 64) {    // K % 128 == 0: whole 8-lane segments
             const u32x4 v = row[k8];
             float p = 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i) p += bf16_lo(v[i]) + bf16_hi(v[i]);
 #pragma unroll
-            for (int o = 8; o >= 1; o >>= 1) p += __shfl_xor(p, o);
-            if ((lane & 15) == 0) mine[k8 >> 4] = p;
+            for (int o = 4; o >= 1; o >>= 1) p += __shfl_xor(p, o);
+            if ((lane & 7) == 0) mine[k8 >> 3] = p;
         }
     }
     __syncthreads();
     if (t < T) {
-        const int per = gsz >> 7, G = K / gsz;
+        const int per = gsz >> 6, G = K / gsz;
         for (int g = lane; g < G; g += 64) {
             float r = 0.f;
             for (int b = 0; b < per; ++b) r += mine[g * per + b];
@@ -165,7 +165,7 @@ hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs,
 hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float *rsg, hipStream_t stream)
 {
     trace_before(KID_ROWSUM, stream);
-    hipLaunchKernelGGL(rowsum_groups_kernel, dim3((T + 3) / 4), dim3(256), (size_t)4 * (K >> 7) * sizeof(float), stream,
+    hipLaunchKernelGGL(rowsum_groups_kernel, dim3((T + 3) / 4), dim3(256), (size_t)4 * (K >> 6) * sizeof(float), stream,
                        X, T, K, gsz, rsg);
     trace_after(KID_ROWSUM, stream);
     return hipGetLastError();

@@ -95,6 +95,10 @@ def test_ragged_shapes_parity(gpu, oracle, bits, N, K, T):
     (3, 1280, 2560, 150, 128),  # several column tiles, 20 groups
     (4, 256, 1152, 70, 128),    # 9 groups: the first contraction half idles through the last one
     (3, 256, 384, 40, 384),     # a single group: the per-channel kernels
+    (4, 256, 512, 150, 64),     # groups of 64: two per 128-feature run
+    (3, 384, 640, 77, 64),
+    (4, 512, 768, 200, 192),    # a multiple of 64 that is not one of 128
+    (3, 1280, 1024, 300, 64),
 ])
 def test_groupwise_training_parity(gpu, oracle, bits, N, K, T, group):
     """Group-wise scales (Sec. 4.2, Table 5) through the tiled contractions: forward, dX and the

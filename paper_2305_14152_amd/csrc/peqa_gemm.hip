@@ -315,7 +315,8 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     }
 #pragma unroll
     for (int sidx = 0; sidx < NSTAGE - 1; ++sidx) issue(sidx < nit ? sidx : nit - 1, sidx);
-    wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4)>();
+    issue_one(2, NSTAGE - 1 < nit ? NSTAGE - 1 : nit - 1, NSTAGE - 1);   // the packed weights run one stage further ahead
+    wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4) + 1>();
     __syncthreads();
     {
         read_b(0, bw[1]);
@@ -329,6 +330,8 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
             static_for<4>([&](auto j) { bfrag[0][i.value][j.value] = next_frag_reg(up, i, j); });
         });
     }
+    // step 0 refills the packed-weight slot of stage 0, which the partner wave may still be reading
+    __syncthreads();
 
     // ---- main loop.  A step is a 32-deep contraction: 32 MFMAs, one per accumulator.  When step
     // `it` starts, its fragments and the packed weights of step it + 1 are in registers, and stages
@@ -336,15 +339,19 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     // after the barrier; everything else sits in their shadow, in fixed slots:
     //   after every MFMA      one register of step it + 1's weight fragments (shift + and_or)
     //   after MFMA 2          LDS read of the packed weights of step it + 2
-    //   after MFMA 5, 13, 21  one DMA for step it + NSTAGE - 1 (the tail re-fetches the last tile:
-    //                         harmless, and it keeps the DMA count per step constant so that a fixed
-    //                         vmcnt tells when a stage has landed)
+    //   after MFMA 5, 13, 21  one DMA each: the two activation tiles of step it + NSTAGE - 1 (into the
+    //                         stage of step it - 1) and the packed weights of step it + NSTAGE (into
+    //                         this step's own stage: they were read two steps ago, and they are the
+    //                         operand that comes from HBM, so they get the longer lead).  The tail
+    //                         re-fetches the last tile: harmless, and it keeps the DMA count per step
+    //                         constant so that a fixed vmcnt tells when a stage has landed
     //   after each 8 MFMAs    the activation fragment just used up is refilled from LDS for step it + 1
     // Two steps per loop trip so that the register buffers are static.
     int cur = 0;                                           // LDS stage of the current step
     auto step = [&](int it, auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         const int pre = it + NSTAGE - 1 < nit ? it + NSTAGE - 1 : nit - 1;
+        const int pre_b = it + NSTAGE < nit ? it + NSTAGE : nit - 1;
         const int nstage = cur + 1 == NSTAGE ? 0 : cur + 1;       // stage of step it + 1
         const int nnstage = nstage + 1 == NSTAGE ? 0 : nstage + 1; // stage of step it + 2
         const int pstage = cur == 0 ? NSTAGE - 1 : cur - 1;       // stage of step it - 1 = of step it + NSTAGE - 1
@@ -370,13 +377,13 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                 if constexpr (m == 2) read_b(nnstage, bw[NXT]);
                 if constexpr (m == 5) issue_one(0, pre, pstage);
                 if constexpr (m == 13) issue_one(1, pre, pstage);
-                if constexpr (m == 21) issue_one(2, pre, pstage);
+                if constexpr (m == 21) issue_one(2, pre_b, cur);
             });
             read_a(nstage, afrag, rt);
         });
         // Own DMA for step it + 3 has landed; the barrier makes every wave's part visible.
         // No wait on LDS reads is needed here: what this step read is overwritten two steps later.
-        wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4)>();
+        wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4) + 1>();
         bare_barrier();
         cur = nstage;
     };

@@ -113,7 +113,40 @@ def small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream, reps=20):
         tr = peqa.trace_end(16)
         kern_us = sum(ms for (_, ms) in tr.values()) * 1e3 / (reps * nsets)
         main_us = tr["gemv"][1] * 1e3 / (reps * nsets)
+        # the same block with the layers that read one X fused into one call each:
+        # (q, k, v), o, (gate, up), down -- 4 calls instead of 7
+        groups, i = [], 0
+        for (_, _, count) in cfg["layers"]:
+            fuse = count - 1 if count == 4 else count          # q, k, v together; o reads another input
+            groups.append(list(range(i, i + fuse)))
+            if fuse != count:
+                groups.append([i + fuse])
+            i += count
+        need_f = max(peqa.workspace_bytes_fused([(layers[j].L, layers[j].packed, layers[j].s0, layers[j].ds,
+                                                  layers[j].z0, layers[j].Y) for j in grp], T) for grp in groups)
+        assert need_f <= ws_bytes
+        bytes_fused = sum(l.N * l.K * bits / 8 + l.N * l.L.groups * 9 + 2 * T * l.N for l in layers) + \
+            sum(2 * T * layers[grp[0]].K for grp in groups)
+
+        def run_fused():
+            for packed_set in sets:
+                for grp in groups:
+                    items = [(layers[j].L, packed_set[j], layers[j].s0, layers[j].ds, layers[j].z0, layers[j].Y)
+                             for j in grp]
+                    peqa.linear_fwd_fused(items, layers[grp[0]].X, T, ws, ws_bytes, stream)
+
+        for _ in range(3):
+            run_fused()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run_fused()
+        torch.cuda.synchronize()
+        fused_us = (time.perf_counter() - t0) / (reps * nsets) * 1e6
         out["T%d" % T] = {
+            "fused_shared_x": {"calls_per_block": len(groups), "bytes_per_block": int(bytes_fused),
+                               "block_us_wall": round(fused_us, 2), "GBs_wall": round(bytes_fused / fused_us / 1e3, 1),
+                               "frac_of_hbm_peak_wall": round(bytes_fused / fused_us / 1e3 / HBM_PEAK_GBS, 4)},
             "bytes_per_block": int(bytes_block),
             "block_us_wall": round(wall_us, 2), "block_us_kernels": round(kern_us, 2),
             "block_us_gemv_kernel": round(main_us, 2),

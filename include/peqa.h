@@ -112,6 +112,29 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
                             uint16_t *Y, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same forward for 1..PEQA_MAX_FUSED layers that read the same X (the query / key / value
+ * projections of an attention block; the gate and up projections of its MLP): equal to calling
+ * peqa_linear_fwd once per item, every item writing its own Y.  All items must share k_in, bits
+ * and group_size (PEQA_ERR_PARAM otherwise).  With T <= 16 (Sec. 3.1, "Inference Latency": bound by
+ * the weight bytes streamed) the layers run side by side in one launch, which matters because
+ * a single LLaMA-size layer at such T is too short to fill the machine; larger T runs them one
+ * after the other.  `items` is a HOST array; workspace: peqa_workspace_bytes_fused() bytes.
+ */
+#define PEQA_MAX_FUSED 4
+typedef struct {
+    peqa_layout layout;
+    const uint32_t *packed;
+    const float *s0;
+    const float *ds;     /* may be NULL */
+    const uint8_t *z0;
+    uint16_t *Y;         /* [T, layout.n_out] bf16 out */
+} peqa_fwd_item;
+
+size_t peqa_workspace_bytes_fused(int32_t n, const peqa_fwd_item *items, int32_t T);
+peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const uint16_t *X, int32_t T,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Backward of Eq. 2 by the chain rule (only the scales are trained, Sec. 3.2):
  *   dX[t,k]   = sum_i dY[t,i] * (s0+ds)[i,g(k)] * (Q[i,k] - z0[i,g(k)])
  *   d_ds[i,g] = sum_t dY[t,i] * sum_{k in g} X[t,k] * (Q[i,k] - z0[i,g])

@@ -27,6 +27,14 @@ struct Workspace {
     size_t rs, dys, crow, partial, table, total;
 };
 
+// matrix-vector path: fp32 partials of the feature slices, for n_total output channels side by side
+size_t gemv_partial_bytes(const peqa_layout *L, size_t n_total, int32_t T)
+{
+    const int chunk = L->group_size > 0 ? L->group_size : L->k_in;
+    const size_t S = (size_t)peqa::gemv_slices((int)n_total, L->k_in, T, chunk);
+    return round256(S * (size_t)T * n_total * sizeof(float));
+}
+
 Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
 {
     Workspace w{};
@@ -34,10 +42,7 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
     const size_t tiles_t = ((size_t)T + 127) / 128;
     size_t off = 0;
     if (op == PEQA_OP_FWD && T <= PEQA_GEMV_MAX_T) {
-        // matrix-vector path: fp32 partials of the feature slices
-        const int chunk = L->group_size > 0 ? L->group_size : L->k_in;
-        const size_t S = (size_t)peqa::gemv_slices(L->n_out, L->k_in, T, chunk);
-        w.partial = off; off += round256(S * (size_t)T * N * sizeof(float));
+        w.partial = off; off += gemv_partial_bytes(L, L->n_out, T);
         w.total = off;
         return w;
     }
@@ -63,6 +68,30 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
 }
 
 peqa_status dev_status(hipError_t e) { return e == hipSuccess ? PEQA_OK : PEQA_ERR_DEVICE; }
+
+// One matrix-vector launch for n <= GEMV_MAX_LAYERS validated layers that share X, K, bits and group size.
+peqa_status gemv_forward(int n, const peqa_fwd_item *items, const uint16_t *X, int32_t T, float *partial,
+                         hipStream_t s)
+{
+    const peqa_layout *L = &items[0].layout;
+    peqa::GemvArgs g{};
+    int tiles = 0;
+    for (int j = 0; j < peqa::GEMV_MAX_LAYERS; ++j) {
+        if (j < n) {
+            tiles += items[j].layout.n_out / 128;
+            g.layer[j] = peqa::GemvLayer{items[j].packed, items[j].s0, items[j].ds, items[j].z0, items[j].Y,
+                                         items[j].layout.n_out, tiles};
+        } else {
+            g.layer[j] = g.layer[n - 1];                   // never selected: its tile_end is the total
+        }
+    }
+    g.n_layers = n;
+    g.X = X; g.partial = partial;
+    g.K = L->k_in; g.G = groups(L); g.T = T;
+    g.chunk = L->group_size > 0 ? L->group_size : L->k_in;
+    g.S = peqa::gemv_slices(tiles * 128, L->k_in, T, g.chunk);
+    return dev_status(peqa::launch_gemv(L->bits, g, s));
+}
 
 bool trace_active();
 
@@ -205,13 +234,8 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const int N = L->n_out, K = L->k_in, ksplit = split_point(K);
     if (T <= PEQA_GEMV_MAX_T) {
-        peqa::GemvArgs g{};
-        g.packed = packed; g.X = X; g.s0 = s0; g.ds = ds; g.z0 = z0; g.Y = Y;
-        g.partial = reinterpret_cast<float *>(ws + w.partial);
-        g.N = N; g.K = K; g.G = groups(L); g.T = T;
-        g.chunk = L->group_size > 0 ? L->group_size : K;
-        g.S = peqa::gemv_slices(N, K, T, g.chunk);
-        return dev_status(peqa::launch_gemv(L->bits, g, s));
+        peqa_fwd_item item{*L, packed, s0, ds, z0, Y};
+        return gemv_forward(1, &item, X, T, reinterpret_cast<float *>(ws + w.partial), s);
     }
     if (grouped(L)) {
         float *sb = reinterpret_cast<float *>(ws + w.table);
@@ -231,6 +255,65 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
     a.s0 = s0; a.ds = ds; a.z0 = z0; a.rs = rs; a.out = Y;
     return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
+}
+
+// Forward of several layers that read the same X.
+static peqa_status check_fused(int32_t n, const peqa_fwd_item *items, int32_t T)
+{
+    if (!items) return PEQA_ERR_NULL;
+    if (n < 1 || n > PEQA_MAX_FUSED) return PEQA_ERR_PARAM;
+    if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
+    for (int j = 0; j < n; ++j) {
+        peqa_status st = peqa_check_layout(&items[j].layout);
+        if (st != PEQA_OK) return st;
+        if (items[j].layout.k_in != items[0].layout.k_in || items[j].layout.bits != items[0].layout.bits ||
+            items[j].layout.group_size != items[0].layout.group_size)
+            return PEQA_ERR_PARAM;
+    }
+    return PEQA_OK;
+}
+
+size_t peqa_workspace_bytes_fused(int32_t n, const peqa_fwd_item *items, int32_t T)
+{
+    if (check_fused(n, items, T) != PEQA_OK) return 0;
+    if (T <= PEQA_GEMV_MAX_T) {
+        size_t n_total = 0;
+        for (int j = 0; j < n; ++j) n_total += (size_t)items[j].layout.n_out;
+        return gemv_partial_bytes(&items[0].layout, n_total, T);
+    }
+    size_t need = 0;                                       // layer by layer: the largest single need
+    for (int j = 0; j < n; ++j) {
+        const size_t b = carve(&items[j].layout, T, PEQA_OP_FWD).total;
+        need = b > need ? b : need;
+    }
+    return need;
+}
+
+peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const uint16_t *X, int32_t T,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    peqa_status st = check_fused(n, items, T);
+    if (st != PEQA_OK) return st;
+    if (!X) return PEQA_ERR_NULL;
+    for (int j = 0; j < n; ++j) {
+        const peqa_fwd_item &it = items[j];
+        if (!it.packed || !it.s0 || !it.z0 || !it.Y) return PEQA_ERR_NULL;
+        if (!aligned16(it.packed) || !aligned16(it.s0) || !aligned16(it.z0) || !aligned16(it.Y) ||
+            (it.ds && !aligned16(it.ds)))
+            return PEQA_ERR_ALIGN;
+    }
+    if (!aligned16(X)) return PEQA_ERR_ALIGN;
+    const size_t need = peqa_workspace_bytes_fused(n, items, T);
+    if (!workspace || workspace_bytes < need) return PEQA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
+    if (T <= PEQA_GEMV_MAX_T)
+        return gemv_forward(n, items, X, T, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+    for (int j = 0; j < n; ++j) {                          // the tiled contraction runs the layers one by one
+        const peqa_fwd_item &it = items[j];
+        st = peqa_linear_fwd(&it.layout, it.packed, it.s0, it.ds, it.z0, X, T, it.Y, workspace, workspace_bytes, stream);
+        if (st != PEQA_OK) return st;
+    }
+    return PEQA_OK;
 }
 
 peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,

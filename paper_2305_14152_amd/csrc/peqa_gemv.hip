@@ -62,7 +62,19 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, q = lane >> 4;
-    const int n0 = blockIdx.x * 128;
+    // which layer this channel tile belongs to (uniform; selects instead of indexing, so that the
+    // argument block stays in scalar registers)
+    const int bx = blockIdx.x;
+    const int li = (bx >= a.layer[0].tile_end) + (bx >= a.layer[1].tile_end) + (bx >= a.layer[2].tile_end);
+    auto pick = [&](auto f) { return li == 0 ? f(a.layer[0]) : li == 1 ? f(a.layer[1]) : li == 2 ? f(a.layer[2]) : f(a.layer[3]); };
+    const uint32_t *l_packed = pick([](const GemvLayer &l) { return l.packed; });
+    const float *l_s0 = pick([](const GemvLayer &l) { return l.s0; });
+    const float *l_ds = pick([](const GemvLayer &l) { return l.ds; });
+    const uint8_t *l_z0 = pick([](const GemvLayer &l) { return l.z0; });
+    uint16_t *l_Y = pick([](const GemvLayer &l) { return l.Y; });
+    const int l_N = pick([](const GemvLayer &l) { return l.N; });
+    const int tile0 = li == 0 ? 0 : li == 1 ? a.layer[0].tile_end : li == 2 ? a.layer[1].tile_end : a.layer[2].tile_end;
+    const int n0 = (bx - tile0) * 128;                           // first channel, within its layer
     const int K = a.K, G = a.G;
     const int chunk_rounds = a.chunk >> 6;                        // 64-feature rounds per scale group
     // this workgroup's rounds [rbeg, rend); wave w takes the w-th quarter of them
@@ -77,8 +89,8 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
     const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
     // the wave's tiles (128 channels x 32 features, TILE bytes each) are contiguous along the features
     constexpr uint32_t TILE = 64 * WPB * 4;
-    const uint8_t *bbase = reinterpret_cast<const uint8_t *>(a.packed) +
-                           ((size_t)blockIdx.x * (K >> 5) + (k0 >> 5)) * TILE;
+    const uint8_t *bbase = reinterpret_cast<const uint8_t *>(l_packed) +
+                           ((size_t)(bx - tile0) * (K >> 5) + (k0 >> 5)) * TILE;
     const uint8_t *xbase = reinterpret_cast<const uint8_t *>(a.X + k0);
     const uint32_t lds_stage = (uint32_t)(uintptr_t)stage + wave * 2 * GV_ROUND_BYTES;
     uint32_t b_voff[NDMA_B], x_voff[2];
@@ -126,9 +138,9 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
             ch[i] = on ? (int)((uint32_t)idx / (uint32_t)cols) : 0;
             jj[i] = on ? idx - ch[i] * cols : 0;
             const size_t si = (size_t)(n0 + ch[i]) * G + g_lo + jj[i];
-            ts[i] = a.s0[si];
-            tz[i] = a.z0[si];
-            td[i] = a.ds ? a.ds[si] : 0.f;
+            ts[i] = l_s0[si];
+            tz[i] = l_z0[si];
+            td[i] = l_ds ? l_ds[si] : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
@@ -236,31 +248,40 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
             for (int w = 0; w < GV_WAVES; ++w) v += red[((w * 8 + ct) * 4 + j) * 64 + lane];
             const int t = 4 * q + j, n = n0 + 8 * c + ct;
             if (t < a.T) {
-                if (a.S == 1) a.Y[(size_t)t * a.N + n] = (uint16_t)float_to_bf16_bits(v);
-                else a.partial[((size_t)blockIdx.y * a.T + t) * a.N + n] = v;
+                if (a.S == 1) l_Y[(size_t)t * l_N + n] = (uint16_t)float_to_bf16_bits(v);
+                else a.partial[((size_t)blockIdx.y * a.T + t) * (gridDim.x * 128) + bx * 128 + 8 * c + ct] = v;
             }
         }
     }
 }
 
-// Y[t,n] = bf16( partial[0][t,n] + partial[1][t,n] + ... ), fixed order.
-__global__ __launch_bounds__(256) void gemv_finish_kernel(const float *__restrict__ partial, int S, size_t tn,
-                                                           uint16_t *__restrict__ Y)
+// Y[t,n] = bf16( partial[0][t,n] + partial[1][t,n] + ... ), fixed order; column n of the side-by-side
+// layers goes to its own layer's Y.
+__global__ __launch_bounds__(256) void gemv_finish_kernel(GemvArgs a)
 {
-    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (j >= tn) return;
+    const int ntot = a.layer[a.n_layers - 1].tile_end * 128;
+    const size_t tn = (size_t)a.T * ntot;
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= tn) return;
+    const int t = (int)(e / ntot), n = (int)(e - (size_t)t * ntot);
     float v = 0.f;
-    for (int s = 0; s < S; ++s) v += partial[(size_t)s * tn + j];
-    Y[j] = (uint16_t)float_to_bf16_bits(v);
+    for (int sl = 0; sl < a.S; ++sl) v += a.partial[(size_t)sl * tn + e];
+    const int tile = n >> 7;
+    const int li = (tile >= a.layer[0].tile_end) + (tile >= a.layer[1].tile_end) + (tile >= a.layer[2].tile_end);
+    auto pick = [&](auto f) { return li == 0 ? f(a.layer[0]) : li == 1 ? f(a.layer[1]) : li == 2 ? f(a.layer[2]) : f(a.layer[3]); };
+    uint16_t *y = pick([](const GemvLayer &l) { return l.Y; });
+    const int ln = pick([](const GemvLayer &l) { return l.N; });
+    const int tile0 = li == 0 ? 0 : li == 1 ? a.layer[0].tile_end : li == 2 ? a.layer[1].tile_end : a.layer[2].tile_end;
+    y[(size_t)t * ln + (n - tile0 * 128)] = (uint16_t)float_to_bf16_bits(v);
 }
 
 }  // namespace
 
-int gemv_slices(int N, int K, int T, int chunk)
+int gemv_slices(int Ntot, int K, int T, int chunk)
 {
     // as many slices as keep every workgroup resident at once (2 per compute unit), every wave at
     // least two rounds long, and the partials small next to the weight bytes
-    const int tiles = N / 128, R = K / 64, chunk_rounds = chunk / 64;
+    const int tiles = Ntot / 128, R = K / 64, chunk_rounds = chunk / 64;
     int S = 512 / tiles;
     if (S > R / (2 * GV_WAVES)) S = R / (2 * GV_WAVES);
     const int by_bytes = T > 4 ? 6 : 16;
@@ -274,16 +295,16 @@ int gemv_slices(int N, int K, int T, int chunk)
 hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
 {
     trace_before(KID_GEMV, stream);
-    const dim3 grid(a.N / 128, a.S);
+    const int tiles = a.layer[a.n_layers - 1].tile_end;
+    const dim3 grid(tiles, a.S);
     if (bits == 4) hipLaunchKernelGGL(gemv_kernel<4>, grid, dim3(GV_WAVES * 64), 0, stream, a);
     else hipLaunchKernelGGL(gemv_kernel<3>, grid, dim3(GV_WAVES * 64), 0, stream, a);
     trace_after(KID_GEMV, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.S == 1) return e;
     trace_before(KID_GEMV_FINISH, stream);
-    const size_t tn = (size_t)a.T * a.N;
-    hipLaunchKernelGGL(gemv_finish_kernel, dim3((unsigned)((tn + 255) / 256)), dim3(256), 0, stream, a.partial, a.S, tn,
-                       a.Y);
+    const size_t tn = (size_t)a.T * tiles * 128;
+    hipLaunchKernelGGL(gemv_finish_kernel, dim3((unsigned)((tn + 255) / 256)), dim3(256), 0, stream, a);
     trace_after(KID_GEMV_FINISH, stream);
     return hipGetLastError();
 }

@@ -38,19 +38,27 @@ struct GemmArgs {
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
 
-// Arguments of the T <= 16 forward (peqa_gemv.hip).
-struct GemvArgs {
+// Arguments of the T <= 16 forward (peqa_gemv.hip): up to GEMV_MAX_LAYERS layers that share X
+// (same K, bit width and group size), laid side by side along the output channels.
+constexpr int GEMV_MAX_LAYERS = 4;
+struct GemvLayer {
     const uint32_t *packed;
-    const uint16_t *X;        // [T, K] bf16
     const float *s0, *ds;     // [N, G]; ds may be NULL
     const uint8_t *z0;        // [N, G]
     uint16_t *Y;              // [T, N] bf16
-    float *partial;           // [S, T, N] fp32 (S > 1)
-    int N, K, G, T;
+    int N;
+    int tile_end;             // channel tiles (of 128) of this layer and all before it
+};
+struct GemvArgs {
+    GemvLayer layer[GEMV_MAX_LAYERS];
+    int n_layers;
+    const uint16_t *X;        // [T, K] bf16
+    float *partial;           // [S, T, Ntot] fp32 (S > 1), Ntot = 128 * layer[n_layers - 1].tile_end
+    int K, G, T;
     int S;                    // feature slices (gemv_slices)
     int chunk;                // features per scale group (K for per-channel layers)
 };
-int gemv_slices(int N, int K, int T, int chunk);
+int gemv_slices(int Ntot, int K, int T, int chunk);
 hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 
 // peqa_small.hip

@@ -14,7 +14,8 @@ PEQA_OP_FWD, PEQA_OP_BWD = 0, 1
 
 EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_workspace_bytes",
            "peqa_status_string", "peqa_bit_location", "peqa_quantize", "peqa_linear_fwd",
-           "peqa_linear_bwd", "peqa_scale_update", "peqa_trace_begin", "peqa_trace_end"]
+           "peqa_linear_bwd", "peqa_scale_update", "peqa_trace_begin", "peqa_trace_end",
+           "peqa_workspace_bytes_fused", "peqa_linear_fwd_fused"]
 
 
 class Layout(ctypes.Structure):
@@ -70,6 +71,10 @@ def lib():
         L.peqa_linear_bwd.restype = i32
         L.peqa_scale_update.argtypes = [sz, vp, vp, vp, vp, vp, ctypes.POINTER(AdamW), vp]
         L.peqa_scale_update.restype = i32
+        L.peqa_workspace_bytes_fused.argtypes = [i32, vp, i32]
+        L.peqa_workspace_bytes_fused.restype = sz
+        L.peqa_linear_fwd_fused.argtypes = [i32, vp, vp, i32, vp, sz, vp]
+        L.peqa_linear_fwd_fused.restype = i32
         L.peqa_trace_begin.argtypes = [i32]
         L.peqa_trace_begin.restype = i32
         L.peqa_trace_end.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32),
@@ -140,6 +145,30 @@ def linear_fwd(L, packed, s0, ds, z0, X, T, Y, workspace, workspace_bytes_, stre
     _check(lib().peqa_linear_fwd(ctypes.byref(L), _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(X), int(T),
                                  _ptr(Y), _ptr(workspace), int(workspace_bytes_), _stream(stream)),
            "peqa_linear_fwd")
+
+
+class FwdItem(ctypes.Structure):
+    _fields_ = [("layout", Layout), ("packed", ctypes.c_void_p), ("s0", ctypes.c_void_p), ("ds", ctypes.c_void_p),
+                ("z0", ctypes.c_void_p), ("Y", ctypes.c_void_p)]
+
+
+def _items(layers):
+    """layers: sequence of (L, packed, s0, ds, z0, Y)."""
+    arr = (FwdItem * len(layers))()
+    for i, (L, packed, s0, ds, z0, Y) in enumerate(layers):
+        arr[i] = FwdItem(L, _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(Y))
+    return arr
+
+
+def workspace_bytes_fused(layers, T):
+    arr = _items(layers)
+    return int(lib().peqa_workspace_bytes_fused(len(layers), ctypes.addressof(arr), int(T)))
+
+
+def linear_fwd_fused(layers, X, T, workspace, workspace_bytes_, stream=None):
+    arr = _items(layers)
+    _check(lib().peqa_linear_fwd_fused(len(layers), ctypes.addressof(arr), _ptr(X), int(T), _ptr(workspace),
+                                       int(workspace_bytes_), _stream(stream)), "peqa_linear_fwd_fused")
 
 
 def linear_bwd(L, packed, s0, ds, z0, X, dY, T, dX, d_ds, workspace, workspace_bytes_, stream=None):

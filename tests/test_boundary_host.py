@@ -99,6 +99,19 @@ def test_argument_validation_needs_no_device(peqa):
     assert u(16, good, good, good, good, good, byref(opt), None) == peqa.PEQA_ERR_PARAM
 
 
+def test_fused_forward_validation_needs_no_device(peqa):
+    a, b = peqa.layout(256, 512, 4), peqa.layout(128, 512, 4)
+    assert peqa.workspace_bytes_fused([(a, 16, 16, None, 16, 16), (b, 16, 16, None, 16, 16)], 4) > 0
+    odd = peqa.layout(128, 256, 4)                      # another K
+    assert peqa.workspace_bytes_fused([(a, 16, 16, None, 16, 16), (odd, 16, 16, None, 16, 16)], 4) == 0
+    with pytest.raises(peqa.PeqaError):
+        peqa.linear_fwd_fused([(a, 16, 16, None, 16, 16), (odd, 16, 16, None, 16, 16)], 16, 4, 16, 1 << 20, stream=0)
+    with pytest.raises(peqa.PeqaError):                 # too many layers
+        peqa.linear_fwd_fused([(a, 16, 16, None, 16, 16)] * 5, 16, 4, 16, 1 << 20, stream=0)
+    with pytest.raises(peqa.PeqaError):                 # a NULL output
+        peqa.linear_fwd_fused([(a, 16, 16, None, 16, None)], 16, 4, 16, 1 << 20, stream=0)
+
+
 def test_product_package_does_not_touch_the_oracle():
     """The product path may not import, read or link anything under oracle/."""
     pkg = os.path.join(ROOT, "paper_2305_14152_amd")

@@ -137,6 +137,38 @@ def test_small_batch_forward_parity(gpu, oracle, bits, N, K, group):
             assert np.abs(Y - Yref).max() <= Y_TOL * np.abs(Yref).max(), (T, np.abs(Y - Yref).max(), np.abs(Yref).max())
 
 
+@pytest.mark.parametrize("bits,Ns,K,group", [
+    (4, (256, 384, 128), 512, 0), (3, (256, 256), 1024, 128), (4, (128, 128, 128, 640), 768, 64), (3, (1280,), 2048, 0),
+])
+def test_fused_forward_parity(gpu, oracle, bits, Ns, K, group):
+    """Several layers reading one X through peqa_linear_fwd_fused: every Y equals the single-layer forward."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    _log("fused bits=%d Ns=%s K=%d g=%d" % (bits, Ns, K, group))
+    seed = 13000 + bits * 1000 + sum(Ns) + K + group
+    layers, refs = [], []
+    for j, N in enumerate(Ns):
+        W = synth.normal_f32(seed + 10 * j, (N, K), 0.02)
+        layer = gpu.GpuLayer(W, bits, group)
+        codes, s0, z0 = oracle.quantize(W, bits, group)
+        ds = synth.normal_f32(seed + 10 * j + 1, s0.shape, 1e-3) if j % 2 == 0 else None
+        layers.append((layer, gpu.to_dev(ds) if ds is not None else None))
+        refs.append((codes, s0, ds, z0))
+    for T in (1, 5, 16, 40):
+        X = synth.normal_bf16(seed + 100 + T, (T, K), 1.0)
+        Xd = gpu.to_dev(X)
+        Ys = [torch.zeros((T, l.N), dtype=torch.int16, device="cuda") for l, _ in layers]
+        items = [(l.L, l.packed, l.s0, dsd, l.z0, Y) for (l, dsd), Y in zip(layers, Ys)]
+        nb = peqa.workspace_bytes_fused(items, T)
+        ws = torch.empty(max(nb, 16), dtype=torch.uint8, device="cuda")
+        peqa.linear_fwd_fused(items, Xd, T, ws, nb)
+        torch.cuda.synchronize()
+        for (codes, s0, ds, z0), Y in zip(refs, Ys):
+            Yref = oracle.fwd(codes, s0, ds, z0, X, group)
+            got = gpu.bf16_dev_to_f64(Y)
+            assert np.abs(got - Yref).max() <= Y_TOL * np.abs(Yref).max(), T
+
+
 def test_quantizer_edge_rows(gpu, oracle):
     """Degenerate, one-sided, tie-laden and outlier rows go through the same decisions."""
     N, K = 128, 256

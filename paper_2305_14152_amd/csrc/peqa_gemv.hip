@@ -50,12 +50,14 @@ __device__ __forceinline__ void gv_wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
-template <int BITS>
-__global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
+// GROUPS_MAX: most scale groups a workgroup may touch: 1 for per-channel layers (1 KB scale tile, three
+// workgroups per compute unit), GV_MAX_PER for group-wise ones (16 KB, two workgroups).
+template <int BITS, int GROUPS_MAX>
+__global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_kernel(GemvArgs a)
 {
     // [wave][2 rounds][6 KB]; reused as [wave][column tile][row][lane] fp32 (32 KB) for the final sum
     __shared__ __align__(16) uint8_t stage[GV_WAVES * 2 * GV_ROUND_BYTES];
-    __shared__ __align__(16) ScaleZero sz[GV_MAX_PER][128];      // [group of the slice][channel], 16 KB
+    __shared__ __align__(16) ScaleZero sz[GROUPS_MAX][128];      // [group of the slice][channel]
     constexpr int WPB = 2 * BITS;
     constexpr int NDMA_B = 2 * 64 * WPB * 4 / 1024;               // 1 KB DMAs for the blocks of a round: 4 / 3
     constexpr int NDMA = NDMA_B + 2;                              // + 2 for the token rows
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
     // scale / zero-point tile of the slice: [groups touched][128 channels].  All its loads are issued
     // together (indices clamped instead of branching, so that the compiler batches them behind a
     // single wait); that wait also covers the two rounds above, which every wave needs next anyway.
-    const int cols = rend > rbeg ? (int)((uint32_t)(rend - 1) / (uint32_t)chunk_rounds) - g_lo + 1 : 1;
+    const int cols = (GROUPS_MAX > 1 && rend > rbeg) ? (int)((uint32_t)(rend - 1) / (uint32_t)chunk_rounds) - g_lo + 1 : 1;
     auto load_tile = [&](auto nb_c) {
         constexpr int NB = decltype(nb_c)::value;                 // batches of 256 entries
         float ts[NB], td[NB];
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(GV_WAVES * 64, 2) void gemv_kernel(GemvArgs a)
         for (int i = 0; i < NB; ++i)
             if (tid + i * GV_WAVES * 64 < 128 * cols) sz[jj[i]][ch[i]] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i]};
     };
-    if (cols <= 2) load_tile(std::integral_constant<int, 1>{});
+    if (GROUPS_MAX == 1 || cols <= 2) load_tile(std::integral_constant<int, 1>{});
     else if (cols <= 4) load_tile(std::integral_constant<int, 2>{});
     else if (cols <= 8) load_tile(std::integral_constant<int, 4>{});
     else load_tile(std::integral_constant<int, 8>{});
@@ -279,10 +281,11 @@ __global__ __launch_bounds__(256) void gemv_finish_kernel(GemvArgs a)
 
 int gemv_slices(int Ntot, int K, int T, int chunk)
 {
-    // as many slices as keep every workgroup resident at once (2 per compute unit), every wave at
-    // least two rounds long, and the partials small next to the weight bytes
+    // as many slices as keep every workgroup resident at once (3 per compute unit for per-channel
+    // layers, 2 for group-wise ones), every wave at least two rounds long, and the partials small
+    // next to the weight bytes
     const int tiles = Ntot / 128, R = K / 64, chunk_rounds = chunk / 64;
-    int S = 512 / tiles;
+    int S = (chunk == K ? 768 : 512) / tiles;
     if (S > R / (2 * GV_WAVES)) S = R / (2 * GV_WAVES);
     const int by_bytes = T > 4 ? 6 : 16;
     if (S > by_bytes) S = by_bytes;
@@ -297,8 +300,14 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
     trace_before(KID_GEMV, stream);
     const int tiles = a.layer[a.n_layers - 1].tile_end;
     const dim3 grid(tiles, a.S);
-    if (bits == 4) hipLaunchKernelGGL(gemv_kernel<4>, grid, dim3(GV_WAVES * 64), 0, stream, a);
-    else hipLaunchKernelGGL(gemv_kernel<3>, grid, dim3(GV_WAVES * 64), 0, stream, a);
+    const bool per_channel = a.chunk == a.K;
+    if (bits == 4) {
+        if (per_channel) hipLaunchKernelGGL((gemv_kernel<4, 1>), grid, dim3(GV_WAVES * 64), 0, stream, a);
+        else hipLaunchKernelGGL((gemv_kernel<4, GV_MAX_PER>), grid, dim3(GV_WAVES * 64), 0, stream, a);
+    } else {
+        if (per_channel) hipLaunchKernelGGL((gemv_kernel<3, 1>), grid, dim3(GV_WAVES * 64), 0, stream, a);
+        else hipLaunchKernelGGL((gemv_kernel<3, GV_MAX_PER>), grid, dim3(GV_WAVES * 64), 0, stream, a);
+    }
     trace_after(KID_GEMV, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.S == 1) return e;

@@ -169,6 +169,34 @@ def test_fused_forward_parity(gpu, oracle, bits, Ns, K, group):
             assert np.abs(got - Yref).max() <= Y_TOL * np.abs(Yref).max(), T
 
 
+@pytest.mark.parametrize("bits,group", [(4, 0), (3, 0), (4, 128), (3, 64)])
+def test_zero_and_negative_scales(gpu, oracle, bits, group):
+    """The trained scale s0 + ds may reach zero or change sign: Y and dX follow it linearly, the scale
+    gradient does not depend on it.  Token counts that are exact tile multiples, and both forward paths."""
+    N, K = 256, 512
+    seed = 15000 + bits * 100 + group
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, group)
+    ds = (-s0).copy()
+    ds[N // 2:] = -2.5 * s0[N // 2:]            # first half of the channels: s = 0; second half: negative
+    for T in (8, 128, 256):
+        X = synth.normal_bf16(seed + T, (T, K), 1.0)
+        dY = synth.normal_bf16(seed + T + 1, (T, N), 1.0)
+        Y = gpu.bf16_dev_to_f64(layer.fwd(X, ds))
+        Yref = oracle.fwd(codes, s0, ds, z0, X, group)
+        assert (Y[:, :N // 2] == 0).all()
+        assert np.abs(Y - Yref).max() <= Y_TOL * np.abs(Yref).max()
+        if T > 16:
+            dX, dds = layer.bwd(X, dY, ds)
+            dXref, gref, _ = oracle.bwd(codes, s0, ds, z0, X, dY, group)
+            assert np.abs(gpu.bf16_dev_to_f64(dX) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+            g = gpu.to_host(dds).astype(np.float64)
+            assert np.linalg.norm(g - gref) <= G_TOL * np.linalg.norm(gref)
+            _, dds0 = layer.bwd(X, dY, None, want_dX=False)
+            assert (gpu.to_host(dds0) == gpu.to_host(dds)).all()      # independent of the scale
+
+
 def test_quantizer_edge_rows(gpu, oracle):
     """Degenerate, one-sided, tie-laden and outlier rows go through the same decisions."""
     N, K = 128, 256

@@ -85,6 +85,7 @@ peqa_status gemv_forward(int n, const peqa_fwd_item *items, const uint16_t *X, i
             g.layer[j] = g.layer[n - 1];                   // never selected: its tile_end is the total
         }
     }
+    if ((uint64_t)T * (uint64_t)tiles * 128u >= ((uint64_t)1 << 31)) return PEQA_ERR_SHAPE;   // 32-bit indexing in there
     g.n_layers = n;
     g.X = X; g.partial = partial;
     g.K = L->k_in; g.G = groups(L); g.T = T;

@@ -261,11 +261,12 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
 // layers goes to its own layer's Y.
 __global__ __launch_bounds__(256) void gemv_finish_kernel(GemvArgs a)
 {
-    const int ntot = a.layer[a.n_layers - 1].tile_end * 128;
-    const size_t tn = (size_t)a.T * ntot;
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    // T <= 16 and at most 2^24 channels: everything fits 32-bit arithmetic
+    const uint32_t ntot = (uint32_t)a.layer[a.n_layers - 1].tile_end * 128u;
+    const uint32_t tn = (uint32_t)a.T * ntot;
+    const uint32_t e = blockIdx.x * 256u + threadIdx.x;
     if (e >= tn) return;
-    const int t = (int)(e / ntot), n = (int)(e - (size_t)t * ntot);
+    const int t = (int)(e / ntot), n = (int)(e - (uint32_t)t * ntot);
     float v = 0.f;
     for (int sl = 0; sl < a.S; ++sl) v += a.partial[(size_t)sl * tn + e];
     const int tile = n >> 7;
@@ -281,11 +282,11 @@ __global__ __launch_bounds__(256) void gemv_finish_kernel(GemvArgs a)
 
 int gemv_slices(int Ntot, int K, int T, int chunk)
 {
-    // as many slices as keep every workgroup resident at once (3 per compute unit for per-channel
-    // layers, 2 for group-wise ones), every wave at least two rounds long, and the partials small
-    // next to the weight bytes
+    // as many slices as give two workgroups per compute unit (measured: more, up to the three that fit
+    // for per-channel layers, only adds partials), every wave at least two rounds long, and the
+    // partials small next to the weight bytes
     const int tiles = Ntot / 128, R = K / 64, chunk_rounds = chunk / 64;
-    int S = (chunk == K ? 768 : 512) / tiles;
+    int S = 512 / tiles;
     if (S > R / (2 * GV_WAVES)) S = R / (2 * GV_WAVES);
     const int by_bytes = T > 4 ? 6 : 16;
     if (S > by_bytes) S = by_bytes;
@@ -300,7 +301,10 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
     trace_before(KID_GEMV, stream);
     const int tiles = a.layer[a.n_layers - 1].tile_end;
     const dim3 grid(tiles, a.S);
-    const bool per_channel = a.chunk == a.K;
+    // Per-channel layers fit three workgroups per compute unit (1 KB scale tile).  That pays only when
+    // there are more workgroups than two per unit: below, the dispatcher would stack three on some
+    // units and leave others with one, so such launches take the 16 KB instantiation (two per unit).
+    const bool per_channel = a.chunk == a.K && tiles * a.S > 512;
     if (bits == 4) {
         if (per_channel) hipLaunchKernelGGL((gemv_kernel<4, 1>), grid, dim3(GV_WAVES * 64), 0, stream, a);
         else hipLaunchKernelGGL((gemv_kernel<4, GV_MAX_PER>), grid, dim3(GV_WAVES * 64), 0, stream, a);

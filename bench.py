@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--config", type=int, default=1, help="workload index (see synth.CONFIGS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-small-batch", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch the forward and backward calls one by one instead of replaying a HIP graph of them")
     ap.add_argument("--serial-backward", action="store_true",
                     help="keep the backward on one stream (for per-kernel profiles; the library otherwise runs "
                          "the scale-gradient chain beside the dX chain)")
@@ -215,12 +217,22 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     step_no = [0]
 
-    def step():
-        step_no[0] += 1
+    def fwd_bwd(st):
         for l in layers:
-            peqa.linear_fwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, T, l.Y, ws, ws_bytes, stream)
+            peqa.linear_fwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, T, l.Y, ws, ws_bytes, st)
         for l in reversed(layers):
-            peqa.linear_bwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, l.dY, T, l.dX, l.dds, ws, ws_bytes, stream)
+            peqa.linear_bwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, l.dY, T, l.dX, l.dds, ws, ws_bytes, st)
+
+    graph = [None]
+
+    def step(use_graph=True):
+        # forward and backward of the 7 layers (one HIP graph, replayed, unless --no-graph), then the
+        # 7 scale updates, which carry the step number and are launched directly
+        step_no[0] += 1
+        if graph[0] is not None and use_graph:
+            graph[0].replay()
+        else:
+            fwd_bwd(stream)
         for l in layers:
             peqa.scale_update(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0, lr=1e-5, step=step_no[0], stream=stream)
 
@@ -232,6 +244,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    step()                                       # first calls create the library's second stream: before any capture
+    torch.cuda.synchronize()
+    if not args.no_graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+            fwd_bwd(torch.cuda.current_stream().cuda_stream)
+        graph[0] = g
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -248,7 +267,7 @@ def main():
     launches_per_step = len(layers) * 8
     peqa.trace_begin(launches_per_step * args.steps + 16)
     for _ in range(args.steps):
-        step()
+        step(use_graph=False)
     torch.cuda.synchronize()
     trace = peqa.trace_end(16)
     gemm_flops = {"gemm_y": 0.0, "gemm_dds": 0.0, "gemm_dx": 0.0}
@@ -286,6 +305,7 @@ def main():
         "tokens_per_s": round(T / (dt / args.steps), 1),
         "flops_per_step": flops_step,
         "quantize_ms_total": round(sum(l.quantize_ms for l in layers), 3),
+        "launch": "eager" if args.no_graph else "hip graph of the 14 forward/backward calls + 7 direct scale updates",
         "kernels": kernels,
         "roofline": roofline,
     }

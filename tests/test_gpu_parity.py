@@ -197,6 +197,42 @@ def test_zero_and_negative_scales(gpu, oracle, bits, group):
             assert (gpu.to_host(dds0) == gpu.to_host(dds)).all()      # independent of the scale
 
 
+def test_graph_capture_replays_match_eager(gpu, oracle):
+    """Forward + backward captured in a HIP graph (the backward forks onto the library's second
+    stream inside the capture): several replays, with eager work and synchronisation between them,
+    all equal to the eager results."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    N, K, T = 384, 512, 200
+    W = synth.normal_f32(77, (N, K), 0.02)
+    layer = gpu.GpuLayer(W, 4, 0)
+    X = gpu.to_dev(synth.normal_bf16(78, (T, K), 1.0))
+    dY = gpu.to_dev(synth.normal_bf16(79, (T, N), 1.0))
+    Y = torch.zeros((T, N), dtype=torch.int16, device="cuda")
+    dX = torch.zeros((T, K), dtype=torch.int16, device="cuda")
+    dds = torch.zeros((N, 1), dtype=torch.float32, device="cuda")
+    nb = max(peqa.workspace_bytes(layer.L, T, peqa.PEQA_OP_FWD), peqa.workspace_bytes(layer.L, T, peqa.PEQA_OP_BWD))
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+
+    def run(stream):
+        peqa.linear_fwd(layer.L, layer.packed, layer.s0, None, layer.z0, X, T, Y, ws, nb, stream)
+        peqa.linear_bwd(layer.L, layer.packed, layer.s0, None, layer.z0, X, dY, T, dX, dds, ws, nb, stream)
+
+    run(torch.cuda.current_stream().cuda_stream)      # eager (also creates the library's stream before capture)
+    torch.cuda.synchronize()
+    want = (Y.clone(), dX.clone(), dds.clone())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        run(torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        for t in (Y, dX, dds):
+            t.fill_(7)                                # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert (Y == want[0]).all() and (dX == want[1]).all() and (dds == want[2]).all(), rep
+
+
 def test_quantizer_edge_rows(gpu, oracle):
     """Degenerate, one-sided, tie-laden and outlier rows go through the same decisions."""
     N, K = 128, 256

@@ -75,6 +75,19 @@ class Layer:
         self.ws_bwd = peqa.workspace_bytes(self.L, T, peqa.PEQA_OP_BWD)
 
 
+def shared_input_groups(cfg):
+    """Indices of the block's layers grouped by the input they read: the first three of a run of four
+    equal layers are q, k, v (the fourth, o, reads the attention output); a run of two is gate, up."""
+    groups, i = [], 0
+    for (_, _, count) in cfg["layers"]:
+        fuse = count - 1 if count == 4 else count
+        groups.append(list(range(i, i + fuse)))
+        if fuse != count:
+            groups.append([i + fuse])
+        i += count
+    return groups
+
+
 def small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream, reps=20):
     """Forward of the block at T = 1 and T = 16 through the matrix-vector path.  Algorithmic bytes per
     layer: packed codes + s0, ds (fp32) and z0 (uint8) per scale + X and Y (bf16).  `wall` is the
@@ -117,13 +130,7 @@ def small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream, reps=20):
         main_us = tr["gemv"][1] * 1e3 / (reps * nsets)
         # the same block with the layers that read one X fused into one call each:
         # (q, k, v), o, (gate, up), down -- 4 calls instead of 7
-        groups, i = [], 0
-        for (_, _, count) in cfg["layers"]:
-            fuse = count - 1 if count == 4 else count          # q, k, v together; o reads another input
-            groups.append(list(range(i, i + fuse)))
-            if fuse != count:
-                groups.append([i + fuse])
-            i += count
+        groups = shared_input_groups(cfg)
         need_f = max(peqa.workspace_bytes_fused([(layers[j].L, layers[j].packed, layers[j].s0, layers[j].ds,
                                                   layers[j].z0, layers[j].Y) for j in grp], T) for grp in groups)
         assert need_f <= ws_bytes
@@ -212,14 +219,20 @@ def main():
             layers.append(Layer(torch, peqa, N, K, bits, group, T, synth.seed_for(args.config, li, 0),
                                 cfg["w_std"], cfg["dy_std"]))
             li += 1
+    # layers that read one input in a decoder block: (q, k, v), o, (gate, up), down
+    groups = shared_input_groups(cfg)
+    for grp in groups:
+        for j in grp[1:]:
+            layers[j].X = layers[grp[0]].X
     ws_bytes = max(max(l.ws_fwd, l.ws_bwd) for l in layers)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     step_no = [0]
 
     def fwd_bwd(st):
-        for l in layers:
-            peqa.linear_fwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, T, l.Y, ws, ws_bytes, st)
+        for grp in groups:                       # one forward call per shared input (row sums of X taken once)
+            items = [(layers[j].L, layers[j].packed, layers[j].s0, layers[j].ds, layers[j].z0, layers[j].Y) for j in grp]
+            peqa.linear_fwd_fused(items, layers[grp[0]].X, T, ws, ws_bytes, st)
         for l in reversed(layers):
             peqa.linear_bwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, l.dY, T, l.dX, l.dds, ws, ws_bytes, st)
 
@@ -305,7 +318,9 @@ def main():
         "tokens_per_s": round(T / (dt / args.steps), 1),
         "flops_per_step": flops_step,
         "quantize_ms_total": round(sum(l.quantize_ms for l in layers), 3),
-        "launch": "eager" if args.no_graph else "hip graph of the 14 forward/backward calls + 7 direct scale updates",
+        "launch": ("eager: " if args.no_graph else "hip graph of: ") +
+                  "%d forward calls (layers sharing an input in one peqa_linear_fwd_fused), %d backward calls; "
+                  "then %d direct scale updates" % (len(groups), len(layers), len(layers)),
         "kernels": kernels,
         "roofline": roofline,
     }

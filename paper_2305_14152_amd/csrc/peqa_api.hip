@@ -95,6 +95,8 @@ peqa_status gemv_forward(int n, const peqa_fwd_item *items, const uint16_t *X, i
 }
 
 bool trace_active();
+peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, const float *rs, hipStream_t s);
 
 // The two halves of the backward (scale gradient; dX) are independent.  When both are wanted, the
 // scale-gradient chain runs on a second stream of the library's own, forked from and joined back
@@ -248,15 +250,27 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
         return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
     }
     float *rs = reinterpret_cast<float *>(ws + w.rs);
+    if (peqa::launch_rowsum(X, T, K, ksplit, rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    return fwd_per_channel(L, packed, s0, ds, z0, X, T, Y, rs, s);
+}
 
-    hipError_t e = peqa::launch_rowsum(X, T, K, ksplit, rs, s);
-    if (e != hipSuccess) return PEQA_ERR_DEVICE;
+}  // extern "C"
+
+namespace {
+// Per-channel forward contraction for T > 16, the row sums of X already in `rs`.
+peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, const float *rs, hipStream_t s)
+{
+    const int N = L->n_out, K = L->k_in;
     peqa::GemmArgs a{};
-    a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
+    a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
     a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
     a.s0 = s0; a.ds = ds; a.z0 = z0; a.rs = rs; a.out = Y;
     return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
 }
+}  // namespace
+
+extern "C" {
 
 // Forward of several layers that read the same X.
 static peqa_status check_fused(int32_t n, const peqa_fwd_item *items, int32_t T)
@@ -309,7 +323,20 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
     if (T <= PEQA_GEMV_MAX_T)
         return gemv_forward(n, items, X, T, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
-    for (int j = 0; j < n; ++j) {                          // the tiled contraction runs the layers one by one
+    // the tiled contraction runs the layers one by one; per-channel layers share the row sums of X
+    if (!grouped(&items[0].layout)) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        float *rs = static_cast<float *>(workspace);       // carve() puts the row sums first
+        if (peqa::launch_rowsum(X, T, items[0].layout.k_in, split_point(items[0].layout.k_in), rs, s) != hipSuccess)
+            return PEQA_ERR_DEVICE;
+        for (int j = 0; j < n; ++j) {
+            const peqa_fwd_item &it = items[j];
+            st = fwd_per_channel(&it.layout, it.packed, it.s0, it.ds, it.z0, X, T, it.Y, rs, s);
+            if (st != PEQA_OK) return st;
+        }
+        return PEQA_OK;
+    }
+    for (int j = 0; j < n; ++j) {
         const peqa_fwd_item &it = items[j];
         st = peqa_linear_fwd(&it.layout, it.packed, it.s0, it.ds, it.z0, X, T, it.Y, workspace, workspace_bytes, stream);
         if (st != PEQA_OK) return st;

@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--config", type=int, default=1, help="workload index (see synth.CONFIGS)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-small-batch", action="store_true")
+    ap.add_argument("--no-kept-product", action="store_true",
+                    help="skip the secondary timing of the variant that keeps the forward's product")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch the forward and backward calls one by one instead of replaying a HIP graph of them")
     ap.add_argument("--serial-backward", action="store_true",
@@ -163,6 +165,40 @@ def small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream, reps=20):
             "frac_of_hbm_peak_wall": round(bytes_block / wall_us / 1e3 / HBM_PEAK_GBS, 4),
         }
     return out
+
+
+def kept_product(torch, peqa, layers, cfg, stream, steps):
+    """The optional variant that keeps P = X (Q - z0)^T from the forward (per-channel layers): the same
+    block step with peqa_linear_fwd_keep / peqa_linear_bwd_kept, which does 4 T N K flops per layer."""
+    T = cfg["T"]
+    fb = max(peqa.workspace_bytes(l.L, T, peqa.PEQA_OP_FWD_KEEP) for l in layers)
+    bb = max(peqa.workspace_bytes(l.L, T, peqa.PEQA_OP_BWD_KEPT) for l in layers)
+    nb = max(fb, bb)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    Ps = [torch.empty((T, l.N), dtype=torch.float32, device="cuda") for l in layers]
+
+    def step(i):
+        for l, P in zip(layers, Ps):
+            peqa.linear_fwd_keep(l.L, l.packed, l.s0, l.ds, l.z0, l.X, T, l.Y, P, ws, nb, stream)
+        for l, P in zip(reversed(layers), reversed(Ps)):
+            peqa.linear_bwd_kept(l.L, l.packed, l.s0, l.ds, l.z0, P, l.dY, T, l.dX, l.dds, ws, nb, stream)
+        for l in layers:
+            peqa.scale_update(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0, lr=1e-5, step=i, stream=stream)
+
+    for i in range(3):
+        step(1000 + i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(2000 + i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    flops = sum(4.0 * T * l.N * l.K for l in layers)
+    return {"what": "same block step with the forward keeping fp32 P (4 T N bytes per layer) and the scale "
+                    "gradient taken from it: 4 T N K flops per layer instead of 6 T N K; eager launches",
+            "ms_per_step": round(dt * 1e3, 4), "tokens_per_s": round(T / dt, 1),
+            "tflops_counted_4TNK": round(flops / dt / 1e12, 2),
+            "kept_bytes": int(sum(P.numel() * 4 for P in Ps))}
 
 
 def cpu_baseline(cfg, seconds):
@@ -306,6 +342,10 @@ def main():
 
     small = small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream) if not args.no_small_batch else None
 
+    kept = None
+    if not args.no_kept_product and not group:
+        kept = kept_product(torch, peqa, layers, cfg, stream, min(args.steps, 10))
+
     out = {
         "metric": "PEQA quantized-linear fwd+bwd TFLOP/s, LLaMA-7B shapes T=2048" if args.config == 1
                   else "PEQA quantized-linear fwd+bwd TFLOP/s, %s" % cfg["name"],
@@ -326,6 +366,8 @@ def main():
     }
     if small is not None:
         out["small_batch"] = small
+    if kept is not None:
+        out["kept_product_variant"] = kept
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_seconds)
         out["cpu_baseline"].pop("tokens_per_s_block_extrapolated")

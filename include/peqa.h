@@ -56,7 +56,12 @@ typedef struct {
     int32_t group_size; /* 0 = one (s, z) per channel; else g with g % 64 == 0, K % g == 0   */
 } peqa_layout;
 
-typedef enum { PEQA_OP_FWD = 0, PEQA_OP_BWD = 1 } peqa_op;
+typedef enum {
+    PEQA_OP_FWD = 0,      /* peqa_linear_fwd        */
+    PEQA_OP_BWD = 1,      /* peqa_linear_bwd        */
+    PEQA_OP_FWD_KEEP = 2, /* peqa_linear_fwd_keep   */
+    PEQA_OP_BWD_KEPT = 3  /* peqa_linear_bwd_kept   */
+} peqa_op;
 
 /* Host-only helpers (no device access). */
 peqa_status peqa_check_layout(const peqa_layout *L);
@@ -146,6 +151,27 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
                             const float *ds, const uint8_t *z0, const uint16_t *X,
                             const uint16_t *dY, int32_t T, uint16_t *dX, float *d_ds,
                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Optional trade of activation memory for arithmetic, per-channel layers only (PEQA_ERR_GROUP for
+ * group-wise ones).  In the scale gradient of Eq. 2,  d_ds[i] = sum_t dY[t,i] * P[t,i]  with
+ *   P[t,i] = sum_k X[t,k] * (Q[i,k] - z0[i]),
+ * and Y[t,i] = (s0+ds)[i] * P[t,i]: the forward already forms P.  peqa_linear_fwd_keep writes it
+ * (fp32, [T, N], caller-owned: 4 T N bytes per layer, against the memory motive of Sec. 3.1) next to
+ * the same Y as peqa_linear_fwd; peqa_linear_bwd_kept then takes d_ds from dY and P with one pass
+ * over both instead of the contraction over X, so that forward + backward cost 4 T N K flops, not
+ * 6 T N K.  dX, NULL arguments and determinism as in peqa_linear_bwd; P may be NULL when d_ds is.
+ *   any T >= 1 (the forward always runs the tiled contraction);
+ *   workspace: peqa_workspace_bytes(L, T, PEQA_OP_FWD_KEEP / PEQA_OP_BWD_KEPT).
+ */
+peqa_status peqa_linear_fwd_keep(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                                 const float *ds, const uint8_t *z0, const uint16_t *X, int32_t T,
+                                 uint16_t *Y, float *P, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                                 const float *ds, const uint8_t *z0, const float *P,
+                                 const uint16_t *dY, int32_t T, uint16_t *dX, float *d_ds,
+                                 void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * One AdamW step on ds (Appendix A names AdamW with a linearly decaying learning rate;

@@ -41,6 +41,19 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
     const size_t N = (size_t)L->n_out, G = (size_t)groups(L);
     const size_t tiles_t = ((size_t)T + 127) / 128;
     size_t off = 0;
+    if (op == PEQA_OP_FWD_KEEP || op == PEQA_OP_BWD_KEPT) {
+        // per-channel only; the forward always takes the tiled contraction (it writes P from its epilogue)
+        if (op == PEQA_OP_FWD_KEEP) {
+            w.rs = off;      off += round256((size_t)T * 2 * sizeof(float));
+        } else {
+            const size_t slices = ((size_t)T + peqa::KEPT_ROWS - 1) / peqa::KEPT_ROWS;
+            w.dys = off;     off += round256((size_t)T * N * sizeof(uint16_t));
+            w.crow = off;    off += round256((size_t)T * sizeof(float));
+            w.partial = off; off += round256(slices * N * sizeof(float));
+        }
+        w.total = off;
+        return w;
+    }
     if (op == PEQA_OP_FWD && T <= PEQA_GEMV_MAX_T) {
         w.partial = off; off += gemv_partial_bytes(L, L->n_out, T);
         w.total = off;
@@ -96,7 +109,8 @@ peqa_status gemv_forward(int n, const peqa_fwd_item *items, const uint16_t *X, i
 
 bool trace_active();
 peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
-                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, const float *rs, hipStream_t s);
+                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, float *P, const float *rs,
+                            hipStream_t s);
 
 // The two halves of the backward (scale gradient; dX) are independent.  When both are wanted, the
 // scale-gradient chain runs on a second stream of the library's own, forked from and joined back
@@ -162,7 +176,11 @@ size_t peqa_num_scales(const peqa_layout *L)
 size_t peqa_workspace_bytes(const peqa_layout *L, int32_t T, int32_t op)
 {
     if (peqa_check_layout(L) != PEQA_OK || T < 1) return 0;
-    if (op != PEQA_OP_FWD && op != PEQA_OP_BWD) return 0;
+    if (op == PEQA_OP_FWD_KEEP || op == PEQA_OP_BWD_KEPT) {
+        if (grouped(L)) return 0;
+    } else if (op != PEQA_OP_FWD && op != PEQA_OP_BWD) {
+        return 0;
+    }
     return carve(L, T, op).total;
 }
 
@@ -251,7 +269,28 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     }
     float *rs = reinterpret_cast<float *>(ws + w.rs);
     if (peqa::launch_rowsum(X, T, K, ksplit, rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
-    return fwd_per_channel(L, packed, s0, ds, z0, X, T, Y, rs, s);
+    return fwd_per_channel(L, packed, s0, ds, z0, X, T, Y, nullptr, rs, s);
+}
+
+peqa_status peqa_linear_fwd_keep(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                                 const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, float *P,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (grouped(L)) return PEQA_ERR_GROUP;
+    if (!packed || !s0 || !z0 || !X || !Y || !P) return PEQA_ERR_NULL;
+    if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(s0) || !aligned16(z0) || !aligned16(X) || !aligned16(Y) || !aligned16(P) ||
+        (ds && !aligned16(ds)))
+        return PEQA_ERR_ALIGN;
+    const Workspace w = carve(L, T, PEQA_OP_FWD_KEEP);
+    if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *rs = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + w.rs);
+    if (peqa::launch_rowsum(X, T, L->k_in, split_point(L->k_in), rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    return fwd_per_channel(L, packed, s0, ds, z0, X, T, Y, P, rs, s);
 }
 
 }  // extern "C"
@@ -259,13 +298,14 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
 namespace {
 // Per-channel forward contraction for T > 16, the row sums of X already in `rs`.
 peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
-                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, const float *rs, hipStream_t s)
+                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, float *P, const float *rs,
+                            hipStream_t s)
 {
     const int N = L->n_out, K = L->k_in;
     peqa::GemmArgs a{};
     a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
     a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
-    a.s0 = s0; a.ds = ds; a.z0 = z0; a.rs = rs; a.out = Y;
+    a.s0 = s0; a.ds = ds; a.z0 = z0; a.rs = rs; a.out = Y; a.P = P;
     return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
 }
 }  // namespace
@@ -331,7 +371,7 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
             return PEQA_ERR_DEVICE;
         for (int j = 0; j < n; ++j) {
             const peqa_fwd_item &it = items[j];
-            st = fwd_per_channel(&it.layout, it.packed, it.s0, it.ds, it.z0, X, T, it.Y, rs, s);
+            st = fwd_per_channel(&it.layout, it.packed, it.s0, it.ds, it.z0, X, T, it.Y, nullptr, rs, s);
             if (st != PEQA_OK) return st;
         }
         return PEQA_OK;
@@ -425,6 +465,45 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
     return PEQA_OK;
 }
 
+peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                                 const uint8_t *z0, const float *P, const uint16_t *dY, int32_t T, uint16_t *dX,
+                                 float *d_ds, void *workspace, size_t workspace_bytes, void *stream)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (grouped(L)) return PEQA_ERR_GROUP;
+    if (!packed || !s0 || !z0 || !dY) return PEQA_ERR_NULL;
+    if (d_ds && !P) return PEQA_ERR_NULL;
+    if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(s0) || !aligned16(z0) || !aligned16(dY) || (P && !aligned16(P)) ||
+        (ds && !aligned16(ds)) || (dX && !aligned16(dX)) || (d_ds && !aligned16(d_ds)))
+        return PEQA_ERR_ALIGN;
+    const Workspace w = carve(L, T, PEQA_OP_BWD_KEPT);
+    if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const int N = L->n_out, K = L->k_in;
+    if (d_ds) {
+        float *partial = reinterpret_cast<float *>(ws + w.partial);
+        const int slices = (T + peqa::KEPT_ROWS - 1) / peqa::KEPT_ROWS;
+        if (peqa::launch_dds_kept(dY, P, T, N, partial, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_reduce_partials(partial, slices, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    }
+    if (dX) {
+        uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
+        float *crow = reinterpret_cast<float *>(ws + w.crow);
+        if (peqa::launch_scale_dy(dY, s0, ds, z0, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        peqa::GemmArgs a{};
+        a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
+        a.tiles_c = (K + 255) / 256; a.tiles_t = (T + 127) / 128;
+        a.crow = crow; a.out = dX;
+        if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    }
+    return PEQA_OK;
+}
+
 peqa_status peqa_scale_update(size_t n_scales, float *ds, const float *d_ds, float *m, float *v, const float *s0,
                               const peqa_adamw *opt, void *stream)
 {
@@ -457,7 +536,7 @@ struct TraceState {
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
-    "gemv_finish", "group_table"};
+    "gemv_finish", "group_table", "dds_kept"};
 
 }  // namespace
 namespace {

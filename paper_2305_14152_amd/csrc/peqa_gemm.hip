@@ -539,7 +539,14 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                             for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j];
                         } else if constexpr (MODE == MODE_Y) {
 #pragma unroll
-                            for (int ct = 0; ct < 8; ++ct) v[ct] = ep_sc[ct] * (sum[ct][j] - ep_zoff[ct] * r);
+                            for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - ep_zoff[ct] * r;
+                            if (a.P) {                     // keep the unscaled product for the backward
+                                f32x4 *dst = reinterpret_cast<f32x4 *>(a.P + (size_t)t * a.C + col0 + 8 * c);
+                                dst[0] = f32x4{v[0], v[1], v[2], v[3]};
+                                dst[1] = f32x4{v[4], v[5], v[6], v[7]};
+                            }
+#pragma unroll
+                            for (int ct = 0; ct < 8; ++ct) v[ct] *= ep_sc[ct];
                         } else {
 #pragma unroll
                             for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - r;

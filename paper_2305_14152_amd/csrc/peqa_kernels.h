@@ -28,6 +28,7 @@ struct GemmArgs {
     const uint16_t *dY;       // [T, N] bf16    (MODE_DDS)
     float *partial;           // [tiles_t, N]   (MODE_DDS) per-token-tile column sums
     uint16_t *out;            // [T, C] bf16    (MODE_Y: Y, MODE_DX: dX)
+    float *P;                 // [T, N] fp32 or NULL (MODE_Y, per-channel): sum_k X[t,k] (Q[i,k] - z0[i]), kept
     // group-wise layers (gsz > 0; a multiple of 128):
     int N;                    // output channels of the layer
     int gsz, G;               // group size and groups per channel
@@ -68,6 +69,8 @@ hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds,
 hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float *rsg, hipStream_t stream);
 hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, int N, int G, float *sb,
                               hipStream_t stream);
+constexpr int KEPT_ROWS = 64;   // token rows per partial of launch_dds_kept
+hipError_t launch_dds_kept(const uint16_t *dY, const float *P, int T, int N, float *partial, hipStream_t stream);
 hipError_t launch_reduce_partials(const float *partial, int ntiles, size_t n, float *out, hipStream_t stream);
 hipError_t launch_adamw(size_t n, float *ds, const float *g, float *m, float *v, const float *s0,
                         float lr, float b1, float b2, float eps, float wd, float inv_c1, float inv_c2,
@@ -83,7 +86,7 @@ void trace_after(int kernel_id, hipStream_t stream);
 
 enum {
     KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
-    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_COUNT
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_COUNT
 };
 
 }  // namespace peqa

@@ -125,6 +125,39 @@ __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restric
     if (tid == 0) crow[t] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
+// Scale gradient from the product P[t,i] = sum_k X[t,k] (Q[i,k] - z0[i]) that the forward kept:
+// partial[slice, i] = sum of dY[t,i] P[t,i] over the KEPT_ROWS token rows of the slice.  A workgroup
+// takes 256 channels (4 per lane) of one slice; wave w adds rows w, w+4, ... in order and the four
+// wave sums meet in LDS in a fixed order.
+__global__ __launch_bounds__(256) void dds_kept_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ P,
+                                                        int T, int N, float *__restrict__ partial)
+{
+    __shared__ f32x4 part[4][64];
+    const int q = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int col = blockIdx.y * 256 + 4 * q;
+    const int tbeg = blockIdx.x * KEPT_ROWS;
+    const int nrows = min(KEPT_ROWS, T - tbeg);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (col < N) {
+        const size_t base = (size_t)tbeg * N + col;
+#pragma unroll 4
+        for (int r = w; r < nrows; r += 4) {
+            const u32x2 d = *reinterpret_cast<const u32x2 *>(dY + base + (size_t)r * N);
+            const f32x4 p = *reinterpret_cast<const f32x4 *>(P + base + (size_t)r * N);
+            acc[0] += bf16_lo(d[0]) * p[0];
+            acc[1] += bf16_hi(d[0]) * p[1];
+            acc[2] += bf16_lo(d[1]) * p[2];
+            acc[3] += bf16_hi(d[1]) * p[3];
+        }
+    }
+    part[w][q] = acc;
+    __syncthreads();
+    if (w == 0 && col < N) {
+        const f32x4 s = ((part[0][q] + part[1][q]) + part[2][q]) + part[3][q];
+        *reinterpret_cast<f32x4 *>(partial + (size_t)blockIdx.x * N + col) = s;
+    }
+}
+
 // out[j] = partial[0][j] + partial[1][j] + ... in that order (deterministic).
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial, int ntiles, size_t n,
                                                                float *__restrict__ out)
@@ -187,6 +220,15 @@ hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds,
     trace_before(KID_SCALE_DY, stream);
     hipLaunchKernelGGL(scale_dy_kernel, dim3(T), dim3(256), 0, stream, dY, s0, ds, z0, N, dYs, crow);
     trace_after(KID_SCALE_DY, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_dds_kept(const uint16_t *dY, const float *P, int T, int N, float *partial, hipStream_t stream)
+{
+    trace_before(KID_DDS_KEPT, stream);
+    hipLaunchKernelGGL(dds_kept_kernel, dim3((T + KEPT_ROWS - 1) / KEPT_ROWS, (N + 255) / 256), dim3(256), 0, stream,
+                       dY, P, T, N, partial);
+    trace_after(KID_DDS_KEPT, stream);
     return hipGetLastError();
 }
 

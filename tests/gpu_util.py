@@ -78,6 +78,31 @@ class GpuLayer:
         return dX, dds
 
 
+    def fwd_keep(self, X_bits, ds=None):
+        torch, peqa = self.torch, self.peqa
+        X = to_dev(X_bits) if isinstance(X_bits, np.ndarray) else X_bits
+        T = X.shape[0]
+        Y = torch.empty((T, self.N), dtype=torch.int16, device="cuda")
+        P = torch.empty((T, self.N), dtype=torch.float32, device="cuda")
+        dsd = to_dev(np.ascontiguousarray(ds, np.float32)) if isinstance(ds, np.ndarray) else ds
+        ws, nb = self.workspace(T, peqa.PEQA_OP_FWD_KEEP)
+        peqa.linear_fwd_keep(self.L, self.packed, self.s0, dsd, self.z0, X, T, Y, P, ws, nb)
+        torch.cuda.synchronize()
+        return Y, P
+
+    def bwd_kept(self, P, dY_bits, ds=None, want_dX=True, want_dds=True):
+        torch, peqa = self.torch, self.peqa
+        dY = to_dev(dY_bits) if isinstance(dY_bits, np.ndarray) else dY_bits
+        T = dY.shape[0]
+        dX = torch.empty((T, self.K), dtype=torch.int16, device="cuda") if want_dX else None
+        dds = torch.empty((self.N, self.G), dtype=torch.float32, device="cuda") if want_dds else None
+        dsd = to_dev(np.ascontiguousarray(ds, np.float32)) if isinstance(ds, np.ndarray) else ds
+        ws, nb = self.workspace(T, peqa.PEQA_OP_BWD_KEPT)
+        peqa.linear_bwd_kept(self.L, self.packed, self.s0, dsd, self.z0, P, dY, T, dX, dds, ws, nb)
+        torch.cuda.synchronize()
+        return dX, dds
+
+
 def bf16_dev_to_f64(t):
     from paper_2305_14152_amd import synth
     return synth.bf16_bits_to_f32(to_host(t).view(np.uint16)).astype(np.float64)

@@ -99,6 +99,27 @@ def test_argument_validation_needs_no_device(peqa):
     assert u(16, good, good, good, good, good, byref(opt), None) == peqa.PEQA_ERR_PARAM
 
 
+def test_kept_product_validation_needs_no_device(peqa):
+    L, Lg = peqa.layout(256, 256, 4), peqa.layout(256, 256, 4, 128)
+    good, bad = 0x10000, 0x10004
+    lib, byref = peqa.lib(), ctypes.byref
+    assert peqa.workspace_bytes(L, 100, peqa.PEQA_OP_FWD_KEEP) > 0
+    assert peqa.workspace_bytes(L, 100, peqa.PEQA_OP_BWD_KEPT) >= 100 * 256 * 2 + 2 * 256 * 4
+    assert peqa.workspace_bytes(Lg, 100, peqa.PEQA_OP_FWD_KEEP) == 0
+    assert peqa.workspace_bytes(Lg, 100, peqa.PEQA_OP_BWD_KEPT) == 0
+    assert peqa.workspace_bytes(L, 100, 4) == 0
+    f = lib.peqa_linear_fwd_keep
+    assert f(byref(Lg), good, good, None, good, good, 8, good, good, good, 1 << 20, None) == peqa.PEQA_ERR_GROUP
+    assert f(byref(L), good, good, None, good, good, 8, good, None, good, 1 << 20, None) == peqa.PEQA_ERR_NULL
+    assert f(byref(L), good, good, None, good, good, 8, good, bad, good, 1 << 20, None) == peqa.PEQA_ERR_ALIGN
+    assert f(byref(L), good, good, None, good, good, 8, good, good, good, 16, None) == peqa.PEQA_ERR_WORKSPACE
+    b = lib.peqa_linear_bwd_kept
+    assert b(byref(Lg), good, good, None, good, good, good, 8, good, good, good, 1 << 30, None) == peqa.PEQA_ERR_GROUP
+    assert b(byref(L), good, good, None, good, None, good, 8, good, good, good, 1 << 30, None) == peqa.PEQA_ERR_NULL
+    assert b(byref(L), good, good, None, good, good, None, 8, good, good, good, 1 << 30, None) == peqa.PEQA_ERR_NULL
+    assert b(byref(L), good, good, None, good, good, good, 8, good, good, good, 64, None) == peqa.PEQA_ERR_WORKSPACE
+
+
 def test_fused_forward_validation_needs_no_device(peqa):
     a, b = peqa.layout(256, 512, 4), peqa.layout(128, 512, 4)
     assert peqa.workspace_bytes_fused([(a, 16, 16, None, 16, 16), (b, 16, 16, None, 16, 16)], 4) > 0

@@ -197,6 +197,49 @@ def test_zero_and_negative_scales(gpu, oracle, bits, group):
             assert (gpu.to_host(dds0) == gpu.to_host(dds)).all()      # independent of the scale
 
 
+@pytest.mark.parametrize("bits,N,K,T", [
+    (4, 384, 640, 200),     # ragged token tile, half-empty column tile
+    (3, 512, 384, 129),
+    (4, 128, 128, 1),       # one token: still the tiled contraction
+    (3, 256, 896, 300),     # 5 slices of 64 rows, the last ragged
+    (4, 640, 1152, 64),     # exactly one slice
+])
+def test_kept_product_training_parity(gpu, oracle, bits, N, K, T):
+    """Forward that keeps P = X (Q - z0)^T and the backward that takes the scale gradient from it."""
+    _log("kept product bits=%d N=%d K=%d T=%d" % (bits, N, K, T))
+    seed = 9100 + bits * 1000 + N + K + T
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dY = synth.normal_bf16(seed + 2, (T, N), 1.0)
+    layer = gpu.GpuLayer(W, bits, 0)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, 0)
+    ds = synth.normal_f32(seed + 3, s0.shape, 1.0) * 0.05 * s0
+    Yk, P = layer.fwd_keep(X, ds)
+    Yref = oracle.fwd(codes, s0, ds, z0, X, 0)
+    assert np.abs(gpu.bf16_dev_to_f64(Yk) - Yref).max() <= Y_TOL * np.abs(Yref).max()
+    if T > 16:                                          # the same contraction kernel as the plain forward
+        assert (gpu.to_host(Yk) == gpu.to_host(layer.fwd(X, ds))).all()
+    # P against the oracle's forward with unit scales (fp32 accumulation of exact bf16 x integer products)
+    Pref = oracle.fwd(codes, np.ones_like(s0), None, z0, X, 0)
+    Ph = gpu.to_host(P).astype(np.float64)
+    assert np.abs(Ph - Pref).max() <= 1e-5 * np.abs(Pref).max()
+    dXk, ddsk = layer.bwd_kept(P, dY, ds)
+    dXref, gref, _ = oracle.bwd(codes, s0, ds, z0, X, dY, 0)
+    assert np.abs(gpu.bf16_dev_to_f64(dXk) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    g = gpu.to_host(ddsk).astype(np.float64)
+    err = np.linalg.norm(g - gref) / np.linalg.norm(gref)
+    _log("  dds rel-L2 from the kept product: %.2e" % err)
+    assert err <= G_TOL
+    # skips, and agreement with the recomputing backward
+    dX2, dds2 = layer.bwd(X, dY, ds)
+    assert (gpu.to_host(dXk) == gpu.to_host(dX2)).all()
+    assert np.linalg.norm(g - gpu.to_host(dds2)) <= 1e-5 * np.linalg.norm(gref)
+    only_dx, none = layer.bwd_kept(None, dY, ds, want_dds=False)
+    assert none is None and (gpu.to_host(only_dx) == gpu.to_host(dXk)).all()
+    none, only_g = layer.bwd_kept(P, dY, ds, want_dX=False)
+    assert none is None and (gpu.to_host(only_g) == gpu.to_host(ddsk)).all()
+
+
 def test_graph_capture_replays_match_eager(gpu, oracle):
     """Forward + backward captured in a HIP graph (the backward forks onto the library's second
     stream inside the capture): several replays, with eager work and synchronisation between them,

@@ -367,6 +367,89 @@ int oracle_bwd(const uint8_t *codes, const float *s0, const float *ds,
     return 0;
 }
 
+/* Appendix K ("Choice of Updating Quantization Scales or Zero-Points") also trains the
+ * zero-points, alone or together with the scales.  The zero-point then is the real number
+ * z = z0 + dz (dz fp32, same shape as the scales; the sum is formed in fp32 as for s), the
+ * codes stay frozen, and Eq. 2 reads  What[i,k] = s[i,g(k)] * (Q[i,k] - z[i,g(k)]).
+ * Forward with such zero-points; dz may be NULL (= 0). */
+int oracle_fwd_z(const uint8_t *codes, const float *s0, const float *ds,
+                 const uint8_t *z0, const float *dz, const uint16_t *X,
+                 int T, int N, int K, int group, double *Y)
+{
+    const int G = groups_of(K, group), gs = gsize_of(K, group);
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < N; ++i) {
+        for (int t = 0; t < T; ++t) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                const size_t sg = (size_t)i * G + k / gs;
+                volatile float sf = ds ? s0[sg] + ds[sg] : s0[sg];
+                volatile float zf = dz ? (float)z0[sg] + dz[sg] : (float)z0[sg];
+                const double w = (double)sf *
+                    ((double)codes[(size_t)i * K + k] - (double)zf);
+                acc += bf16_to_double(X[(size_t)t * K + k]) * w;
+            }
+            Y[(size_t)t * N + i] = acc;
+        }
+    }
+    return 0;
+}
+
+/* Chain rule through that forward:
+ *   dX[t,k]  = sum_i dY[t,i] * s[i,g(k)] * (Q[i,k] - z[i,g(k)])
+ *   dds[i,g] = sum_t dY[t,i] * sum_{k in g} X[t,k] * (Q[i,k] - z[i,g])
+ *   ddz[i,g] = sum_t dY[t,i] * sum_{k in g} X[t,k] * (-s[i,g])
+ * (What depends on z only through the term -s*z).  Any output may be NULL. */
+int oracle_bwd_z(const uint8_t *codes, const float *s0, const float *ds,
+                 const uint8_t *z0, const float *dz, const uint16_t *X,
+                 const uint16_t *dY, int T, int N, int K, int group,
+                 double *dX, double *dds, double *ddz)
+{
+    const int G = groups_of(K, group), gs = gsize_of(K, group);
+    if (dX) {
+#pragma omp parallel for schedule(static)
+        for (int t = 0; t < T; ++t) {
+            for (int k = 0; k < K; ++k) {
+                double acc = 0.0;
+                for (int i = 0; i < N; ++i) {
+                    const size_t sg = (size_t)i * G + k / gs;
+                    volatile float sf = ds ? s0[sg] + ds[sg] : s0[sg];
+                    volatile float zf = dz ? (float)z0[sg] + dz[sg] : (float)z0[sg];
+                    const double w = (double)sf *
+                        ((double)codes[(size_t)i * K + k] - (double)zf);
+                    acc += bf16_to_double(dY[(size_t)t * N + i]) * w;
+                }
+                dX[(size_t)t * K + k] = acc;
+            }
+        }
+    }
+    if (dds || ddz) {
+#pragma omp parallel for schedule(static)
+        for (int i = 0; i < N; ++i) {
+            for (int g = 0; g < G; ++g) {
+                const size_t sg = (size_t)i * G + g;
+                volatile float sf = ds ? s0[sg] + ds[sg] : s0[sg];
+                volatile float zf = dz ? (float)z0[sg] + dz[sg] : (float)z0[sg];
+                double acc_s = 0.0, acc_z = 0.0;
+                for (int t = 0; t < T; ++t) {
+                    double P = 0.0, R = 0.0;
+                    for (int k = g * gs; k < (g + 1) * gs; ++k) {
+                        const double x = bf16_to_double(X[(size_t)t * K + k]);
+                        P += x * ((double)codes[(size_t)i * K + k] - (double)zf);
+                        R += x;
+                    }
+                    const double d = bf16_to_double(dY[(size_t)t * N + i]);
+                    acc_s += d * P;
+                    acc_z += d * R * (-(double)sf);
+                }
+                if (dds) dds[sg] = acc_s;
+                if (ddz) ddz[sg] = acc_z;
+            }
+        }
+    }
+    return 0;
+}
+
 /* One AdamW step on ds (Appendix A names AdamW; constants are call
  * parameters).  The decayed parameter is the actual scale s0 + ds, since the
  * paper trains the scale itself:

@@ -162,6 +162,39 @@ def bwd(codes, s0, ds, z0, X_bf16, dY_bf16, group=0, want_dX=True, want_P=True, 
     return dX, gP, gW
 
 
+def fwd_z(codes, s0, ds, z0, dz, X_bf16, group=0):
+    """Forward with trainable zero-points z = z0 + dz (Appendix K), fp64."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, K = codes.shape
+    X = np.ascontiguousarray(X_bf16, dtype=np.uint16)
+    T = X.shape[0]
+    assert X.shape == (T, K)
+    s0, ds, dz = _f32(s0), _f32(ds), _f32(dz)
+    z0 = np.ascontiguousarray(z0, dtype=np.uint8)
+    Y = np.empty((T, N), np.float64)
+    _chk(lib().oracle_fwd_z(_p(codes), _p(s0), _p(ds), _p(z0), _p(dz), _p(X), T, N, K, group, _p(Y)), "fwd_z")
+    return Y
+
+
+def bwd_z(codes, s0, ds, z0, dz, X_bf16, dY_bf16, group=0, want_dX=True):
+    """Returns (dX | None, dds, ddz) for zero-points z = z0 + dz (Appendix K), fp64."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    N, K = codes.shape
+    X = np.ascontiguousarray(X_bf16, dtype=np.uint16)
+    dY = np.ascontiguousarray(dY_bf16, dtype=np.uint16)
+    T = X.shape[0]
+    assert X.shape == (T, K) and dY.shape == (T, N)
+    G = num_groups(K, group)
+    s0, ds, dz = _f32(s0), _f32(ds), _f32(dz)
+    z0 = np.ascontiguousarray(z0, dtype=np.uint8)
+    dX = np.empty((T, K), np.float64) if want_dX else None
+    gs = np.empty((N, G), np.float64)
+    gz = np.empty((N, G), np.float64)
+    _chk(lib().oracle_bwd_z(_p(codes), _p(s0), _p(ds), _p(z0), _p(dz), _p(X), _p(dY), T, N, K, group,
+                            _p(dX), _p(gs), _p(gz)), "bwd_z")
+    return dX, gs, gz
+
+
 def adamw(ds, g, m, v, s0, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, step=1):
     """One AdamW step in fp64; returns new (ds, m, v) without touching the inputs."""
     ds = np.array(ds, dtype=np.float64).ravel().copy()

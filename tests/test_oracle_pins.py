@@ -388,6 +388,64 @@ def test_scale_gradient_fd_two_routes_euler_and_independence(oracle, bits, group
     assert (gP2 == gP).all()
 
 
+# ----------------------------------------------------------------------------
+# Trainable zero-points (Appendix K)
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("bits,group", [(4, 0), (3, 16), (4, 8)])
+def test_zero_point_training_pins(oracle, bits, group):
+    N, K, T = 16, 32, 10
+    L = _rand_layer(oracle, N, K, bits, group, 700 + bits + group, T=T)
+    codes, s0, ds, z0, X, dY = (L[k] for k in ("codes", "s0", "ds", "z0", "X", "dY"))
+    G = s0.shape[1]
+    dYf = synth.bf16_bits_to_f32(dY).astype(np.float64)
+    Xf = synth.bf16_bits_to_f32(X).astype(np.float64)
+    # dz = 0 (and dz absent) is the frozen zero-point path, bit for bit
+    zero = np.zeros_like(s0)
+    Y0 = oracle.fwd(codes, s0, ds, z0, X, group)
+    assert (oracle.fwd_z(codes, s0, ds, z0, None, X, group) == Y0).all()
+    assert (oracle.fwd_z(codes, s0, ds, z0, zero, X, group) == Y0).all()
+    dX0, g0, _ = oracle.bwd(codes, s0, ds, z0, X, dY, group)
+    dXz, gsz, _ = oracle.bwd_z(codes, s0, ds, z0, zero, X, dY, group)
+    assert (dXz == dX0).all() and (gsz == g0).all()
+    # a whole step of the zero-point is a shift of the integer codes: (Q + 1) - (z0 + 1) = Q - z0
+    low = (codes // 2).astype(np.uint8)                           # leaves room to add one
+    up = (low + 1).astype(np.uint8)
+    one = np.ones_like(s0)
+    np.testing.assert_allclose(oracle.fwd_z(up, s0, ds, z0, one, X, group), oracle.fwd(low, s0, ds, z0, X, group),
+                               rtol=1e-13, atol=1e-13)
+    # general dz against a library matmul on explicitly built weights
+    dz = synth.normal_f32(991 + bits, s0.shape, 0.7)
+    s = (s0 + ds).astype(np.float32).astype(np.float64)
+    z = (z0.astype(np.float32) + dz).astype(np.float32).astype(np.float64)
+    What = _expand(s, K) * (codes.astype(np.float64) - _expand(z, K))
+    Yz = oracle.fwd_z(codes, s0, ds, z0, dz, X, group)
+    np.testing.assert_allclose(Yz, Xf @ What.T, rtol=1e-12, atol=1e-12)
+    dX, gs, gz = oracle.bwd_z(codes, s0, ds, z0, dz, X, dY, group)
+    np.testing.assert_allclose(dX, dYf @ What, rtol=1e-12, atol=1e-12)
+    # central differences of L = <dY, Y> in dz and in ds (L is linear in each); realised fp32 steps
+    for (i, g) in [(0, 0), (7, G - 1), (15, G // 2)]:
+        for name, base, grad in (("z", dz, gz), ("s", ds, gs)):
+            bp, bm = base.copy(), base.copy()
+            bp[i, g] += np.float32(0.25); bm[i, g] -= np.float32(0.25)
+            if name == "z":
+                hp = np.float64(np.float32(np.float32(z0[i, g]) + bp[i, g])) - np.float64(np.float32(np.float32(z0[i, g]) + bm[i, g]))
+                Lp = (dYf * oracle.fwd_z(codes, s0, ds, z0, bp, X, group)).sum()
+                Lm = (dYf * oracle.fwd_z(codes, s0, ds, z0, bm, X, group)).sum()
+            else:
+                hp = np.float64(np.float32(s0[i, g] + bp[i, g])) - np.float64(np.float32(s0[i, g] + bm[i, g]))
+                Lp = (dYf * oracle.fwd_z(codes, s0, bp, z0, dz, X, group)).sum()
+                Lm = (dYf * oracle.fwd_z(codes, s0, bm, z0, dz, X, group)).sum()
+            assert abs((Lp - Lm) / hp - grad[i, g]) <= 1e-9 * max(1.0, abs(grad[i, g])), name
+    # closed form: all-ones X and dY give ddz = -s * T * (features per group)
+    ones_x = synth.f32_to_bf16_bits(np.ones((T, K), np.float32))
+    ones_y = synth.f32_to_bf16_bits(np.ones((T, N), np.float32))
+    _, _, gz1 = oracle.bwd_z(codes, s0, ds, z0, dz, ones_x, ones_y, group, want_dX=False)
+    np.testing.assert_allclose(gz1, -s * T * (K // G), rtol=1e-13)
+    # the zero-point gradient does not depend on the zero-point or the codes
+    _, _, gz2 = oracle.bwd_z(up, s0, ds, z0, None, X, dY, group, want_dX=False)
+    assert (gz2 == gz).all()
+
+
 def test_scale_gradient_brute_force_python_loops(oracle):
     """Tiny layer, every sum written as a Python loop straight from the chain rule."""
     N, K, T, g = 8, 16, 3, 8

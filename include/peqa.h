@@ -60,7 +60,9 @@ typedef enum {
     PEQA_OP_FWD = 0,      /* peqa_linear_fwd        */
     PEQA_OP_BWD = 1,      /* peqa_linear_bwd        */
     PEQA_OP_FWD_KEEP = 2, /* peqa_linear_fwd_keep   */
-    PEQA_OP_BWD_KEPT = 3  /* peqa_linear_bwd_kept   */
+    PEQA_OP_BWD_KEPT = 3, /* peqa_linear_bwd_kept   */
+    PEQA_OP_FWD_Z = 4,    /* peqa_linear_fwd_z      */
+    PEQA_OP_BWD_Z = 5     /* peqa_linear_bwd_z      */
 } peqa_op;
 
 /* Host-only helpers (no device access). */
@@ -172,6 +174,27 @@ peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, c
                                  const float *ds, const uint8_t *z0, const float *P,
                                  const uint16_t *dY, int32_t T, uint16_t *dX, float *d_ds,
                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Trainable zero-points (Appendix K, "Choice of Updating Quantization Scales or Zero-Points": zero-points
+ * only, or zero-points and scales together).  The zero-point becomes the real number z = z0 + dz with
+ * dz [N, G] fp32 (NULL = 0); the codes stay frozen and Eq. 2 reads What = (s0+ds) (Q - z).
+ *   peqa_linear_fwd_z:  Y as peqa_linear_fwd with z in place of z0 (every T, per-channel and group-wise).
+ *   peqa_linear_bwd_z:  dX and d_ds as peqa_linear_bwd with z in place of z0, and
+ *     d_dz[i,g] = -(s0+ds)[i,g] * sum_t dY[t,i] * sum_{k in g} X[t,k]      [N, G] fp32 out, or NULL to skip
+ *   (z enters What only through -s z).  X may be NULL when d_ds and d_dz both are.
+ *   dz is updated with peqa_scale_update(n, dz, d_dz, m, v, s0, opt): with opt->weight_decay = 0 the
+ *   s0 argument is read but has no effect (pass the scales).
+ *   workspace: peqa_workspace_bytes(L, T, PEQA_OP_FWD_Z / PEQA_OP_BWD_Z).
+ */
+peqa_status peqa_linear_fwd_z(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                              const float *ds, const uint8_t *z0, const float *dz, const uint16_t *X,
+                              int32_t T, uint16_t *Y, void *workspace, size_t workspace_bytes,
+                              void *stream);
+peqa_status peqa_linear_bwd_z(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                              const float *ds, const uint8_t *z0, const float *dz, const uint16_t *X,
+                              const uint16_t *dY, int32_t T, uint16_t *dX, float *d_ds, float *d_dz,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * One AdamW step on ds (Appendix A names AdamW with a linearly decaying learning rate;

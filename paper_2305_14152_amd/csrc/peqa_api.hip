@@ -24,7 +24,7 @@ inline int split_point(int n) { return (n / 2) / 64 * 64; }
 constexpr int PEQA_GEMV_MAX_T = 16;   // forward calls with at most this many tokens take the matrix-vector path
 
 struct Workspace {
-    size_t rs, dys, crow, partial, table, total;
+    size_t rs, dys, crow, partial, table, rsz, zpartial, total;
 };
 
 // matrix-vector path: fp32 partials of the feature slices, for n_total output channels side by side
@@ -37,6 +37,16 @@ size_t gemv_partial_bytes(const peqa_layout *L, size_t n_total, int32_t T)
 
 Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
 {
+    if (op == PEQA_OP_FWD_Z) return carve(L, T, PEQA_OP_FWD);
+    if (op == PEQA_OP_BWD_Z) {
+        // the plain backward's needs, then the group sums of X and the partials of the zero-point gradient
+        Workspace w = carve(L, T, PEQA_OP_BWD);
+        const size_t slices = ((size_t)T + peqa::KEPT_ROWS - 1) / peqa::KEPT_ROWS;
+        const size_t NG = (size_t)L->n_out * (size_t)groups(L);
+        w.rsz = w.total;      w.total += round256((size_t)T * groups(L) * sizeof(float));
+        w.zpartial = w.total; w.total += round256(slices * NG * sizeof(float));
+        return w;
+    }
     Workspace w{};
     const size_t N = (size_t)L->n_out, G = (size_t)groups(L);
     const size_t tiles_t = ((size_t)T + 127) / 128;
@@ -83,8 +93,8 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
 peqa_status dev_status(hipError_t e) { return e == hipSuccess ? PEQA_OK : PEQA_ERR_DEVICE; }
 
 // One matrix-vector launch for n <= GEMV_MAX_LAYERS validated layers that share X, K, bits and group size.
-peqa_status gemv_forward(int n, const peqa_fwd_item *items, const uint16_t *X, int32_t T, float *partial,
-                         hipStream_t s)
+peqa_status gemv_forward(int n, const peqa_fwd_item *items, const float *dz, const uint16_t *X, int32_t T,
+                         float *partial, hipStream_t s)
 {
     const peqa_layout *L = &items[0].layout;
     peqa::GemvArgs g{};
@@ -92,7 +102,8 @@ peqa_status gemv_forward(int n, const peqa_fwd_item *items, const uint16_t *X, i
     for (int j = 0; j < peqa::GEMV_MAX_LAYERS; ++j) {
         if (j < n) {
             tiles += items[j].layout.n_out / 128;
-            g.layer[j] = peqa::GemvLayer{items[j].packed, items[j].s0, items[j].ds, items[j].z0, items[j].Y,
+            // dz (a trained zero-point offset) is only ever passed with a single layer
+            g.layer[j] = peqa::GemvLayer{items[j].packed, items[j].s0, items[j].ds, items[j].z0, dz, items[j].Y,
                                          items[j].layout.n_out, tiles};
         } else {
             g.layer[j] = g.layer[n - 1];                   // never selected: its tile_end is the total
@@ -109,8 +120,8 @@ peqa_status gemv_forward(int n, const peqa_fwd_item *items, const uint16_t *X, i
 
 bool trace_active();
 peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
-                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, float *P, const float *rs,
-                            hipStream_t s);
+                            const uint8_t *z0, const float *dz, const uint16_t *X, int32_t T, uint16_t *Y, float *P,
+                            const float *rs, hipStream_t s);
 
 // The two halves of the backward (scale gradient; dX) are independent.  When both are wanted, the
 // scale-gradient chain runs on a second stream of the library's own, forked from and joined back
@@ -178,7 +189,7 @@ size_t peqa_workspace_bytes(const peqa_layout *L, int32_t T, int32_t op)
     if (peqa_check_layout(L) != PEQA_OK || T < 1) return 0;
     if (op == PEQA_OP_FWD_KEEP || op == PEQA_OP_BWD_KEPT) {
         if (grouped(L)) return 0;
-    } else if (op != PEQA_OP_FWD && op != PEQA_OP_BWD) {
+    } else if (op != PEQA_OP_FWD && op != PEQA_OP_BWD && op != PEQA_OP_FWD_Z && op != PEQA_OP_BWD_Z) {
         return 0;
     }
     return carve(L, T, op).total;
@@ -236,16 +247,16 @@ peqa_status peqa_quantize(const peqa_layout *L, const float *W0, uint32_t *packe
                                             static_cast<hipStream_t>(stream)));
 }
 
-peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
-                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, void *workspace,
-                            size_t workspace_bytes, void *stream)
+static peqa_status fwd_impl(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const float *dz, const uint16_t *X, int32_t T, uint16_t *Y,
+                            void *workspace, size_t workspace_bytes, void *stream)
 {
     peqa_status st = peqa_check_layout(L);
     if (st != PEQA_OK) return st;
     if (!packed || !s0 || !z0 || !X || !Y) return PEQA_ERR_NULL;
     if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
     if (!aligned16(packed) || !aligned16(s0) || !aligned16(z0) || !aligned16(X) || !aligned16(Y) ||
-        (ds && !aligned16(ds)))
+        (ds && !aligned16(ds)) || (dz && !aligned16(dz)))
         return PEQA_ERR_ALIGN;
     const Workspace w = carve(L, T, PEQA_OP_FWD);
     if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
@@ -256,11 +267,11 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     const int N = L->n_out, K = L->k_in, ksplit = split_point(K);
     if (T <= PEQA_GEMV_MAX_T) {
         peqa_fwd_item item{*L, packed, s0, ds, z0, Y};
-        return gemv_forward(1, &item, X, T, reinterpret_cast<float *>(ws + w.partial), s);
+        return gemv_forward(1, &item, dz, X, T, reinterpret_cast<float *>(ws + w.partial), s);
     }
     if (grouped(L)) {
         float *sb = reinterpret_cast<float *>(ws + w.table);
-        if (peqa::launch_group_table(s0, ds, z0, N, groups(L), sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_group_table(s0, ds, z0, dz, N, groups(L), sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
         a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
         a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
@@ -269,7 +280,21 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     }
     float *rs = reinterpret_cast<float *>(ws + w.rs);
     if (peqa::launch_rowsum(X, T, K, ksplit, rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
-    return fwd_per_channel(L, packed, s0, ds, z0, X, T, Y, nullptr, rs, s);
+    return fwd_per_channel(L, packed, s0, ds, z0, dz, X, T, Y, nullptr, rs, s);
+}
+
+peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, void *workspace,
+                            size_t workspace_bytes, void *stream)
+{
+    return fwd_impl(L, packed, s0, ds, z0, nullptr, X, T, Y, workspace, workspace_bytes, stream);
+}
+
+peqa_status peqa_linear_fwd_z(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                              const uint8_t *z0, const float *dz, const uint16_t *X, int32_t T, uint16_t *Y,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fwd_impl(L, packed, s0, ds, z0, dz, X, T, Y, workspace, workspace_bytes, stream);
 }
 
 peqa_status peqa_linear_fwd_keep(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
@@ -290,7 +315,7 @@ peqa_status peqa_linear_fwd_keep(const peqa_layout *L, const uint32_t *packed, c
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *rs = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + w.rs);
     if (peqa::launch_rowsum(X, T, L->k_in, split_point(L->k_in), rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
-    return fwd_per_channel(L, packed, s0, ds, z0, X, T, Y, P, rs, s);
+    return fwd_per_channel(L, packed, s0, ds, z0, nullptr, X, T, Y, P, rs, s);
 }
 
 }  // extern "C"
@@ -298,14 +323,14 @@ peqa_status peqa_linear_fwd_keep(const peqa_layout *L, const uint32_t *packed, c
 namespace {
 // Per-channel forward contraction for T > 16, the row sums of X already in `rs`.
 peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
-                            const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, float *P, const float *rs,
-                            hipStream_t s)
+                            const uint8_t *z0, const float *dz, const uint16_t *X, int32_t T, uint16_t *Y, float *P,
+                            const float *rs, hipStream_t s)
 {
     const int N = L->n_out, K = L->k_in;
     peqa::GemmArgs a{};
     a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
     a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
-    a.s0 = s0; a.ds = ds; a.z0 = z0; a.rs = rs; a.out = Y; a.P = P;
+    a.s0 = s0; a.ds = ds; a.z0 = z0; a.dz = dz; a.rs = rs; a.out = Y; a.P = P;
     return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
 }
 }  // namespace
@@ -362,7 +387,7 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
     if (!workspace || workspace_bytes < need) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
     if (T <= PEQA_GEMV_MAX_T)
-        return gemv_forward(n, items, X, T, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+        return gemv_forward(n, items, nullptr, X, T, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
     // the tiled contraction runs the layers one by one; per-channel layers share the row sums of X
     if (!grouped(&items[0].layout)) {
         hipStream_t s = static_cast<hipStream_t>(stream);
@@ -371,7 +396,7 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
             return PEQA_ERR_DEVICE;
         for (int j = 0; j < n; ++j) {
             const peqa_fwd_item &it = items[j];
-            st = fwd_per_channel(&it.layout, it.packed, it.s0, it.ds, it.z0, X, T, it.Y, nullptr, rs, s);
+            st = fwd_per_channel(&it.layout, it.packed, it.s0, it.ds, it.z0, nullptr, X, T, it.Y, nullptr, rs, s);
             if (st != PEQA_OK) return st;
         }
         return PEQA_OK;
@@ -384,19 +409,22 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
     return PEQA_OK;
 }
 
-peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
-                            const uint8_t *z0, const uint16_t *X, const uint16_t *dY, int32_t T, uint16_t *dX,
-                            float *d_ds, void *workspace, size_t workspace_bytes, void *stream)
+// Backward shared by peqa_linear_bwd (dz = d_dz = NULL, op = PEQA_OP_BWD) and peqa_linear_bwd_z.
+static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const float *dz, const uint16_t *X, const uint16_t *dY, int32_t T,
+                            uint16_t *dX, float *d_ds, float *d_dz, int32_t op, void *workspace,
+                            size_t workspace_bytes, void *stream)
 {
     peqa_status st = peqa_check_layout(L);
     if (st != PEQA_OK) return st;
     if (!packed || !s0 || !z0 || !dY) return PEQA_ERR_NULL;
-    if (d_ds && !X) return PEQA_ERR_NULL;
+    if ((d_ds || d_dz) && !X) return PEQA_ERR_NULL;
     if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
     if (!aligned16(packed) || !aligned16(s0) || !aligned16(z0) || !aligned16(dY) || (X && !aligned16(X)) ||
-        (ds && !aligned16(ds)) || (dX && !aligned16(dX)) || (d_ds && !aligned16(d_ds)))
+        (ds && !aligned16(ds)) || (dX && !aligned16(dX)) || (d_ds && !aligned16(d_ds)) || (dz && !aligned16(dz)) ||
+        (d_dz && !aligned16(d_dz)))
         return PEQA_ERR_ALIGN;
-    const Workspace w = carve(L, T, PEQA_OP_BWD);
+    const Workspace w = carve(L, T, op);
     if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
 
@@ -405,24 +433,32 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
     const int N = L->n_out, K = L->k_in;
     const int tiles_t = (T + 127) / 128;
 
+    const int slices = (T + peqa::KEPT_ROWS - 1) / peqa::KEPT_ROWS;
     if (grouped(L)) {
         const int G = groups(L);
-        if (d_ds) {
-            float *rsb = reinterpret_cast<float *>(ws + w.rs);
-            float *partial = reinterpret_cast<float *>(ws + w.partial);
+        float *rsb = reinterpret_cast<float *>(ws + w.rs);
+        if (d_ds || d_dz) {
             if (peqa::launch_rowsum_groups(X, T, K, L->group_size, rsb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        }
+        if (d_dz) {
+            float *zp = reinterpret_cast<float *>(ws + w.zpartial);
+            if (peqa::launch_dz_partial(dY, rsb, T, N, G, zp, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (peqa::launch_dz_finish(zp, slices, (size_t)N * G, s0, ds, d_dz, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        }
+        if (d_ds) {
+            float *partial = reinterpret_cast<float *>(ws + w.partial);
             peqa::GemmArgs a{};
             a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
             a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
             a.N = N; a.gsz = L->group_size; a.G = G;
-            a.z0 = z0; a.rs = rsb; a.dY = dY; a.partial = partial;
+            a.z0 = z0; a.dz = dz; a.rs = rsb; a.dY = dY; a.partial = partial;
             if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
             if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N * G, d_ds, s) != hipSuccess)
                 return PEQA_ERR_DEVICE;
         }
         if (dX) {
             float *sb = reinterpret_cast<float *>(ws + w.table);
-            if (peqa::launch_group_table(s0, ds, z0, N, G, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (peqa::launch_group_table(s0, ds, z0, dz, N, G, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
             peqa::GemmArgs a{};
             a.packed = packed; a.A = dY; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
             a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
@@ -446,7 +482,7 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
         peqa::GemmArgs a{};
         a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
         a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
-        a.z0 = z0; a.rs = rs; a.dY = dY; a.partial = partial;
+        a.z0 = z0; a.dz = dz; a.rs = rs; a.dY = dY; a.partial = partial;
         if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, sg) != hipSuccess) return PEQA_ERR_DEVICE;
         if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, sg) != hipSuccess) return PEQA_ERR_DEVICE;
         if (side && hipEventRecord(side->join, side->stream) != hipSuccess) return PEQA_ERR_DEVICE;
@@ -454,15 +490,40 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
     if (dX) {
         uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
         float *crow = reinterpret_cast<float *>(ws + w.crow);
-        if (peqa::launch_scale_dy(dY, s0, ds, z0, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
         a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
         a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
         a.crow = crow; a.out = dX;
         if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
+    if (d_dz) {
+        // sums of every row of X (one group spanning K), then the two-stage column reduction
+        float *rsz = reinterpret_cast<float *>(ws + w.rsz);
+        float *zp = reinterpret_cast<float *>(ws + w.zpartial);
+        if (peqa::launch_rowsum_groups(X, T, K, K, rsz, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_dz_partial(dY, rsz, T, N, 1, zp, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_dz_finish(zp, slices, (size_t)N, s0, ds, d_dz, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    }
     if (side && hipStreamWaitEvent(s, side->join, 0) != hipSuccess) return PEQA_ERR_DEVICE;
     return PEQA_OK;
+}
+
+peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                            const uint8_t *z0, const uint16_t *X, const uint16_t *dY, int32_t T, uint16_t *dX,
+                            float *d_ds, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return bwd_impl(L, packed, s0, ds, z0, nullptr, X, dY, T, dX, d_ds, nullptr, PEQA_OP_BWD, workspace,
+                    workspace_bytes, stream);
+}
+
+peqa_status peqa_linear_bwd_z(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                              const uint8_t *z0, const float *dz, const uint16_t *X, const uint16_t *dY, int32_t T,
+                              uint16_t *dX, float *d_ds, float *d_dz, void *workspace, size_t workspace_bytes,
+                              void *stream)
+{
+    return bwd_impl(L, packed, s0, ds, z0, dz, X, dY, T, dX, d_ds, d_dz, PEQA_OP_BWD_Z, workspace, workspace_bytes,
+                    stream);
 }
 
 peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
@@ -494,7 +555,7 @@ peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, c
     if (dX) {
         uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
         float *crow = reinterpret_cast<float *>(ws + w.crow);
-        if (peqa::launch_scale_dy(dY, s0, ds, z0, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_scale_dy(dY, s0, ds, z0, nullptr, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
         a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
         a.tiles_c = (K + 255) / 256; a.tiles_t = (T + 127) / 128;
@@ -536,7 +597,7 @@ struct TraceState {
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
-    "gemv_finish", "group_table", "dds_kept"};
+    "gemv_finish", "group_table", "dds_kept", "dz_partial", "dz_finish"};
 
 }  // namespace
 namespace {

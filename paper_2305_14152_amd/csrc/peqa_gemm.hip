@@ -399,10 +399,20 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
             const int g = half_on ? grp : a.G - 1;
 #pragma unroll
             for (int ct = 0; ct < 8; ++ct) ep_zoff[ct] = kCodeOffset + (float)a.z0[(size_t)(col0 + 8 * c + ct) * a.G + g];
+            if (a.dz) {
+#pragma unroll
+                for (int ct = 0; ct < 8; ++ct) ep_zoff[ct] += a.dz[(size_t)(col0 + 8 * c + ct) * a.G + g];
+            }
         } else if constexpr (MODE != MODE_DX) {
             const u32x2 zz = *reinterpret_cast<const u32x2 *>(a.z0 + col0 + 8 * c);
 #pragma unroll
             for (int ct = 0; ct < 8; ++ct) ep_zoff[ct] = kCodeOffset + (float)((zz[ct >> 2] >> (8 * (ct & 3))) & 0xFFu);
+            if (a.dz) {
+                const f32x4 z_lo = *reinterpret_cast<const f32x4 *>(a.dz + col0 + 8 * c);
+                const f32x4 z_hi = *reinterpret_cast<const f32x4 *>(a.dz + col0 + 8 * c + 4);
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct) { ep_zoff[ct] += z_lo[ct]; ep_zoff[4 + ct] += z_hi[ct]; }
+            }
         }
         if constexpr (MODE == MODE_Y) {
             const f32x4 s_lo = *reinterpret_cast<const f32x4 *>(a.s0 + col0 + 8 * c);

@@ -37,7 +37,7 @@ constexpr int GV_MAX_PER = 16;       // most scale groups a slice may touch (bou
 constexpr int GV_B_BYTES = 4096;     // packed blocks of one round of one wave (4 KB at 4 bits, 3 KB at 3 bits)
 constexpr int GV_ROUND_BYTES = GV_B_BYTES + 2048;   // + 16 token rows x 128 B
 
-struct ScaleZero { float s, zoff; };  // s0 + ds and 16 + z0
+struct ScaleZero { float s, zoff; };  // s0 + ds and 16 + z0 + dz
 
 __device__ __forceinline__ void gv_dma16(uint32_t voff, const void *sbase, uint32_t lds_dst)
 {
@@ -73,6 +73,7 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
     const float *l_s0 = pick([](const GemvLayer &l) { return l.s0; });
     const float *l_ds = pick([](const GemvLayer &l) { return l.ds; });
     const uint8_t *l_z0 = pick([](const GemvLayer &l) { return l.z0; });
+    const float *l_dz = pick([](const GemvLayer &l) { return l.dz; });
     uint16_t *l_Y = pick([](const GemvLayer &l) { return l.Y; });
     const int l_N = pick([](const GemvLayer &l) { return l.N; });
     const int tile0 = li == 0 ? 0 : li == 1 ? a.layer[0].tile_end : li == 2 ? a.layer[1].tile_end : a.layer[2].tile_end;
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
     const int cols = (GROUPS_MAX > 1 && rend > rbeg) ? (int)((uint32_t)(rend - 1) / (uint32_t)chunk_rounds) - g_lo + 1 : 1;
     auto load_tile = [&](auto nb_c) {
         constexpr int NB = decltype(nb_c)::value;                 // batches of 256 entries
-        float ts[NB], td[NB];
+        float ts[NB], td[NB], tdz[NB];
         uint8_t tz[NB];
         int ch[NB], jj[NB];
 #pragma unroll
@@ -143,10 +144,11 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
             ts[i] = l_s0[si];
             tz[i] = l_z0[si];
             td[i] = l_ds ? l_ds[si] : 0.f;
+            tdz[i] = l_dz ? l_dz[si] : 0.f;
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            if (tid + i * GV_WAVES * 64 < 128 * cols) sz[jj[i]][ch[i]] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i]};
+            if (tid + i * GV_WAVES * 64 < 128 * cols) sz[jj[i]][ch[i]] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i] + tdz[i]};
     };
     if (GROUPS_MAX == 1 || cols <= 2) load_tile(std::integral_constant<int, 1>{});
     else if (cols <= 4) load_tile(std::integral_constant<int, 2>{});

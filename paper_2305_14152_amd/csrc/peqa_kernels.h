@@ -23,6 +23,7 @@ struct GemmArgs {
     const float *s0;          // [N]            (MODE_Y)
     const float *ds;          // [N] or NULL    (MODE_Y)
     const uint8_t *z0;        // [N]            (MODE_Y, MODE_DDS)
+    const float *dz;          // [N] or NULL: trained zero-point offset, z = z0 + dz (MODE_Y, MODE_DDS; [N, G] if grouped)
     const float *rs;          // [T, 2] sums of X[t, :] over each contraction half (MODE_Y, MODE_DDS)
     const float *crow;        // [T] sum_i A[t,i] (16 + z_i)                      (MODE_DX)
     const uint16_t *dY;       // [T, N] bf16    (MODE_DDS)
@@ -46,6 +47,7 @@ struct GemvLayer {
     const uint32_t *packed;
     const float *s0, *ds;     // [N, G]; ds may be NULL
     const uint8_t *z0;        // [N, G]
+    const float *dz;          // [N, G] or NULL: trained zero-point offset
     uint16_t *Y;              // [T, N] bf16
     int N;
     int tile_end;             // channel tiles (of 128) of this layer and all before it
@@ -64,11 +66,17 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 
 // peqa_small.hip
 hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream);
-hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0,
+hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0, const float *dz,
                            int T, int N, uint16_t *dYs, float *crow, hipStream_t stream);
 hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float *rsg, hipStream_t stream);
-hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, int N, int G, float *sb,
-                              hipStream_t stream);
+hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, const float *dz, int N, int G,
+                              float *sb, hipStream_t stream);
+// zero-point gradient: partial [ceil(T / KEPT_ROWS), N, G] from dY and the group sums rsg [T, G] of X, then
+// d_dz[j] = -(s0 + ds)[j] * (sum of the partials)
+hipError_t launch_dz_partial(const uint16_t *dY, const float *rsg, int T, int N, int G, float *partial,
+                             hipStream_t stream);
+hipError_t launch_dz_finish(const float *partial, int slices, size_t n, const float *s0, const float *ds, float *d_dz,
+                            hipStream_t stream);
 constexpr int KEPT_ROWS = 64;   // token rows per partial of launch_dds_kept
 hipError_t launch_dds_kept(const uint16_t *dY, const float *P, int T, int N, float *partial, hipStream_t stream);
 hipError_t launch_reduce_partials(const float *partial, int ntiles, size_t n, float *out, hipStream_t stream);
@@ -86,7 +94,7 @@ void trace_after(int kernel_id, hipStream_t stream);
 
 enum {
     KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
-    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_COUNT
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_DZ_PARTIAL, KID_DZ_FINISH, KID_COUNT
 };
 
 }  // namespace peqa

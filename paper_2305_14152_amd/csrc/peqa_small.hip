@@ -69,11 +69,11 @@ __global__ __launch_bounds__(256) void rowsum_groups_kernel(const uint16_t *__re
     }
 }
 
-// sb[g, n] = (s, -s (16 + z)) with s = (s0 + ds)[n, g], z = z0[n, g]: the per-group table from which the
-// grouped contractions scale their weights.
+// sb[g, n] = (s, -s (16 + z)) with s = (s0 + ds)[n, g], z = (z0 + dz)[n, g]: the per-group table from which
+// the grouped contractions scale their weights.
 __global__ __launch_bounds__(256) void group_table_kernel(const float *__restrict__ s0, const float *__restrict__ ds,
-                                                           const uint8_t *__restrict__ z0, int N, int G,
-                                                           float *__restrict__ sb)
+                                                           const uint8_t *__restrict__ z0, const float *__restrict__ dz,
+                                                           int N, int G, float *__restrict__ sb)
 {
     const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;   // = n * G + g
     if (j >= (size_t)N * G) return;
@@ -81,14 +81,15 @@ __global__ __launch_bounds__(256) void group_table_kernel(const float *__restric
     const float s = ds ? s0[j] + ds[j] : s0[j];
     float *o = sb + (g * N + n) * 2;
     o[0] = s;
-    o[1] = -s * (kCodeOffset + (float)z0[j]);
+    o[1] = -s * (kCodeOffset + (float)z0[j] + (dz ? dz[j] : 0.f));
 }
 
-// dYs[t,i] = bf16(dY[t,i] * (s0+ds)[i]);  crow[t] = sum_i dYs[t,i] * (16 + z0[i])  (per-channel).
+// dYs[t,i] = bf16(dY[t,i] * (s0+ds)[i]);  crow[t] = sum_i dYs[t,i] * (16 + z0[i] + dz[i])  (per-channel).
 // crow uses the rounded dYs so that it cancels the code offset of the dX contraction exactly.
 __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ s0,
                                                         const float *__restrict__ ds, const uint8_t *__restrict__ z0,
-                                                        int N, uint16_t *__restrict__ dYs, float *__restrict__ crow)
+                                                        const float *__restrict__ dz, int N,
+                                                        uint16_t *__restrict__ dYs, float *__restrict__ crow)
 {
     __shared__ float red[4];
     const int t = blockIdx.x, tid = threadIdx.x;
@@ -107,15 +108,22 @@ __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restric
             for (int i = 0; i < 4; ++i) { s[i] += da[i]; s[4 + i] += db[i]; }
         }
         const u32x2 zz = *reinterpret_cast<const u32x2 *>(z0 + 8 * n8);
+        float zo[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) zo[i] = kCodeOffset + (float)((zz[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+        if (dz) {
+            const f32x4 za = *reinterpret_cast<const f32x4 *>(dz + 8 * n8);
+            const f32x4 zb = *reinterpret_cast<const f32x4 *>(dz + 8 * n8 + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { zo[i] += za[i]; zo[4 + i] += zb[i]; }
+        }
         u32x4 o;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const uint32_t lo = float_to_bf16_bits(bf16_lo(v[p]) * s[2 * p]);
             const uint32_t hi = float_to_bf16_bits(bf16_hi(v[p]) * s[2 * p + 1]);
             o[p] = lo | (hi << 16);
-            const float zl = kCodeOffset + (float)((zz[(2 * p) >> 2] >> (8 * ((2 * p) & 3))) & 0xFFu);
-            const float zh = kCodeOffset + (float)((zz[(2 * p + 1) >> 2] >> (8 * ((2 * p + 1) & 3))) & 0xFFu);
-            acc += bf16_bits_to_float(lo) * zl + bf16_bits_to_float(hi) * zh;
+            acc += bf16_bits_to_float(lo) * zo[2 * p] + bf16_bits_to_float(hi) * zo[2 * p + 1];
         }
         dst[n8] = o;
     }
@@ -156,6 +164,72 @@ __global__ __launch_bounds__(256) void dds_kept_kernel(const uint16_t *__restric
         const f32x4 s = ((part[0][q] + part[1][q]) + part[2][q]) + part[3][q];
         *reinterpret_cast<f32x4 *>(partial + (size_t)blockIdx.x * N + col) = s;
     }
+}
+
+// Zero-point gradient, first stage (Appendix K trains zero-points too; z enters Eq. 2 only through -s z, so
+// d_dz[i,g] = -s[i,g] * sum_t dY[t,i] R[t,g] with R[t,g] the sum of X[t,k] over scale group g):
+// partial[slice, i, g] = sum over the slice's KEPT_ROWS token rows of dY[t,i] * R[t,g].
+// A workgroup takes 256 channels (4 per lane) of one slice and walks the groups 8 at a time; wave w
+// adds rows w, w+4, ... in order; the four wave sums meet in LDS in a fixed order.
+__global__ __launch_bounds__(256) void dz_partial_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ rsg,
+                                                          int T, int N, int G, float *__restrict__ partial)
+{
+    __shared__ float part[4][32][64];                        // [wave][channel-in-lane * 8 + group][lane]
+    const int q = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = blockIdx.y * 256 + 4 * q;
+    const int tbeg = blockIdx.x * KEPT_ROWS;
+    const int nrows = min(KEPT_ROWS, T - tbeg);
+    const bool on = col < N;
+    for (int gc = 0; gc < G; gc += 8) {
+        float acc[4][8];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[cc][j] = 0.f;
+        if (on) {
+            for (int r = w; r < nrows; r += 4) {
+                const size_t t = (size_t)(tbeg + r);
+                const u32x2 d = *reinterpret_cast<const u32x2 *>(dY + t * N + col);
+                const float dv[4] = {bf16_lo(d[0]), bf16_hi(d[0]), bf16_lo(d[1]), bf16_hi(d[1])};
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float R = rsg[t * G + min(gc + j, G - 1)];   // groups past G are dropped at the store
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) acc[cc][j] += dv[cc] * R;
+                }
+            }
+        }
+        __syncthreads();                                     // the previous chunk's sums have been read
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) part[w][cc * 8 + j][q] = acc[cc][j];
+        __syncthreads();
+        if (w == 0 && on) {
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int e = cc * 8 + j;
+                    const float s = ((part[0][e][q] + part[1][e][q]) + part[2][e][q]) + part[3][e][q];
+                    if (gc + j < G) partial[((size_t)blockIdx.x * N + col + cc) * G + gc + j] = s;
+                }
+        }
+    }
+}
+
+// d_dz[j] = -(s0 + ds)[j] * (partial[0][j] + partial[1][j] + ...) in that order.
+__global__ __launch_bounds__(256) void dz_finish_kernel(const float *__restrict__ partial, int slices, size_t n,
+                                                         const float *__restrict__ s0, const float *__restrict__ ds,
+                                                         float *__restrict__ d_dz)
+{
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    float s = 0.f;
+    for (int tt = 0; tt < slices; ++tt) s += partial[(size_t)tt * n + j];
+    const float sc = ds ? s0[j] + ds[j] : s0[j];
+    d_dz[j] = -sc * s;
 }
 
 // out[j] = partial[0][j] + partial[1][j] + ... in that order (deterministic).
@@ -204,21 +278,22 @@ hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float 
     return hipGetLastError();
 }
 
-hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, int N, int G, float *sb,
-                              hipStream_t stream)
+hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, const float *dz, int N, int G,
+                              float *sb, hipStream_t stream)
 {
     trace_before(KID_GROUP_TABLE, stream);
     const size_t n = (size_t)N * G;
-    hipLaunchKernelGGL(group_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, ds, z0, N, G, sb);
+    hipLaunchKernelGGL(group_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, ds, z0, dz, N, G,
+                       sb);
     trace_after(KID_GROUP_TABLE, stream);
     return hipGetLastError();
 }
 
-hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0, int T, int N,
-                           uint16_t *dYs, float *crow, hipStream_t stream)
+hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0, const float *dz,
+                           int T, int N, uint16_t *dYs, float *crow, hipStream_t stream)
 {
     trace_before(KID_SCALE_DY, stream);
-    hipLaunchKernelGGL(scale_dy_kernel, dim3(T), dim3(256), 0, stream, dY, s0, ds, z0, N, dYs, crow);
+    hipLaunchKernelGGL(scale_dy_kernel, dim3(T), dim3(256), 0, stream, dY, s0, ds, z0, dz, N, dYs, crow);
     trace_after(KID_SCALE_DY, stream);
     return hipGetLastError();
 }
@@ -229,6 +304,26 @@ hipError_t launch_dds_kept(const uint16_t *dY, const float *P, int T, int N, flo
     hipLaunchKernelGGL(dds_kept_kernel, dim3((T + KEPT_ROWS - 1) / KEPT_ROWS, (N + 255) / 256), dim3(256), 0, stream,
                        dY, P, T, N, partial);
     trace_after(KID_DDS_KEPT, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_dz_partial(const uint16_t *dY, const float *rsg, int T, int N, int G, float *partial,
+                             hipStream_t stream)
+{
+    trace_before(KID_DZ_PARTIAL, stream);
+    hipLaunchKernelGGL(dz_partial_kernel, dim3((T + KEPT_ROWS - 1) / KEPT_ROWS, (N + 255) / 256), dim3(256), 0, stream,
+                       dY, rsg, T, N, G, partial);
+    trace_after(KID_DZ_PARTIAL, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_dz_finish(const float *partial, int slices, size_t n, const float *s0, const float *ds, float *d_dz,
+                            hipStream_t stream)
+{
+    trace_before(KID_DZ_FINISH, stream);
+    hipLaunchKernelGGL(dz_finish_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, partial, slices, n,
+                       s0, ds, d_dz);
+    trace_after(KID_DZ_FINISH, stream);
     return hipGetLastError();
 }
 

@@ -10,12 +10,13 @@ LIB_PATH = os.path.join(_HERE, "libpeqa_hip.so")
 PEQA_OK = 0
 PEQA_ERR_NULL, PEQA_ERR_SHAPE, PEQA_ERR_BITS, PEQA_ERR_GROUP = 1, 2, 3, 4
 PEQA_ERR_ALIGN, PEQA_ERR_WORKSPACE, PEQA_ERR_DEVICE, PEQA_ERR_PARAM = 5, 6, 7, 8
-PEQA_OP_FWD, PEQA_OP_BWD, PEQA_OP_FWD_KEEP, PEQA_OP_BWD_KEPT = 0, 1, 2, 3
+PEQA_OP_FWD, PEQA_OP_BWD, PEQA_OP_FWD_KEEP, PEQA_OP_BWD_KEPT, PEQA_OP_FWD_Z, PEQA_OP_BWD_Z = 0, 1, 2, 3, 4, 5
 
 EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_workspace_bytes",
            "peqa_status_string", "peqa_bit_location", "peqa_quantize", "peqa_linear_fwd",
            "peqa_linear_bwd", "peqa_scale_update", "peqa_trace_begin", "peqa_trace_end",
-           "peqa_workspace_bytes_fused", "peqa_linear_fwd_fused", "peqa_linear_fwd_keep", "peqa_linear_bwd_kept"]
+           "peqa_workspace_bytes_fused", "peqa_linear_fwd_fused", "peqa_linear_fwd_keep", "peqa_linear_bwd_kept",
+           "peqa_linear_fwd_z", "peqa_linear_bwd_z"]
 
 
 class Layout(ctypes.Structure):
@@ -73,6 +74,10 @@ def lib():
         L.peqa_linear_fwd_keep.restype = i32
         L.peqa_linear_bwd_kept.argtypes = [LP, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.peqa_linear_bwd_kept.restype = i32
+        L.peqa_linear_fwd_z.argtypes = [LP, vp, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.peqa_linear_fwd_z.restype = i32
+        L.peqa_linear_bwd_z.argtypes = [LP, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.peqa_linear_bwd_z.restype = i32
         L.peqa_scale_update.argtypes = [sz, vp, vp, vp, vp, vp, ctypes.POINTER(AdamW), vp]
         L.peqa_scale_update.restype = i32
         L.peqa_workspace_bytes_fused.argtypes = [i32, vp, i32]
@@ -191,6 +196,18 @@ def linear_bwd_kept(L, packed, s0, ds, z0, P, dY, T, dX, d_ds, workspace, worksp
     _check(lib().peqa_linear_bwd_kept(ctypes.byref(L), _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(P), _ptr(dY),
                                       int(T), _ptr(dX), _ptr(d_ds), _ptr(workspace), int(workspace_bytes_),
                                       _stream(stream)), "peqa_linear_bwd_kept")
+
+
+def linear_fwd_z(L, packed, s0, ds, z0, dz, X, T, Y, workspace, workspace_bytes_, stream=None):
+    _check(lib().peqa_linear_fwd_z(ctypes.byref(L), _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(dz), _ptr(X),
+                                   int(T), _ptr(Y), _ptr(workspace), int(workspace_bytes_), _stream(stream)),
+           "peqa_linear_fwd_z")
+
+
+def linear_bwd_z(L, packed, s0, ds, z0, dz, X, dY, T, dX, d_ds, d_dz, workspace, workspace_bytes_, stream=None):
+    _check(lib().peqa_linear_bwd_z(ctypes.byref(L), _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(dz), _ptr(X),
+                                   _ptr(dY), int(T), _ptr(dX), _ptr(d_ds), _ptr(d_dz), _ptr(workspace),
+                                   int(workspace_bytes_), _stream(stream)), "peqa_linear_bwd_z")
 
 
 def scale_update(n_scales, ds, d_ds, m, v, s0, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, step=1,

@@ -103,6 +103,34 @@ class GpuLayer:
         return dX, dds
 
 
+    def fwd_z(self, X_bits, ds=None, dz=None):
+        torch, peqa = self.torch, self.peqa
+        X = to_dev(X_bits) if isinstance(X_bits, np.ndarray) else X_bits
+        T = X.shape[0]
+        Y = torch.empty((T, self.N), dtype=torch.int16, device="cuda")
+        dsd = to_dev(np.ascontiguousarray(ds, np.float32)) if isinstance(ds, np.ndarray) else ds
+        dzd = to_dev(np.ascontiguousarray(dz, np.float32)) if isinstance(dz, np.ndarray) else dz
+        ws, nb = self.workspace(T, peqa.PEQA_OP_FWD_Z)
+        peqa.linear_fwd_z(self.L, self.packed, self.s0, dsd, self.z0, dzd, X, T, Y, ws, nb)
+        torch.cuda.synchronize()
+        return Y
+
+    def bwd_z(self, X_bits, dY_bits, ds=None, dz=None, want_dX=True, want_dds=True, want_ddz=True):
+        torch, peqa = self.torch, self.peqa
+        X = to_dev(X_bits) if isinstance(X_bits, np.ndarray) else X_bits
+        dY = to_dev(dY_bits) if isinstance(dY_bits, np.ndarray) else dY_bits
+        T = dY.shape[0]
+        dX = torch.empty((T, self.K), dtype=torch.int16, device="cuda") if want_dX else None
+        dds = torch.empty((self.N, self.G), dtype=torch.float32, device="cuda") if want_dds else None
+        ddz = torch.empty((self.N, self.G), dtype=torch.float32, device="cuda") if want_ddz else None
+        dsd = to_dev(np.ascontiguousarray(ds, np.float32)) if isinstance(ds, np.ndarray) else ds
+        dzd = to_dev(np.ascontiguousarray(dz, np.float32)) if isinstance(dz, np.ndarray) else dz
+        ws, nb = self.workspace(T, peqa.PEQA_OP_BWD_Z)
+        peqa.linear_bwd_z(self.L, self.packed, self.s0, dsd, self.z0, dzd, X, dY, T, dX, dds, ddz, ws, nb)
+        torch.cuda.synchronize()
+        return dX, dds, ddz
+
+
 def bf16_dev_to_f64(t):
     from paper_2305_14152_amd import synth
     return synth.bf16_bits_to_f32(to_host(t).view(np.uint16)).astype(np.float64)

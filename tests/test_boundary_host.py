@@ -107,7 +107,7 @@ def test_kept_product_validation_needs_no_device(peqa):
     assert peqa.workspace_bytes(L, 100, peqa.PEQA_OP_BWD_KEPT) >= 100 * 256 * 2 + 2 * 256 * 4
     assert peqa.workspace_bytes(Lg, 100, peqa.PEQA_OP_FWD_KEEP) == 0
     assert peqa.workspace_bytes(Lg, 100, peqa.PEQA_OP_BWD_KEPT) == 0
-    assert peqa.workspace_bytes(L, 100, 4) == 0
+    assert peqa.workspace_bytes(L, 100, 9) == 0
     f = lib.peqa_linear_fwd_keep
     assert f(byref(Lg), good, good, None, good, good, 8, good, good, good, 1 << 20, None) == peqa.PEQA_ERR_GROUP
     assert f(byref(L), good, good, None, good, good, 8, good, None, good, 1 << 20, None) == peqa.PEQA_ERR_NULL
@@ -118,6 +118,25 @@ def test_kept_product_validation_needs_no_device(peqa):
     assert b(byref(L), good, good, None, good, None, good, 8, good, good, good, 1 << 30, None) == peqa.PEQA_ERR_NULL
     assert b(byref(L), good, good, None, good, good, None, 8, good, good, good, 1 << 30, None) == peqa.PEQA_ERR_NULL
     assert b(byref(L), good, good, None, good, good, good, 8, good, good, good, 64, None) == peqa.PEQA_ERR_WORKSPACE
+
+
+def test_zero_point_training_validation_needs_no_device(peqa):
+    L, Lg = peqa.layout(256, 256, 4), peqa.layout(256, 256, 4, 128)
+    good, bad = 0x10000, 0x10004
+    lib, byref = peqa.lib(), ctypes.byref
+    assert peqa.workspace_bytes(L, 100, peqa.PEQA_OP_FWD_Z) == peqa.workspace_bytes(L, 100, peqa.PEQA_OP_FWD)
+    for lay in (L, Lg):
+        assert peqa.workspace_bytes(lay, 100, peqa.PEQA_OP_BWD_Z) > peqa.workspace_bytes(lay, 100, peqa.PEQA_OP_BWD)
+    f = lib.peqa_linear_fwd_z
+    assert f(byref(L), good, good, None, good, bad, good, 8, good, good, 1 << 20, None) == peqa.PEQA_ERR_ALIGN
+    assert f(byref(L), good, good, None, good, good, None, 8, good, good, 1 << 20, None) == peqa.PEQA_ERR_NULL
+    assert f(byref(L), good, good, None, good, good, good, 8, good, good, 16, None) == peqa.PEQA_ERR_WORKSPACE
+    b = lib.peqa_linear_bwd_z
+    # the zero-point gradient needs X
+    assert b(byref(L), good, good, None, good, None, None, good, 8, None, None, good, good, 1 << 30, None) == peqa.PEQA_ERR_NULL
+    assert b(byref(L), good, good, None, good, None, good, good, 8, None, None, bad, good, 1 << 30, None) == peqa.PEQA_ERR_ALIGN
+    need = peqa.workspace_bytes(L, 8, peqa.PEQA_OP_BWD_Z)
+    assert b(byref(L), good, good, None, good, None, good, good, 8, good, good, good, good, need - 1, None) == peqa.PEQA_ERR_WORKSPACE
 
 
 def test_fused_forward_validation_needs_no_device(peqa):

@@ -240,6 +240,60 @@ def test_kept_product_training_parity(gpu, oracle, bits, N, K, T):
     assert none is None and (gpu.to_host(only_g) == gpu.to_host(ddsk)).all()
 
 
+@pytest.mark.parametrize("bits,N,K,T,group", [
+    (4, 384, 640, 200, 0),      # per-channel, tiled contraction
+    (3, 256, 896, 300, 0),
+    (4, 256, 512, 5, 0),        # matrix-vector forward
+    (3, 384, 768, 16, 128),
+    (4, 256, 1024, 150, 128),   # group-wise
+    (3, 384, 768, 130, 64),
+    (4, 256, 768, 70, 192),
+    (3, 128, 1408, 90, 128),    # 11 groups: two group chunks of the zero-point reduction, the second ragged
+])
+def test_zero_point_training_parity(gpu, oracle, bits, N, K, T, group):
+    """Zero-points z = z0 + dz as trainable parameters: forward, dX, scale and zero-point gradients."""
+    _log("zero-point training bits=%d N=%d K=%d T=%d g=%d" % (bits, N, K, T, group))
+    seed = 9500 + bits * 1000 + N + K + T + group
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dY = synth.normal_bf16(seed + 2, (T, N), 1.0)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, group)
+    ds = synth.normal_f32(seed + 3, s0.shape, 1.0) * 0.05 * s0
+    dz = synth.normal_f32(seed + 4, s0.shape, 0.5)
+    Y = gpu.bf16_dev_to_f64(layer.fwd_z(X, ds, dz))
+    Yref = oracle.fwd_z(codes, s0, ds, z0, dz, X, group)
+    assert np.abs(Y - Yref).max() <= Y_TOL * np.abs(Yref).max()
+    # without dz it is the plain forward, bit for bit
+    assert (gpu.to_host(layer.fwd_z(X, ds, None)) == gpu.to_host(layer.fwd(X, ds))).all()
+    dX, dds, ddz = layer.bwd_z(X, dY, ds, dz)
+    dXref, gs_ref, gz_ref = oracle.bwd_z(codes, s0, ds, z0, dz, X, dY, group)
+    assert np.abs(gpu.bf16_dev_to_f64(dX) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    gs = gpu.to_host(dds).astype(np.float64)
+    gz = gpu.to_host(ddz).astype(np.float64)
+    es = np.linalg.norm(gs - gs_ref) / np.linalg.norm(gs_ref)
+    ez = np.linalg.norm(gz - gz_ref) / np.linalg.norm(gz_ref)
+    _log("  rel-L2: d_ds %.2e  d_dz %.2e" % (es, ez))
+    assert es <= G_TOL and ez <= G_TOL
+    # the zero-point gradient alone (zero-points only, Appendix K), and it ignores dz
+    none_x, none_s, only_z = layer.bwd_z(X, dY, ds, None, want_dX=False, want_dds=False)
+    assert none_x is None and none_s is None
+    assert (gpu.to_host(only_z) == gpu.to_host(ddz)).all()
+    # one AdamW step on dz against the oracle's (no weight decay on zero-points)
+    import torch
+    dzd = gpu.to_dev(dz)
+    m = torch.zeros_like(dzd); v = torch.zeros_like(dzd)
+    from paper_2305_14152_amd import peqa
+    lr = float(np.float32(1e-2))
+    b1, b2, eps = (float(np.float32(x)) for x in (0.9, 0.999, 1e-8))
+    peqa.scale_update(dzd.numel(), dzd, ddz, m, v, layer.s0, lr=lr, step=1)
+    torch.cuda.synchronize()
+    n = dz.size
+    ref = oracle.adamw(dz.astype(np.float64).ravel(), gpu.to_host(ddz).astype(np.float64).ravel(), np.zeros(n),
+                       np.zeros(n), s0.astype(np.float64).ravel(), lr, b1, b2, eps, 0.0, 1)
+    assert np.abs(gpu.to_host(dzd).ravel() - ref[0]).max() <= 1e-6 * max(1.0, np.abs(ref[0]).max())
+
+
 def test_graph_capture_replays_match_eager(gpu, oracle):
     """Forward + backward captured in a HIP graph (the backward forks onto the library's second
     stream inside the capture): several replays, with eager work and synchronisation between them,

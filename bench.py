@@ -313,13 +313,14 @@ def main():
     tflops = flops_step / (dt / args.steps) / 1e12
 
     # per-kernel durations: the same steps again, every launch bracketed by HIP events
-    launches_per_step = len(layers) * 8
+    launches_per_step = len(layers) * 12
     peqa.trace_begin(launches_per_step * args.steps + 16)
     for _ in range(args.steps):
         step(use_graph=False)
     torch.cuda.synchronize()
     trace = peqa.trace_end(16)
-    gemm_flops = {"gemm_y": 0.0, "gemm_dds": 0.0, "gemm_dx": 0.0}
+    # gemm_dw: the scale gradient of group-wise layers (contraction over tokens), same 2 T N K flops
+    gemm_flops = {"gemm_y": 0.0, "gemm_dds": 0.0, "gemm_dx": 0.0, "gemm_dw": 0.0}
     for l in layers:
         for k in gemm_flops:
             gemm_flops[k] += 2.0 * T * l.N * l.K * args.steps

@@ -148,6 +148,9 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
  *   dX [T, K] bf16 out, or NULL to skip; d_ds [N, G] fp32 out (overwritten, not
  *   accumulated), or NULL to skip.  X may be NULL when d_ds is NULL.
  *   The result is deterministic (fixed reduction order, no atomics).
+ *   Group-wise layers take d_ds by the other order of the two sums,
+ *   d_ds[i,g] = sum_{k in g} (sum_t dY[t,i] X[t,k]) (Q[i,k] - z0[i,g]); their backward workspace
+ *   therefore also holds transposed copies of X and dY (2 (K + N) T' bytes, T' = T rounded up to 64).
  */
 peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const float *s0,
                             const float *ds, const uint8_t *z0, const uint16_t *X,

@@ -6,14 +6,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpeqa_hip.so")
-SOURCES = ["peqa_api.hip", "peqa_quantize.hip", "peqa_small.hip", "peqa_gemm.hip", "peqa_gemv.hip"]
+SOURCES = ["peqa_api.hip", "peqa_quantize.hip", "peqa_small.hip", "peqa_gemm.hip", "peqa_gemv.hip", "peqa_dw.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage"]
 # Kernels that queue global -> LDS DMA from inline assembly and count s_waitcnt vmcnt by hand: a
 # register spill would add scratch loads and stores (also counted by vmcnt) that the hand count does
 # not know about, so the build refuses any scratch use in them.
-NO_SCRATCH = ("gemm_kernel", "gemv_kernel")
+NO_SCRATCH = ("gemm_kernel", "gemv_kernel", "dw_kernel")
 
 
 def check_no_scratch(remarks):

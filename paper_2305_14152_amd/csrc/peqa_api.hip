@@ -24,7 +24,7 @@ inline int split_point(int n) { return (n / 2) / 64 * 64; }
 constexpr int PEQA_GEMV_MAX_T = 16;   // forward calls with at most this many tokens take the matrix-vector path
 
 struct Workspace {
-    size_t rs, dys, crow, partial, table, rsz, zpartial, total;
+    size_t rs, dys, crow, partial, table, rsz, zpartial, xt, dyt, pc, total;
 };
 
 // matrix-vector path: fp32 partials of the feature slices, for n_total output channels side by side
@@ -74,8 +74,13 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
         // group and per-(token tile, channel, group) partials for the scale gradient
         w.table = off;   off += round256(N * G * 2 * sizeof(float));
         if (op == PEQA_OP_BWD) {
+            const size_t Tp = ((size_t)T + 63) / 64 * 64, K = (size_t)L->k_in;
             w.rs = off;      off += round256((size_t)T * G * sizeof(float));
             w.partial = off; off += round256(tiles_t * N * G * sizeof(float));
+            // scale gradient by the token contraction: both operands transposed, per-chunk results
+            w.xt = off;      off += round256(K * Tp * sizeof(uint16_t));
+            w.dyt = off;     off += round256(N * Tp * sizeof(uint16_t));
+            w.pc = off;      off += round256(N * (K / 64) * sizeof(float));
         }
         w.total = off;
         return w;
@@ -136,6 +141,15 @@ struct Side {
 };
 constexpr int kMaxDevices = 64;
 Side g_side[kMaxDevices];
+
+// Scale gradient of group-wise layers: by the contraction over tokens (default), or, with
+// PEQA_GROUPED_DDS=pairs in the environment (read at every call), by the contraction over features, one
+// pair of scale groups per workgroup: the older, slower route, kept for comparison.
+bool grouped_dds_by_tokens()
+{
+    const char *e = getenv("PEQA_GROUPED_DDS");
+    return !(e && strcmp(e, "pairs") == 0);
+}
 
 Side *side_stream()
 {
@@ -437,7 +451,8 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     if (grouped(L)) {
         const int G = groups(L);
         float *rsb = reinterpret_cast<float *>(ws + w.rs);
-        if (d_ds || d_dz) {
+        const bool by_tokens = grouped_dds_by_tokens();
+        if ((d_ds && !by_tokens) || d_dz) {
             if (peqa::launch_rowsum_groups(X, T, K, L->group_size, rsb, s) != hipSuccess) return PEQA_ERR_DEVICE;
         }
         if (d_dz) {
@@ -445,7 +460,20 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
             if (peqa::launch_dz_partial(dY, rsb, T, N, G, zp, s) != hipSuccess) return PEQA_ERR_DEVICE;
             if (peqa::launch_dz_finish(zp, slices, (size_t)N * G, s0, ds, d_dz, s) != hipSuccess) return PEQA_ERR_DEVICE;
         }
-        if (d_ds) {
+        const int Tp = (T + 63) / 64 * 64;
+        if (d_ds && by_tokens) {
+            uint16_t *xt = reinterpret_cast<uint16_t *>(ws + w.xt), *dyt = reinterpret_cast<uint16_t *>(ws + w.dyt);
+            float *pc = reinterpret_cast<float *>(ws + w.pc);
+            if (peqa::launch_transpose_pad(X, T, K, Tp, xt, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (peqa::launch_transpose_pad(dY, T, N, Tp, dyt, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            peqa::DwArgs a{};
+            a.Xt = xt; a.dYt = dyt; a.packed = packed; a.z0 = z0; a.dz = dz; a.pc = pc;
+            a.N = N; a.K = K; a.Tp = Tp; a.gsz = L->group_size; a.G = G;
+            a.tiles_f = (K + 255) / 256; a.tiles_c = (N + 255) / 256;
+            if (peqa::launch_dw(L->bits, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (peqa::launch_chunk_reduce(pc, (size_t)N * G, L->group_size / 64, d_ds, s) != hipSuccess)
+                return PEQA_ERR_DEVICE;
+        } else if (d_ds) {
             float *partial = reinterpret_cast<float *>(ws + w.partial);
             peqa::GemmArgs a{};
             a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
@@ -597,7 +625,7 @@ struct TraceState {
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
-    "gemv_finish", "group_table", "dds_kept", "dz_partial", "dz_finish"};
+    "gemv_finish", "group_table", "dds_kept", "dz_partial", "dz_finish", "transpose_pad", "gemm_dw"};
 
 }  // namespace
 namespace {

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace peqa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -195,6 +197,35 @@ __device__ __forceinline__ f32x4 read_acc(const f32x4 &acc)
 __device__ __forceinline__ void mfma_result_fence()
 {
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
+
+// Global -> LDS DMA of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l.  The source
+// is sbase (uniform) + voff (per lane).  Issued from inline assembly so that the compiler does not
+// serialise the ring with a conservative vmcnt(0); completion is tracked by hand with wait_vmcnt().
+__device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t lds_dst)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
+}
+// Activation tiles sit in LDS as rows of 64 B (four 16-byte chunks).  Chunk j of row r is stored at
+// position j ^ a_swizzle(r): with it, the 16-byte reads of 8 (16) consecutive rows at one logical
+// chunk fall into 8 (16) different 16-byte bank groups of a 128 (256) byte LDS line.
+__device__ __forceinline__ int a_swizzle(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (N > 0) {
+        static_for<N - 1>(f);
+        f(std::integral_constant<int, N - 1>{});
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; other counters left open
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
 }  // namespace peqa

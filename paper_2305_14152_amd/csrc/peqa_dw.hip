@@ -1,0 +1,311 @@
+// Scale gradient of group-wise layers by the second route of the chain rule on Eq. 2:
+//
+//   dW[i,k]   = sum_t dY[t,i] X[t,k]                         (plain bf16 contraction over tokens)
+//   d_ds[i,g] = sum_{k in g} dW[i,k] (Q[i,k] - z[i,g])       (codes applied once, in the epilogue)
+//
+// The first route (contract X with the codes group by group, then reduce over tokens) restarts its
+// accumulators at every scale group: with 128 features per group a workgroup gets four steps of
+// contraction between a ring fill and an epilogue.  Here the contraction runs over all tokens without a
+// restart, no code is unpacked inside the loop, and the groups only appear in the epilogue.
+//
+// Both operands are needed with the token index contiguous, so X and dY are first transposed
+// (transpose_pad_kernel) into step-major arrays [Tp / 32][rows][32] (rows = K or N, Tp = T rounded up to
+// 64, zero-filled): the 64 bytes a row contributes to one 32-token step of the contraction sit next to
+// those of its neighbour rows, so a tile of 256 rows is 16 contiguous KB per step.  (With plain [rows][Tp]
+// arrays every 64-byte piece is half a cache line on its own, 2 Tp bytes from the next, and the loop
+// is bound by the request rate of the L2: measured 1.5 us per step against 0.5 us of matrix work.)
+//
+// dw_kernel: one workgroup = 4 waves = a 256 (features) x 256 (channels) tile of dW; waves 2 x 2, one per
+// SIMD, each a 128 x 128 accumulator (8 x 8 MFMA 16x16x32 tiles in 256 AGPRs).  Both operands come from
+// LDS here, and the LDS port is what bounds this loop: a 128 x 128 wave tile reads 256 B of fragments per
+// matrix instruction, a 64 x 128 one 384 B (measured: twice the matrix pipe's time per step).  A wave's
+// 128 features are two 64-feature chunks, the unit in which the epilogue reports (every group is a
+// whole number of chunks).  Operands go global -> LDS by DMA into a ring of 4 stages of 32 KB (one
+// 32-token step: 256 + 256 rows of 64 B, XOR-swizzled as in the other contraction kernel); fragments
+// for step it + 1 are read from LDS while step it's matrix instructions run.  The epilogue reads each
+// lane's codes straight from the packed array, forms sum dW Q - z sum dW over each chunk with two
+// shuffles, and writes pc[i, chunk]; chunk_reduce_kernel adds the chunks of every group in order.
+#include "peqa_device.h"
+#include "peqa_kernels.h"
+
+namespace peqa {
+
+namespace {
+
+constexpr int DW_TF = 256;                       // features per workgroup
+constexpr int DW_TC = 256;                       // channels per workgroup
+constexpr int DW_NST = 4;                        // ring depth
+constexpr int DW_A_BYTES = DW_TF * 64;           // 16 KB: 256 feature rows x 32 tokens
+constexpr int DW_STAGE = (DW_TF + DW_TC) * 64;   // 32 KB
+constexpr int DW_LDS = DW_NST * DW_STAGE;        // 128 KB
+#ifndef PEQA_DW_WM
+#define PEQA_DW_WM 4
+#endif
+constexpr int DW_WM = PEQA_DW_WM;                // waves along the features: see dw_kernel
+
+// Code of (channel row r, feature column cc) of one packed 8x8 block (the layout of peqa.h).
+template <int BITS>
+__device__ __forceinline__ uint32_t code_at(const uint32_t *blk, int r, int cc)
+{
+    if constexpr (BITS == 4) {
+        return (blk[r] >> (4 * ((cc >> 1) + 4 * (cc & 1)))) & 15u;
+    } else {
+        const int u = 4 * (r >> 1) + (cc >> 1), h = 16 * (cc & 1), par = r & 1;
+        if (u < 15) return (blk[2 * (u / 5) + par] >> (h + 3 * (u % 5))) & 7u;
+        const uint32_t b0 = (blk[par] >> (15 + h)) & 1u, b1 = (blk[2 + par] >> (15 + h)) & 1u,
+                       b2 = (blk[4 + par] >> (15 + h)) & 1u;
+        return b0 | (b1 << 1) | (b2 << 2);
+    }
+}
+
+// WM = waves along the features (2: 128 x 128 wave tiles, one wave per SIMD; 4: 64 x 128, two per SIMD)
+template <int BITS, int WM>
+__global__ __launch_bounds__(128 * WM, 1) void dw_kernel(DwArgs a)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    constexpr int WPB = 2 * BITS;
+    constexpr int NRT = 16 / WM;                           // accumulator row tiles per wave
+    constexpr int DW_DMA = 16 / WM;                        // DMA instructions per wave per step (32 of 1 KB per stage)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;              // feature part, channel half
+    const int c = lane & 15, q = lane >> 4;
+
+    // workgroup -> tile: the 32 workgroups that run together on one XCD take a patch of 4 feature tiles
+    // x 8 channel tiles, so that operand rows are shared through that XCD's L2
+    int tile_f, tile_c;
+    {
+        const int wg = blockIdx.x;
+        const int xcd = wg & 7, local = wg >> 3;
+        const int g = (local >> 5) * 8 + xcd, r = local & 31;
+        const int patches_f = (a.tiles_f + 3) / 4;
+        tile_f = (g % patches_f) * 4 + (r & 3);
+        tile_c = (g / patches_f) * 8 + (r >> 2);
+    }
+    if (tile_f >= a.tiles_f || tile_c >= a.tiles_c) return;   // padding of a ragged patch (uniform)
+
+    const int k0 = tile_f * DW_TF, n0 = tile_c * DW_TC;
+    const int nsteps = a.Tp >> 5;                          // even: Tp % 64 == 0
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+
+    // DMA j of wave w is wave-load d = DW_DMA w + j of the stage: 0..15 = feature rows 16 d .. + 15 of Xt,
+    // 16..31 = channel rows 16 (d - 16) .. of dYt.  Lane s lands at row s / 4, chunk position s % 4 and
+    // fetches the chunk that the swizzle assigns there.  Rows past the matrix are clamped to its last
+    // row: their products are computed and dropped.
+    uint32_t voff[DW_DMA];
+    const uint8_t *src = reinterpret_cast<const uint8_t *>(wave < WM ? a.Xt : a.dYt);
+    const size_t step_bytes = (size_t)(wave < WM ? a.K : a.N) * 64;   // one 32-token step of all rows
+    {
+        const int row_l = lane >> 2, pos = lane & 3;
+        const uint32_t chunk = (uint32_t)(pos ^ a_swizzle(row_l));
+        const int first = wave < WM ? k0 : n0, limit = (wave < WM ? a.K : a.N) - 1;
+#pragma unroll
+        for (int j = 0; j < DW_DMA; ++j) {
+            int row = first + 16 * (DW_DMA * (wave % WM) + j) + row_l;
+            row = row < limit ? row : limit;
+            voff[j] = (uint32_t)row * 64u + chunk * 16u;
+        }
+    }
+    auto issue_one = [&](int j, int it, int stage) {
+        const int s = it < nsteps ? it : nsteps - 1;       // the tail re-fetches the last step: constant DMA count
+        dma16(voff[j], src + (size_t)s * step_bytes, lds_base + stage * DW_STAGE + (DW_DMA * wave + j) * 1024);
+    };
+    auto issue = [&](int it, int stage) {
+#pragma unroll
+        for (int j = 0; j < DW_DMA; ++j) issue_one(j, it, stage);
+    };
+
+    f32x4 acc[NRT][8];
+#pragma unroll
+    for (int i = 0; i < NRT; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int sw = (q ^ a_swizzle(c)) << 4;
+    const int a_off = (16 * NRT * wm + c) * 64 + sw;       // + rt * 1024
+    const int b_off = DW_A_BYTES + (128 * wn + c) * 64 + sw;   // + ct * 1024
+    auto read_a = [&](int stage, int rt) {
+        return *reinterpret_cast<const u32x4 *>(lds + stage * DW_STAGE + a_off + rt * 1024);
+    };
+    auto read_b = [&](int stage, int ct) {
+        return *reinterpret_cast<const u32x4 *>(lds + stage * DW_STAGE + b_off + ct * 1024);
+    };
+
+    // ---- prologue: four stages queued; the first two complete before the first fragments are read
+    issue(0, 0);
+    issue(1, 1);
+    issue(2, 2);
+    issue(3, 3);
+    wait_vmcnt<2 * DW_DMA>();
+    __syncthreads();
+    u32x4 afrag[2][NRT], bfrag[8];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) afrag[0][rt] = read_a(0, rt);
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) bfrag[ct] = read_b(0, ct);
+    // step 0 refills stage 0: every wave must have taken its fragments out of it
+    __syncthreads();
+
+    // ---- main loop.  At the start of step `it` its fragments are in registers and stage it + 1 is
+    // complete and visible.  The step queues stage it + 4 into its own slot (its fragments left that slot
+    // during step it - 1, before the last barrier) while it runs its matrix instructions column tile by
+    // column tile, and refills every fragment from stage it + 1 right after its last use.  The closing
+    // wait leaves the DMAs of this step and the one before outstanding: stage it + 2 has landed, three
+    // steps after it was queued; the barrier makes it visible.
+    int cur = 0;
+    auto step = [&](int it, auto cur_c) {
+        constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+        const int nstage = (cur + 1) & (DW_NST - 1);
+        static_for<8>([&](auto ct_c) {
+            constexpr int ct = ct_c.value;
+            static_for<NRT>([&](auto rt_c) { mfma16_acc(acc[rt_c.value][ct], afrag[CUR][rt_c.value], bfrag[ct]); });
+            // the DMAs are spread over the step: queued in one burst after the barrier, they hold back the
+            // matrix instructions behind them until the memory pipe has taken all of them
+            if constexpr (ct % (8 / DW_DMA) == 0) issue_one(ct / (8 / DW_DMA), it + 4, cur);
+            bfrag[ct] = read_b(nstage, ct);
+            if constexpr (NRT == 8) afrag[NXT][ct] = read_a(nstage, ct);
+            else if constexpr ((ct & 1) == 1) afrag[NXT][ct >> 1] = read_a(nstage, ct >> 1);
+        });
+        wait_vmcnt<2 * DW_DMA>();
+        bare_barrier();
+        cur = nstage;
+    };
+    for (int it = 0; it < nsteps; it += 2) {
+        step(it, std::integral_constant<int, 0>{});
+        step(it + 1, std::integral_constant<int, 1>{});
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    mfma_result_fence();
+
+    // ---- epilogue: this wave's features are the chunks fb / 64 + h (accumulator rows rt = 4 h .. 4 h + 3);
+    // lane (c, q) holds, per accumulator tile (rt, ct), features fb + 16 rt + 4 q + j (j = 0..3) of
+    // channel cb + 16 ct + c
+    const int fb = k0 + 16 * NRT * wm, cb = n0 + 128 * wn;
+    if (cb >= a.N) return;                                 // wave-uniform (N % 128 == 0)
+    const int nchunks = a.K >> 6;
+    const size_t tile_row_words = (size_t)(a.K >> 5) * 64 * WPB;   // words per row of 128-channel tiles
+    static_for<NRT / 4>([&](auto h_c) {
+        constexpr int h = h_c.value;
+        const int fh = fb + 64 * h;
+        if (fh >= a.K) return;                             // wave-uniform (K % 64 == 0)
+        const int chunk = fh >> 6, grp = fh / a.gsz;
+        static_for<8>([&](auto ct_c) {
+            constexpr int ct = ct_c.value;
+            const int i = cb + 16 * ct + c;
+            const uint32_t *ch_tile = a.packed + (size_t)(i >> 7) * tile_row_words + (size_t)(((i >> 3) & 15) * 4) * WPB;
+            float s1 = 0.f, s0 = 0.f;
+            static_for<4>([&](auto r_c) {
+                constexpr int rt = 4 * h + r_c.value;
+                const f32x4 v = read_acc(acc[rt][ct]);
+                const int f = fb + 16 * rt + 4 * q;        // first of the lane's 4 features: one code block
+                const uint32_t *blk = ch_tile + (size_t)(f >> 5) * 64 * WPB + ((f >> 3) & 3) * WPB;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float code = (float)code_at<BITS>(blk, i & 7, (f & 7) + j);
+                    s1 += v[j] * code;
+                    s0 += v[j];
+                }
+            });
+            s1 += __shfl_xor(s1, 16); s0 += __shfl_xor(s0, 16);
+            s1 += __shfl_xor(s1, 32); s0 += __shfl_xor(s0, 32);
+            if (q == 0) {
+                const size_t sg = (size_t)i * a.G + grp;
+                const float z = (float)a.z0[sg] + (a.dz ? a.dz[sg] : 0.f);
+                a.pc[(size_t)i * nchunks + chunk] = s1 - z * s0;
+            }
+        });
+    });
+}
+
+// dst[t / 32][cc][t % 32] = src[t, cc] for t < T, 0 for T <= t < Tp.  64 x 64 tiles through LDS; C % 64 == 0.
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t *__restrict__ src, int T, int C, int Tp,
+                                                             uint16_t *__restrict__ dst)
+{
+    __shared__ uint16_t tile[64][64 + 2];
+    const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int ch = threadIdx.x & 7;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = (threadIdx.x >> 3) + 32 * h, t = t0 + row;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (t < T) v = *reinterpret_cast<const u32x4 *>(src + (size_t)t * C + c0 + 8 * ch);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            tile[row][8 * ch + 2 * e] = (uint16_t)(v[e] & 0xFFFFu);
+            tile[row][8 * ch + 2 * e + 1] = (uint16_t)(v[e] >> 16);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int cc = (threadIdx.x >> 3) + 32 * h;
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = (uint32_t)tile[8 * ch + 2 * e][cc] | ((uint32_t)tile[8 * ch + 2 * e + 1][cc] << 16);
+        const int t = t0 + 8 * ch;                        // 8 tokens of one 32-token step
+        *reinterpret_cast<u32x4 *>(dst + ((size_t)(t >> 5) * C + c0 + cc) * 32 + (t & 31)) = o;
+    }
+}
+
+// d_ds[i, g] = sum of pc[i, chunk] over the gsz / 64 chunks of group g, in order.
+__global__ __launch_bounds__(256) void chunk_reduce_kernel(const float *__restrict__ pc, size_t n, int per,
+                                                            float *__restrict__ d_ds)
+{
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;   // = i * G + g; the chunks of j are contiguous
+    if (j >= n) return;
+    float s = 0.f;
+    for (int e = 0; e < per; ++e) s += pc[j * per + e];
+    d_ds[j] = s;
+}
+
+constexpr int kMaxDev = 64;
+bool g_attr_done[2][kMaxDev];
+
+}  // namespace
+
+hipError_t launch_transpose_pad(const uint16_t *src, int T, int C, int Tp, uint16_t *dst, hipStream_t stream)
+{
+    trace_before(KID_TRANSPOSE, stream);
+    hipLaunchKernelGGL(transpose_pad_kernel, dim3(Tp / 64, C / 64), dim3(256), 0, stream, src, T, C, Tp, dst);
+    trace_after(KID_TRANSPOSE, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_dw(int bits, const DwArgs &a, hipStream_t stream)
+{
+    // what the kernel's indexing assumes
+    if (a.K % 64 != 0 || a.N % 128 != 0 || a.Tp % 64 != 0 || a.Tp < 64 || a.gsz % 64 != 0 || a.K % a.gsz != 0)
+        return hipErrorInvalidValue;
+    if ((uint64_t)(a.K > a.N ? a.K : a.N) * 64u >= ((uint64_t)1 << 32)) return hipErrorInvalidValue;   // 32-bit DMA offsets
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+    auto kern = bits == 4 ? dw_kernel<4, DW_WM> : dw_kernel<3, DW_WM>;
+    bool &done = g_attr_done[bits == 4][dev];
+    if (!done) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS);
+        if (e != hipSuccess) return e;
+        done = true;
+    }
+    // patches of 4 x 8 tiles, 32 workgroup ids per patch and XCD
+    const int patches_f = (a.tiles_f + 3) / 4, patches_c = (a.tiles_c + 7) / 8;
+    const int npatch = patches_f * patches_c;
+    const unsigned grid = (unsigned)(((npatch + 7) / 8) * 8 * 32);
+    trace_before(KID_GEMM_DW, stream);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(128 * DW_WM), DW_LDS, stream, a);
+    trace_after(KID_GEMM_DW, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_chunk_reduce(const float *pc, size_t n, int per, float *d_ds, hipStream_t stream)
+{
+    trace_before(KID_REDUCE, stream);
+    hipLaunchKernelGGL(chunk_reduce_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, pc, n, per, d_ds);
+    trace_after(KID_REDUCE, stream);
+    return hipGetLastError();
+}
+
+}  // namespace peqa

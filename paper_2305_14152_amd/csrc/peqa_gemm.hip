@@ -51,35 +51,6 @@ constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES > 128 * 1024 ? NSTAGE * STAGE_BYT
 constexpr int TBL_BYTES = 4 * 2 * 1024;                    // grouped MODE_Y / MODE_DX: 2 x 1 KB of (s, b) per (column half, contraction half);
                                                            // twice that for MODE_DX when groups end inside a 128-feature run
 
-// Global -> LDS DMA of 16 bytes per lane: lane l's bytes land at lds_dst + 16 l.  The source
-// is sbase (uniform) + voff (per lane).  Issued from inline assembly so that the compiler does not
-// serialise the ring with a conservative vmcnt(0); completion is tracked by hand with wait_vmcnt().
-__device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t lds_dst)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
-}
-// Activation tiles sit in LDS as rows of 64 B (four 16-byte chunks).  Chunk j of row r is stored at
-// position j ^ a_swizzle(r): with it, the 16-byte reads of 8 (16) consecutive rows at one logical
-// chunk fall into 8 (16) different 16-byte bank groups of a 128 (256) byte LDS line.
-__device__ __forceinline__ int a_swizzle(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
-
-template <int N, class F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (N > 0) {
-        static_for<N - 1>(f);
-        f(std::integral_constant<int, N - 1>{});
-    }
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; other counters left open
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
-}
-
 template <int BITS, int MODE, bool GROUPED>
 __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 {

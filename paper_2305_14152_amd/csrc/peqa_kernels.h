@@ -40,6 +40,23 @@ struct GemmArgs {
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
 
+// Arguments of the token contraction dW = dY^T X with the codes applied in its epilogue (peqa_dw.hip):
+// the scale gradient of group-wise layers.
+struct DwArgs {
+    const uint16_t *Xt;       // [Tp / 32, K, 32] bf16: X transposed in 32-token steps, tokens padded with zeros to Tp
+    const uint16_t *dYt;      // [Tp / 32, N, 32] bf16
+    const uint32_t *packed;   // packed codes of the layer
+    const uint8_t *z0;        // [N, G]
+    const float *dz;          // [N, G] or NULL
+    float *pc;                // [N, K / 64] out: sum over each 64-feature chunk of dW[i,k] (Q[i,k] - z[i,g(k)])
+    int N, K, Tp;             // Tp % 64 == 0
+    int gsz, G;               // group size (multiple of 64) and groups per channel
+    int tiles_f, tiles_c;     // ceil(K / 256), ceil(N / 256)
+};
+hipError_t launch_transpose_pad(const uint16_t *src, int T, int C, int Tp, uint16_t *dst, hipStream_t stream);
+hipError_t launch_dw(int bits, const DwArgs &a, hipStream_t stream);
+hipError_t launch_chunk_reduce(const float *pc, size_t n, int per, float *d_ds, hipStream_t stream);
+
 // Arguments of the T <= 16 forward (peqa_gemv.hip): up to GEMV_MAX_LAYERS layers that share X
 // (same K, bit width and group size), laid side by side along the output channels.
 constexpr int GEMV_MAX_LAYERS = 4;
@@ -94,7 +111,7 @@ void trace_after(int kernel_id, hipStream_t stream);
 
 enum {
     KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
-    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_DZ_PARTIAL, KID_DZ_FINISH, KID_COUNT
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_DZ_PARTIAL, KID_DZ_FINISH, KID_TRANSPOSE, KID_GEMM_DW, KID_COUNT
 };
 
 }  // namespace peqa

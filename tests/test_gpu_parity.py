@@ -294,6 +294,33 @@ def test_zero_point_training_parity(gpu, oracle, bits, N, K, T, group):
     assert np.abs(gpu.to_host(dzd).ravel() - ref[0]).max() <= 1e-6 * max(1.0, np.abs(ref[0]).max())
 
 
+@pytest.mark.parametrize("bits,N,K,T,group", [(4, 384, 768, 200, 128), (3, 256, 640, 130, 64), (3, 640, 512, 1, 256)])
+def test_groupwise_scale_gradient_both_routes(gpu, oracle, bits, N, K, T, group):
+    """The group-wise scale gradient by the contraction over tokens (default) and by the contraction over
+    features (PEQA_GROUPED_DDS=pairs, read at every call): each against the oracle."""
+    import os
+    _log("both routes bits=%d N=%d K=%d T=%d g=%d" % (bits, N, K, T, group))
+    seed = 9800 + bits * 1000 + N + K + T + group
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dY = synth.normal_bf16(seed + 2, (T, N), 1.0)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, group)
+    _, gref, _ = oracle.bwd(codes, s0, None, z0, X, dY, group, want_dX=False)
+    got = {}
+    for route in ("tokens", "pairs"):
+        os.environ["PEQA_GROUPED_DDS"] = route
+        try:
+            _, dds = layer.bwd(X, dY, None, want_dX=False)
+        finally:
+            del os.environ["PEQA_GROUPED_DDS"]
+        got[route] = gpu.to_host(dds).astype(np.float64)
+        err = np.linalg.norm(got[route] - gref) / np.linalg.norm(gref)
+        _log("  %s: rel-L2 %.2e" % (route, err))
+        assert err <= G_TOL
+    assert np.linalg.norm(got["tokens"] - got["pairs"]) <= 1e-4 * np.linalg.norm(gref)
+
+
 def test_graph_capture_replays_match_eager(gpu, oracle):
     """Forward + backward captured in a HIP graph (the backward forks onto the library's second
     stream inside the capture): several replays, with eager work and synchronisation between them,

@@ -163,8 +163,14 @@ __global__ __launch_bounds__(128 * WM, 1) void dw_kernel(DwArgs a)
             // matrix instructions behind them until the memory pipe has taken all of them
             if constexpr (ct % (8 / DW_DMA) == 0) issue_one(ct / (8 / DW_DMA), it + 4, cur);
             bfrag[ct] = read_b(nstage, ct);
-            if constexpr (NRT == 8) afrag[NXT][ct] = read_a(nstage, ct);
-            else if constexpr ((ct & 1) == 1) afrag[NXT][ct >> 1] = read_a(nstage, ct >> 1);
+            // the next step's first matrix instructions need all its row fragments: those are fetched in
+            // the first half of this step, so that only a column fragment is still on its way at the barrier
+            if constexpr (ct < 4) {
+                static_for<NRT / 4>([&](auto e_c) {
+                    constexpr int rt = ct * (NRT / 4) + e_c.value;
+                    afrag[NXT][rt] = read_a(nstage, rt);
+                });
+            }
         });
         wait_vmcnt<2 * DW_DMA>();
         bare_barrier();

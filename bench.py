@@ -154,10 +154,30 @@ def small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream, reps=20):
             run_fused()
         torch.cuda.synchronize()
         fused_us = (time.perf_counter() - t0) / (reps * nsets) * 1e6
+        # the same calls replayed as one HIP graph (how a decode loop would launch them)
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=torch.cuda.Stream()):
+            cap = torch.cuda.current_stream().cuda_stream
+            for packed_set in sets:
+                for grp in groups:
+                    items = [(layers[j].L, packed_set[j], layers[j].s0, layers[j].ds, layers[j].z0, layers[j].Y)
+                             for j in grp]
+                    peqa.linear_fwd_fused(items, layers[grp[0]].X, T, ws, ws_bytes, cap)
+        for _ in range(3):
+            gr.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            gr.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t0) / (reps * nsets) * 1e6
+        del gr
         out["T%d" % T] = {
             "fused_shared_x": {"calls_per_block": len(groups), "bytes_per_block": int(bytes_fused),
                                "block_us_wall": round(fused_us, 2), "GBs_wall": round(bytes_fused / fused_us / 1e3, 1),
-                               "frac_of_hbm_peak_wall": round(bytes_fused / fused_us / 1e3 / HBM_PEAK_GBS, 4)},
+                               "frac_of_hbm_peak_wall": round(bytes_fused / fused_us / 1e3 / HBM_PEAK_GBS, 4),
+                               "block_us_hip_graph": round(graph_us, 2),
+                               "frac_of_hbm_peak_hip_graph": round(bytes_fused / graph_us / 1e3 / HBM_PEAK_GBS, 4)},
             "bytes_per_block": int(bytes_block),
             "block_us_wall": round(wall_us, 2), "block_us_kernels": round(kern_us, 2),
             "block_us_gemv_kernel": round(main_us, 2),

@@ -82,3 +82,50 @@ def test_full_size_layer(gpu, oracle, cfg, li):
             Ys = gpu.bf16_dev_to_f64(layer.fwd(Xs, ds))
             Ysref = oracle.fwd(codes, s0, ds, z0, Xs, group)
             assert np.abs(Ys - Ysref).max() <= Y_TOL * np.abs(Ysref).max()
+
+
+@pytest.mark.parametrize("cfg,li", [(1, 1), (4, 1)])
+def test_full_size_variants(gpu, oracle, cfg, li):
+    """The optional paths at the benchmark's sizes, on sampled rows and channels: the kept-product
+    backward (per-channel workload) and trainable zero-points (both workloads)."""
+    c = synth.CONFIGS[cfg]
+    N, K, _ = c["layers"][li]
+    bits, group, T = c["bits"], c["group"], c["T"]
+    print("full size variants cfg=%d layer=%d N=%d K=%d T=%d bits=%d g=%d" % (cfg, li, N, K, T, bits, group), flush=True)
+    rng = np.random.default_rng(2000 * cfg + li)
+    W = synth.weights(cfg, li)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = oracle.quantize(W, bits, group)
+    del W
+    layer.W0 = None
+    X = synth.activations(cfg, li)
+    dY = synth.output_grads(cfg, li)
+    ds = synth.normal_f32(78 + cfg, s0.shape, 1e-3 * float(np.mean(s0)))
+    dz = synth.normal_f32(79 + cfg, s0.shape, 0.4)
+    ts = _sample(T, (128, 1024), rng, 3)
+    ns = _sample(N, (128, 256, N // 2), rng, 8)
+    dYn = np.ascontiguousarray(dY[:, ns])
+
+    # trainable zero-points
+    Y = gpu.bf16_dev_to_f64(layer.fwd_z(X, ds, dz))
+    Yref = oracle.fwd_z(codes[ns], s0[ns], ds[ns], z0[ns], dz[ns], X[ts], group)
+    assert np.abs(Y[np.ix_(ts, ns)] - Yref).max() <= Y_TOL * np.abs(Yref).max()
+    dX, dds, ddz = layer.bwd_z(X, dY, ds, dz)
+    dXref, _, _ = oracle.bwd_z(codes, s0, ds, z0, dz, X[ts], dY[ts], group)
+    assert np.abs(gpu.bf16_dev_to_f64(dX)[ts] - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    _, gs_ref, gz_ref = oracle.bwd_z(codes[ns], s0[ns], ds[ns], z0[ns], dz[ns], X, dYn, group, want_dX=False)
+    gs = gpu.to_host(dds).astype(np.float64)[ns]
+    gz = gpu.to_host(ddz).astype(np.float64)[ns]
+    assert np.linalg.norm(gs - gs_ref) <= G_TOL * np.linalg.norm(gs_ref)
+    assert np.linalg.norm(gz - gz_ref) <= G_TOL * np.linalg.norm(gz_ref)
+
+    if group == 0:
+        # kept product: P on the sampled entries, the scale gradient of the sampled channels from it
+        Yk, P = layer.fwd_keep(X, ds)
+        Pref = oracle.fwd(codes[ns], np.ones_like(s0[ns]), None, z0[ns], X[ts], 0)
+        Ph = gpu.to_host(P).astype(np.float64)[np.ix_(ts, ns)]
+        assert np.abs(Ph - Pref).max() <= 1e-5 * np.abs(Pref).max()
+        _, ddsk = layer.bwd_kept(P, dY, ds, want_dX=False)
+        _, gref, _ = oracle.bwd(codes[ns], s0[ns], ds[ns], z0[ns], X, dYn, 0, want_dX=False)
+        gk = gpu.to_host(ddsk).astype(np.float64)[ns]
+        assert np.linalg.norm(gk - gref) <= G_TOL * np.linalg.norm(gref)

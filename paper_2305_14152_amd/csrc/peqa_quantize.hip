@@ -6,9 +6,15 @@
 // and assembles whole packed words in LDS so that they leave in runs of 4 blocks (a tile row).
 // HBM-bound: 4 N K bytes in, N K b / 8 bytes out.
 //
-// Every fp32 step below is a single IEEE operation (correctly rounded divide, no
-// reciprocal, no fused multiply-add), because the codes must match the definition bit
-// for bit.
+// Every fp32 step below is a single IEEE operation (correctly rounded divide, no fused
+// multiply-add), because the codes must match the definition bit for bit.  The one divide per
+// weight, w / s, is the exception in form only: it is taken as (float)((double)w * rs) with
+// rs = 1.0 / (double)s formed once per scale by a correctly rounded fp64 divide.  That product is
+// within 2^-52 (relative) of the true quotient, while the quotient of two fp32 numbers is never
+// closer than 2^-49 (relative) to a point midway between two fp32 numbers (w - m s is a non-zero
+// multiple of the last bit of a 49-bit product), so rounding it to fp32 gives the correctly
+// rounded fp32 quotient: the same bits, at a third of the instructions (the correctly rounded fp32
+// divide sequence made this kernel ALU-bound at 2.2 TB/s).
 #include "peqa_device.h"
 #include "peqa_kernels.h"
 
@@ -80,6 +86,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
         if (j < nb) {
             const int k = k0 + 8 * j, g = k / gs;
             const float s = s_s[r * G + g];
+            const double rs = 1.0 / (double)s;
             const int z = s_z[r * G + g];
             const f32x4 va = *reinterpret_cast<const f32x4 *>(row + k);
             const f32x4 vb = *reinterpret_cast<const f32x4 *>(row + k + 4);
@@ -87,7 +94,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
             uint32_t qv[8];
 #pragma unroll
             for (int cidx = 0; cidx < 8; ++cidx) {
-                int q = (int)rintf(__fdiv_rn(w[cidx], s)) + z;
+                int q = (int)rintf((float)((double)w[cidx] * rs)) + z;
                 q = q < 0 ? 0 : (q > qmax ? qmax : q);
                 qv[cidx] = (uint32_t)q;
             }
@@ -130,6 +137,176 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
     }
 }
 
+// The same quantizer with the eight rows of a workgroup held in registers between the range pass and
+// the code pass, so that W0 is read from memory once: 1024 threads, 128 per channel row, thread
+// (r, l) keeps the 4-float vectors l, l + 128, ... (NV of them) of row r.  Arithmetic per element is
+// that of quantize_kernel, operation for operation.  Serves K <= 512 NV.
+template <int BITS, int NV>
+__global__ __launch_bounds__(1024) void quantize_resident_kernel(const float *__restrict__ W0, int K, int gs, int G,
+                                                                  uint32_t *__restrict__ packed,
+                                                                  float *__restrict__ s0, uint8_t *__restrict__ z0)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    // [8][G] each: bits of max(w, 0), bits of max(-w, 0) (non-negative floats order like their bit
+    // patterns, so the range reduction is an integer max: exact and order-free), then s and z
+    uint32_t *s_max = reinterpret_cast<uint32_t *>(smem);
+    uint32_t *s_neg = s_max + 8 * G;
+    float *s_s = reinterpret_cast<float *>(s_neg + 8 * G);
+    int *s_z = reinterpret_cast<int *>(s_s + 8 * G);
+    double *s_rs = reinterpret_cast<double *>(s_z + 8 * G);             // [8][G] 1 / s in fp64
+    uint32_t *s_codes = reinterpret_cast<uint32_t *>(s_rs + 8 * G);      // [8][K / 4] words = one byte per code
+
+    constexpr int qmax = (1 << BITS) - 1;
+    constexpr int WPB = 2 * BITS;
+    const int tid = threadIdx.x, r = tid >> 7, l = tid & 127;
+    const int ib = blockIdx.x;
+    const int K4 = K >> 2;
+    const f32x4 *row = reinterpret_cast<const f32x4 *>(W0 + (size_t)(ib * 8 + r) * K);
+
+    f32x4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int k4 = l + 128 * i;
+        v[i] = k4 < K4 ? row[k4] : f32x4{0.f, 0.f, 0.f, 0.f};      // zeros are neutral: the range always holds 0
+    }
+    for (int e = tid; e < 16 * G; e += 1024) s_max[e] = 0u;          // s_max and s_neg
+    __syncthreads();
+
+    // ---- range per (channel, group): 16 lanes hold 64 consecutive features, always of one group
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        float xmax = 0.f, xneg = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (v[i][e] > xmax) xmax = v[i][e];
+            if (-v[i][e] > xneg) xneg = -v[i][e];
+        }
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) {
+            const float a = __shfl_xor(xmax, o), b = __shfl_xor(xneg, o);
+            if (a > xmax) xmax = a;
+            if (b > xneg) xneg = b;
+        }
+        const int k4 = l + 128 * i;
+        if ((l & 15) == 0 && k4 < K4) {
+            const int g = (4 * k4) / gs;
+            atomicMax(&s_max[r * G + g], __float_as_uint(xmax));
+            atomicMax(&s_neg[r * G + g], __float_as_uint(xneg));
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < 8 * G; e += 1024) {
+        const float xmax = __uint_as_float(s_max[e]);
+        const float xneg = __uint_as_float(s_neg[e]);
+        const float xmin = xneg > 0.f ? -xneg : 0.f;
+        const float range = __fsub_rn(xmax, xmin);
+        float s = __fdiv_rn(range, (float)qmax);
+        int z;
+        if (!(s > 0.f)) {
+            s = 1.f;
+            z = 0;
+        } else {
+            z = (int)rintf(__fdiv_rn(-xmin, s));
+            z = z < 0 ? 0 : (z > qmax ? qmax : z);
+        }
+        s_s[e] = s;
+        s_z[e] = z;
+        s_rs[e] = 1.0 / (double)s;
+        const int rr = e / G, g = e - rr * G;
+        s0[(size_t)(ib * 8 + rr) * G + g] = s;
+        z0[(size_t)(ib * 8 + rr) * G + g] = (uint8_t)z;
+    }
+    __syncthreads();
+
+    // ---- codes of all eight rows into LDS (one byte per code, [8][K]), then the packed words
+    const size_t out_row = (size_t)(ib / 16) * (K / 32) * 64 + (size_t)(ib % 16) * 4;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int k4 = l + 128 * i;
+        if (k4 < K4) {
+            const int g = (4 * k4) / gs;
+            const double rs = s_rs[r * G + g];
+            const int z = s_z[r * G + g];
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int q = (int)rintf((float)((double)v[i][e] * rs)) + z;
+                q = q < 0 ? 0 : (q > qmax ? qmax : q);
+                w |= (uint32_t)q << (8 * e);
+            }
+            s_codes[r * K4 + k4] = w;
+        }
+    }
+    __syncthreads();
+    const int nwords = (K >> 3) * WPB;                               // packed words of this row of blocks
+    for (int e = tid; e < nwords; e += 1024) {
+        const int kb = e / WPB, wi = e % WPB;
+        uint32_t word = 0;
+        if constexpr (BITS == 4) {
+            // word wi = channel wi of the block: nibble cc / 2 + 4 (cc % 2) holds feature cc
+            const uint32_t lo = s_codes[wi * K4 + 2 * kb], hi = s_codes[wi * K4 + 2 * kb + 1];
+#pragma unroll
+            for (int cc = 0; cc < 8; ++cc) {
+                const uint32_t q = ((cc < 4 ? lo : hi) >> (8 * (cc & 3))) & 0xFFu;
+                word |= q << (4 * (cc / 2 + 4 * (cc % 2)));
+            }
+        } else {
+            const uint8_t *codes = reinterpret_cast<const uint8_t *>(s_codes);   // [8][K]
+            const int m = wi >> 1, par = wi & 1;
+            auto code = [&](int ch, int cc) { return (uint32_t)codes[(size_t)ch * K + 8 * kb + cc]; };
+#pragma unroll
+            for (int f = 0; f < 5; ++f) {
+                const int u = 5 * m + f;
+                if (u < 15) {
+                    const int ch = 2 * (u >> 2) + par, pr = u & 3;
+                    word |= code(ch, 2 * pr) << (3 * f);
+                    word |= code(ch, 2 * pr + 1) << (16 + 3 * f);
+                }
+            }
+            word |= ((code(6 + par, 6) >> m) & 1u) << 15;
+            word |= ((code(6 + par, 7) >> m) & 1u) << 31;
+        }
+        packed[(out_row + (size_t)(kb >> 2) * 64 + (kb & 3)) * WPB + wi] = word;
+    }
+}
+
+constexpr int kMaxDevQ = 64;
+
+template <int BITS, int NV>
+hipError_t launch_resident(const float *W0, int N, int K, int gs, int G, uint32_t *packed, float *s0, uint8_t *z0,
+                           hipStream_t stream)
+{
+    static int attr_bytes[kMaxDevQ];                                  // dynamic LDS allowed so far, per device
+    const size_t smem = (size_t)48 * G * 4 + (size_t)8 * K;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevQ) return hipErrorInvalidDevice;
+    if (smem > 48 * 1024 && (int)smem > attr_bytes[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(quantize_resident_kernel<BITS, NV>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_bytes[dev] = (int)smem;
+    }
+    hipLaunchKernelGGL((quantize_resident_kernel<BITS, NV>), dim3(N / 8), dim3(1024), smem, stream, W0, K, gs, G, packed,
+                       s0, z0);
+    return hipSuccess;
+}
+
+// true if a register-resident instantiation took the call (K <= 12288 and the LDS need fits)
+template <int BITS>
+bool launch_resident_for(const float *W0, int N, int K, int gs, int G, uint32_t *packed, float *s0, uint8_t *z0,
+                         hipStream_t stream, hipError_t *err)
+{
+    if ((size_t)48 * G * 4 + (size_t)8 * K > 150 * 1024) return false;
+    const int nv = (K + 511) / 512;
+    if (nv <= 8) *err = launch_resident<BITS, 8>(W0, N, K, gs, G, packed, s0, z0, stream);
+    else if (nv <= 16) *err = launch_resident<BITS, 16>(W0, N, K, gs, G, packed, s0, z0, stream);
+    else if (nv <= 24) *err = launch_resident<BITS, 24>(W0, N, K, gs, G, packed, s0, z0, stream);
+    else return false;
+    return true;
+}
+
 }  // namespace
 
 hipError_t launch_quantize(const float *W0, int N, int K, int bits, int group, uint32_t *packed, float *s0,
@@ -138,7 +315,13 @@ hipError_t launch_quantize(const float *W0, int N, int K, int bits, int group, u
     const int gs = group > 0 ? group : K, G = K / gs;
     const size_t smem = (size_t)16 * G * 4 + 2048;
     trace_before(KID_QUANTIZE, stream);
-    if (bits == 4)
+    // rows up to 12288 features stay in registers between the two passes; longer ones are read twice
+    hipError_t err = hipSuccess;
+    const bool resident = bits == 4 ? launch_resident_for<4>(W0, N, K, gs, G, packed, s0, z0, stream, &err)
+                                    : launch_resident_for<3>(W0, N, K, gs, G, packed, s0, z0, stream, &err);
+    if (resident) {
+        if (err != hipSuccess) return err;
+    } else if (bits == 4)
         hipLaunchKernelGGL(quantize_kernel<4>, dim3(N / 8), dim3(256), smem, stream, W0, K, gs, G, packed, s0, z0);
     else
         hipLaunchKernelGGL(quantize_kernel<3>, dim3(N / 8), dim3(256), smem, stream, W0, K, gs, G, packed, s0, z0);

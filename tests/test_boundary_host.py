@@ -160,3 +160,31 @@ def test_product_package_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower() or f == "synth.py", f
+
+
+def test_fp64_reciprocal_product_is_the_correctly_rounded_fp32_quotient():
+    """The quantize kernels take w / s as (float)((double)w * (1.0 / (double)s)).  The identity with the
+    correctly rounded fp32 divide (what Eq. 1's reference arithmetic uses) is checked here on the host:
+    random operands over many binades, the operand ranges the quantizer sees, and quotients placed next
+    to points midway between two fp32 numbers."""
+    rng = np.random.default_rng(2024)
+
+    def check(w, s):
+        w = w.astype(np.float32)
+        s = s.astype(np.float32)
+        ref = w / s                                                   # IEEE fp32 divide
+        alt = (w.astype(np.float64) * (1.0 / s.astype(np.float64))).astype(np.float32)
+        bad = np.nonzero(ref.view(np.uint32) != alt.view(np.uint32))[0]
+        assert bad.size == 0, (w[bad[:3]], s[bad[:3]])
+
+    n = 2_000_000
+    check(rng.standard_normal(n) * 0.02, np.abs(rng.standard_normal(n)) * 0.01 + 1e-4)
+    check(np.ldexp(rng.uniform(1, 2, n), rng.integers(-60, 60, n)) * rng.choice([-1.0, 1.0], n),
+          np.ldexp(rng.uniform(1, 2, n), rng.integers(-60, 60, n)))
+    # quotients as close to a midpoint as fp32 operands allow: w = fl(m * s) for 25-bit odd m
+    m = (rng.integers(1 << 23, 1 << 24, n).astype(np.float64) * 2 + 1) / (1 << 24)      # 25 significant bits
+    s = rng.integers(1 << 23, 1 << 24, n).astype(np.float64) / (1 << 23)
+    for nudge in (0, 1, -1):
+        w = (m * s).astype(np.float32)
+        w = (w.view(np.int32) + nudge).view(np.float32)
+        check(w, s)

@@ -221,6 +221,17 @@ def kept_product(torch, peqa, layers, cfg, stream, steps):
             "kept_bytes": int(sum(P.numel() * 4 for P in Ps))}
 
 
+def device_info(torch):
+    """What the run saw of the device, and the denominators the fractions above use."""
+    p = torch.cuda.get_device_properties(0)
+    clock_khz = getattr(p, "clock_rate", None)
+    return {"name": p.name, "compute_units": p.multi_processor_count,
+            "max_clock_mhz": round(clock_khz / 1e3) if clock_khz else None,
+            "hbm_bytes": p.total_memory,
+            "mfma_peak_used": "2500 TFLOP/s dense bf16 (published; 256 CUs x 4096 flop/clk x 2.4 GHz = 2517)",
+            "hbm_peak_used": "8000 GB/s (published)"}
+
+
 def cpu_baseline(cfg, seconds):
     """The oracle as it stands, on a bounded sample: the first layer shape of the workload,
     forward + dX + scale gradient on a few token rows (rows are independent for Y and dX, and the
@@ -384,6 +395,7 @@ def main():
                   "then %d direct scale updates" % (len(groups), len(layers), len(layers)),
         "kernels": kernels,
         "roofline": roofline,
+        "device": device_info(torch),
     }
     if small is not None:
         out["small_batch"] = small

@@ -119,6 +119,87 @@ int oracle_quantize(const float *W0, int N, int K, int bits, int group,
     return 0;
 }
 
+/* Sec. 3.2 initialises s0, z0 "to minimize ||W0 - What0||_F" but gives no procedure
+ * (the experiments use plain round-to-nearest).  The usual procedure is a grid search over
+ * clipped ranges, which is what this function states: for every (channel, group) and every
+ * ratio r_j = 1 - j * step, step = (1 - min_ratio) / (n_ratios - 1), j = 0 .. n_ratios - 1
+ * (r_0 = 1 is Eq. 1 as it stands):
+ *   lo = r_j * xmin,  hi = r_j * xmax,  s = (hi - lo) / (2^b - 1),  z = rint(-lo / s),
+ *   Q = clamp(rint(w / s) + z, 0, 2^b - 1)            (the degenerate rule as in Eq. 1)
+ *   err_j = sum_k (w - s * (Q - z))^2
+ * and the candidate with the smallest err_j (the first of equal ones) is kept.
+ * Every step that decides a code is one fp32 operation, as in oracle_quantize; the residual
+ * w - s * (Q - z) is formed in fp32 (one multiply, one subtract), squared and summed in fp64.
+ * choice[N*G] (may be NULL) receives the index j that was kept. */
+int oracle_quantize_search(const float *W0, int N, int K, int bits, int group,
+                           int n_ratios, float min_ratio,
+                           uint8_t *codes, float *s0, uint8_t *z0, int *choice)
+{
+    int rc = check_layout(N, K, bits, group);
+    if (rc) return rc;
+    if (n_ratios < 1 || !(min_ratio > 0.0f) || min_ratio > 1.0f) return 5;
+    const int G = groups_of(K, group), gs = gsize_of(K, group);
+    const int qmax = (1 << bits) - 1;
+    volatile float span = 1.0f - min_ratio;
+    volatile float step = n_ratios > 1 ? span / (float)(n_ratios - 1) : 0.0f;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < N; ++i) {
+        for (int g = 0; g < G; ++g) {
+            const float *w = W0 + (size_t)i * K + (size_t)g * gs;
+            float xmin = 0.0f, xmax = 0.0f;
+            for (int k = 0; k < gs; ++k) {
+                if (w[k] < xmin) xmin = w[k];
+                if (w[k] > xmax) xmax = w[k];
+            }
+            double best_err = 0.0;
+            float best_s = 1.0f;
+            int best_z = 0, best_j = -1;
+            for (int j = 0; j < n_ratios; ++j) {
+                volatile float jf = (float)j * step;
+                volatile float r = 1.0f - jf;
+                volatile float lo = r * xmin;
+                volatile float hi = r * xmax;
+                volatile float range = hi - lo;
+                volatile float s = range / (float)qmax;
+                int z;
+                if (!(s > 0.0f)) {
+                    s = 1.0f;
+                    z = 0;
+                } else {
+                    volatile float zr = -lo / s;
+                    z = (int)rintf(zr);
+                    if (z < 0) z = 0;
+                    if (z > qmax) z = qmax;
+                }
+                double err = 0.0;
+                for (int k = 0; k < gs; ++k) {
+                    volatile float t = w[k] / s;
+                    int q = (int)rintf(t) + z;
+                    if (q < 0) q = 0;
+                    if (q > qmax) q = qmax;
+                    volatile float back = s * (float)(q - z);
+                    volatile float d = w[k] - back;
+                    err += (double)d * (double)d;
+                }
+                if (best_j < 0 || err < best_err) {
+                    best_err = err; best_s = s; best_z = z; best_j = j;
+                }
+            }
+            s0[(size_t)i * G + g] = best_s;
+            z0[(size_t)i * G + g] = (uint8_t)best_z;
+            if (choice) choice[(size_t)i * G + g] = best_j;
+            for (int k = 0; k < gs; ++k) {
+                volatile float t = w[k] / best_s;
+                int q = (int)rintf(t) + best_z;
+                if (q < 0) q = 0;
+                if (q > qmax) q = qmax;
+                codes[(size_t)i * K + (size_t)g * gs + k] = (uint8_t)q;
+            }
+        }
+    }
+    return 0;
+}
+
 /* The same quantizer evaluated in fp64 throughout: a sanity shadow of the
  * fp32 definition above (not a parity criterion).  s0 is returned as double. */
 int oracle_quantize_f64(const float *W0, int N, int K, int bits, int group,

@@ -74,6 +74,22 @@ def quantize(W0, bits, group=0):
     return codes, s0, z0
 
 
+def quantize_search(W0, bits, group=0, n_ratios=20, min_ratio=0.5):
+    """Error-minimising initialisation over a grid of clipped ranges.  Returns (codes, s0, z0, choice)."""
+    W0 = np.ascontiguousarray(W0, dtype=np.float32)
+    N, K = W0.shape
+    G = num_groups(K, group)
+    codes = np.empty((N, K), np.uint8)
+    s0 = np.empty((N, G), np.float32)
+    z0 = np.empty((N, G), np.uint8)
+    choice = np.empty((N, G), np.int32)
+    f = lib().oracle_quantize_search
+    f.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 5 + [ctypes.c_float] + [ctypes.c_void_p] * 4
+    _chk(f(_p(W0), N, K, bits, group, int(n_ratios), float(min_ratio), _p(codes), _p(s0), _p(z0), _p(choice)),
+         "quantize_search")
+    return codes, s0, z0, choice
+
+
 def quantize_f64(W0, bits, group=0):
     """fp64 shadow of the quantizer.  Returns (codes, s0 f64, z0, dist-to-tie f64)."""
     W0 = np.ascontiguousarray(W0, dtype=np.float32)

@@ -389,6 +389,80 @@ def test_scale_gradient_fd_two_routes_euler_and_independence(oracle, bits, group
 
 
 # ----------------------------------------------------------------------------
+# Error-minimising initialisation (Sec. 3.2: s0, z0 "to minimize ||W0 - What0||_F")
+# ----------------------------------------------------------------------------
+def _recon_error(oracle, W, codes, s0, z0, group):
+    """sum_k (w - s (Q - z))^2 per (channel, group), in fp64 from the returned parameters."""
+    What = oracle.dequant(codes, s0, None, z0, group)
+    N, K = W.shape
+    G = s0.shape[1]
+    return ((W.astype(np.float64) - What) ** 2).reshape(N, G, K // G).sum(axis=2)
+
+
+@pytest.mark.parametrize("bits,group", [(4, 0), (3, 0), (4, 64), (3, 128)])
+def test_search_invariants(oracle, bits, group):
+    N, K = 24, 256
+    r = np.random.default_rng(800 + bits + group)
+    W = (r.standard_normal((N, K)) * 0.02).astype(np.float32)
+    W[::5, ::37] *= 6.0                                              # some rows with outliers
+    plain = oracle.quantize(W, bits, group)
+    # a grid of one ratio, or of ratios that are all 1, is Eq. 1 itself
+    for n, m in ((1, 0.5), (4, 1.0)):
+        c, s, z, ch = oracle.quantize_search(W, bits, group, n, m)
+        assert (c == plain[0]).all() and (s.view(np.uint32) == plain[1].view(np.uint32)).all() and (z == plain[2]).all()
+        assert (ch == 0).all()
+    c, s, z, ch = oracle.quantize_search(W, bits, group, 24, 0.4)
+    assert c.max() <= 2 ** bits - 1 and ch.min() >= 0 and ch.max() < 24
+    e_search = _recon_error(oracle, W, c, s, z, group)
+    e_plain = _recon_error(oracle, W, *plain, group)
+    # candidate 0 is the plain range, so the search can only do better; with outliers it does
+    assert (e_search <= e_plain * (1 + 1e-12)).all()
+    assert (e_search < 0.9 * e_plain).any()
+    assert (ch > 0).any() and ((ch == 0) == (e_search == e_plain)).all()
+    # where the plain range was kept, the result is the plain one
+    keep = ch == 0
+    assert (s[keep].view(np.uint32) == plain[1][keep].view(np.uint32)).all() and (z[keep] == plain[2][keep]).all()
+    # exact scale invariance: W * 2^k gives the same codes and choices, s0 scaled by 2^k
+    c2, s2, z2, ch2 = oracle.quantize_search(W * np.float32(8.0), bits, group, 24, 0.4)
+    assert (c2 == c).all() and (z2 == z).all() and (ch2 == ch).all() and (s2 == s * np.float32(8.0)).all()
+    # the kept candidate's scale is the stated one: s = r_j (xmax - xmin) / qmax up to fp32 rounding
+    G = s.shape[1]
+    Wg = W.reshape(N, G, K // G)
+    rng_ = np.maximum(Wg.max(axis=2), 0).astype(np.float64) - np.minimum(Wg.min(axis=2), 0).astype(np.float64)
+    ratio = 1.0 - ch * (0.6 / 23)
+    np.testing.assert_allclose(s, ratio * rng_ / (2 ** bits - 1), rtol=1e-5)
+
+
+def test_search_brute_force_tiny(oracle):
+    """Every candidate of a tiny layer evaluated with scalar numpy fp32 arithmetic in Python loops."""
+    bits, n, m = 3, 7, 0.5
+    qmax = 2 ** bits - 1
+    r = np.random.default_rng(5)
+    W = (r.standard_normal((128, 32)) * 0.05).astype(np.float32)
+    W[3, 7] = 1.0
+    _, s, z, ch = oracle.quantize_search(W, bits, 0, n, m)
+    f = np.float32
+    step = f(f(1.0) - f(m)) / f(n - 1)
+    for i in (0, 3, 64, 127):
+        xmin = min(f(0), W[i].min()); xmax = max(f(0), W[i].max())
+        errs = []
+        for j in range(n):
+            rj = f(1.0) - f(f(j) * step)
+            lo, hi = f(rj * xmin), f(rj * xmax)
+            sj = f(f(hi - lo) / f(qmax))
+            zj = int(min(max(np.rint(f(-lo / sj)), 0), qmax))
+            e = 0.0
+            for k in range(32):
+                q = int(min(max(int(np.rint(f(W[i, k] / sj))) + zj, 0), qmax))
+                d = f(W[i, k] - f(sj * f(q - zj)))
+                e += float(d) * float(d)
+            errs.append((e, sj, zj))
+        best = min(range(n), key=lambda j: (errs[j][0], j))
+        assert ch[i, 0] == best
+        assert s[i, 0] == errs[best][1] and z[i, 0] == errs[best][2]
+
+
+# ----------------------------------------------------------------------------
 # Trainable zero-points (Appendix K)
 # ----------------------------------------------------------------------------
 @pytest.mark.parametrize("bits,group", [(4, 0), (3, 16), (4, 8)])

@@ -104,6 +104,21 @@ peqa_status peqa_quantize(const peqa_layout *L, const float *W0, uint32_t *packe
                           float *s0, uint8_t *z0, void *stream);
 
 /*
+ * Error-minimising initialisation.  Sec. 3.2 asks for s0, z0 "to minimize ||W0 - What0||_F" without a
+ * procedure (the experiments use the plain range of Eq. 1); this is the usual grid over clipped ranges.
+ * For j = 0 .. n_ratios-1 with r_j = 1 - j * (1 - min_ratio) / (n_ratios - 1)  (r_0 = 1: Eq. 1 itself),
+ * every (channel, group) is quantized with the range [r_j xmin, r_j xmax] exactly as in peqa_quantize,
+ * and the candidate with the smallest sum_k (w - s (Q - z))^2 is kept (the first of equal ones).
+ * Residuals are formed in fp32 and their squares summed in fp64.  n_ratios = 1 equals peqa_quantize.
+ *   1 <= n_ratios <= 1024, 0 < min_ratio <= 1 (PEQA_ERR_PARAM otherwise);
+ *   supported where a row block fits on chip: K <= 12288 and 384 G + 9 K <= 153600 (PEQA_ERR_SHAPE).
+ *   Arguments as peqa_quantize.
+ */
+peqa_status peqa_quantize_search(const peqa_layout *L, const float *W0, int32_t n_ratios,
+                                 float min_ratio, uint32_t *packed, float *s0, uint8_t *z0,
+                                 void *stream);
+
+/*
  * Eq. 2 forward:  Y[t,i] = sum_k X[t,k] * (s0+ds)[i,g(k)] * (Q[i,k] - z0[i,g(k)]).
  *   ds may be NULL (= 0).  X [T, K] bf16 in, Y [T, N] bf16 out, T >= 1.
  *   bf16 operands, fp32 accumulation.  T <= 16 takes the bandwidth-bound

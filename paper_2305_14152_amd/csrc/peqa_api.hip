@@ -297,6 +297,22 @@ static peqa_status fwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     return fwd_per_channel(L, packed, s0, ds, z0, dz, X, T, Y, nullptr, rs, s);
 }
 
+peqa_status peqa_quantize_search(const peqa_layout *L, const float *W0, int32_t n_ratios, float min_ratio,
+                                 uint32_t *packed, float *s0, uint8_t *z0, void *stream)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (!W0 || !packed || !s0 || !z0) return PEQA_ERR_NULL;
+    if (n_ratios < 1 || n_ratios > 1024 || !(min_ratio > 0.f) || min_ratio > 1.f) return PEQA_ERR_PARAM;
+    if (!aligned16(W0) || !aligned16(packed) || !aligned16(s0) || !aligned16(z0)) return PEQA_ERR_ALIGN;
+    if (!peqa::quantize_resident_fits(L->k_in, groups(L), true)) return PEQA_ERR_SHAPE;
+    // the grid step, in fp32 as the definition has it
+    volatile float span = 1.0f - min_ratio;
+    volatile float step = n_ratios > 1 ? span / (float)(n_ratios - 1) : 0.0f;
+    return dev_status(peqa::launch_quantize_search(W0, L->n_out, L->k_in, L->bits, L->group_size, n_ratios, step,
+                                                   packed, s0, z0, static_cast<hipStream_t>(stream)));
+}
+
 peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
                             const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, void *workspace,
                             size_t workspace_bytes, void *stream)

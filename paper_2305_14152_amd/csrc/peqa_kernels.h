@@ -105,6 +105,11 @@ hipError_t launch_adamw(size_t n, float *ds, const float *g, float *m, float *v,
 hipError_t launch_quantize(const float *W0, int N, int K, int bits, int group, uint32_t *packed,
                            float *s0, uint8_t *z0, hipStream_t stream);
 
+// error-minimising variant (clipped-range grid); only where the rows fit in registers and LDS
+bool quantize_resident_fits(int K, int G, bool search);
+hipError_t launch_quantize_search(const float *W0, int N, int K, int bits, int group, int n_ratios, float step,
+                                  uint32_t *packed, float *s0, uint8_t *z0, hipStream_t stream);
+
 // Tracing hook: every launch goes through these so that peqa_trace_* can time it.
 void trace_before(int kernel_id, hipStream_t stream);
 void trace_after(int kernel_id, hipStream_t stream);

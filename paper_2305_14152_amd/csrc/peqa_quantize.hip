@@ -18,6 +18,12 @@
 #include "peqa_device.h"
 #include "peqa_kernels.h"
 
+// No fused multiply-add anywhere in this file: every product below is rounded before it is added or
+// subtracted, as the definition has it.  Products and differences are written with plain operators for
+// that reason: the __fmul_rn / __fsub_rn spellings are header functions compiled outside this pragma,
+// and the compiler fuses them (measured: scales one ulp off the definition).
+#pragma clang fp contract(off)
+
 namespace peqa {
 
 namespace {
@@ -60,7 +66,7 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
             if (b > xmax) xmax = b;
         }
         if (jl == 0) {
-            const float range = __fsub_rn(xmax, xmin);
+            const float range = xmax - xmin;
             float s = __fdiv_rn(range, (float)qmax);
             int z;
             if (!(s > 0.f)) {
@@ -141,10 +147,18 @@ __global__ __launch_bounds__(256) void quantize_kernel(const float *__restrict__
 // the code pass, so that W0 is read from memory once: 1024 threads, 128 per channel row, thread
 // (r, l) keeps the 4-float vectors l, l + 128, ... (NV of them) of row r.  Arithmetic per element is
 // that of quantize_kernel, operation for operation.  Serves K <= 512 NV.
-template <int BITS, int NV>
+//
+// SEARCH: the error-minimising initialisation of Sec. 3.2 over a grid of clipped ranges.  For ratio
+// r_j = 1 - j * step (j = 0 .. n_ratios - 1; r_0 = 1 is Eq. 1 as it stands) the range of every
+// (channel, group) becomes [r_j xmin, r_j xmax]; the candidate with the smallest
+// sum_k (w - s (Q - z))^2 is kept (the first of equal ones).  Residuals are formed in fp32 (one
+// multiply, one subtract), squared and summed in fp64: 16 lanes by shuffles, then the 64-feature
+// segments of a group in order, so the result does not depend on timing.
+template <int BITS, int NV, bool SEARCH>
 __global__ __launch_bounds__(1024) void quantize_resident_kernel(const float *__restrict__ W0, int K, int gs, int G,
                                                                   uint32_t *__restrict__ packed,
-                                                                  float *__restrict__ s0, uint8_t *__restrict__ z0)
+                                                                  float *__restrict__ s0, uint8_t *__restrict__ z0,
+                                                                  int n_ratios, float step)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     // [8][G] each: bits of max(w, 0), bits of max(-w, 0) (non-negative floats order like their bit
@@ -155,6 +169,12 @@ __global__ __launch_bounds__(1024) void quantize_resident_kernel(const float *__
     int *s_z = reinterpret_cast<int *>(s_s + 8 * G);
     double *s_rs = reinterpret_cast<double *>(s_z + 8 * G);             // [8][G] 1 / s in fp64
     uint32_t *s_codes = reinterpret_cast<uint32_t *>(s_rs + 8 * G);      // [8][K / 4] words = one byte per code
+    // SEARCH only: the best candidate so far per (channel, group), and the error sums per 64-feature segment
+    double *b_err = reinterpret_cast<double *>(s_codes + 2 * K);        // [8][G]
+    double *b_rs = b_err + 8 * G;
+    double *seg_err = b_rs + 8 * G;                                     // [8][K / 64]
+    float *b_s = reinterpret_cast<float *>(seg_err + (K >> 3));
+    int *b_z = reinterpret_cast<int *>(b_s + 8 * G);
 
     constexpr int qmax = (1 << BITS) - 1;
     constexpr int WPB = 2 * BITS;
@@ -195,11 +215,19 @@ __global__ __launch_bounds__(1024) void quantize_resident_kernel(const float *__
         }
     }
     __syncthreads();
-    for (int e = tid; e < 8 * G; e += 1024) {
+    // (s, z, 1 / s) of candidate j for entry e = r * G + g
+    auto candidate = [&](int e, int j) {
         const float xmax = __uint_as_float(s_max[e]);
         const float xneg = __uint_as_float(s_neg[e]);
-        const float xmin = xneg > 0.f ? -xneg : 0.f;
-        const float range = __fsub_rn(xmax, xmin);
+        float xmin = xneg > 0.f ? -xneg : 0.f;
+        float hi = xmax;
+        if constexpr (SEARCH) {
+            const float jstep = (float)j * step;
+            const float ratio = 1.f - jstep;
+            xmin = ratio * xmin;
+            hi = ratio * hi;
+        }
+        const float range = hi - xmin;
         float s = __fdiv_rn(range, (float)qmax);
         int z;
         if (!(s > 0.f)) {
@@ -212,11 +240,62 @@ __global__ __launch_bounds__(1024) void quantize_resident_kernel(const float *__
         s_s[e] = s;
         s_z[e] = z;
         s_rs[e] = 1.0 / (double)s;
-        const int rr = e / G, g = e - rr * G;
-        s0[(size_t)(ib * 8 + rr) * G + g] = s;
-        z0[(size_t)(ib * 8 + rr) * G + g] = (uint8_t)z;
-    }
+    };
+    for (int e = tid; e < 8 * G; e += 1024) candidate(e, 0);
     __syncthreads();
+    if constexpr (SEARCH) {
+        const int segs = K >> 6, per = gs >> 6;                          // segments per row / per group
+        for (int j = 0; j < n_ratios; ++j) {
+            // squared residuals of candidate j, this thread's vectors, summed over 16 lanes = one segment
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int k4 = l + 128 * i;
+                double err = 0.0;
+                if (k4 < K4) {
+                    const int g = (4 * k4) / gs;
+                    const float sc = s_s[r * G + g];
+                    const double rs = s_rs[r * G + g];
+                    const int z = s_z[r * G + g];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        int q = (int)rintf((float)((double)v[i][e] * rs)) + z;
+                        q = q < 0 ? 0 : (q > qmax ? qmax : q);
+                        const float back = sc * (float)(q - z);
+                        const float d = v[i][e] - back;
+                        err += (double)d * (double)d;
+                    }
+                }
+#pragma unroll
+                for (int o = 8; o >= 1; o >>= 1) err += __shfl_xor(err, o);
+                if ((l & 15) == 0 && k4 < K4) seg_err[r * segs + (k4 >> 4)] = err;
+            }
+            __syncthreads();
+            for (int e = tid; e < 8 * G; e += 1024) {
+                const int rr = e / G, g = e - rr * G;
+                double err = 0.0;
+                for (int q = 0; q < per; ++q) err += seg_err[rr * segs + g * per + q];
+                if (j == 0 || err < b_err[e]) {
+                    b_err[e] = err;
+                    b_s[e] = s_s[e];
+                    b_z[e] = s_z[e];
+                    b_rs[e] = s_rs[e];
+                }
+                if (j + 1 < n_ratios) {
+                    candidate(e, j + 1);
+                } else {
+                    s_s[e] = b_s[e];
+                    s_z[e] = b_z[e];
+                    s_rs[e] = b_rs[e];
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int e = tid; e < 8 * G; e += 1024) {
+        const int rr = e / G, g = e - rr * G;
+        s0[(size_t)(ib * 8 + rr) * G + g] = s_s[e];
+        z0[(size_t)(ib * 8 + rr) * G + g] = (uint8_t)s_z[e];
+    }
 
     // ---- codes of all eight rows into LDS (one byte per code, [8][K]), then the packed words
     const size_t out_row = (size_t)(ib / 16) * (K / 32) * 64 + (size_t)(ib % 16) * 4;
@@ -271,39 +350,44 @@ __global__ __launch_bounds__(1024) void quantize_resident_kernel(const float *__
 }
 
 constexpr int kMaxDevQ = 64;
+}  // namespace
+bool quantize_resident_fits(int K, int G, bool search);
+namespace {
 
-template <int BITS, int NV>
+// dynamic LDS of quantize_resident_kernel
+size_t resident_lds(int K, int G, bool search) { return (size_t)(search ? 384 : 192) * G + (size_t)(search ? 9 : 8) * K; }
+
+template <int BITS, int NV, bool SEARCH>
 hipError_t launch_resident(const float *W0, int N, int K, int gs, int G, uint32_t *packed, float *s0, uint8_t *z0,
-                           hipStream_t stream)
+                           int n_ratios, float step, hipStream_t stream)
 {
     static int attr_bytes[kMaxDevQ];                                  // dynamic LDS allowed so far, per device
-    const size_t smem = (size_t)48 * G * 4 + (size_t)8 * K;
+    const size_t smem = resident_lds(K, G, SEARCH);
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= kMaxDevQ) return hipErrorInvalidDevice;
     if (smem > 48 * 1024 && (int)smem > attr_bytes[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(quantize_resident_kernel<BITS, NV>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(quantize_resident_kernel<BITS, NV, SEARCH>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_bytes[dev] = (int)smem;
     }
-    hipLaunchKernelGGL((quantize_resident_kernel<BITS, NV>), dim3(N / 8), dim3(1024), smem, stream, W0, K, gs, G, packed,
-                       s0, z0);
+    hipLaunchKernelGGL((quantize_resident_kernel<BITS, NV, SEARCH>), dim3(N / 8), dim3(1024), smem, stream, W0, K, gs, G,
+                       packed, s0, z0, n_ratios, step);
     return hipSuccess;
 }
 
 // true if a register-resident instantiation took the call (K <= 12288 and the LDS need fits)
-template <int BITS>
+template <int BITS, bool SEARCH>
 bool launch_resident_for(const float *W0, int N, int K, int gs, int G, uint32_t *packed, float *s0, uint8_t *z0,
-                         hipStream_t stream, hipError_t *err)
+                         int n_ratios, float step, hipStream_t stream, hipError_t *err)
 {
-    if ((size_t)48 * G * 4 + (size_t)8 * K > 150 * 1024) return false;
+    if (!quantize_resident_fits(K, G, SEARCH)) return false;
     const int nv = (K + 511) / 512;
-    if (nv <= 8) *err = launch_resident<BITS, 8>(W0, N, K, gs, G, packed, s0, z0, stream);
-    else if (nv <= 16) *err = launch_resident<BITS, 16>(W0, N, K, gs, G, packed, s0, z0, stream);
-    else if (nv <= 24) *err = launch_resident<BITS, 24>(W0, N, K, gs, G, packed, s0, z0, stream);
-    else return false;
+    if (nv <= 8) *err = launch_resident<BITS, 8, SEARCH>(W0, N, K, gs, G, packed, s0, z0, n_ratios, step, stream);
+    else if (nv <= 16) *err = launch_resident<BITS, 16, SEARCH>(W0, N, K, gs, G, packed, s0, z0, n_ratios, step, stream);
+    else *err = launch_resident<BITS, 24, SEARCH>(W0, N, K, gs, G, packed, s0, z0, n_ratios, step, stream);
     return true;
 }
 
@@ -317,8 +401,8 @@ hipError_t launch_quantize(const float *W0, int N, int K, int bits, int group, u
     trace_before(KID_QUANTIZE, stream);
     // rows up to 12288 features stay in registers between the two passes; longer ones are read twice
     hipError_t err = hipSuccess;
-    const bool resident = bits == 4 ? launch_resident_for<4>(W0, N, K, gs, G, packed, s0, z0, stream, &err)
-                                    : launch_resident_for<3>(W0, N, K, gs, G, packed, s0, z0, stream, &err);
+    const bool resident = bits == 4 ? launch_resident_for<4, false>(W0, N, K, gs, G, packed, s0, z0, 1, 0.f, stream, &err)
+                                    : launch_resident_for<3, false>(W0, N, K, gs, G, packed, s0, z0, 1, 0.f, stream, &err);
     if (resident) {
         if (err != hipSuccess) return err;
     } else if (bits == 4)
@@ -327,6 +411,24 @@ hipError_t launch_quantize(const float *W0, int N, int K, int bits, int group, u
         hipLaunchKernelGGL(quantize_kernel<3>, dim3(N / 8), dim3(256), smem, stream, W0, K, gs, G, packed, s0, z0);
     trace_after(KID_QUANTIZE, stream);
     return hipGetLastError();
+}
+
+bool quantize_resident_fits(int K, int G, bool search)
+{
+    return K <= 12288 && resident_lds(K, G, search) <= 150 * 1024;
+}
+
+hipError_t launch_quantize_search(const float *W0, int N, int K, int bits, int group, int n_ratios, float step,
+                                  uint32_t *packed, float *s0, uint8_t *z0, hipStream_t stream)
+{
+    const int gs = group > 0 ? group : K, G = K / gs;
+    hipError_t err = hipSuccess;
+    trace_before(KID_QUANTIZE, stream);
+    const bool done = bits == 4 ? launch_resident_for<4, true>(W0, N, K, gs, G, packed, s0, z0, n_ratios, step, stream, &err)
+                                : launch_resident_for<3, true>(W0, N, K, gs, G, packed, s0, z0, n_ratios, step, stream, &err);
+    trace_after(KID_QUANTIZE, stream);
+    if (!done) return hipErrorInvalidValue;
+    return err != hipSuccess ? err : hipGetLastError();
 }
 
 }  // namespace peqa

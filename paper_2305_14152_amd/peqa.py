@@ -16,7 +16,7 @@ EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_wo
            "peqa_status_string", "peqa_bit_location", "peqa_quantize", "peqa_linear_fwd",
            "peqa_linear_bwd", "peqa_scale_update", "peqa_trace_begin", "peqa_trace_end",
            "peqa_workspace_bytes_fused", "peqa_linear_fwd_fused", "peqa_linear_fwd_keep", "peqa_linear_bwd_kept",
-           "peqa_linear_fwd_z", "peqa_linear_bwd_z"]
+           "peqa_linear_fwd_z", "peqa_linear_bwd_z", "peqa_quantize_search"]
 
 
 class Layout(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib():
         L.peqa_bit_location.restype = i32
         L.peqa_quantize.argtypes = [LP, vp, vp, vp, vp, vp]
         L.peqa_quantize.restype = i32
+        L.peqa_quantize_search.argtypes = [LP, vp, i32, ctypes.c_float, vp, vp, vp, vp]
+        L.peqa_quantize_search.restype = i32
         L.peqa_linear_fwd.argtypes = [LP, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.peqa_linear_fwd.restype = i32
         L.peqa_linear_bwd.argtypes = [LP, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
@@ -148,6 +150,11 @@ def bit_location(L, i, k, t):
 def quantize(L, W0, packed, s0, z0, stream=None):
     _check(lib().peqa_quantize(ctypes.byref(L), _ptr(W0), _ptr(packed), _ptr(s0), _ptr(z0), _stream(stream)),
            "peqa_quantize")
+
+
+def quantize_search(L, W0, n_ratios, min_ratio, packed, s0, z0, stream=None):
+    _check(lib().peqa_quantize_search(ctypes.byref(L), _ptr(W0), int(n_ratios), float(min_ratio), _ptr(packed),
+                                      _ptr(s0), _ptr(z0), _stream(stream)), "peqa_quantize_search")
 
 
 def linear_fwd(L, packed, s0, ds, z0, X, T, Y, workspace, workspace_bytes_, stream=None):

@@ -139,6 +139,20 @@ def test_zero_point_training_validation_needs_no_device(peqa):
     assert b(byref(L), good, good, None, good, None, good, good, 8, good, good, good, good, need - 1, None) == peqa.PEQA_ERR_WORKSPACE
 
 
+def test_quantize_search_validation_needs_no_device(peqa):
+    L = peqa.layout(256, 256, 4)
+    good, bad = 0x10000, 0x10004
+    f, byref = peqa.lib().peqa_quantize_search, ctypes.byref
+    assert f(byref(L), good, 0, 0.5, good, good, good, None) == peqa.PEQA_ERR_PARAM
+    assert f(byref(L), good, 8, 0.0, good, good, good, None) == peqa.PEQA_ERR_PARAM
+    assert f(byref(L), good, 8, 1.5, good, good, good, None) == peqa.PEQA_ERR_PARAM
+    assert f(byref(L), None, 8, 0.5, good, good, good, None) == peqa.PEQA_ERR_NULL
+    assert f(byref(L), good, 8, 0.5, bad, good, good, None) == peqa.PEQA_ERR_ALIGN
+    # rows that do not fit on chip are refused, not mis-handled
+    assert f(byref(peqa.layout(128, 22016, 4)), good, 8, 0.5, good, good, good, None) == peqa.PEQA_ERR_SHAPE
+    assert f(byref(peqa.layout(128, 12288, 4, 64)), good, 8, 0.5, good, good, good, None) == peqa.PEQA_ERR_SHAPE
+
+
 def test_fused_forward_validation_needs_no_device(peqa):
     a, b = peqa.layout(256, 512, 4), peqa.layout(128, 512, 4)
     assert peqa.workspace_bytes_fused([(a, 16, 16, None, 16, 16), (b, 16, 16, None, 16, 16)], 4) > 0

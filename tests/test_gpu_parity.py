@@ -321,6 +321,54 @@ def test_groupwise_scale_gradient_both_routes(gpu, oracle, bits, N, K, T, group)
     assert np.linalg.norm(got["tokens"] - got["pairs"]) <= 1e-4 * np.linalg.norm(gref)
 
 
+@pytest.mark.parametrize("bits,N,K,group,n,m", [
+    (4, 256, 512, 0, 20, 0.5),
+    (3, 384, 1152, 0, 16, 0.4),
+    (4, 128, 4096, 128, 12, 0.6),     # 8 register vectors per thread, 32 groups
+    (3, 256, 640, 64, 24, 0.5),
+    (4, 128, 6144, 0, 8, 0.7),        # 12 vectors per thread: the 16-vector instantiation
+    (3, 128, 11008, 0, 6, 0.5),       # 22 vectors per thread: the 24-vector instantiation, ragged last step
+    (4, 256, 256, 0, 1, 0.5),         # a single ratio is the plain quantizer
+])
+def test_quantize_search_parity(gpu, oracle, bits, N, K, group, n, m):
+    """Error-minimising initialisation: scales, zero-points and packed codes bit for bit, except where two
+    candidates tie to within the rounding of the error sums (then either is right)."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    _log("search bits=%d N=%d K=%d g=%d n=%d min=%.2f" % (bits, N, K, group, n, m))
+    seed = 9900 + bits * 1000 + N + K + group
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    W[::3, ::41] *= 5.0                                              # outliers, so that clipping pays
+    W[5, :] = 0.0                                                    # a degenerate row
+    L = peqa.layout(N, K, bits, group)
+    G = L.groups
+    Wd = gpu.to_dev(W)
+    packed = torch.empty(peqa.packed_words(L), dtype=torch.int32, device="cuda")
+    s0 = torch.empty((N, G), dtype=torch.float32, device="cuda")
+    z0 = torch.empty((N, G), dtype=torch.uint8, device="cuda")
+    peqa.quantize_search(L, Wd, n, m, packed, s0, z0)
+    torch.cuda.synchronize()
+    codes, rs0, rz0, choice = oracle.quantize_search(W, bits, group, n, m)
+    gs0, gz0 = gpu.to_host(s0), gpu.to_host(z0)
+    same = (gs0.view(np.uint32) == rs0.view(np.uint32)) & (gz0 == rz0)
+    _log("  groups kept beyond the plain range: %d of %d; differing from the oracle: %d"
+         % (int((choice > 0).sum()), choice.size, int((~same).sum())))
+    gcodes = oracle.unpack(gpu.to_host(packed, np.uint32), N, K, bits)
+    gsz = K // G
+    if not same.all():
+        # a different candidate is acceptable only as a tie: equal reconstruction error to 1e-12
+        Wg = W.astype(np.float64).reshape(N, G, gsz)
+        e_ref = ((Wg - oracle.dequant(codes, rs0, None, rz0, group).reshape(N, G, gsz)) ** 2).sum(axis=2)
+        e_gpu = ((Wg - oracle.dequant(gcodes, gs0, None, gz0, group).reshape(N, G, gsz)) ** 2).sum(axis=2)
+        assert (np.abs(e_gpu - e_ref)[~same] <= 1e-12 * e_ref[~same]).all()
+        assert (~same).sum() <= max(1, same.size // 1000)
+    ok = np.repeat(same, gsz, axis=1)
+    assert (gcodes[ok] == codes[ok]).all()
+    if n == 1:
+        plain = oracle.quantize(W, bits, group)
+        assert same.all() and (gcodes == plain[0]).all()
+
+
 def test_graph_capture_replays_match_eager(gpu, oracle):
     """Forward + backward captured in a HIP graph (the backward forks onto the library's second
     stream inside the capture): several replays, with eager work and synchronisation between them,

@@ -221,12 +221,12 @@ def kept_product(torch, peqa, layers, cfg, stream, steps):
             "kept_bytes": int(sum(P.numel() * 4 for P in Ps))}
 
 
-def device_info(torch):
+def device_info(torch, peqa):
     """What the run saw of the device, and the denominators the fractions above use."""
     p = torch.cuda.get_device_properties(0)
-    clock_khz = getattr(p, "clock_rate", None)
-    return {"name": p.name, "compute_units": p.multi_processor_count,
-            "max_clock_mhz": round(clock_khz / 1e3) if clock_khz else None,
+    cus, clock_khz = peqa.device_info()
+    return {"name": p.name, "compute_units": cus,
+            "max_clock_mhz": round(clock_khz / 1e3),
             "hbm_bytes": p.total_memory,
             "mfma_peak_used": "2500 TFLOP/s dense bf16 (published; 256 CUs x 4096 flop/clk x 2.4 GHz = 2517)",
             "hbm_peak_used": "8000 GB/s (published)"}
@@ -307,14 +307,14 @@ def main():
 
     def step(use_graph=True):
         # forward and backward of the 7 layers (one HIP graph, replayed, unless --no-graph), then the
-        # 7 scale updates, which carry the step number and are launched directly
+        # 7 scale updates (one launch), which carry the step number and are launched directly
         step_no[0] += 1
         if graph[0] is not None and use_graph:
             graph[0].replay()
         else:
             fwd_bwd(stream)
-        for l in layers:
-            peqa.scale_update(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0, lr=1e-5, step=step_no[0], stream=stream)
+        peqa.scale_update_multi([(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0) for l in layers], lr=1e-5,
+                                step=step_no[0], stream=stream)
 
     if args.pmc_calibration:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
@@ -392,10 +392,10 @@ def main():
         "quantize_ms_total": round(sum(l.quantize_ms for l in layers), 3),
         "launch": ("eager: " if args.no_graph else "hip graph of: ") +
                   "%d forward calls (layers sharing an input in one peqa_linear_fwd_fused), %d backward calls; "
-                  "then %d direct scale updates" % (len(groups), len(layers), len(layers)),
+                  "then the %d scale updates in one direct launch" % (len(groups), len(layers), len(layers)),
         "kernels": kernels,
         "roofline": roofline,
-        "device": device_info(torch),
+        "device": device_info(torch, peqa),
     }
     if small is not None:
         out["small_batch"] = small

@@ -230,6 +230,27 @@ peqa_status peqa_scale_update(size_t n_scales, float *ds, const float *d_ds, flo
                               const float *s0, const peqa_adamw *opt, void *stream);
 
 /*
+ * The same step on the scales of 1..PEQA_MAX_UPDATE layers in one launch (a decoder block's seven
+ * updates are each a few microseconds of work behind a launch): equal to calling peqa_scale_update
+ * once per item with the same `opt`.  `items` is a HOST array.
+ */
+#define PEQA_MAX_UPDATE 16
+typedef struct {
+    size_t n_scales;
+    float *ds;           /* in/out */
+    const float *d_ds;
+    float *m, *v;        /* in/out */
+    const float *s0;
+} peqa_update_item;
+
+peqa_status peqa_scale_update_multi(int32_t n, const peqa_update_item *items, const peqa_adamw *opt,
+                                    void *stream);
+
+/* Compute units and peak engine clock (kHz) of the current device, as the HIP runtime reports them
+ * (for benchmark reports: the denominators of roofline fractions). */
+peqa_status peqa_device_info(int32_t *compute_units, int32_t *clock_khz);
+
+/*
  * Per-kernel timing for benchmarks.  peqa_trace_begin() makes every kernel the library
  * launches afterwards be bracketed by HIP events on its stream (it creates the events:
  * call it outside any region that must not allocate).  peqa_trace_end() synchronises those

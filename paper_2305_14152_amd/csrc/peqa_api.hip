@@ -625,6 +625,49 @@ peqa_status peqa_scale_update(size_t n_scales, float *ds, const float *d_ds, flo
                                          static_cast<hipStream_t>(stream)));
 }
 
+peqa_status peqa_device_info(int32_t *compute_units, int32_t *clock_khz)
+{
+    if (!compute_units || !clock_khz) return PEQA_ERR_NULL;
+    int dev = 0, cus = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess)
+        return PEQA_ERR_DEVICE;
+    *compute_units = cus;
+    *clock_khz = khz;
+    return PEQA_OK;
+}
+
+peqa_status peqa_scale_update_multi(int32_t n, const peqa_update_item *items, const peqa_adamw *opt, void *stream)
+{
+    if (!items || !opt) return PEQA_ERR_NULL;
+    if (n < 1 || n > PEQA_MAX_UPDATE) return PEQA_ERR_PARAM;
+    if (opt->step < 1 || !(opt->beta1 >= 0.f && opt->beta1 < 1.f) || !(opt->beta2 >= 0.f && opt->beta2 < 1.f) ||
+        !(opt->eps >= 0.f) || !(opt->lr == opt->lr) || !(opt->weight_decay == opt->weight_decay))
+        return PEQA_ERR_PARAM;
+    peqa::AdamwMulti a{};
+    unsigned long long total = 0;
+    for (int j = 0; j < n; ++j) {
+        const peqa_update_item &it = items[j];
+        if (!it.ds || !it.d_ds || !it.m || !it.v || !it.s0) return PEQA_ERR_NULL;
+        if (it.n_scales == 0 || it.n_scales > ((size_t)1 << 38)) return PEQA_ERR_SHAPE;
+        if (!aligned16(it.ds) || !aligned16(it.d_ds) || !aligned16(it.m) || !aligned16(it.v) || !aligned16(it.s0))
+            return PEQA_ERR_ALIGN;
+        total += it.n_scales;
+        a.ds[j] = it.ds; a.g[j] = it.d_ds; a.m[j] = it.m; a.v[j] = it.v; a.s0[j] = it.s0; a.end[j] = total;
+    }
+    if (total > ((unsigned long long)1 << 38)) return PEQA_ERR_SHAPE;
+    for (int j = n; j < peqa::ADAMW_MAX_TENSORS; ++j) {
+        a.ds[j] = a.ds[n - 1]; a.g[j] = a.g[n - 1]; a.m[j] = a.m[n - 1]; a.v[j] = a.v[n - 1]; a.s0[j] = a.s0[n - 1];
+        a.end[j] = total;
+    }
+    a.n_tensors = n;
+    const double c1 = 1.0 - pow((double)opt->beta1, (double)opt->step);
+    const double c2 = 1.0 - pow((double)opt->beta2, (double)opt->step);
+    return dev_status(peqa::launch_adamw_multi(a, opt->lr, opt->beta1, opt->beta2, opt->eps, opt->weight_decay,
+                                               (float)(1.0 / c1), (float)(1.0 / c2), static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"
 
 // ---------------------------------------------------------------------------------------

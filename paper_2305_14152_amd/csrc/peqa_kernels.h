@@ -101,6 +101,21 @@ hipError_t launch_adamw(size_t n, float *ds, const float *g, float *m, float *v,
                         float lr, float b1, float b2, float eps, float wd, float inv_c1, float inv_c2,
                         hipStream_t stream);
 
+// AdamW on several parameter vectors in one launch: tensor j holds elements [end[j-1], end[j]) of the
+// launch's index space
+constexpr int ADAMW_MAX_TENSORS = 16;
+struct AdamwMulti {
+    float *ds[ADAMW_MAX_TENSORS];
+    const float *g[ADAMW_MAX_TENSORS];
+    float *m[ADAMW_MAX_TENSORS];
+    float *v[ADAMW_MAX_TENSORS];
+    const float *s0[ADAMW_MAX_TENSORS];
+    unsigned long long end[ADAMW_MAX_TENSORS];   // running totals; unused entries repeat the last
+    int n_tensors;
+};
+hipError_t launch_adamw_multi(const AdamwMulti &a, float lr, float b1, float b2, float eps, float wd, float inv_c1,
+                              float inv_c2, hipStream_t stream);
+
 // peqa_quantize.hip
 hipError_t launch_quantize(const float *W0, int N, int K, int bits, int group, uint32_t *packed,
                            float *s0, uint8_t *z0, hipStream_t stream);

@@ -259,7 +259,43 @@ __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float *__restrict_
     ds[j] = d - lr * ((mj * inv_c1) / (sqrtf(vj * inv_c2) + eps) + wd * (s0[j] + d));
 }
 
+// The same update over several parameter vectors laid end to end in one index space.
+__global__ __launch_bounds__(256) void adamw_multi_kernel(AdamwMulti a, float lr, float b1, float b2, float eps,
+                                                           float wd, float inv_c1, float inv_c2)
+{
+    const unsigned long long idx = (unsigned long long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.end[ADAMW_MAX_TENSORS - 1]) return;
+    int t = 0;
+#pragma unroll
+    for (int i = 0; i < ADAMW_MAX_TENSORS - 1; ++i) t += idx >= a.end[i];
+    // selects instead of indexing: the argument block stays in scalar registers
+    float *ds = a.ds[0]; const float *g = a.g[0]; float *m = a.m[0]; float *v = a.v[0]; const float *s0 = a.s0[0];
+    unsigned long long beg = 0;
+#pragma unroll
+    for (int i = 1; i < ADAMW_MAX_TENSORS; ++i)
+        if (t == i) { ds = a.ds[i]; g = a.g[i]; m = a.m[i]; v = a.v[i]; s0 = a.s0[i]; beg = a.end[i - 1]; }
+    const size_t j = (size_t)(idx - beg);
+    const float gj = g[j];
+    const float mj = b1 * m[j] + (1.f - b1) * gj;
+    const float vj = b2 * v[j] + (1.f - b2) * gj * gj;
+    m[j] = mj;
+    v[j] = vj;
+    const float d = ds[j];
+    ds[j] = d - lr * ((mj * inv_c1) / (sqrtf(vj * inv_c2) + eps) + wd * (s0[j] + d));
+}
+
 }  // namespace
+
+hipError_t launch_adamw_multi(const AdamwMulti &a, float lr, float b1, float b2, float eps, float wd, float inv_c1,
+                              float inv_c2, hipStream_t stream)
+{
+    const unsigned long long total = a.end[ADAMW_MAX_TENSORS - 1];
+    trace_before(KID_ADAMW, stream);
+    hipLaunchKernelGGL(adamw_multi_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, a, lr, b1, b2, eps,
+                       wd, inv_c1, inv_c2);
+    trace_after(KID_ADAMW, stream);
+    return hipGetLastError();
+}
 
 hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream)
 {

@@ -16,7 +16,8 @@ EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_wo
            "peqa_status_string", "peqa_bit_location", "peqa_quantize", "peqa_linear_fwd",
            "peqa_linear_bwd", "peqa_scale_update", "peqa_trace_begin", "peqa_trace_end",
            "peqa_workspace_bytes_fused", "peqa_linear_fwd_fused", "peqa_linear_fwd_keep", "peqa_linear_bwd_kept",
-           "peqa_linear_fwd_z", "peqa_linear_bwd_z", "peqa_quantize_search"]
+           "peqa_linear_fwd_z", "peqa_linear_bwd_z", "peqa_quantize_search",
+           "peqa_scale_update_multi", "peqa_device_info"]
 
 
 class Layout(ctypes.Structure):
@@ -82,6 +83,8 @@ def lib():
         L.peqa_linear_bwd_z.restype = i32
         L.peqa_scale_update.argtypes = [sz, vp, vp, vp, vp, vp, ctypes.POINTER(AdamW), vp]
         L.peqa_scale_update.restype = i32
+        L.peqa_scale_update_multi.argtypes = [i32, vp, ctypes.POINTER(AdamW), vp]
+        L.peqa_scale_update_multi.restype = i32
         L.peqa_workspace_bytes_fused.argtypes = [i32, vp, i32]
         L.peqa_workspace_bytes_fused.restype = sz
         L.peqa_linear_fwd_fused.argtypes = [i32, vp, vp, i32, vp, sz, vp]
@@ -150,6 +153,31 @@ def bit_location(L, i, k, t):
 def quantize(L, W0, packed, s0, z0, stream=None):
     _check(lib().peqa_quantize(ctypes.byref(L), _ptr(W0), _ptr(packed), _ptr(s0), _ptr(z0), _stream(stream)),
            "peqa_quantize")
+
+
+class UpdateItem(ctypes.Structure):
+    _fields_ = [("n_scales", ctypes.c_size_t), ("ds", ctypes.c_void_p), ("d_ds", ctypes.c_void_p),
+                ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("s0", ctypes.c_void_p)]
+
+
+def scale_update_multi(tensors, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, step=1, stream=None):
+    """tensors: sequence of (n_scales, ds, d_ds, m, v, s0)."""
+    arr = (UpdateItem * len(tensors))()
+    for i, (n, ds, d_ds, m, v, s0) in enumerate(tensors):
+        arr[i] = UpdateItem(int(n), _ptr(ds), _ptr(d_ds), _ptr(m), _ptr(v), _ptr(s0))
+    opt = AdamW(lr, beta1, beta2, eps, weight_decay, int(step))
+    _check(lib().peqa_scale_update_multi(len(tensors), ctypes.addressof(arr), ctypes.byref(opt), _stream(stream)),
+           "peqa_scale_update_multi")
+
+
+def device_info():
+    """(compute units, peak engine clock in kHz) of the current device."""
+    cus, khz = ctypes.c_int32(0), ctypes.c_int32(0)
+    f = lib().peqa_device_info
+    f.argtypes = [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    f.restype = ctypes.c_int32
+    _check(f(ctypes.byref(cus), ctypes.byref(khz)), "peqa_device_info")
+    return cus.value, khz.value
 
 
 def quantize_search(L, W0, n_ratios, min_ratio, packed, s0, z0, stream=None):

@@ -153,6 +153,32 @@ def test_quantize_search_validation_needs_no_device(peqa):
     assert f(byref(peqa.layout(128, 12288, 4, 64)), good, 8, 0.5, good, good, good, None) == peqa.PEQA_ERR_SHAPE
 
 
+def test_scale_update_multi_validation_needs_no_device(peqa):
+    good, bad = 0x10000, 0x10004
+    lib, byref = peqa.lib(), ctypes.byref
+    opt = peqa.AdamW(1e-3, 0.9, 0.999, 1e-8, 0.0, 1)
+    def items(*rows):
+        arr = (peqa.UpdateItem * len(rows))()
+        for i, row in enumerate(rows):
+            arr[i] = peqa.UpdateItem(*row)
+        return arr
+    f = lib.peqa_scale_update_multi
+    ok = (16, good, good, good, good, good)
+    arr = items(ok, ok)
+    assert f(0, ctypes.addressof(arr), byref(opt), None) == peqa.PEQA_ERR_PARAM
+    assert f(17, ctypes.addressof(arr), byref(opt), None) == peqa.PEQA_ERR_PARAM
+    assert f(2, None, byref(opt), None) == peqa.PEQA_ERR_NULL
+    arr = items(ok, (16, good, None, good, good, good))
+    assert f(2, ctypes.addressof(arr), byref(opt), None) == peqa.PEQA_ERR_NULL
+    arr = items(ok, (16, good, good, bad, good, good))
+    assert f(2, ctypes.addressof(arr), byref(opt), None) == peqa.PEQA_ERR_ALIGN
+    arr = items(ok, (0, good, good, good, good, good))
+    assert f(2, ctypes.addressof(arr), byref(opt), None) == peqa.PEQA_ERR_SHAPE
+    opt.step = 0
+    arr = items(ok)
+    assert f(1, ctypes.addressof(arr), byref(opt), None) == peqa.PEQA_ERR_PARAM
+
+
 def test_fused_forward_validation_needs_no_device(peqa):
     a, b = peqa.layout(256, 512, 4), peqa.layout(128, 512, 4)
     assert peqa.workspace_bytes_fused([(a, 16, 16, None, 16, 16), (b, 16, 16, None, 16, 16)], 4) > 0

@@ -482,6 +482,34 @@ def test_scale_update_parity(gpu, oracle):
         np.testing.assert_allclose(gpu.to_host(d["v"]), ref[2], rtol=1e-6, atol=1e-30)
 
 
+def test_scale_update_multi_equals_single_calls(gpu):
+    """Several parameter vectors in one launch: bit-identical to one peqa_scale_update per vector."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    r = np.random.default_rng(11)
+    sizes = [4096, 11008, 128, 4096 * 32, 5120 * 40 + 256]
+    def fresh():
+        out = []
+        for n in sizes:
+            s0 = (np.abs(r.standard_normal(n)) * 0.01 + 1e-3).astype(np.float32)
+            t = dict(s0=s0, ds=(r.standard_normal(n) * 1e-4).astype(np.float32), g=r.standard_normal(n).astype(np.float32),
+                     m=(r.standard_normal(n) * 0.1).astype(np.float32), v=np.abs(r.standard_normal(n)).astype(np.float32))
+            out.append(t)
+        return out
+    host = fresh()
+    a = [{k: gpu.to_dev(x) for k, x in t.items()} for t in host]
+    b = [{k: gpu.to_dev(x) for k, x in t.items()} for t in host]
+    kw = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, step=3)
+    peqa.scale_update_multi([(t["ds"].numel(), t["ds"], t["g"], t["m"], t["v"], t["s0"]) for t in a], **kw)
+    for t in b:
+        peqa.scale_update(t["ds"].numel(), t["ds"], t["g"], t["m"], t["v"], t["s0"], **kw)
+    torch.cuda.synchronize()
+    for ta, tb, th in zip(a, b, host):
+        for k in ("ds", "m", "v"):
+            assert (gpu.to_host(ta[k]).view(np.uint32) == gpu.to_host(tb[k]).view(np.uint32)).all(), k
+            assert not (gpu.to_host(ta[k]) == th[k]).all()           # and something was updated
+
+
 def test_trace_reports_kernels(gpu):
     from paper_2305_14152_amd import peqa
     W = synth.normal_f32(5, (256, 256), 0.02)

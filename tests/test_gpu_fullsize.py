@@ -129,3 +129,32 @@ def test_full_size_variants(gpu, oracle, cfg, li):
         _, gref, _ = oracle.bwd(codes[ns], s0[ns], ds[ns], z0[ns], X, dYn, 0, want_dX=False)
         gk = gpu.to_host(ddsk).astype(np.float64)[ns]
         assert np.linalg.norm(gk - gref) <= G_TOL * np.linalg.norm(gref)
+
+
+def test_full_size_quantize_search(gpu, oracle):
+    """Error-minimising initialisation of a whole 4096 x 4096 layer (8 register vectors per thread, 512
+    workgroups): every scale, zero-point and packed word against the oracle."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    cfg, li, n, m = 1, 0, 8, 0.5
+    c = synth.CONFIGS[cfg]
+    N, K, _ = c["layers"][li]
+    bits, group = c["bits"], c["group"]
+    print("full size search N=%d K=%d bits=%d n=%d" % (N, K, bits, n), flush=True)
+    W = synth.weights(cfg, li)
+    L = peqa.layout(N, K, bits, group)
+    packed = torch.empty(peqa.packed_words(L), dtype=torch.int32, device="cuda")
+    s0 = torch.empty((N, L.groups), dtype=torch.float32, device="cuda")
+    z0 = torch.empty((N, L.groups), dtype=torch.uint8, device="cuda")
+    Wd = gpu.to_dev(W)
+    peqa.quantize_search(L, Wd, n, m, packed, s0, z0)
+    torch.cuda.synchronize()
+    codes, rs0, rz0, choice = oracle.quantize_search(W, bits, group, n, m)
+    same = (gpu.to_host(s0).view(np.uint32) == rs0.view(np.uint32)) & (gpu.to_host(z0) == rz0)
+    print("  candidates kept beyond the plain range: %d of %d; rows differing: %d"
+          % (int((choice > 0).sum()), choice.size, int((~same).sum())), flush=True)
+    assert (~same).sum() <= 2                                       # only exact-to-rounding ties may differ
+    rows = same[:, 0]
+    words = gpu.to_host(packed, np.uint32)
+    got = oracle.unpack(words, N, K, bits)
+    assert (got[rows] == codes[rows]).all()

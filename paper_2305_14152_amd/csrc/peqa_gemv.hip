@@ -10,11 +10,15 @@
 // and scale in fp32.  Per-channel layers are one group spanning the whole slice.
 //
 // Grid: (N / 128 channel tiles) x (S feature slices).  The K / 64 rounds of 64 features are dealt
-// evenly to the slices and, inside a slice, to the 4 waves of the workgroup (a wave may start or
+// evenly to the slices and, inside a slice, to the waves of the workgroup (a wave may start or
 // stop in the middle of a scale group: the fold above is linear in the features, so it is applied
 // to whatever part of a group the wave has seen); the waves are summed through LDS at the end.
 // S > 1 leaves fp32 partials [S, T, N] in the workspace for gemv_finish_kernel to add up in a fixed
-// order.
+// order.  Two shapes of workgroup: 4 waves (two or three workgroups per compute unit, S chosen so that
+// the machine is full), and, for per-channel layers of 128 to 256 channel tiles, 12 waves that take
+// the whole of K (S = 1): the same twelve waves per compute unit, but the sum over the feature ranges
+// stays in LDS, so there are no partials and no second launch.  (With fewer tiles than that the
+// compute units left idle cost more than the second launch saves: measured.)
 //
 // A wave moves its operands in rounds of 64 features (two MFMA steps): the packed blocks of its 16
 // channel-block rows and the matching 128 bytes of each of the 16 token rows, by global -> LDS DMA
@@ -32,7 +36,9 @@ namespace peqa {
 
 namespace {
 
-constexpr int GV_WAVES = 4;
+constexpr int GV_WAVES = 4;          // waves of the sliced workgroup
+constexpr int GV_WAVES_WHOLE = 12;   // waves of the workgroup that takes all of K
+constexpr int GV_WHOLE_MIN_TILES = 128, GV_WHOLE_MAX_TILES = 256;
 constexpr int GV_MAX_PER = 16;       // most scale groups a slice may touch (bounds the scale tile in LDS)
 constexpr int GV_B_BYTES = 4096;     // packed blocks of one round of one wave (4 KB at 4 bits, 3 KB at 3 bits)
 constexpr int GV_ROUND_BYTES = GV_B_BYTES + 2048;   // + 16 token rows x 128 B
@@ -52,11 +58,11 @@ __device__ __forceinline__ void gv_wait_vmcnt()
 
 // GROUPS_MAX: most scale groups a workgroup may touch: 1 for per-channel layers (1 KB scale tile, three
 // workgroups per compute unit), GV_MAX_PER for group-wise ones (16 KB, two workgroups).
-template <int BITS, int GROUPS_MAX>
-__global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_kernel(GemvArgs a)
+template <int BITS, int GROUPS_MAX, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 2)) void gemv_kernel(GemvArgs a)
 {
-    // [wave][2 rounds][6 KB]; reused as [wave][column tile][row][lane] fp32 (32 KB) for the final sum
-    __shared__ __align__(16) uint8_t stage[GV_WAVES * 2 * GV_ROUND_BYTES];
+    // [wave][2 rounds][6 KB]; reused as [wave][column tile][row][lane] fp32 (8 KB per wave) for the final sum
+    extern __shared__ __align__(16) uint8_t stage[];
     __shared__ __align__(16) ScaleZero sz[GROUPS_MAX][128];      // [group of the slice][channel]
     constexpr int WPB = 2 * BITS;
     constexpr int NDMA_B = 2 * 64 * WPB * 4 / 1024;               // 1 KB DMAs for the blocks of a round: 4 / 3
@@ -80,11 +86,11 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
     const int n0 = (bx - tile0) * 128;                           // first channel, within its layer
     const int K = a.K, G = a.G;
     const int chunk_rounds = a.chunk >> 6;                        // 64-feature rounds per scale group
-    // this workgroup's rounds [rbeg, rend); wave w takes the w-th quarter of them
+    // this workgroup's rounds [rbeg, rend); wave w takes the w-th of WAVES equal parts of them
     const uint32_t R = (uint32_t)K >> 6;
     const int rbeg = (int)(blockIdx.y * R / (uint32_t)a.S), rend = (int)((blockIdx.y + 1) * R / (uint32_t)a.S);
-    const int wr0 = rbeg + ((wave * (rend - rbeg)) >> 2);
-    const int nrounds = rbeg + (((wave + 1) * (rend - rbeg)) >> 2) - wr0;
+    const int wr0 = rbeg + (int)((uint32_t)(wave * (rend - rbeg)) / (uint32_t)WAVES);
+    const int nrounds = rbeg + (int)((uint32_t)((wave + 1) * (rend - rbeg)) / (uint32_t)WAVES) - wr0;
     const int k0 = wr0 << 6;                                      // first feature of this wave
     const int g_lo = (uint32_t)rbeg / (uint32_t)chunk_rounds;     // first scale group this workgroup touches
 
@@ -136,7 +142,7 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
         int ch[NB], jj[NB];
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int idx = tid + i * GV_WAVES * 64;
+            const int idx = tid + i * WAVES * 64;
             const bool on = idx < 128 * cols;
             ch[i] = on ? (int)((uint32_t)idx / (uint32_t)cols) : 0;
             jj[i] = on ? idx - ch[i] * cols : 0;
@@ -148,7 +154,7 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            if (tid + i * GV_WAVES * 64 < 128 * cols) sz[jj[i]][ch[i]] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i] + tdz[i]};
+            if (tid + i * WAVES * 64 < 128 * cols) sz[jj[i]][ch[i]] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i] + tdz[i]};
     };
     if (GROUPS_MAX == 1 || cols <= 2) load_tile(std::integral_constant<int, 1>{});
     else if (cols <= 4) load_tile(std::integral_constant<int, 2>{});
@@ -241,20 +247,16 @@ __global__ __launch_bounds__(GV_WAVES * 64, GROUPS_MAX == 1 ? 3 : 2) void gemv_k
 #pragma unroll
         for (int j = 0; j < 4; ++j) red[((wave * 8 + ct) * 4 + j) * 64 + lane] = y[ct][j];
     __syncthreads();
-    // thread (wave, lane) finishes column tiles 2 wave, 2 wave + 1 of lane's rows/column
+    // the 8 column tiles x 4 rows x 64 lanes of results are dealt to the threads; each adds the waves in order
+    for (int idx = tid; idx < 8 * 4 * 64; idx += WAVES * 64) {
+        const int ct = idx >> 8, j = (idx >> 6) & 3, ln = idx & 63;
+        float v = 0.f;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int ct = 2 * wave + i;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float v = 0.f;
-#pragma unroll
-            for (int w = 0; w < GV_WAVES; ++w) v += red[((w * 8 + ct) * 4 + j) * 64 + lane];
-            const int t = 4 * q + j, n = n0 + 8 * c + ct;
-            if (t < a.T) {
-                if (a.S == 1) l_Y[(size_t)t * l_N + n] = (uint16_t)float_to_bf16_bits(v);
-                else a.partial[((size_t)blockIdx.y * a.T + t) * (gridDim.x * 128) + bx * 128 + 8 * c + ct] = v;
-            }
+        for (int w = 0; w < WAVES; ++w) v += red[((w * 8 + ct) * 4 + j) * 64 + ln];
+        const int t = 4 * (ln >> 4) + j, n = n0 + 8 * (ln & 15) + ct;
+        if (t < a.T) {
+            if (a.S == 1) l_Y[(size_t)t * l_N + n] = (uint16_t)float_to_bf16_bits(v);
+            else a.partial[((size_t)blockIdx.y * a.T + t) * (gridDim.x * 128) + bx * 128 + 8 * (ln & 15) + ct] = v;
         }
     }
 }
@@ -288,6 +290,9 @@ int gemv_slices(int Ntot, int K, int T, int chunk)
     // for per-channel layers, only adds partials), every wave at least two rounds long, and the
     // partials small next to the weight bytes
     const int tiles = Ntot / 128, R = K / 64, chunk_rounds = chunk / 64;
+    // per-channel layers that fill half to all of the compute units with one tile each: one 12-wave
+    // workgroup per tile takes all of K
+    if (chunk == K && tiles >= GV_WHOLE_MIN_TILES && tiles <= GV_WHOLE_MAX_TILES) return 1;
     int S = 512 / tiles;
     if (S > R / (2 * GV_WAVES)) S = R / (2 * GV_WAVES);
     const int by_bytes = T > 4 ? 6 : 16;
@@ -300,19 +305,39 @@ int gemv_slices(int Ntot, int K, int T, int chunk)
 
 hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
 {
-    trace_before(KID_GEMV, stream);
     const int tiles = a.layer[a.n_layers - 1].tile_end;
     const dim3 grid(tiles, a.S);
+    constexpr int SLICED_LDS = GV_WAVES * 2 * GV_ROUND_BYTES, WHOLE_LDS = GV_WAVES_WHOLE * 2 * GV_ROUND_BYTES;
+    const bool whole = a.chunk == a.K && a.S == 1 && tiles >= GV_WHOLE_MIN_TILES && tiles <= GV_WHOLE_MAX_TILES;
+    if (whole) {
+        // 144 KB of dynamic LDS: allowed once per device and instantiation
+        static bool allowed[2][64];
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (!allowed[bits == 4][dev]) {
+            const void *f = bits == 4 ? reinterpret_cast<const void *>(gemv_kernel<4, 1, GV_WAVES_WHOLE>)
+                                      : reinterpret_cast<const void *>(gemv_kernel<3, 1, GV_WAVES_WHOLE>);
+            e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, WHOLE_LDS);
+            if (e != hipSuccess) return e;
+            allowed[bits == 4][dev] = true;
+        }
+    }
+    trace_before(KID_GEMV, stream);
     // Per-channel layers fit three workgroups per compute unit (1 KB scale tile).  That pays only when
     // there are more workgroups than two per unit: below, the dispatcher would stack three on some
     // units and leave others with one, so such launches take the 16 KB instantiation (two per unit).
     const bool per_channel = a.chunk == a.K && tiles * a.S > 512;
-    if (bits == 4) {
-        if (per_channel) hipLaunchKernelGGL((gemv_kernel<4, 1>), grid, dim3(GV_WAVES * 64), 0, stream, a);
-        else hipLaunchKernelGGL((gemv_kernel<4, GV_MAX_PER>), grid, dim3(GV_WAVES * 64), 0, stream, a);
+    if (whole) {
+        if (bits == 4) hipLaunchKernelGGL((gemv_kernel<4, 1, GV_WAVES_WHOLE>), grid, dim3(GV_WAVES_WHOLE * 64), WHOLE_LDS, stream, a);
+        else hipLaunchKernelGGL((gemv_kernel<3, 1, GV_WAVES_WHOLE>), grid, dim3(GV_WAVES_WHOLE * 64), WHOLE_LDS, stream, a);
+    } else if (bits == 4) {
+        if (per_channel) hipLaunchKernelGGL((gemv_kernel<4, 1, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
+        else hipLaunchKernelGGL((gemv_kernel<4, GV_MAX_PER, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
     } else {
-        if (per_channel) hipLaunchKernelGGL((gemv_kernel<3, 1>), grid, dim3(GV_WAVES * 64), 0, stream, a);
-        else hipLaunchKernelGGL((gemv_kernel<3, GV_MAX_PER>), grid, dim3(GV_WAVES * 64), 0, stream, a);
+        if (per_channel) hipLaunchKernelGGL((gemv_kernel<3, 1, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
+        else hipLaunchKernelGGL((gemv_kernel<3, GV_MAX_PER, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
     }
     trace_after(KID_GEMV, stream);
     hipError_t e = hipGetLastError();

@@ -119,6 +119,10 @@ def test_groupwise_training_parity(gpu, oracle, bits, N, K, T, group):
 @pytest.mark.parametrize("bits,N,K,group", [
     (4, 256, 512, 0), (3, 384, 640, 0), (3, 256, 1024, 128), (4, 512, 768, 64), (3, 640, 1152, 128),
     (4, 256, 512, 256), (3, 128, 128, 0), (4, 1280, 2048, 128),
+    # 128-256 channel tiles, per-channel: the 12-wave workgroups that take all of K
+    (4, 16384, 256, 0),       # 4 rounds for 12 waves: most waves have nothing to do
+    (3, 20480, 1536, 0),      # 160 tiles, 2 rounds per wave
+    (4, 32768, 896, 0),       # 256 tiles, 14 rounds: uneven shares
 ])
 def test_small_batch_forward_parity(gpu, oracle, bits, N, K, group):
     """The T <= 16 matrix-vector path, per-channel and group-wise, every T from 1 to 16 sampled."""
@@ -139,6 +143,7 @@ def test_small_batch_forward_parity(gpu, oracle, bits, N, K, group):
 
 @pytest.mark.parametrize("bits,Ns,K,group", [
     (4, (256, 384, 128), 512, 0), (3, (256, 256), 1024, 128), (4, (128, 128, 128, 640), 768, 64), (3, (1280,), 2048, 0),
+    (4, (8192, 8192, 4096), 384, 0),       # 160 tiles together: the 12-wave workgroups, three layers side by side
 ])
 def test_fused_forward_parity(gpu, oracle, bits, Ns, K, group):
     """Several layers reading one X through peqa_linear_fwd_fused: every Y equals the single-layer forward."""

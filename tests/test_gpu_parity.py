@@ -515,6 +515,57 @@ def test_scale_update_multi_equals_single_calls(gpu):
             assert not (gpu.to_host(ta[k]) == th[k]).all()           # and something was updated
 
 
+@pytest.mark.parametrize("bits,group,T", [(4, 0, 150), (3, 128, 150), (4, 0, 9), (3, 64, 16)])
+def test_buffers_at_16_byte_offsets(gpu, oracle, bits, group, T):
+    """The boundary asks for 16-byte alignment only: every tensor here starts 16 bytes into its allocation."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    N, K = 384, 640
+    seed = 7700 + bits + group + T
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dY = synth.normal_bf16(seed + 2, (T, N), 1.0)
+    codes, s0, z0 = oracle.quantize(W, bits, group)
+    L = peqa.layout(N, K, bits, group)
+    G = L.groups
+
+    def shifted(a, torch_dtype):
+        """A device copy of `a` that starts 16 bytes past a 256-byte aligned allocation."""
+        flat = np.ascontiguousarray(a).reshape(-1)
+        pad = 16 // flat.dtype.itemsize
+        buf = torch.zeros(flat.size + pad, dtype=torch_dtype, device="cuda")
+        view = buf[pad:]
+        view.copy_(gpu.to_dev(flat).view(torch_dtype))
+        assert view.data_ptr() % 256 == 16
+        return view
+
+    Wd = shifted(W, torch.float32)
+    packed = torch.zeros(peqa.packed_words(L) + 4, dtype=torch.int32, device="cuda")[4:]
+    s0d = torch.zeros(N * G + 4, dtype=torch.float32, device="cuda")[4:]
+    z0d = torch.zeros(N * G + 16, dtype=torch.uint8, device="cuda")[16:]
+    peqa.quantize(L, Wd, packed, s0d, z0d)
+    torch.cuda.synchronize()
+    assert (gpu.to_host(packed, np.uint32) == oracle.pack(codes, bits)).all()
+    assert (gpu.to_host(s0d).view(np.uint32) == s0.reshape(-1).view(np.uint32)).all()
+    assert (gpu.to_host(z0d) == z0.reshape(-1)).all()
+    Xd = shifted(X.view(np.int16), torch.int16)
+    dYd = shifted(dY.view(np.int16), torch.int16)
+    Y = torch.zeros(T * N + 8, dtype=torch.int16, device="cuda")[8:]
+    dX = torch.zeros(T * K + 8, dtype=torch.int16, device="cuda")[8:]
+    dds = torch.zeros(N * G + 4, dtype=torch.float32, device="cuda")[4:]
+    nb = max(peqa.workspace_bytes(L, T, peqa.PEQA_OP_FWD), peqa.workspace_bytes(L, T, peqa.PEQA_OP_BWD))
+    ws = torch.zeros(nb + 16, dtype=torch.uint8, device="cuda")[16:]
+    peqa.linear_fwd(L, packed, s0d, None, z0d, Xd, T, Y, ws, nb)
+    peqa.linear_bwd(L, packed, s0d, None, z0d, Xd, dYd, T, dX, dds, ws, nb)
+    torch.cuda.synchronize()
+    Yref = oracle.fwd(codes, s0, None, z0, X, group)
+    dXref, gref, _ = oracle.bwd(codes, s0, None, z0, X, dY, group)
+    assert np.abs(gpu.bf16_dev_to_f64(Y).reshape(T, N) - Yref).max() <= Y_TOL * np.abs(Yref).max()
+    assert np.abs(gpu.bf16_dev_to_f64(dX).reshape(T, K) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    g = gpu.to_host(dds).astype(np.float64).reshape(N, G)
+    assert np.linalg.norm(g - gref) <= G_TOL * np.linalg.norm(gref)
+
+
 def test_trace_reports_kernels(gpu):
     from paper_2305_14152_amd import peqa
     W = synth.normal_f32(5, (256, 256), 0.02)

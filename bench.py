@@ -184,7 +184,41 @@ def small_batch(torch, peqa, layers, cfg, ws, ws_bytes, stream, reps=20):
             "GBs_wall": round(bytes_block / wall_us / 1e3, 1), "GBs_kernels": round(bytes_block / kern_us / 1e3, 1),
             "frac_of_hbm_peak_wall": round(bytes_block / wall_us / 1e3 / HBM_PEAK_GBS, 4),
         }
+    out["large_layer"] = large_layer(torch, peqa, cfg, stream)
     return out
+
+
+def large_layer(torch, peqa, cfg, stream, reps=10):
+    """What the matrix-vector kernel reaches when one launch is long enough to hide its ramp: a single
+    32768 x 16384 layer of this workload's bit width (per-channel), T = 1, two rotating weight sets."""
+    N, K, T, bits = 32768, 16384, 1, cfg["bits"]
+    L = peqa.layout(N, K, bits, 0)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(777)
+    sets = [torch.randint(-2 ** 31, 2 ** 31 - 1, (peqa.packed_words(L),), generator=g, device="cuda", dtype=torch.int32)
+            for _ in range(2)]
+    s0 = torch.full((N, 1), 0.01, dtype=torch.float32, device="cuda")
+    z0 = torch.full((N, 1), 7, dtype=torch.uint8, device="cuda")
+    X = torch.randn((T, K), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    nb = peqa.workspace_bytes(L, T, peqa.PEQA_OP_FWD)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+
+    def run():
+        for pk in sets:
+            peqa.linear_fwd(L, pk, s0, None, z0, X, T, Y, ws, nb, stream)
+
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / (reps * len(sets)) * 1e6
+    nbytes = N * K * bits / 8 + N * 9 + 2 * T * (K + N)
+    return {"shape": "%dx%d, %d-bit per-channel, T=%d" % (N, K, bits, T), "bytes": int(nbytes), "us_wall": round(us, 2),
+            "GBs_wall": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak_wall": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
 
 
 def kept_product(torch, peqa, layers, cfg, stream, steps):

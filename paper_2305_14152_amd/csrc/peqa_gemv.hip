@@ -294,6 +294,9 @@ int gemv_slices(int Ntot, int K, int T, int chunk)
     // workgroup per tile takes all of K
     if (chunk == K && tiles >= GV_WHOLE_MIN_TILES && tiles <= GV_WHOLE_MAX_TILES) return 1;
     int S = 512 / tiles;
+    // between one and one and a half tiles per compute unit a single slice leaves the units with one
+    // 4-wave workgroup each: two slices (up to three workgroups per unit) stream better, partials included
+    if (chunk == K && tiles > GV_WHOLE_MAX_TILES && 2 * tiles <= 768) S = 2;
     if (S > R / (2 * GV_WAVES)) S = R / (2 * GV_WAVES);
     const int by_bytes = T > 4 ? 6 : 16;
     if (S > by_bytes) S = by_bytes;

@@ -13,11 +13,8 @@
  *   - `stream` is a hipStream_t passed opaquely (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise and never allocate or free device
  *     memory.  All work of a call is ordered after what the stream held before the call and
- *     before what is enqueued after it.  (peqa_linear_bwd, when asked for both gradients,
- *     runs one of its two independent halves on a stream of the library's own, forked from
- *     and joined back into `stream` with events; that stream and its two events are created
- *     once per device at the first such call; PEQA_SERIAL_BWD=1 in the environment turns
- *     this off.)
+ *     before what is enqueued after it; the library creates no streams or events of its own,
+ *     so every call may be recorded by stream capture.
  *   - Arguments are validated on the host before the device is touched, so the
  *     error paths work on a machine without a GPU.  Return value: peqa_status.
  *   - bf16 tensors are passed as uint16_t bit patterns.

@@ -326,12 +326,23 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
     step_no = [0]
 
+    # per-channel layers: the row sums of every distinct input are taken once per step (peqa_row_sums) and
+    # handed to the forward of the layers that read it and to their backward
+    share_sums = not group
+    for grp in groups:
+        rs = torch.empty((T, 2), dtype=torch.float32, device="cuda") if share_sums else None
+        for j in grp:
+            layers[j].rs = rs
+
     def fwd_bwd(st):
-        for grp in groups:                       # one forward call per shared input (row sums of X taken once)
+        for grp in groups:                       # one forward call per shared input
+            first = layers[grp[0]]
             items = [(layers[j].L, layers[j].packed, layers[j].s0, layers[j].ds, layers[j].z0, layers[j].Y) for j in grp]
-            peqa.linear_fwd_fused(items, layers[grp[0]].X, T, ws, ws_bytes, st)
+            if share_sums:
+                peqa.row_sums(first.X, T, first.K, first.rs, st)
+            peqa.linear_fwd_fused_rs(items, first.X, first.rs, T, ws, ws_bytes, st)
         for l in reversed(layers):
-            peqa.linear_bwd(l.L, l.packed, l.s0, l.ds, l.z0, l.X, l.dY, T, l.dX, l.dds, ws, ws_bytes, st)
+            peqa.linear_bwd_rs(l.L, l.packed, l.s0, l.ds, l.z0, l.X, l.rs, l.dY, T, l.dX, l.dds, ws, ws_bytes, st)
 
     graph = [None]
 
@@ -421,7 +432,8 @@ def main():
         "flops_per_step": flops_step,
         "quantize_ms_total": round(sum(l.quantize_ms for l in layers), 3),
         "launch": ("hip graph of: " if args.graph else "direct launches: ") +
-                  "%d forward calls (layers sharing an input in one peqa_linear_fwd_fused), %d backward calls; "
+                  "%d forward calls (layers sharing an input in one peqa_linear_fwd_fused_rs, its row sums taken "
+                  "once per step by peqa_row_sums and reused by the backward), %d backward calls; "
                   "then the %d scale updates in one direct launch" % (len(groups), len(layers), len(layers)),
         "kernels": kernels,
         "roofline": roofline,

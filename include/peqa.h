@@ -170,6 +170,25 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Row sums shared between calls.  The per-channel contractions for T > 16 take the code offset and the
+ * zero-point out of the contraction through the sums of every row of X over the two halves of K,
+ *   row_sums[t] = ( sum_{k < ks} X[t,k],  sum_{k >= ks} X[t,k] ),   ks = (K / 2) rounded down to 64,
+ * which peqa_linear_fwd(_fused) and peqa_linear_bwd otherwise take themselves at every call (a launch of
+ * several microseconds each).  A training step can take them once per activation with peqa_row_sums
+ * ([T, 2] fp32: 8 T bytes to keep until the backward) and hand them to the forward of the layers that read
+ * that X and, later, to their backward.  row_sums = NULL makes these calls equal to the plain ones; calls
+ * that do not use such sums (T <= 16, group-wise layers) ignore the argument.
+ */
+peqa_status peqa_row_sums(const uint16_t *X, int32_t T, int32_t K, float *row_sums, void *stream);
+peqa_status peqa_linear_fwd_fused_rs(int32_t n, const peqa_fwd_item *items, const uint16_t *X,
+                                     const float *row_sums, int32_t T, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+peqa_status peqa_linear_bwd_rs(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                               const float *ds, const uint8_t *z0, const uint16_t *X,
+                               const float *row_sums, const uint16_t *dY, int32_t T, uint16_t *dX,
+                               float *d_ds, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Optional trade of activation memory for arithmetic, per-channel layers only (PEQA_ERR_GROUP for
  * group-wise ones).  In the scale gradient of Eq. 2,  d_ds[i] = sum_t dY[t,i] * P[t,i]  with
  *   P[t,i] = sum_k X[t,k] * (Q[i,k] - z0[i]),

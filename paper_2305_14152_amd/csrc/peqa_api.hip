@@ -365,9 +365,10 @@ size_t peqa_workspace_bytes_fused(int32_t n, const peqa_fwd_item *items, int32_t
     return need;
 }
 
-peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const uint16_t *X, int32_t T,
-                                  void *workspace, size_t workspace_bytes, void *stream)
+static peqa_status fwd_fused_impl(int32_t n, const peqa_fwd_item *items, const uint16_t *X, const float *row_sums,
+                                  int32_t T, void *workspace, size_t workspace_bytes, void *stream)
 {
+    if (row_sums && !aligned16(row_sums)) return PEQA_ERR_ALIGN;
     peqa_status st = check_fused(n, items, T);
     if (st != PEQA_OK) return st;
     if (!X) return PEQA_ERR_NULL;
@@ -387,9 +388,13 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
     // the tiled contraction runs the layers one by one; per-channel layers share the row sums of X
     if (!grouped(&items[0].layout)) {
         hipStream_t s = static_cast<hipStream_t>(stream);
-        float *rs = static_cast<float *>(workspace);       // carve() puts the row sums first
-        if (peqa::launch_rowsum(X, T, items[0].layout.k_in, split_point(items[0].layout.k_in), rs, s) != hipSuccess)
-            return PEQA_ERR_DEVICE;
+        const float *rs = row_sums;
+        if (!rs) {
+            float *own = static_cast<float *>(workspace);  // carve() puts the row sums first
+            if (peqa::launch_rowsum(X, T, items[0].layout.k_in, split_point(items[0].layout.k_in), own, s) != hipSuccess)
+                return PEQA_ERR_DEVICE;
+            rs = own;
+        }
         for (int j = 0; j < n; ++j) {
             const peqa_fwd_item &it = items[j];
             st = fwd_per_channel(&it.layout, it.packed, it.s0, it.ds, it.z0, nullptr, X, T, it.Y, nullptr, rs, s);
@@ -405,12 +410,25 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
     return PEQA_OK;
 }
 
+peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const uint16_t *X, int32_t T,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fwd_fused_impl(n, items, X, nullptr, T, workspace, workspace_bytes, stream);
+}
+
+peqa_status peqa_linear_fwd_fused_rs(int32_t n, const peqa_fwd_item *items, const uint16_t *X, const float *row_sums,
+                                     int32_t T, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return fwd_fused_impl(n, items, X, row_sums, T, workspace, workspace_bytes, stream);
+}
+
 // Backward shared by peqa_linear_bwd (dz = d_dz = NULL, op = PEQA_OP_BWD) and peqa_linear_bwd_z.
 static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
-                            const uint8_t *z0, const float *dz, const uint16_t *X, const uint16_t *dY, int32_t T,
-                            uint16_t *dX, float *d_ds, float *d_dz, int32_t op, void *workspace,
-                            size_t workspace_bytes, void *stream)
+                            const uint8_t *z0, const float *dz, const uint16_t *X, const float *row_sums,
+                            const uint16_t *dY, int32_t T, uint16_t *dX, float *d_ds, float *d_dz, int32_t op,
+                            void *workspace, size_t workspace_bytes, void *stream)
 {
+    if (row_sums && !aligned16(row_sums)) return PEQA_ERR_ALIGN;
     peqa_status st = peqa_check_layout(L);
     if (st != PEQA_OK) return st;
     if (!packed || !s0 || !z0 || !dY) return PEQA_ERR_NULL;
@@ -483,10 +501,15 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     // small kernels, beside each other on a second stream measured 2-6 % slower on the 7B block, launched
     // one by one (the events cost more than they hide) and as a captured graph alike.
     if (d_ds) {
-        float *rs = reinterpret_cast<float *>(ws + w.rs);
+        // row sums of X over the two contraction halves: the caller's (peqa_row_sums), or taken here
+        const float *rs = row_sums;
         float *partial = reinterpret_cast<float *>(ws + w.partial);
         const int ksplit = split_point(K);
-        if (peqa::launch_rowsum(X, T, K, ksplit, rs, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (!rs) {
+            float *own = reinterpret_cast<float *>(ws + w.rs);
+            if (peqa::launch_rowsum(X, T, K, ksplit, own, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            rs = own;
+        }
         peqa::GemmArgs a{};
         a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
         a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
@@ -519,7 +542,24 @@ peqa_status peqa_linear_bwd(const peqa_layout *L, const uint32_t *packed, const 
                             const uint8_t *z0, const uint16_t *X, const uint16_t *dY, int32_t T, uint16_t *dX,
                             float *d_ds, void *workspace, size_t workspace_bytes, void *stream)
 {
-    return bwd_impl(L, packed, s0, ds, z0, nullptr, X, dY, T, dX, d_ds, nullptr, PEQA_OP_BWD, workspace,
+    return bwd_impl(L, packed, s0, ds, z0, nullptr, X, nullptr, dY, T, dX, d_ds, nullptr, PEQA_OP_BWD, workspace,
+                    workspace_bytes, stream);
+}
+
+peqa_status peqa_row_sums(const uint16_t *X, int32_t T, int32_t K, float *row_sums, void *stream)
+{
+    if (!X || !row_sums) return PEQA_ERR_NULL;
+    if (T < 1 || T > (1 << 24) || K < 128 || K % 128 != 0) return PEQA_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(row_sums)) return PEQA_ERR_ALIGN;
+    return dev_status(peqa::launch_rowsum(X, T, K, split_point(K), row_sums, static_cast<hipStream_t>(stream)));
+}
+
+peqa_status peqa_linear_bwd_rs(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                               const uint8_t *z0, const uint16_t *X, const float *row_sums, const uint16_t *dY,
+                               int32_t T, uint16_t *dX, float *d_ds, void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    return bwd_impl(L, packed, s0, ds, z0, nullptr, X, row_sums, dY, T, dX, d_ds, nullptr, PEQA_OP_BWD, workspace,
                     workspace_bytes, stream);
 }
 
@@ -528,8 +568,8 @@ peqa_status peqa_linear_bwd_z(const peqa_layout *L, const uint32_t *packed, cons
                               uint16_t *dX, float *d_ds, float *d_dz, void *workspace, size_t workspace_bytes,
                               void *stream)
 {
-    return bwd_impl(L, packed, s0, ds, z0, dz, X, dY, T, dX, d_ds, d_dz, PEQA_OP_BWD_Z, workspace, workspace_bytes,
-                    stream);
+    return bwd_impl(L, packed, s0, ds, z0, dz, X, nullptr, dY, T, dX, d_ds, d_dz, PEQA_OP_BWD_Z, workspace,
+                    workspace_bytes, stream);
 }
 
 peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,

@@ -17,7 +17,8 @@ EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_wo
            "peqa_linear_bwd", "peqa_scale_update", "peqa_trace_begin", "peqa_trace_end",
            "peqa_workspace_bytes_fused", "peqa_linear_fwd_fused", "peqa_linear_fwd_keep", "peqa_linear_bwd_kept",
            "peqa_linear_fwd_z", "peqa_linear_bwd_z", "peqa_quantize_search",
-           "peqa_scale_update_multi", "peqa_device_info"]
+           "peqa_scale_update_multi", "peqa_device_info",
+           "peqa_row_sums", "peqa_linear_fwd_fused_rs", "peqa_linear_bwd_rs"]
 
 
 class Layout(ctypes.Structure):
@@ -85,6 +86,12 @@ def lib():
         L.peqa_scale_update.restype = i32
         L.peqa_scale_update_multi.argtypes = [i32, vp, ctypes.POINTER(AdamW), vp]
         L.peqa_scale_update_multi.restype = i32
+        L.peqa_row_sums.argtypes = [vp, i32, i32, vp, vp]
+        L.peqa_row_sums.restype = i32
+        L.peqa_linear_fwd_fused_rs.argtypes = [i32, vp, vp, vp, i32, vp, sz, vp]
+        L.peqa_linear_fwd_fused_rs.restype = i32
+        L.peqa_linear_bwd_rs.argtypes = [LP, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
+        L.peqa_linear_bwd_rs.restype = i32
         L.peqa_workspace_bytes_fused.argtypes = [i32, vp, i32]
         L.peqa_workspace_bytes_fused.restype = sz
         L.peqa_linear_fwd_fused.argtypes = [i32, vp, vp, i32, vp, sz, vp]
@@ -178,6 +185,23 @@ def device_info():
     f.restype = ctypes.c_int32
     _check(f(ctypes.byref(cus), ctypes.byref(khz)), "peqa_device_info")
     return cus.value, khz.value
+
+
+def row_sums(X, T, K, rs, stream=None):
+    _check(lib().peqa_row_sums(_ptr(X), int(T), int(K), _ptr(rs), _stream(stream)), "peqa_row_sums")
+
+
+def linear_fwd_fused_rs(layers, X, rs, T, workspace, workspace_bytes_, stream=None):
+    arr = _items(layers)
+    _check(lib().peqa_linear_fwd_fused_rs(len(layers), ctypes.addressof(arr), _ptr(X), _ptr(rs), int(T),
+                                          _ptr(workspace), int(workspace_bytes_), _stream(stream)),
+           "peqa_linear_fwd_fused_rs")
+
+
+def linear_bwd_rs(L, packed, s0, ds, z0, X, rs, dY, T, dX, d_ds, workspace, workspace_bytes_, stream=None):
+    _check(lib().peqa_linear_bwd_rs(ctypes.byref(L), _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(X), _ptr(rs),
+                                    _ptr(dY), int(T), _ptr(dX), _ptr(d_ds), _ptr(workspace), int(workspace_bytes_),
+                                    _stream(stream)), "peqa_linear_bwd_rs")
 
 
 def quantize_search(L, W0, n_ratios, min_ratio, packed, s0, z0, stream=None):

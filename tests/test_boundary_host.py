@@ -179,6 +179,18 @@ def test_scale_update_multi_validation_needs_no_device(peqa):
     assert f(1, ctypes.addressof(arr), byref(opt), None) == peqa.PEQA_ERR_PARAM
 
 
+def test_row_sums_validation_needs_no_device(peqa):
+    good, bad = 0x10000, 0x10004
+    f = peqa.lib().peqa_row_sums
+    assert f(None, 8, 256, good, None) == peqa.PEQA_ERR_NULL
+    assert f(good, 0, 256, good, None) == peqa.PEQA_ERR_SHAPE
+    assert f(good, 8, 192, good, None) == peqa.PEQA_ERR_SHAPE
+    assert f(good, 8, 256, bad, None) == peqa.PEQA_ERR_ALIGN
+    L = peqa.layout(256, 256, 4)
+    b = peqa.lib().peqa_linear_bwd_rs
+    assert b(ctypes.byref(L), good, good, None, good, good, bad, good, 8, good, good, good, 1 << 30, None) == peqa.PEQA_ERR_ALIGN
+
+
 def test_fused_forward_validation_needs_no_device(peqa):
     a, b = peqa.layout(256, 512, 4), peqa.layout(128, 512, 4)
     assert peqa.workspace_bytes_fused([(a, 16, 16, None, 16, 16), (b, 16, 16, None, 16, 16)], 4) > 0

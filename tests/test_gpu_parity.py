@@ -566,6 +566,42 @@ def test_buffers_at_16_byte_offsets(gpu, oracle, bits, group, T):
     assert np.linalg.norm(g - gref) <= G_TOL * np.linalg.norm(gref)
 
 
+def test_shared_row_sums_equal_the_plain_calls(gpu, oracle):
+    """peqa_row_sums once, then the forward and backward that take the sums: bit-identical to the calls that
+    take them themselves; the sums themselves against a plain fp64 sum of the bf16 inputs."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    bits, N, K, T = 4, 384, 640, 200
+    W = synth.normal_f32(31, (N, K), 0.02)
+    X = synth.normal_bf16(32, (T, K), 1.0)
+    dY = synth.normal_bf16(33, (T, N), 1.0)
+    layer = gpu.GpuLayer(W, bits, 0)
+    Xd, dYd = gpu.to_dev(X), gpu.to_dev(dY)
+    rs = torch.empty((T, 2), dtype=torch.float32, device="cuda")
+    peqa.row_sums(Xd, T, K, rs)
+    torch.cuda.synchronize()
+    Xf = synth.bf16_bits_to_f32(X).astype(np.float64)
+    ks = (K // 2) // 64 * 64
+    ref = np.stack([Xf[:, :ks].sum(axis=1), Xf[:, ks:].sum(axis=1)], axis=1)
+    assert np.abs(gpu.to_host(rs) - ref).max() <= 1e-5 * np.abs(Xf).sum(axis=1).max()
+    # forward
+    Y1 = torch.empty((T, N), dtype=torch.int16, device="cuda")
+    items = [(layer.L, layer.packed, layer.s0, None, layer.z0, Y1)]
+    nb = peqa.workspace_bytes_fused(items, T)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    peqa.linear_fwd_fused_rs(items, Xd, rs, T, ws, nb)
+    torch.cuda.synchronize()
+    assert (gpu.to_host(Y1) == gpu.to_host(layer.fwd(Xd, None))).all()
+    # backward
+    dX0, g0 = layer.bwd(Xd, dYd, None)
+    dX1 = torch.empty_like(dX0); g1 = torch.empty_like(g0)
+    wsb, nbb = layer.workspace(T, peqa.PEQA_OP_BWD)
+    peqa.linear_bwd_rs(layer.L, layer.packed, layer.s0, None, layer.z0, Xd, rs, dYd, T, dX1, g1, wsb, nbb)
+    torch.cuda.synchronize()
+    assert (gpu.to_host(dX1) == gpu.to_host(dX0)).all()
+    assert (gpu.to_host(g1).view(np.uint32) == gpu.to_host(g0).view(np.uint32)).all()
+
+
 def test_trace_reports_kernels(gpu):
     from paper_2305_14152_amd import peqa
     W = synth.normal_f32(5, (256, 256), 0.02)

@@ -4,7 +4,9 @@
 One "step" = one training pass over the seven linears of a LLaMA-7B decoder block
 (4-bit per-channel codes, T = 2048 tokens): forward Y, backward dX, scale gradient d_ds
 and the AdamW scale update, all through the C-ABI library.  Quantization is the method's
-one-time decomposition step and is done (and timed) once before the loop.
+one-time decomposition step and is done (and timed) once before the loop.  The layers of the block
+that read one input (q, k, v; gate, up) run stacked along their output channels as one layer each,
+which is a property of the packed layout, not another kernel (--separate runs the seven one by one).
 
 Prints ONE JSON line: fwd+bwd TFLOP/s counting 6*T*N*K flops per layer (three dense
 contractions: forward, dX, and the product recomputed for the scale gradient), with
@@ -36,6 +38,9 @@ def parse():
     ap.add_argument("--no-small-batch", action="store_true")
     ap.add_argument("--no-kept-product", action="store_true",
                     help="skip the secondary timing of the variant that keeps the forward's product")
+    ap.add_argument("--separate", action="store_true",
+                    help="run q, k, v and gate, up as separate layers (7 forward and 7 backward contractions "
+                         "of each kind) instead of stacked along their output channels (4 of each kind)")
     ap.add_argument("--graph", action="store_true",
                     help="replay a HIP graph of the forward and backward calls instead of launching them one by "
                          "one (measured about 1 %% slower than the direct launches on this workload)")
@@ -73,6 +78,34 @@ class Layer:
         self.dX = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
         self.ws_fwd = peqa.workspace_bytes(self.L, T, peqa.PEQA_OP_FWD)
         self.ws_bwd = peqa.workspace_bytes(self.L, T, peqa.PEQA_OP_BWD)
+
+
+def stack_layers(torch, peqa, members, bits, group):
+    """One layer out of layers that read the same input, stacked along the output channels.  Packed
+    codes are stored by rows of 128-channel tiles and s0, z0, ds by channel, so the stacked layer's
+    arrays are the members' arrays one after the other: Y and dY become [T, sum N] (each member a
+    column slice), and the backward returns the gradient of the shared input, i.e. the sum of the
+    members' dX, from one contraction over all sum N channels."""
+    first = members[0]
+    st = Layer.__new__(Layer)
+    st.N, st.K, st.T = sum(m.N for m in members), first.K, first.T
+    st.L = peqa.layout(st.N, st.K, bits, group)
+    st.packed = torch.cat([m.packed for m in members])
+    st.s0 = torch.cat([m.s0 for m in members])
+    st.z0 = torch.cat([m.z0 for m in members])
+    assert st.packed.numel() == peqa.packed_words(st.L)
+    st.quantize_ms = 0.0
+    st.ds = torch.zeros_like(st.s0)
+    st.m = torch.zeros_like(st.s0)
+    st.v = torch.zeros_like(st.s0)
+    st.dds = torch.empty_like(st.s0)
+    st.X = first.X
+    st.dY = torch.cat([m.dY for m in members], dim=1).contiguous()
+    st.Y = torch.empty((st.T, st.N), dtype=torch.bfloat16, device="cuda")
+    st.dX = torch.empty((st.T, st.K), dtype=torch.bfloat16, device="cuda")
+    st.ws_fwd = peqa.workspace_bytes(st.L, st.T, peqa.PEQA_OP_FWD)
+    st.ws_bwd = peqa.workspace_bytes(st.L, st.T, peqa.PEQA_OP_BWD)
+    return st
 
 
 def shared_input_groups(cfg):
@@ -321,7 +354,16 @@ def main():
     for grp in groups:
         for j in grp[1:]:
             layers[j].X = layers[grp[0]].X
-    ws_bytes = max(max(l.ws_fwd, l.ws_bwd) for l in layers)
+    # the layers the timed step runs: (q, k, v) and (gate, up) stacked along the output channels into one
+    # layer each unless --separate
+    block = layers
+    if not args.separate:
+        block = [layers[grp[0]] if len(grp) == 1 else stack_layers(torch, peqa, [layers[j] for j in grp], bits, group)
+                 for grp in groups]
+        groups_run = [[i] for i in range(len(block))]
+    else:
+        groups_run = groups
+    ws_bytes = max(max(l.ws_fwd, l.ws_bwd) for l in layers + block)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     step_no = [0]
@@ -329,32 +371,32 @@ def main():
     # per-channel layers: the row sums of every distinct input are taken once per step (peqa_row_sums) and
     # handed to the forward of the layers that read it and to their backward
     share_sums = not group
-    for grp in groups:
+    for grp in groups_run:
         rs = torch.empty((T, 2), dtype=torch.float32, device="cuda") if share_sums else None
         for j in grp:
-            layers[j].rs = rs
+            block[j].rs = rs
 
     def fwd_bwd(st):
-        for grp in groups:                       # one forward call per shared input
-            first = layers[grp[0]]
-            items = [(layers[j].L, layers[j].packed, layers[j].s0, layers[j].ds, layers[j].z0, layers[j].Y) for j in grp]
+        for grp in groups_run:                   # one forward call per shared input
+            first = block[grp[0]]
+            items = [(block[j].L, block[j].packed, block[j].s0, block[j].ds, block[j].z0, block[j].Y) for j in grp]
             if share_sums:
                 peqa.row_sums(first.X, T, first.K, first.rs, st)
             peqa.linear_fwd_fused_rs(items, first.X, first.rs, T, ws, ws_bytes, st)
-        for l in reversed(layers):
+        for l in reversed(block):
             peqa.linear_bwd_rs(l.L, l.packed, l.s0, l.ds, l.z0, l.X, l.rs, l.dY, T, l.dX, l.dds, ws, ws_bytes, st)
 
     graph = [None]
 
     def step(use_graph=True):
-        # forward and backward of the 7 layers (launched one by one, or one HIP graph replayed with --graph),
-        # then the 7 scale updates (one launch), which carry the step number
+        # forward and backward of the block's layers (launched one by one, or one HIP graph replayed with
+        # --graph), then their scale updates (one launch), which carry the step number
         step_no[0] += 1
         if graph[0] is not None and use_graph:
             graph[0].replay()
         else:
             fwd_bwd(stream)
-        peqa.scale_update_multi([(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0) for l in layers], lr=1e-5,
+        peqa.scale_update_multi([(l.ds.numel(), l.ds, l.dds, l.m, l.v, l.s0) for l in block], lr=1e-5,
                                 step=step_no[0], stream=stream)
 
     if args.pmc_calibration:
@@ -393,7 +435,7 @@ def main():
     trace = peqa.trace_end(16)
     # gemm_dw: the scale gradient of group-wise layers (contraction over tokens), same 2 T N K flops
     gemm_flops = {"gemm_y": 0.0, "gemm_dds": 0.0, "gemm_dx": 0.0, "gemm_dw": 0.0}
-    for l in layers:
+    for l in block:
         for k in gemm_flops:
             gemm_flops[k] += 2.0 * T * l.N * l.K * args.steps
     dom = max((k for k in gemm_flops if k in trace), key=lambda k: trace[k][1])
@@ -426,7 +468,10 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: 7 linears of one decoder block, %d-bit %s, T=%d, fwd + dX + d_ds + AdamW"
-                               % (cfg["name"], bits, "per-channel" if not group else "g%d" % group, T)},
+                               % (cfg["name"], bits, "per-channel" if not group else "g%d" % group, T),
+                   "layers_run": "7 separate layers" if args.separate else
+                                 "q,k,v and gate,up each stacked along the output channels (same weights, same flops): "
+                                 "%d layers of N = %s" % (len(block), [l.N for l in block])},
         "frac_of_bf16_mfma_peak": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
         "tokens_per_s": round(T / (dt / args.steps), 1),
         "flops_per_step": flops_step,
@@ -434,7 +479,7 @@ def main():
         "launch": ("hip graph of: " if args.graph else "direct launches: ") +
                   "%d forward calls (layers sharing an input in one peqa_linear_fwd_fused_rs, its row sums taken "
                   "once per step by peqa_row_sums and reused by the backward), %d backward calls; "
-                  "then the %d scale updates in one direct launch" % (len(groups), len(layers), len(layers)),
+                  "then the %d scale updates in one direct launch" % (len(groups_run), len(block), len(block)),
         "kernels": kernels,
         "roofline": roofline,
         "device": device_info(torch, peqa),

@@ -23,6 +23,15 @@
  *
  * Shape limits: N % 128 == 0, K % 128 == 0 (every LLaMA-family linear satisfies
  * this).  group_size is 0 or a multiple of 64 that divides K.
+ *
+ * Stacking.  The packed array is stored by rows of 128-channel tiles and the scale-shaped
+ * arrays by channel, so layers with equal K, bits and group_size that read the same input
+ * (the query, key and value projections; gate and up) can be laid one after the other in
+ * memory -- each quantized by its own peqa_quantize call into its slice of packed, s0, z0 --
+ * and then run as ONE layer with N = the sum of theirs: Y and dY are [T, sum N] with every
+ * member a column range, d_ds is the members' gradients one after the other, and dX is the
+ * gradient of the shared input (the sum of the members' dX) from a single contraction.
+ * Results per member are bit-identical to running it alone; only dX, a sum, is new.
  */
 #ifndef PEQA_H
 #define PEQA_H

@@ -174,6 +174,69 @@ def test_fused_forward_parity(gpu, oracle, bits, Ns, K, group):
             assert np.abs(got - Yref).max() <= Y_TOL * np.abs(Yref).max(), T
 
 
+@pytest.mark.parametrize("bits,Ns,K,T,group", [
+    (4, (256, 128, 384), 512, 200, 0), (3, (384, 384), 640, 130, 0), (4, (128, 256), 768, 9, 0),
+    (3, (256, 128, 128), 512, 150, 128), (4, (384, 256), 768, 70, 64),
+])
+def test_stacked_layers(gpu, oracle, bits, Ns, K, T, group):
+    """Layers that read one input, stacked along the output channels, are one layer whose arrays are the
+    members' arrays one after the other: quantized member by member into slices of the stacked arrays it
+    gives the members' Y and scale gradients bit for bit, and dX is the sum of the members' dX."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    _log("stacked bits=%d Ns=%s K=%d T=%d g=%d" % (bits, Ns, K, T, group))
+    seed = 17000 + bits * 1000 + sum(Ns) + K + T + group
+    Ws = [synth.normal_f32(seed + 10 * j, (N, K), 0.02) for j, N in enumerate(Ns)]
+    members = [gpu.GpuLayer(W, bits, group) for W in Ws]
+    # the stacked layer, quantized through slices of its own arrays
+    Nsum = sum(Ns)
+    L = peqa.layout(Nsum, K, bits, group)
+    G = L.groups
+    packed = torch.empty(peqa.packed_words(L), dtype=torch.int32, device="cuda")
+    s0 = torch.empty((Nsum, G), dtype=torch.float32, device="cuda")
+    z0 = torch.empty((Nsum, G), dtype=torch.uint8, device="cuda")
+    w_off = n_off = 0
+    for m in members:
+        nw = peqa.packed_words(m.L)
+        peqa.quantize(m.L, m.W0, packed[w_off:w_off + nw], s0[n_off:n_off + m.N], z0[n_off:n_off + m.N])
+        w_off += nw
+        n_off += m.N
+    torch.cuda.synchronize()
+    assert w_off == packed.numel()
+    whole = gpu.GpuLayer(np.concatenate(Ws), bits, group)          # the stack quantized as one matrix
+    assert (gpu.to_host(packed) == gpu.to_host(whole.packed)).all()
+    assert (gpu.to_host(s0).view(np.uint32) == gpu.to_host(whole.s0).view(np.uint32)).all()
+    assert (gpu.to_host(z0) == gpu.to_host(whole.z0)).all()
+    assert (gpu.to_host(packed) == np.concatenate([gpu.to_host(m.packed) for m in members])).all()
+
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dYs = [synth.normal_bf16(seed + 2 + j, (T, N), 1.0) for j, N in enumerate(Ns)]
+    dss = [synth.normal_f32(seed + 50 + j, (N, G), 1e-3) for j, N in enumerate(Ns)]
+    ds_all = np.concatenate(dss)
+    Y = whole.fwd(X, ds_all)
+    Yh = gpu.to_host(Y)
+    n_off = 0
+    for m, ds in zip(members, dss):
+        assert (Yh[:, n_off:n_off + m.N] == gpu.to_host(m.fwd(X, ds))).all()
+        n_off += m.N
+    if T <= 16:
+        return                                                     # the backward takes T of any size; one case is enough
+    dX, dds = whole.bwd(X, np.concatenate(dYs, axis=1), ds_all)
+    ddsh = gpu.to_host(dds)
+    dXref = np.zeros((T, K))
+    n_off = 0
+    for m, W, ds, dY in zip(members, Ws, dss, dYs):
+        _, g_m = m.bwd(X, dY, ds, want_dX=False)
+        assert (ddsh[n_off:n_off + m.N].view(np.uint32) == gpu.to_host(g_m).view(np.uint32)).all()
+        codes, s0_m, z0_m = oracle.quantize(W, bits, group)
+        dXm, gref, _ = oracle.bwd(codes, s0_m, ds, z0_m, X, dY, group)
+        err = np.linalg.norm(ddsh[n_off:n_off + m.N].astype(np.float64) - gref) / np.linalg.norm(gref)
+        assert err <= G_TOL
+        dXref += dXm
+        n_off += m.N
+    assert np.abs(gpu.bf16_dev_to_f64(dX) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+
+
 @pytest.mark.parametrize("bits,group", [(4, 0), (3, 0), (4, 128), (3, 64)])
 def test_zero_and_negative_scales(gpu, oracle, bits, group):
     """The trained scale s0 + ds may reach zero or change sign: Y and dX follow it linearly, the scale

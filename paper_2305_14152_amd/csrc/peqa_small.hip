@@ -24,12 +24,21 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
     const u32x4 *row = reinterpret_cast<const u32x4 *>(X + (size_t)t * K);
     float s[2] = {0.f, 0.f};
     const int split8 = ksplit >> 3;
-    for (int k8 = lane; k8 < (K >> 3); k8 += 64) {
-        const u32x4 v = row[k8];
-        float p = 0.f;
+    const int n8 = K >> 3;
+    // four 16-byte loads of a lane in flight; chunks past the row's end re-read its first chunk and add nothing
+    for (int k8 = lane; k8 < n8; k8 += 256) {
+        u32x4 v[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p += bf16_lo(v[i]) + bf16_hi(v[i]);
-        if (k8 < split8) s[0] += p; else s[1] += p;
+        for (int u = 0; u < 4; ++u) v[u] = row[k8 + 64 * u < n8 ? k8 + 64 * u : 0];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float p = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p += bf16_lo(v[u][i]) + bf16_hi(v[u][i]);
+            const int kk = k8 + 64 * u;
+            s[0] += kk < split8 ? p : 0.f;
+            s[1] += kk >= split8 && kk < n8 ? p : 0.f;
+        }
     }
     s[0] = wave_sum(s[0]);
     s[1] = wave_sum(s[1]);
@@ -238,8 +247,17 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 {
     const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= n) return;
+    // eight loads in flight, added in tile order
     float s = 0.f;
-    for (int tt = 0; tt < ntiles; ++tt) s += partial[(size_t)tt * n + j];
+    int tt = 0;
+    for (; tt + 8 <= ntiles; tt += 8) {
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = partial[(size_t)(tt + u) * n + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += p[u];
+    }
+    for (; tt < ntiles; ++tt) s += partial[(size_t)tt * n + j];
     out[j] = s;
 }
 

@@ -13,7 +13,7 @@
  *   - `stream` is a hipStream_t passed opaquely (NULL = the default stream).
  *     Calls only enqueue work; they never synchronise and never allocate or free device
  *     memory.  All work of a call is ordered after what the stream held before the call and
- *     before what is enqueued after it; the library creates no streams or events of its own,
+ *     before what is enqueued after it; the library creates no streams and (outside peqa_trace_begin) no events,
  *     so every call may be recorded by stream capture.
  *   - Arguments are validated on the host before the device is touched, so the
  *     error paths work on a machine without a GPU.  Return value: peqa_status.

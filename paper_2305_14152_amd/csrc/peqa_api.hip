@@ -17,9 +17,10 @@ inline int groups(const peqa_layout *L) { return L->group_size > 0 ? L->k_in / L
 // A single group per channel is the per-channel layer, and takes its kernels.
 inline bool grouped(const peqa_layout *L) { return groups(L) > 1; }
 
-// Contraction index at which the second half of a contraction of length n starts:
-// half of it, rounded down to the step of 64 (n % 128 == 0 makes both halves non-empty).
-inline int split_point(int n) { return (n / 2) / 64 * 64; }
+// Contraction index at which the second half of a contraction of length n starts: the contraction
+// kernels give each of their two wave groups one half (n % 128 == 0, so both are whole steps of 64),
+// and the row sums their epilogues use are taken over the same halves.
+inline int split_point(int n) { return n / 2; }
 
 constexpr int PEQA_GEMV_MAX_T = 16;   // forward calls with at most this many tokens take the matrix-vector path
 
@@ -253,7 +254,7 @@ static peqa_status fwd_impl(const peqa_layout *L, const uint32_t *packed, const 
         float *sb = reinterpret_cast<float *>(ws + w.table);
         if (peqa::launch_group_table(s0, ds, z0, dz, N, groups(L), sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
-        a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
+        a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K;
         a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
         a.N = N; a.gsz = L->group_size; a.G = groups(L); a.sb = sb; a.out = Y;
         return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
@@ -324,7 +325,7 @@ peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const 
 {
     const int N = L->n_out, K = L->k_in;
     peqa::GemmArgs a{};
-    a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
+    a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K;
     a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
     a.s0 = s0; a.ds = ds; a.z0 = z0; a.dz = dz; a.rs = rs; a.out = Y; a.P = P;
     return dev_status(peqa::launch_gemm(L->bits, peqa::MODE_Y, a, s));
@@ -476,7 +477,7 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
         } else if (d_ds) {
             float *partial = reinterpret_cast<float *>(ws + w.partial);
             peqa::GemmArgs a{};
-            a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = split_point(K);
+            a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K;
             a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
             a.N = N; a.gsz = L->group_size; a.G = G;
             a.z0 = z0; a.dz = dz; a.rs = rsb; a.dY = dY; a.partial = partial;
@@ -488,7 +489,7 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
             float *sb = reinterpret_cast<float *>(ws + w.table);
             if (peqa::launch_group_table(s0, ds, z0, dz, N, G, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
             peqa::GemmArgs a{};
-            a.packed = packed; a.A = dY; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
+            a.packed = packed; a.A = dY; a.T = T; a.KC = N; a.C = K; a.K = K;
             a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
             a.N = N; a.gsz = L->group_size; a.G = G; a.sb = sb; a.out = dX;
             if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
@@ -511,7 +512,7 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
             rs = own;
         }
         peqa::GemmArgs a{};
-        a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K; a.ksplit = ksplit;
+        a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K;
         a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
         a.z0 = z0; a.dz = dz; a.rs = rs; a.dY = dY; a.partial = partial;
         if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
@@ -522,7 +523,7 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
         float *crow = reinterpret_cast<float *>(ws + w.crow);
         if (peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
-        a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
+        a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K;
         a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
         a.crow = crow; a.out = dX;
         if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
@@ -603,7 +604,7 @@ peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, c
         float *crow = reinterpret_cast<float *>(ws + w.crow);
         if (peqa::launch_scale_dy(dY, s0, ds, z0, nullptr, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
-        a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K; a.ksplit = split_point(N);
+        a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K;
         a.tiles_c = (K + 255) / 256; a.tiles_t = (T + 127) / 128;
         a.crow = crow; a.out = dX;
         if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;

@@ -22,14 +22,16 @@
 // the zero-point and the scale are applied in the epilogue from row sums of the other
 // operand:   sum_k X (Q - z) = sum_k X (16 + Q) - (16 + z) sum_k X.
 //
-// Group-wise scales (Sec. 4.2 and Table 5; group size a multiple of 128) use the GROUPED instantiations:
+// Group-wise scales (Sec. 4.2 and Table 5; group size a multiple of 64) use the GROUPED instantiations:
 //   MODE_Y, MODE_DX : the scale cannot leave the contraction, so every weight enters the MFMA as
 //                     bf16( s[i,g] (Q[i,k] - z[i,g]) ), formed in fp32 from a per-group table of
 //                     (s, -s (16 + z)) that rides through LDS next to the operand ring; the
 //                     epilogue is a plain store and the activation operand is X / dY itself.
 //   MODE_DDS        : one workgroup contracts one pair of scale groups (blockIdx.y), each
 //                     contraction half one group, and the column-reduced epilogue writes one
-//                     partial per (token tile, channel, group).
+//                     partial per (token tile, channel, group).  This is the older of two routes to
+//                     the grouped scale gradient (the default contracts over tokens, peqa_dw.hip)
+//                     and runs only on request (PEQA_GROUPED_DDS=pairs).
 #include <type_traits>
 
 #include "peqa_device.h"

@@ -17,7 +17,6 @@ struct GemmArgs {
     int KC;                   // contraction length: K (MODE_Y/DDS) or N (MODE_DX)
     int C;                    // output columns:     N (MODE_Y/DDS) or K (MODE_DX)
     int K;                    // input features of the layer (fixes the block stride of `packed`)
-    int ksplit;               // contraction index where the second half starts (multiple of 64)
     int tiles_c, tiles_t;     // ceil(C/256), ceil(T/128)
     int patch_t;              // token tiles per L2 patch (1, 2 or 4; set by launch_gemm)
     const float *s0;          // [N]            (MODE_Y)
@@ -30,7 +29,7 @@ struct GemmArgs {
     float *partial;           // [tiles_t, N]   (MODE_DDS) per-token-tile column sums
     uint16_t *out;            // [T, C] bf16    (MODE_Y: Y, MODE_DX: dX)
     float *P;                 // [T, N] fp32 or NULL (MODE_Y, per-channel): sum_k X[t,k] (Q[i,k] - z0[i]), kept
-    // group-wise layers (gsz > 0; a multiple of 128):
+    // group-wise layers (gsz > 0; a multiple of 64):
     int N;                    // output channels of the layer
     int gsz, G;               // group size and groups per channel
     const float *sb;          // [G, N, 2] (s0 + ds, -(s0 + ds)(16 + z0))  (MODE_Y, MODE_DX)

@@ -438,9 +438,8 @@ def test_quantize_search_parity(gpu, oracle, bits, N, K, group, n, m):
 
 
 def test_graph_capture_replays_match_eager(gpu, oracle):
-    """Forward + backward captured in a HIP graph (the backward forks onto the library's second
-    stream inside the capture): several replays, with eager work and synchronisation between them,
-    all equal to the eager results."""
+    """Forward + backward captured in a HIP graph: several replays, with eager work and
+    synchronisation between them, all equal to the eager results."""
     import torch
     from paper_2305_14152_amd import peqa
     N, K, T = 384, 512, 200

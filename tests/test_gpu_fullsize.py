@@ -37,14 +37,30 @@ def _sample(n, edges, rng, count):
 CASES = [(cfg, li) for cfg in (1, 2, 3, 4) for li in range(3)]
 
 
+# the layers bench.py runs stacked along their output channels: q, k, v and gate, up of configs 1 and 4
+STACKED = [(1, 0, 3), (1, 1, 2), (4, 0, 3), (4, 1, 2)]
+
+
 @pytest.mark.parametrize("cfg,li", CASES)
 def test_full_size_layer(gpu, oracle, cfg, li):
+    _full_size_layer(gpu, oracle, cfg, li, 1)
+
+
+@pytest.mark.parametrize("cfg,li,count", STACKED)
+def test_full_size_stacked_layer(gpu, oracle, cfg, li, count):
+    """`count` layers of one shape as one layer of count x N channels (dY and Y [T, count x N], dX the
+    gradient of the shared input), the shapes of bench.py's default run."""
+    _full_size_layer(gpu, oracle, cfg, li, count)
+
+
+def _full_size_layer(gpu, oracle, cfg, li, count):
     c = synth.CONFIGS[cfg]
     N, K, _ = c["layers"][li]
+    N *= count
     bits, group, T = c["bits"], c["group"], c["T"]
-    print("full size cfg=%d layer=%d N=%d K=%d T=%d bits=%d g=%d" % (cfg, li, N, K, T, bits, group), flush=True)
-    rng = np.random.default_rng(1000 * cfg + li)
-    W = synth.weights(cfg, li)
+    print("full size cfg=%d layer=%d x%d N=%d K=%d T=%d bits=%d g=%d" % (cfg, li, count, N, K, T, bits, group), flush=True)
+    rng = np.random.default_rng(1000 * cfg + li + 100 * (count - 1))
+    W = synth.weights(cfg, li, N=N)
     layer = gpu.GpuLayer(W, bits, group)
     codes, s0, z0 = oracle.quantize(W, bits, group)
     packed, gs0, gz0 = layer.host_quant()
@@ -55,11 +71,10 @@ def test_full_size_layer(gpu, oracle, cfg, li):
     layer.W0 = None
 
     X = synth.activations(cfg, li)
-    dY = synth.output_grads(cfg, li)
+    dY = synth.output_grads(cfg, li, N=N)
     ds = synth.normal_f32(77 + cfg, s0.shape, 1e-3 * float(np.mean(s0)))
     ts = _sample(T, (128, 1024), rng, 3)
-    ns = _sample(N, (128, 256, N // 2), rng, 8)
-    ks = None
+    ns = _sample(N, (128, 256, N // 2, N // count), rng, 8)
 
     # forward: sampled rows x sampled channels
     Y = gpu.bf16_dev_to_f64(layer.fwd(X, ds))

@@ -32,6 +32,8 @@
 //                     partial per (token tile, channel, group).  This is the older of two routes to
 //                     the grouped scale gradient (the default contracts over tokens, peqa_dw.hip)
 //                     and runs only on request (PEQA_GROUPED_DDS=pairs).
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "peqa_device.h"
@@ -47,24 +49,28 @@ constexpr int KSTEP = 32;                                  // contraction depth 
 constexpr int NSTAGE = 6;                                  // LDS ring depth
 constexpr int A_HALF_BYTES = TILE_T * KSTEP * 2;           // 8 KB: 128 rows x 32 bf16 of one contraction half
 constexpr int B_WAVE_BYTES = 2048;                         // one packed 8x8 block per lane (32 B / 24 B)
-constexpr int STAGE_BYTES = 2 * A_HALF_BYTES + 4 * B_WAVE_BYTES;   // 24 KB
+// A ring stage holds, per contraction half the workgroup runs (KW = 2 or 1), one 128 x 32 activation tile and
+// the packed weights of the two column halves: 24 KB or 12 KB.
+constexpr int stage_bytes(int kw) { return kw * (A_HALF_BYTES + 2 * B_WAVE_BYTES); }
 constexpr int DMA_PER_ITER = 3;                            // DMA instructions per wave per iteration
-constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES > 128 * 1024 ? NSTAGE * STAGE_BYTES : 128 * 1024;   // ring / epilogue exchange (128 KB)
-constexpr int TBL_BYTES = 4 * 2 * 1024;                    // grouped MODE_Y / MODE_DX: 2 x 1 KB of (s, b) per (column half, contraction half);
-                                                           // twice that for MODE_DX when groups end inside a 128-feature run
+constexpr int ring_bytes(int kw) { return NSTAGE * stage_bytes(kw); }   // 144 KB (the epilogue's exchange of 128 KB reuses it) or 72 KB
+constexpr int tbl_bytes(int kw) { return 2 * kw * 2 * 1024; }           // grouped MODE_Y / MODE_DX: 2 x 1 KB of (s, b) per (column half, contraction half);
+                                                                        // twice that for MODE_DX when groups end inside a 128-feature run
 
-template <int BITS, int MODE, bool GROUPED>
-__global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
+template <int BITS, int MODE, bool GROUPED, int KW>
+__global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
 {
+    constexpr int STAGE_BYTES = stage_bytes(KW);
     extern __shared__ __align__(16) uint8_t lds[];
     constexpr int WPB = 2 * BITS;                          // words per 8x8 block
     constexpr bool ALONG_CH = (MODE == MODE_DX);           // contraction over output channels
     constexpr bool SCALED = GROUPED && MODE != MODE_DDS;   // weights enter the MFMA already scaled
     constexpr bool PAIRED = GROUPED && MODE == MODE_DDS;   // one scale group per contraction half
+    static_assert(KW == 2 || (KW == 1 && !PAIRED), "the paired scale gradient needs both contraction halves");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
-    const int wt = wave & 1, wn = (wave >> 1) & 1, wk = wave >> 2;   // token half, column half, contraction half
+    const int wt = wave & 1, wn = (wave >> 1) & 1, wk = KW == 2 ? wave >> 2 : 0;   // token half, column half, contraction half
     const int c = lane & 15, q = lane >> 4;
 
     // workgroup -> tile.  Workgroup ids are dealt round-robin to the 8 XCDs and every CU holds one
@@ -99,10 +105,13 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         nit = a.gsz / KSTEP;                               // >= 2 and even: the group size is a multiple of 64
         grp = 2 * (int)blockIdx.y + wk;
         half_on = grp < a.G;
-    } else {
+    } else if constexpr (KW == 2) {
         kh0 = 0;
         kh1 = KC >> 1;                                     // both waves of a column half take KC/2
         nit = kh1 / KSTEP;                                 // loop iterations (>= 2: KC % 128 == 0)
+    } else {
+        kh0 = kh1 = 0;
+        nit = KC / KSTEP;                                  // a multiple of 4
     }
     const int kbeg = wk ? kh1 : kh0;
     const uint32_t magic = kMagic;
@@ -112,13 +121,18 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     // Wave-load m = 8 i + wave covers contraction half m / 8, rows 16 (m % 8) .. +16; lane s lands at
     // byte 16 s of that 1 KB, i.e. row s / 4, chunk position s % 4, and fetches the chunk that the
     // XOR swizzle assigns to that position.
-    uint32_t a_voff;
+    // With a single contraction half the four waves fetch the tile's 128 rows in two wave-loads each:
+    // rows 16 wave .. and 64 + 16 wave .. (the swizzle only looks at row % 16).
+    uint32_t a_voff, a_voff_hi = 0;
     {
         const int row_l = lane >> 2, pos = lane & 3;
         const int chunk = pos ^ a_swizzle(row_l);
-        int row = wave * 16 + row_l;
-        row = t0 + row < T ? row : T - 1 - t0;
-        a_voff = (uint32_t)row * (uint32_t)KC * 2u + (uint32_t)chunk * 16u;
+        auto voff_of = [&](int row) {
+            row = t0 + row < T ? row : T - 1 - t0;
+            return (uint32_t)row * (uint32_t)KC * 2u + (uint32_t)chunk * 16u;
+        };
+        a_voff = voff_of(wave * 16 + row_l);
+        if constexpr (KW == 1) a_voff_hi = voff_of(64 + wave * 16 + row_l);
     }
     const uint8_t *a_base = reinterpret_cast<const uint8_t *>(a.A) + (size_t)t0 * KC * 2;
 
@@ -169,18 +183,22 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     const int slot = wn + 2 * wk;
     if constexpr (BITS == 3) { if (wt) b_voff = b_voff2; }
 
-    // One of the three DMAs of a step: 0, 1 = activation tile (contraction half 0, 1), 2 = packed weights.
+    // One of the three DMAs of a step: 0, 1 = activation tile (contraction half 0, 1; or, with one half, rows
+    // 0..63 and 64..127), 2 = packed weights.
     // 4-bit weights: the two 16-byte halves of every lane's block go to the two token-half waves;
     // 3-bit: chunks 0..63 and 64..95 of the slot (lanes 32..63 of the second repeat chunks 64..95
     // into the slot's unused tail).
     auto issue_one = [&](int which, int it, int stage) {
         const uint32_t sb = lds_base + stage * STAGE_BYTES;
         if (which < 2) {
-            dma16(a_voff, a_base + (size_t)it * KSTEP * 2 + (size_t)(which ? kh1 : kh0) * 2,
-                  sb + which * A_HALF_BYTES + wave * 1024);
+            if constexpr (KW == 2)
+                dma16(a_voff, a_base + (size_t)it * KSTEP * 2 + (size_t)(which ? kh1 : kh0) * 2,
+                      sb + which * A_HALF_BYTES + wave * 1024);
+            else
+                dma16(which ? a_voff_hi : a_voff, a_base + (size_t)it * KSTEP * 2, sb + which * (A_HALF_BYTES / 2) + wave * 1024);
         } else {
             const uint8_t *bp = b_src(it) + (BITS == 4 ? wt * 16 : 0);
-            dma16(b_voff, bp, sb + 2 * A_HALF_BYTES + slot * B_WAVE_BYTES + wt * 1024);
+            dma16(b_voff, bp, sb + KW * A_HALF_BYTES + slot * B_WAVE_BYTES + wt * 1024);
         }
     };
     auto issue = [&](int it, int stage) {
@@ -257,7 +275,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
 
     // row = 64 wt + 16 rt + c and the swizzle only looks at row % 16
     const int a_read_off = wk * A_HALF_BYTES + (64 * wt + c) * 64 + ((q ^ a_swizzle(c)) << 4);
-    const int b_read_off = 2 * A_HALF_BYTES + slot * B_WAVE_BYTES + b_lane_off;
+    const int b_read_off = KW * A_HALF_BYTES + slot * B_WAVE_BYTES + b_lane_off;
     auto read_b = [&](int stage, uint32_t *bw) {
         const uint8_t *st = lds + stage * STAGE_BYTES + b_read_off;
         if constexpr (BITS == 4) {
@@ -366,6 +384,19 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
     }
     // Epilogue parameters are fetched while the last DMAs drain: per-column scale and zero-point of
     // this lane's 8 columns, per-row correction terms of the 8 rows this wave finishes (MODE_Y, MODE_DX)
+    // correction term of row 4 q + j of this wave's row tile rt: the row sum of X (MODE_Y) or crow (MODE_DX)
+    auto row_term = [&](int rt, int j) -> float {
+        int t = t0 + 64 * wt + rt * 16 + 4 * q + j;
+        t = t < T ? t : T - 1;
+        if constexpr (MODE == MODE_Y) {
+            const u32x2 r2 = *reinterpret_cast<const u32x2 *>(a.rs + 2 * t);
+            return __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
+        } else if constexpr (MODE == MODE_DX) {
+            return a.crow[t];
+        } else {
+            return 0.f;
+        }
+    };
     float ep_sc[8], ep_zoff[8], ep_row[8];
     if (wave_on && !SCALED) {
         if constexpr (PAIRED) {
@@ -401,16 +432,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
         }
         if constexpr (MODE != MODE_DDS) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int t = t0 + 64 * wt + (2 * wk + (i >> 2)) * 16 + 4 * q + (i & 3);
-                t = t < T ? t : T - 1;
-                if constexpr (MODE == MODE_Y) {
-                    const u32x2 r2 = *reinterpret_cast<const u32x2 *>(a.rs + 2 * t);
-                    ep_row[i] = __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
-                } else {
-                    ep_row[i] = a.crow[t];
-                }
-            }
+            for (int i = 0; i < 8; ++i) ep_row[i] = row_term(2 * wk + (i >> 2), i & 3);
         }
     }
     wait_vmcnt<0>();
@@ -437,8 +459,14 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                     const int t = row_of(rt, j), tc = t < T ? t : T - 1;
                     dst[j] = *reinterpret_cast<const u32x4 *>(a.dY + (size_t)tc * a.C + col0 + 8 * c);
                     // row sum of X over this contraction half, or over this half's scale group
-                    if constexpr (PAIRED) rdst[j] = a.rs[(size_t)tc * a.G + (half_on ? grp : a.G - 1)];
-                    else rdst[j] = a.rs[2 * tc + wk];
+                    if constexpr (PAIRED) {
+                        rdst[j] = a.rs[(size_t)tc * a.G + (half_on ? grp : a.G - 1)];
+                    } else if constexpr (KW == 2) {
+                        rdst[j] = a.rs[2 * tc + wk];
+                    } else {
+                        const u32x2 r2 = *reinterpret_cast<const u32x2 *>(a.rs + 2 * tc);
+                        rdst[j] = __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
+                    }
                 }
             };
             load_rows(std::integral_constant<int, 0>{}, dyv[0], rsv[0]);
@@ -466,7 +494,7 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
             colsum[ct] += __shfl_xor(colsum[ct], 16);
             colsum[ct] += __shfl_xor(colsum[ct], 32);
         }
-        float *red = reinterpret_cast<float *>(lds);           // [8 waves][128]
+        float *red = reinterpret_cast<float *>(lds);           // [waves][128]
         if (q == 0) {
 #pragma unroll
             for (int ct = 0; ct < 8; ++ct) red[wave * 128 + 8 * c + ct] = colsum[ct];
@@ -485,12 +513,65 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                     dst[0] = r0[0] + r0[128];
                     if (g0 + 1 < a.G) dst[1] = r0[4 * 128] + r0[5 * 128];
                 }
-            } else {
+            } else if constexpr (KW == 2) {
                 if (n < a.C)
                     a.partial[(size_t)tile_t * a.C + n] = (r0[0] + r0[128]) + (r0[4 * 128] + r0[5 * 128]);
+            } else {
+                if (n < a.C) a.partial[(size_t)tile_t * a.C + n] = r0[0] + r0[128];
             }
         }
     } else {
+        // rows 4 q + j (j = 0..3) of row tile rt, whose sums over the whole contraction are in sum[ct][j];
+        // r[j] = their correction terms
+        auto store_rows = [&](int rt, const f32x4 *sum, const float *r_) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int t = t0 + 64 * wt + rt * 16 + 4 * q + j;
+                if (t < T) {
+                    float v[8];
+                    const float r = r_[j];
+                    if constexpr (SCALED) {
+#pragma unroll
+                        for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j];
+                    } else if constexpr (MODE == MODE_Y) {
+#pragma unroll
+                        for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - ep_zoff[ct] * r;
+                        if (a.P) {                         // keep the unscaled product for the backward
+                            f32x4 *dst = reinterpret_cast<f32x4 *>(a.P + (size_t)t * a.C + col0 + 8 * c);
+                            dst[0] = f32x4{v[0], v[1], v[2], v[3]};
+                            dst[1] = f32x4{v[4], v[5], v[6], v[7]};
+                        }
+#pragma unroll
+                        for (int ct = 0; ct < 8; ++ct) v[ct] *= ep_sc[ct];
+                    } else {
+#pragma unroll
+                        for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - r;
+                    }
+                    u32x4 o;
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) o[p] = pack_bf16x2(v[2 * p], v[2 * p + 1]);
+                    *reinterpret_cast<u32x4 *>(a.out + (size_t)t * a.C + col0 + 8 * c) = o;
+                }
+            }
+        };
+        if constexpr (KW == 1) {
+            // one contraction range per workgroup: every wave holds the finished sums of its four row tiles;
+            // the correction terms of the last two are fetched while the first two are stored
+            if (wave_on) {
+                float ep_row_hi[8];
+                if constexpr (!SCALED) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) ep_row_hi[i] = row_term(2 + (i >> 2), i & 3);
+                }
+#pragma unroll
+                for (int rt = 0; rt < 4; ++rt) {
+                    f32x4 sum[8];
+#pragma unroll
+                    for (int ct = 0; ct < 8; ++ct) sum[ct] = acc[rt][ct];
+                    store_rows(rt, sum, rt < 2 ? ep_row + 4 * rt : ep_row_hi + 4 * (rt - 2));
+                }
+            }
+        } else {
         // sum the two contraction halves: wave wk keeps row tiles [2 wk, 2 wk + 2) and sends the others
         f32x4 *xch = reinterpret_cast<f32x4 *>(lds);           // [8 waves][16 tiles][64 lanes]
         auto finish = [&](auto keep_c) {
@@ -511,58 +592,47 @@ __global__ __launch_bounds__(512, 1) void gemm_kernel(GemmArgs a)
                 f32x4 sum[8];
 #pragma unroll
                 for (int ct = 0; ct < 8; ++ct) sum[ct] = acc[KEEP + rtl][ct] + theirs[(rtl * 8 + ct) * 64];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int t = t0 + 64 * wt + (KEEP + rtl) * 16 + 4 * q + j;
-                    if (t < T) {
-                        float v[8];
-                        const float r = ep_row[4 * rtl + j];
-                        if constexpr (SCALED) {
-#pragma unroll
-                            for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j];
-                        } else if constexpr (MODE == MODE_Y) {
-#pragma unroll
-                            for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - ep_zoff[ct] * r;
-                            if (a.P) {                     // keep the unscaled product for the backward
-                                f32x4 *dst = reinterpret_cast<f32x4 *>(a.P + (size_t)t * a.C + col0 + 8 * c);
-                                dst[0] = f32x4{v[0], v[1], v[2], v[3]};
-                                dst[1] = f32x4{v[4], v[5], v[6], v[7]};
-                            }
-#pragma unroll
-                            for (int ct = 0; ct < 8; ++ct) v[ct] *= ep_sc[ct];
-                        } else {
-#pragma unroll
-                            for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j] - r;
-                        }
-                        u32x4 o;
-#pragma unroll
-                        for (int p = 0; p < 4; ++p) o[p] = pack_bf16x2(v[2 * p], v[2 * p + 1]);
-                        *reinterpret_cast<u32x4 *>(a.out + (size_t)t * a.C + col0 + 8 * c) = o;
-                    }
-                }
+                store_rows(KEEP + rtl, sum, ep_row + 4 * rtl);
             }
         };
         if (wk == 0) finish(std::integral_constant<int, 0>{});
         else finish(std::integral_constant<int, 2>{});
+        }
     }
 }
 
 }  // namespace
 
-int gemm_lds_bytes() { return LDS_BYTES + 2 * TBL_BYTES; }
+// Contraction halves per workgroup.  Eight waves with two halves, one workgroup per compute unit, when a launch
+// has at most one tile per compute unit (a lone four-wave workgroup leaves every SIMD a single wave, which
+// measures 7-10 % slower); otherwise four waves with the whole range and two workgroups per compute unit
+// (72 KB of LDS each), which fill the same four SIMDs with two waves each, need no exchange of partial sums,
+// and hide one workgroup's ring fill and epilogue behind the other's loop.  PEQA_GEMM_WAVES=4 or 8 in the
+// environment (read at every launch) forces one of them, for tests and comparisons.
+static int halves_per_workgroup(int tiles, bool paired)
+{
+    if (paired) return 2;
+    if (const char *e = getenv("PEQA_GEMM_WAVES")) {
+        if (e[0] == '4') return 1;
+        if (e[0] == '8') return 2;
+    }
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    return tiles > cus ? 1 : 2;
+}
 
-template <int BITS, int MODE, bool GROUPED>
+template <int BITS, int MODE, bool GROUPED, int KW>
 static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
 {
     // dynamic LDS: the ring, plus the scale tables of the grouped forward / dX (twice as large for dX
     // when groups end inside a 128-feature run)
-    const int lds_bytes = LDS_BYTES + (GROUPED && MODE != MODE_DDS ? (MODE == MODE_DX && (a.gsz & 127) ? 2 : 1) * TBL_BYTES : 0);
+    const int lds_bytes = ring_bytes(KW) + (GROUPED && MODE != MODE_DDS ? (MODE == MODE_DX && (a.gsz & 127) ? 2 : 1) * tbl_bytes(KW) : 0);
     // the limit is a per-device attribute of every instantiation; raised to what a launch needs
     static int attr_bytes[64] = {0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     if (attr_bytes[dev] < lds_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MODE, GROUPED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MODE, GROUPED, KW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_bytes[dev] = lds_bytes;
@@ -572,17 +642,27 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
     const int grid = ((patches + 7) / 8) * 8 * 32;
     // grouped scale gradient: one pair of scale groups per workgroup along y
     const int gy = GROUPED && MODE == MODE_DDS ? (a.G + 1) / 2 : 1;
-    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED>), dim3(grid, gy), dim3(512), lds_bytes, stream, a);
+    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW>), dim3(grid, gy), dim3(256 * KW), lds_bytes, stream, a);
     return hipGetLastError();
+}
+
+template <int BITS, int MODE, bool GROUPED>
+static hipError_t launch_halves(const GemmArgs &a, hipStream_t stream)
+{
+    constexpr bool PAIRED = GROUPED && MODE == MODE_DDS;
+    if constexpr (!PAIRED) {
+        if (halves_per_workgroup(a.tiles_t * a.tiles_c, false) == 1) return launch_one<BITS, MODE, GROUPED, 1>(a, stream);
+    }
+    return launch_one<BITS, MODE, GROUPED, 2>(a, stream);
 }
 
 template <int BITS, bool GROUPED>
 static hipError_t dispatch_mode(int mode, const GemmArgs &a, hipStream_t stream)
 {
     switch (mode) {
-    case MODE_Y: return launch_one<BITS, MODE_Y, GROUPED>(a, stream);
-    case MODE_DDS: return launch_one<BITS, MODE_DDS, GROUPED>(a, stream);
-    default: return launch_one<BITS, MODE_DX, GROUPED>(a, stream);
+    case MODE_Y: return launch_halves<BITS, MODE_Y, GROUPED>(a, stream);
+    case MODE_DDS: return launch_halves<BITS, MODE_DDS, GROUPED>(a, stream);
+    default: return launch_halves<BITS, MODE_DX, GROUPED>(a, stream);
     }
 }
 

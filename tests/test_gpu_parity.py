@@ -116,6 +116,40 @@ def test_groupwise_training_parity(gpu, oracle, bits, N, K, T, group):
     _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, None, group)
 
 
+@pytest.mark.parametrize("bits,N,K,T,group", [
+    (4, 384, 640, 200, 0), (3, 384, 640, 200, 0), (4, 128, 128, 17, 0), (3, 512, 384, 129, 0), (3, 256, 896, 300, 0),
+    (4, 896, 256, 300, 0), (4, 1280, 512, 520, 0),
+    (3, 256, 512, 200, 128), (4, 256, 512, 64, 256), (3, 384, 384, 129, 128), (4, 384, 640, 300, 128),
+    (3, 1280, 2560, 150, 128), (4, 256, 512, 150, 64), (3, 384, 640, 77, 64), (4, 512, 768, 200, 192),
+])
+def test_four_wave_contraction_parity(gpu, oracle, monkeypatch, bits, N, K, T, group):
+    """The contraction kernels' second form (four waves over the whole contraction range, two workgroups per
+    compute unit), which launches of at least two tiles per compute unit take by themselves, forced here on
+    small shapes; the same checks as for the eight-wave form, and the two forms against each other."""
+    _log("four waves bits=%d N=%d K=%d T=%d g=%d" % (bits, N, K, T, group))
+    seed = 19000 + bits * 1000 + N + K + T + group
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dY = synth.normal_bf16(seed + 2, (T, N), 1.0)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, group)
+    ds = synth.normal_f32(seed + 3, s0.shape, 1e-3)
+    monkeypatch.setenv("PEQA_GEMM_WAVES", "8")
+    Y8 = gpu.bf16_dev_to_f64(layer.fwd(X, ds))
+    dX8, g8 = layer.bwd(X, dY, ds)
+    monkeypatch.setenv("PEQA_GEMM_WAVES", "4")
+    e = _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, ds, group)
+    _log("  errors: %.2e %.2e" % e)
+    _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, None, group)
+    Y4 = gpu.bf16_dev_to_f64(layer.fwd(X, ds))
+    dX4, g4 = layer.bwd(X, dY, ds)
+    # the two forms add the same products in a different order: a last bf16 bit here and there
+    assert np.abs(Y4 - Y8).max() <= 2.0 ** -7 * np.abs(Y8).max()
+    assert np.abs(gpu.bf16_dev_to_f64(dX4) - gpu.bf16_dev_to_f64(dX8)).max() <= 2.0 ** -7 * np.abs(gpu.bf16_dev_to_f64(dX8)).max()
+    g4h, g8h = gpu.to_host(g4).astype(np.float64), gpu.to_host(g8).astype(np.float64)
+    assert np.linalg.norm(g4h - g8h) <= 1e-5 * np.linalg.norm(g8h)
+
+
 @pytest.mark.parametrize("bits,N,K,group", [
     (4, 256, 512, 0), (3, 384, 640, 0), (3, 256, 1024, 128), (4, 512, 768, 64), (3, 640, 1152, 128),
     (4, 256, 512, 256), (3, 128, 128, 0), (4, 1280, 2048, 128),

@@ -516,12 +516,15 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
         a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
         a.z0 = z0; a.dz = dz; a.rs = rs; a.dY = dY; a.partial = partial;
         if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
-        if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        // the sum of the partials rides in the dX half's first launch when there is one
+        if (!dX && peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
     if (dX) {
         uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
         float *crow = reinterpret_cast<float *>(ws + w.crow);
-        if (peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, reinterpret_cast<const float *>(ws + w.partial),
+                                  tiles_t, d_ds ? (size_t)N : 0, d_ds, s) != hipSuccess)
+            return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
         a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K;
         a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
@@ -597,12 +600,15 @@ peqa_status peqa_linear_bwd_kept(const peqa_layout *L, const uint32_t *packed, c
         float *partial = reinterpret_cast<float *>(ws + w.partial);
         const int slices = (T + peqa::KEPT_ROWS - 1) / peqa::KEPT_ROWS;
         if (peqa::launch_dds_kept(dY, P, T, N, partial, s) != hipSuccess) return PEQA_ERR_DEVICE;
-        if (peqa::launch_reduce_partials(partial, slices, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (!dX && peqa::launch_reduce_partials(partial, slices, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
     if (dX) {
         uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
         float *crow = reinterpret_cast<float *>(ws + w.crow);
-        if (peqa::launch_scale_dy(dY, s0, ds, z0, nullptr, T, N, dys, crow, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        const int slices = (T + peqa::KEPT_ROWS - 1) / peqa::KEPT_ROWS;
+        if (peqa::launch_scale_dy(dY, s0, ds, z0, nullptr, T, N, dys, crow, reinterpret_cast<const float *>(ws + w.partial),
+                                  slices, d_ds ? (size_t)N : 0, d_ds, s) != hipSuccess)
+            return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
         a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K;
         a.tiles_c = (K + 255) / 256; a.tiles_t = (T + 127) / 128;

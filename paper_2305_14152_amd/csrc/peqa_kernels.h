@@ -82,8 +82,11 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 
 // peqa_small.hip
 hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream);
+// dYs = bf16(dY (s0 + ds)) and crow; with n_red > 0 the same launch also sums `ntiles` partial vectors of n_red
+// floats into red_out (launch_reduce_partials' job), an independent piece of work of the same backward
 hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0, const float *dz,
-                           int T, int N, uint16_t *dYs, float *crow, hipStream_t stream);
+                           int T, int N, uint16_t *dYs, float *crow, const float *partial, int ntiles, size_t n_red,
+                           float *red_out, hipStream_t stream);
 hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float *rsg, hipStream_t stream);
 hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, const float *dz, int N, int G,
                               float *sb, hipStream_t stream);

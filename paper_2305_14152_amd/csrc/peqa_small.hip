@@ -93,20 +93,55 @@ __global__ __launch_bounds__(256) void group_table_kernel(const float *__restric
     o[1] = -s * (kCodeOffset + (float)z0[j] + (dz ? dz[j] : 0.f));
 }
 
+// out[j] = partial[0][j] + partial[1][j] + ... in that order (deterministic).
+__device__ __forceinline__ void reduce_partials_at(const float *__restrict__ partial, int ntiles, size_t n, size_t j,
+                                                   float *__restrict__ out)
+{
+    if (j >= n) return;
+    // eight loads in flight, added in tile order
+    float s = 0.f;
+    int tt = 0;
+    for (; tt + 8 <= ntiles; tt += 8) {
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = partial[(size_t)(tt + u) * n + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += p[u];
+    }
+    for (; tt < ntiles; ++tt) s += partial[(size_t)tt * n + j];
+    out[j] = s;
+}
+
 // dYs[t,i] = bf16(dY[t,i] * (s0+ds)[i]);  crow[t] = sum_i dYs[t,i] * (16 + z0[i] + dz[i])  (per-channel).
 // crow uses the rounded dYs so that it cancels the code offset of the dX contraction exactly.
+// A workgroup takes SDY_ROWS token rows, so that the per-channel parameters are read once per four rows.
+// Workgroups past the last row block do an independent job in the same launch: the fixed-order sum of the
+// scale-gradient partials (n_red = 0: none), which the backward needs between its two contractions too.
+constexpr int SDY_ROWS = 4;
 __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ s0,
                                                         const float *__restrict__ ds, const uint8_t *__restrict__ z0,
-                                                        const float *__restrict__ dz, int N,
-                                                        uint16_t *__restrict__ dYs, float *__restrict__ crow)
+                                                        const float *__restrict__ dz, int T, int N,
+                                                        uint16_t *__restrict__ dYs, float *__restrict__ crow,
+                                                        const float *__restrict__ partial, int ntiles, size_t n_red,
+                                                        float *__restrict__ red_out)
 {
-    __shared__ float red[4];
-    const int t = blockIdx.x, tid = threadIdx.x;
-    const u32x4 *src = reinterpret_cast<const u32x4 *>(dY + (size_t)t * N);
-    u32x4 *dst = reinterpret_cast<u32x4 *>(dYs + (size_t)t * N);
-    float acc = 0.f;
-    for (int n8 = tid; n8 < (N >> 3); n8 += 256) {
-        const u32x4 v = src[n8];
+    __shared__ float red[SDY_ROWS][4];
+    const int tid = threadIdx.x;
+    const int row_blocks = (T + SDY_ROWS - 1) / SDY_ROWS;
+    if ((int)blockIdx.x >= row_blocks) {
+        reduce_partials_at(partial, ntiles, n_red, (size_t)((int)blockIdx.x - row_blocks) * 256 + tid, red_out);
+        return;
+    }
+    const int t0 = blockIdx.x * SDY_ROWS, rows = min(SDY_ROWS, T - t0);
+    const int n8s = N >> 3;
+    float acc[SDY_ROWS];
+#pragma unroll
+    for (int r = 0; r < SDY_ROWS; ++r) acc[r] = 0.f;
+    for (int n8 = tid; n8 < n8s; n8 += 256) {
+        u32x4 v[SDY_ROWS];                                 // rows past T re-read the last one and are dropped
+#pragma unroll
+        for (int r = 0; r < SDY_ROWS; ++r)
+            v[r] = reinterpret_cast<const u32x4 *>(dY + (size_t)(t0 + min(r, rows - 1)) * N)[n8];
         const f32x4 sa = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8);
         const f32x4 sb = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8 + 4);
         float s[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
@@ -126,20 +161,26 @@ __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restric
 #pragma unroll
             for (int i = 0; i < 4; ++i) { zo[i] += za[i]; zo[4 + i] += zb[i]; }
         }
-        u32x4 o;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uint32_t lo = float_to_bf16_bits(bf16_lo(v[p]) * s[2 * p]);
-            const uint32_t hi = float_to_bf16_bits(bf16_hi(v[p]) * s[2 * p + 1]);
-            o[p] = lo | (hi << 16);
-            acc += bf16_bits_to_float(lo) * zo[2 * p] + bf16_bits_to_float(hi) * zo[2 * p + 1];
+        for (int r = 0; r < SDY_ROWS; ++r) {
+            u32x4 o;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t lo = float_to_bf16_bits(bf16_lo(v[r][p]) * s[2 * p]);
+                const uint32_t hi = float_to_bf16_bits(bf16_hi(v[r][p]) * s[2 * p + 1]);
+                o[p] = lo | (hi << 16);
+                acc[r] += bf16_bits_to_float(lo) * zo[2 * p] + bf16_bits_to_float(hi) * zo[2 * p + 1];
+            }
+            if (r < rows) reinterpret_cast<u32x4 *>(dYs + (size_t)(t0 + r) * N)[n8] = o;
         }
-        dst[n8] = o;
     }
-    acc = wave_sum(acc);
-    if ((tid & 63) == 0) red[tid >> 6] = acc;
+#pragma unroll
+    for (int r = 0; r < SDY_ROWS; ++r) {
+        acc[r] = wave_sum(acc[r]);
+        if ((tid & 63) == 0) red[r][tid >> 6] = acc[r];
+    }
     __syncthreads();
-    if (tid == 0) crow[t] = (red[0] + red[1]) + (red[2] + red[3]);
+    if (tid < rows) crow[t0 + tid] = (red[tid][0] + red[tid][1]) + (red[tid][2] + red[tid][3]);
 }
 
 // Scale gradient from the product P[t,i] = sum_k X[t,k] (Q[i,k] - z0[i]) that the forward kept:
@@ -241,24 +282,10 @@ __global__ __launch_bounds__(256) void dz_finish_kernel(const float *__restrict_
     d_dz[j] = -sc * s;
 }
 
-// out[j] = partial[0][j] + partial[1][j] + ... in that order (deterministic).
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial, int ntiles, size_t n,
                                                                float *__restrict__ out)
 {
-    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (j >= n) return;
-    // eight loads in flight, added in tile order
-    float s = 0.f;
-    int tt = 0;
-    for (; tt + 8 <= ntiles; tt += 8) {
-        float p[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = partial[(size_t)(tt + u) * n + j];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) s += p[u];
-    }
-    for (; tt < ntiles; ++tt) s += partial[(size_t)tt * n + j];
-    out[j] = s;
+    reduce_partials_at(partial, ntiles, n, (size_t)blockIdx.x * 256 + threadIdx.x, out);
 }
 
 __global__ __launch_bounds__(256) void adamw_kernel(size_t n, float *__restrict__ ds, const float *__restrict__ g,
@@ -344,10 +371,13 @@ hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z
 }
 
 hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0, const float *dz,
-                           int T, int N, uint16_t *dYs, float *crow, hipStream_t stream)
+                           int T, int N, uint16_t *dYs, float *crow, const float *partial, int ntiles, size_t n_red,
+                           float *red_out, hipStream_t stream)
 {
     trace_before(KID_SCALE_DY, stream);
-    hipLaunchKernelGGL(scale_dy_kernel, dim3(T), dim3(256), 0, stream, dY, s0, ds, z0, dz, N, dYs, crow);
+    const unsigned blocks = (unsigned)((T + SDY_ROWS - 1) / SDY_ROWS) + (unsigned)((n_red + 255) / 256);
+    hipLaunchKernelGGL(scale_dy_kernel, dim3(blocks), dim3(256), 0, stream, dY, s0, ds, z0, dz, T, N, dYs, crow, partial,
+                       ntiles, n_red, red_out);
     trace_after(KID_SCALE_DY, stream);
     return hipGetLastError();
 }

@@ -173,12 +173,19 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         }
     }
     if (!wave_on) { b_voff = lane * 32; b_voff2 = lane * 32; }
-    // packed bytes of contraction step `it` of this wave (a wave without columns re-reads tile 0)
-    auto b_src = [&](int it) -> const uint8_t * {
-        if (!wave_on) return reinterpret_cast<const uint8_t *>(a.packed);
-        if constexpr (!ALONG_CH) return b_base + (size_t)it * TILE;
-        const int m = m0 + it;
-        return b_base + (size_t)(m >> 2) * tile_row + (size_t)(m & 3) * (16 * BLK);
+    // Packed bytes of this wave's contraction steps.  They are fetched strictly in order, one step per call
+    // (the last one again and again once the range is used up; a wave without columns re-reads tile 0), so a
+    // running pointer advanced with selects stands in for the address arithmetic: branches in the loop cost
+    // the wave's instruction stream more than the few scalar operations.
+    const uint8_t *b_next = reinterpret_cast<const uint8_t *>(a.packed);
+    if (wave_on) b_next = ALONG_CH ? b_base + (size_t)(m0 >> 2) * tile_row + (size_t)(m0 & 3) * (16 * BLK) : b_base;
+    int b_idx = 0;                                         // step b_next points at
+    auto b_advance = [&]() {
+        const bool more = wave_on && b_idx < nit - 1;
+        size_t inc = TILE;
+        if constexpr (ALONG_CH) inc = ((m0 + b_idx) & 3) == 3 ? tile_row - 3 * (size_t)(16 * BLK) : (size_t)(16 * BLK);
+        b_next += more ? inc : 0;
+        b_idx += more ? 1 : 0;
     };
     const int slot = wn + 2 * wk;
     if constexpr (BITS == 3) { if (wt) b_voff = b_voff2; }
@@ -197,8 +204,9 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
             else
                 dma16(which ? a_voff_hi : a_voff, a_base + (size_t)it * KSTEP * 2, sb + which * (A_HALF_BYTES / 2) + wave * 1024);
         } else {
-            const uint8_t *bp = b_src(it) + (BITS == 4 ? wt * 16 : 0);
+            const uint8_t *bp = b_next + (BITS == 4 ? wt * 16 : 0);   // `it` is implied: the calls come in step order
             dma16(b_voff, bp, sb + KW * A_HALF_BYTES + slot * B_WAVE_BYTES + wt * 1024);
+            b_advance();
         }
     };
     auto issue = [&](int it, int stage) {

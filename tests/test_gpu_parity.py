@@ -150,6 +150,34 @@ def test_four_wave_contraction_parity(gpu, oracle, monkeypatch, bits, N, K, T, g
     assert np.linalg.norm(g4h - g8h) <= 1e-5 * np.linalg.norm(g8h)
 
 
+@pytest.mark.parametrize("bits,N,K,T,group", [(4, 1152, 512, 9000, 0), (3, 640, 768, 16500, 128)])
+def test_many_ragged_tiles(gpu, oracle, bits, N, K, T, group):
+    """More tiles than compute units with a ragged last token tile and a half-empty last column tile: the
+    launch takes the four-wave form by itself and runs several workgroups per compute unit one after the
+    other.  Forward, dX and the scale gradient on sampled token rows and channels."""
+    _log("many tiles bits=%d N=%d K=%d T=%d g=%d" % (bits, N, K, T, group))
+    seed = 21000 + bits * 1000 + N + K + T + group
+    rng = np.random.default_rng(seed)
+    W = synth.normal_f32(seed, (N, K), 0.02)
+    X = synth.normal_bf16(seed + 1, (T, K), 1.0)
+    dY = synth.normal_bf16(seed + 2, (T, N), 1.0)
+    layer = gpu.GpuLayer(W, bits, group)
+    codes, s0, z0 = _check_quant(gpu, oracle, layer, W, bits, group)
+    ds = synth.normal_f32(seed + 3, s0.shape, 1e-3)
+    ts = np.unique(np.concatenate([[0, 127, 128, T - 1, T - 2, (T // 128) * 128, (T // 128) * 128 - 1],
+                                   rng.integers(0, T, size=40)]))
+    ns = np.unique(np.concatenate([[0, 255, 256, N - 1, N - 128, N - 129], rng.integers(0, N, size=24)]))
+    Y = gpu.bf16_dev_to_f64(layer.fwd(X, ds))
+    Yref = oracle.fwd(codes, s0, ds, z0, X[ts], group)
+    assert np.abs(Y[ts] - Yref).max() <= Y_TOL * np.abs(Yref).max()
+    dX, dds = layer.bwd(X, dY, ds)
+    dXref, _, _ = oracle.bwd(codes, s0, ds, z0, X[ts], dY[ts], group)
+    assert np.abs(gpu.bf16_dev_to_f64(dX)[ts] - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    _, gref, _ = oracle.bwd(codes[ns], s0[ns], ds[ns], z0[ns], X, np.ascontiguousarray(dY[:, ns]), group)
+    g = gpu.to_host(dds).astype(np.float64)[ns]
+    assert np.linalg.norm(g - gref) <= G_TOL * np.linalg.norm(gref)
+
+
 @pytest.mark.parametrize("bits,N,K,group", [
     (4, 256, 512, 0), (3, 384, 640, 0), (3, 256, 1024, 128), (4, 512, 768, 64), (3, 640, 1152, 128),
     (4, 256, 512, 256), (3, 128, 128, 0), (4, 1280, 2048, 128),

@@ -204,8 +204,12 @@ __device__ __forceinline__ void mfma_result_fence()
 // serialise the ring with a conservative vmcnt(0); completion is tracked by hand with wait_vmcnt().
 __device__ __forceinline__ void dma16(uint32_t voff, const void *sbase, uint32_t lds_dst)
 {
+    // sbase is the same in every lane; saying so keeps it in scalar registers wherever the compiler cannot tell
+    const uint64_t u = (uint64_t)(uintptr_t)sbase;
+    const uint64_t ub = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(u >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)u);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(voff), "s"(sbase), "s"(lds_dst) : "memory");
+                 :: "v"(voff), "s"(ub), "s"(lds_dst) : "memory");
 }
 // Activation tiles sit in LDS as rows of 64 B (four 16-byte chunks).  Chunk j of row r is stored at
 // position j ^ a_swizzle(r): with it, the 16-byte reads of 8 (16) consecutive rows at one logical

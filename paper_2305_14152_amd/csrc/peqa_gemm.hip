@@ -127,7 +127,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     {
         const int row_l = lane >> 2, pos = lane & 3;
         const int chunk = pos ^ a_swizzle(row_l);
-        auto voff_of = [&](int row) {
+        auto voff_of = [&](int row) __attribute__((always_inline)) {
             row = t0 + row < T ? row : T - 1 - t0;
             return (uint32_t)row * (uint32_t)KC * 2u + (uint32_t)chunk * 16u;
         };
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     const uint8_t *b_next = reinterpret_cast<const uint8_t *>(a.packed);
     if (wave_on) b_next = ALONG_CH ? b_base + (size_t)(m0 >> 2) * tile_row + (size_t)(m0 & 3) * (16 * BLK) : b_base;
     int b_idx = 0;                                         // step b_next points at
-    auto b_advance = [&]() {
+    auto b_advance = [&]() __attribute__((always_inline)) {
         const bool more = wave_on && b_idx < nit - 1;
         size_t inc = TILE;
         if constexpr (ALONG_CH) inc = ((m0 + b_idx) & 3) == 3 ? tile_row - 3 * (size_t)(16 * BLK) : (size_t)(16 * BLK);
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     // 4-bit weights: the two 16-byte halves of every lane's block go to the two token-half waves;
     // 3-bit: chunks 0..63 and 64..95 of the slot (lanes 32..63 of the second repeat chunks 64..95
     // into the slot's unused tail).
-    auto issue_one = [&](int which, int it, int stage) {
+    auto issue_one = [&](int which, int it, int stage) __attribute__((always_inline)) {
         const uint32_t sb = lds_base + stage * STAGE_BYTES;
         if (which < 2) {
             if constexpr (KW == 2)
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
             b_advance();
         }
     };
-    auto issue = [&](int it, int stage) {
+    auto issue = [&](int it, int stage) __attribute__((always_inline)) {
         issue_one(0, it, stage);
         issue_one(1, it, stage);
         issue_one(2, it, stage);
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     const int bshift = (!ALONG_CH && fine) ? 1 : 2;
     const uint32_t tbuf = (ALONG_CH && fine) ? 2048 : 1024;    // bytes per buffer
     const uint32_t tbl_off = NSTAGE * STAGE_BYTES + slot * 2 * tbuf;
-    auto issue_table = [&](int B) {
+    auto issue_table = [&](int B) __attribute__((always_inline)) {
         const int last = (KC >> (5 + bshift)) - 1;
         B = B < last ? B : last;
         const size_t g = ALONG_CH ? (size_t)((col0 + (fine ? 64 * wt : 0)) / a.gsz) : (size_t)((B << (5 + bshift)) / a.gsz);
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     // built, which keeps 14 registers free.
     float sc[8], bo[8];
     const uint8_t *tbl_row = nullptr;
-    auto read_table = [&](int m) {
+    auto read_table = [&](int m) __attribute__((always_inline)) {
         tbl_row = lds + tbl_off + ((m >> bshift) & 1) * tbuf +
                   (ALONG_CH ? (fine ? (c >> 3) * 1024 : 0) + (m & 3) * 256 + q * 64 : c * 64);
         if constexpr (ALONG_CH) {
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         }
     };
     // register J of fragment I of the next step: plain (16 + Q) pairs, or scaled weights
-    auto next_frag_reg = [&](const BlockUnpacker<BITS, ALONG_CH> &up, auto i_c, auto j_c) -> uint32_t {
+    auto next_frag_reg = [&](const BlockUnpacker<BITS, ALONG_CH> &up, auto i_c, auto j_c) __attribute__((always_inline)) -> uint32_t {
         constexpr int I = decltype(i_c)::value, J = decltype(j_c)::value;
         const uint32_t pr = up.template frag_reg<I, J>(magic);
         if constexpr (!SCALED) {
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     // row = 64 wt + 16 rt + c and the swizzle only looks at row % 16
     const int a_read_off = wk * A_HALF_BYTES + (64 * wt + c) * 64 + ((q ^ a_swizzle(c)) << 4);
     const int b_read_off = KW * A_HALF_BYTES + slot * B_WAVE_BYTES + b_lane_off;
-    auto read_b = [&](int stage, uint32_t *bw) {
+    auto read_b = [&](int stage, uint32_t *bw) __attribute__((always_inline)) {
         const uint8_t *st = lds + stage * STAGE_BYTES + b_read_off;
         if constexpr (BITS == 4) {
             const u32x4 v0 = *reinterpret_cast<const u32x4 *>(st);
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         }
     };
 
-    auto read_a = [&](int stage, u32x4 *afrag, int rt) {
+    auto read_a = [&](int stage, u32x4 *afrag, int rt) __attribute__((always_inline)) {
         afrag[rt] = *reinterpret_cast<const u32x4 *>(lds + stage * STAGE_BYTES + a_read_off + rt * 16 * 64);
     };
 
@@ -345,9 +345,108 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     //                         re-fetches the last tile: harmless, and it keeps the DMA count per step
     //                         constant so that a fixed vmcnt tells when a stage has landed
     //   after each 8 MFMAs    the activation fragment just used up is refilled from LDS for step it + 1
-    // Two steps per loop trip so that the register buffers are static.
+    // NSTAGE steps per loop trip, so that the ring stage of every step is a compile-time constant: LDS
+    // destinations and read offsets are then literals.  With the stage in a register, forty-odd scalar
+    // instructions of ring and address arithmetic ran at the top of every step, which every wave went through
+    // right after the barrier and before its first matrix instruction; measured on a loop of the same
+    // instruction mix, forty dependent scalar instructions there cost 0.11 us per step.  What is left per step is
+    // one running source pointer for the activation tiles, one for the packed weights, and the step counter.
+    static_assert(NSTAGE % 2 == 0, "the register buffers alternate with the step's parity");
+    // LDS reads take a 16-bit literal offset: the stages of the first and of the second half of the ring are
+    // addressed from one lane-dependent base register each (kept live across the loop), the rest is literal.
+    constexpr int HALF_RING = (NSTAGE / 2) * STAGE_BYTES;
+    static_assert((NSTAGE / 2 - 1) * STAGE_BYTES + 4096 <= 65536, "literal offsets of LDS reads");
+    const uint8_t *a_rd[2] = {lds + a_read_off, lds + a_read_off + HALF_RING};
+    const uint8_t *b_rd[2] = {lds + b_read_off, lds + b_read_off + HALF_RING};
+    auto read_a_st = [&](auto st_c, u32x4 *af, int rt) __attribute__((always_inline)) {
+        constexpr int ST = decltype(st_c)::value;
+        af[rt] = *reinterpret_cast<const u32x4 *>(a_rd[ST / (NSTAGE / 2)] + (ST % (NSTAGE / 2)) * STAGE_BYTES + rt * 16 * 64);
+    };
+    auto read_b_st = [&](auto st_c, uint32_t *w) __attribute__((always_inline)) {
+        constexpr int ST = decltype(st_c)::value;
+        const uint8_t *st = b_rd[ST / (NSTAGE / 2)] + (ST % (NSTAGE / 2)) * STAGE_BYTES;
+        if constexpr (BITS == 4) {
+            const u32x4 v0 = *reinterpret_cast<const u32x4 *>(st);
+            const u32x4 v1 = *reinterpret_cast<const u32x4 *>(st + 1024);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { w[i] = v0[i]; w[4 + i] = v1[i]; }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const u32x2 v = *reinterpret_cast<const u32x2 *>(st + 8 * i);
+                w[2 * i] = v[0];
+                w[2 * i + 1] = v[1];
+            }
+        }
+    };
+    const uint8_t *a_ptr = a_base + (size_t)(NSTAGE - 1 < nit ? NSTAGE - 1 : nit - 1) * KSTEP * 2 + (KW == 2 ? (size_t)kh0 * 2 : 0);
+    const uint32_t a_voff_2 = KW == 2 ? a_voff + (uint32_t)(kh1 - kh0) * 2u : a_voff_hi;   // second activation DMA, same source pointer
+    const uint32_t dst_a = lds_base + wave * 1024;
+    const uint32_t dst_b = lds_base + KW * A_HALF_BYTES + slot * B_WAVE_BYTES + wt * 1024;
+    // (inlined by force: ten copies are more than the inliner takes by itself, and a call would pass the
+    // captured scalars through memory)
+    auto step = [&](int it, auto stage_c) __attribute__((always_inline)) {
+        constexpr int S = decltype(stage_c)::value;             // LDS stage of this step
+        constexpr int CUR = S & 1, NXT = CUR ^ 1;
+        constexpr int NS = (S + 1) % NSTAGE;                    // stage of step it + 1
+        constexpr int NNS = (S + 2) % NSTAGE;                   // stage of step it + 2
+        constexpr int PS = (S + NSTAGE - 1) % NSTAGE;           // stage of step it - 1 = of step it + NSTAGE - 1
+        if constexpr (SCALED) {
+            // the fragments built in this step belong to contraction step m = m0 + it + 1
+            const int m = m0 + it + 1;
+            read_table(m);
+            // The buffer of the block before m's was last read in the previous step: fetch the block
+            // after m's into it.  With blocks of four steps this is done at the block's second step
+            // (three steps of lead); with blocks of two, at its first (two steps: the DMA is complete
+            // after the next step's wait and visible after its barrier, just in time).
+            if ((m & ((1 << bshift) - 1)) == (bshift == 2 ? 1 : 0) && table_wave) issue_table((m >> bshift) + 1);
+        }
+        BlockUnpacker<BITS, ALONG_CH> up;
+        up.prepare(bw[CUR]);
+        static_for<4>([&](auto rt_c) {
+            constexpr int rt = rt_c.value;
+            static_for<8>([&](auto ct_c) {
+                constexpr int ct = ct_c.value, m = 8 * rt + ct;
+                mfma16_acc(acc[rt][ct], afrag[rt], bfrag[CUR][ct]);
+                bfrag[NXT][2 * rt + (ct >> 2)][ct & 3] =
+                    next_frag_reg(up, std::integral_constant<int, 2 * rt + (ct >> 2)>{}, std::integral_constant<int, (ct & 3)>{});
+                if constexpr (m == 2) read_b_st(std::integral_constant<int, NNS>{}, bw[NXT]);
+                if constexpr (m == 5) dma16(a_voff, a_ptr, dst_a + PS * STAGE_BYTES);
+                if constexpr (m == 13) dma16(a_voff_2, a_ptr, dst_a + PS * STAGE_BYTES + (KW == 2 ? A_HALF_BYTES : A_HALF_BYTES / 2));
+                if constexpr (m == 21) {
+                    dma16(b_voff, b_next + (BITS == 4 ? wt * 16 : 0), dst_b + S * STAGE_BYTES);
+                    b_advance();
+                    // the activation tiles of the next step's DMAs: one step further, until the range is used up
+                    a_ptr += it + NSTAGE - 1 < nit - 1 ? KSTEP * 2 : 0;
+                }
+            });
+            read_a_st(std::integral_constant<int, NS>{}, afrag, rt);
+        });
+        // Own DMA for step it + 3 has landed; the barrier makes every wave's part visible.
+        // No wait on LDS reads is needed here: what this step read is overwritten two steps later.
+        wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4) + 1>();
+        bare_barrier();
+    };
+    // The eight-wave form (and one grouped instantiation of the four-wave form) does not fit into its registers
+    // when unrolled that far -- the compiler spills, which the hand-counted DMA queue cannot take -- and keeps
+    // the stage in a register, two steps per trip (the register buffers alternate).
+    constexpr bool RING_UNROLL = KW == 1 && !(SCALED && ALONG_CH && BITS == 4);
+    if constexpr (RING_UNROLL) {
+        int it = 0;
+        for (; it + NSTAGE <= nit; it += NSTAGE)
+            static_for<NSTAGE>([&](auto s_c) { step(it + decltype(s_c)::value, s_c); });
+        // nit is even (KC % 128 == 0): none, two or four steps are left, in stages 0..3
+        if (nit - it >= 2) {
+            step(it, std::integral_constant<int, 0>{});
+            step(it + 1, std::integral_constant<int, 1>{});
+        }
+        if (nit - it >= 4) {
+            step(it + 2, std::integral_constant<int, 2>{});
+            step(it + 3, std::integral_constant<int, 3>{});
+        }
+    } else {
     int cur = 0;                                           // LDS stage of the current step
-    auto step = [&](int it, auto cur_c) {
+    auto step2 = [&](int it, auto cur_c) __attribute__((always_inline)) {
         constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
         const int pre = it + NSTAGE - 1 < nit ? it + NSTAGE - 1 : nit - 1;
         const int pre_b = it + NSTAGE < nit ? it + NSTAGE : nit - 1;
@@ -387,13 +486,20 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         cur = nstage;
     };
     for (int it = 0; it < nit; it += 2) {                  // nit is even: KC % 128 == 0
-        step(it, std::integral_constant<int, 0>{});
-        step(it + 1, std::integral_constant<int, 1>{});
+        step2(it, std::integral_constant<int, 0>{});
+        step2(it + 1, std::integral_constant<int, 1>{});
     }
+    }
+    // The epilogue works out its lane indices afresh (from a copy of the thread index that the compiler cannot
+    // connect to the first one), so that none of them has to be held in a register through the loop.
+    {
+    int tid_e = threadIdx.x;
+    asm volatile("" : "+v"(tid_e));
+    const int tid = tid_e, lane = tid & 63, c = lane & 15, q = lane >> 4;
     // Epilogue parameters are fetched while the last DMAs drain: per-column scale and zero-point of
     // this lane's 8 columns, per-row correction terms of the 8 rows this wave finishes (MODE_Y, MODE_DX)
     // correction term of row 4 q + j of this wave's row tile rt: the row sum of X (MODE_Y) or crow (MODE_DX)
-    auto row_term = [&](int rt, int j) -> float {
+    auto row_term = [&](int rt, int j) __attribute__((always_inline)) -> float {
         int t = t0 + 64 * wt + rt * 16 + 4 * q + j;
         t = t < T ? t : T - 1;
         if constexpr (MODE == MODE_Y) {
@@ -457,10 +563,10 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
             // This lane's 16 rows are t0 + 64 wt + 16 rt + 4 q + j.  Rows past T are clamped for the
             // loads and masked in the sum, so that all loads are unconditional: dY and the row sums
             // four rows at a time, the next four in flight while these are used.
-            auto row_of = [&](int rt, int j) { return t0 + 64 * wt + rt * 16 + 4 * q + j; };
+            auto row_of = [&](int rt, int j) __attribute__((always_inline)) { return t0 + 64 * wt + rt * 16 + 4 * q + j; };
             u32x4 dyv[2][4];
             float rsv[2][4];
-            auto load_rows = [&](auto rt_c, u32x4 *dst, float *rdst) {
+            auto load_rows = [&](auto rt_c, u32x4 *dst, float *rdst) __attribute__((always_inline)) {
                 constexpr int rt = decltype(rt_c)::value;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -531,7 +637,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     } else {
         // rows 4 q + j (j = 0..3) of row tile rt, whose sums over the whole contraction are in sum[ct][j];
         // r[j] = their correction terms
-        auto store_rows = [&](int rt, const f32x4 *sum, const float *r_) {
+        auto store_rows = [&](int rt, const f32x4 *sum, const float *r_) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int t = t0 + 64 * wt + rt * 16 + 4 * q + j;
@@ -582,7 +688,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         } else {
         // sum the two contraction halves: wave wk keeps row tiles [2 wk, 2 wk + 2) and sends the others
         f32x4 *xch = reinterpret_cast<f32x4 *>(lds);           // [8 waves][16 tiles][64 lanes]
-        auto finish = [&](auto keep_c) {
+        auto finish = [&](auto keep_c) __attribute__((always_inline)) {
             constexpr int KEEP = decltype(keep_c)::value;      // first row tile this wave keeps
             constexpr int SEND = 2 - KEEP;
             {
@@ -606,6 +712,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         if (wk == 0) finish(std::integral_constant<int, 0>{});
         else finish(std::integral_constant<int, 2>{});
         }
+    }
     }
 }
 

@@ -501,6 +501,7 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     // unit), so everything stays in order on the caller's stream: running the two chains, or only their
     // small kernels, beside each other on a second stream measured 2-6 % slower on the 7B block, launched
     // one by one (the events cost more than they hide) and as a captured graph alike.
+    const bool dys_in_dds = d_ds && dX && peqa::gemm_four_waves(tiles_t * ((N + 255) / 256));
     if (d_ds) {
         // row sums of X over the two contraction halves: the caller's (peqa_row_sums), or taken here
         const float *rs = row_sums;
@@ -515,14 +516,24 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
         a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K;
         a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
         a.z0 = z0; a.dz = dz; a.rs = rs; a.dY = dY; a.partial = partial;
+        // When dX is wanted too and this contraction runs two workgroups per compute unit, the scaled copy of dY
+        // for the dX contraction is made by spare workgroups of the same launch; the partials are then summed
+        // by a launch of their own.  Otherwise that sum rides in the scale_dy launch of the dX half.
+        if (dys_in_dds) {
+            a.s0 = s0; a.ds = ds;
+            a.sdy_blocks = (T + 3) / 4;
+            a.sdy_out = reinterpret_cast<uint16_t *>(ws + w.dys);
+            a.sdy_crow = reinterpret_cast<float *>(ws + w.crow);
+        }
         if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
-        // the sum of the partials rides in the dX half's first launch when there is one
-        if (!dX && peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if ((!dX || dys_in_dds) && peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess)
+            return PEQA_ERR_DEVICE;
     }
     if (dX) {
         uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
         float *crow = reinterpret_cast<float *>(ws + w.crow);
-        if (peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, reinterpret_cast<const float *>(ws + w.partial),
+        if (!dys_in_dds &&
+            peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, reinterpret_cast<const float *>(ws + w.partial),
                                   tiles_t, d_ds ? (size_t)N : 0, d_ds, s) != hipSuccess)
             return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};

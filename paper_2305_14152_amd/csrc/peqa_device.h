@@ -164,6 +164,69 @@ struct BlockUnpacker {
     }
 };
 
+// Per-channel backward, the part of dY the dX contraction reads:  dYs[t,i] = bf16(dY[t,i] (s0 + ds)[i])  and
+// crow[t] = sum_i dYs[t,i] (16 + z0[i] + dz[i])  (from the rounded dYs, so that it cancels the code offset of the
+// contraction exactly), for the SDY_ROWS token rows of row block `blk`, by one workgroup of 256 threads
+// (the per-channel parameters are read once per four rows).  `red` is 16 floats of LDS.
+constexpr int SDY_ROWS = 4;
+__device__ __forceinline__ void scale_dy_rows(const uint16_t *__restrict__ dY, const float *__restrict__ s0,
+                                              const float *__restrict__ ds, const uint8_t *__restrict__ z0,
+                                              const float *__restrict__ dz, int T, int N, uint16_t *__restrict__ dYs,
+                                              float *__restrict__ crow, int blk, float *red)
+{
+    const int tid = threadIdx.x;
+    const int t0 = blk * SDY_ROWS, rows = min(SDY_ROWS, T - t0);
+    const int n8s = N >> 3;
+    float acc[SDY_ROWS];
+#pragma unroll
+    for (int r = 0; r < SDY_ROWS; ++r) acc[r] = 0.f;
+    for (int n8 = tid; n8 < n8s; n8 += 256) {
+        u32x4 v[SDY_ROWS];                                 // rows past T re-read the last one and are dropped
+#pragma unroll
+        for (int r = 0; r < SDY_ROWS; ++r)
+            v[r] = reinterpret_cast<const u32x4 *>(dY + (size_t)(t0 + min(r, rows - 1)) * N)[n8];
+        const f32x4 sa = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8);
+        const f32x4 sb = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8 + 4);
+        float s[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
+        if (ds) {
+            const f32x4 da = *reinterpret_cast<const f32x4 *>(ds + 8 * n8);
+            const f32x4 db = *reinterpret_cast<const f32x4 *>(ds + 8 * n8 + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { s[i] += da[i]; s[4 + i] += db[i]; }
+        }
+        const u32x2 zz = *reinterpret_cast<const u32x2 *>(z0 + 8 * n8);
+        float zo[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) zo[i] = kCodeOffset + (float)((zz[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+        if (dz) {
+            const f32x4 za = *reinterpret_cast<const f32x4 *>(dz + 8 * n8);
+            const f32x4 zb = *reinterpret_cast<const f32x4 *>(dz + 8 * n8 + 4);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { zo[i] += za[i]; zo[4 + i] += zb[i]; }
+        }
+#pragma unroll
+        for (int r = 0; r < SDY_ROWS; ++r) {
+            u32x4 o;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t lo = float_to_bf16_bits(bf16_lo(v[r][p]) * s[2 * p]);
+                const uint32_t hi = float_to_bf16_bits(bf16_hi(v[r][p]) * s[2 * p + 1]);
+                o[p] = lo | (hi << 16);
+                acc[r] += bf16_bits_to_float(lo) * zo[2 * p] + bf16_bits_to_float(hi) * zo[2 * p + 1];
+            }
+            if (r < rows) reinterpret_cast<u32x4 *>(dYs + (size_t)(t0 + r) * N)[n8] = o;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < SDY_ROWS; ++r) {
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) acc[r] += __shfl_xor(acc[r], o);
+        if ((tid & 63) == 0) red[r * 4 + (tid >> 6)] = acc[r];
+    }
+    __syncthreads();
+    if (tid < rows) crow[t0 + tid] = (red[tid * 4] + red[tid * 4 + 1]) + (red[tid * 4 + 2] + red[tid * 4 + 3]);
+}
+
 // s_barrier alone: no implied wait on outstanding LDS or memory operations.
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 

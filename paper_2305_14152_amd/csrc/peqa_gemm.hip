@@ -68,6 +68,16 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     constexpr bool PAIRED = GROUPED && MODE == MODE_DDS;   // one scale group per contraction half
     static_assert(KW == 2 || (KW == 1 && !PAIRED), "the paired scale gradient needs both contraction halves");
 
+    if constexpr (MODE == MODE_DDS && !GROUPED && KW == 1) {
+        // Workgroups past the tiles: an independent, bandwidth-bound job of the same backward (the scaled copy of
+        // dY that the dX contraction reads).  They are dispatched last and take the places that the last tiles
+        // leave free on the compute units, so most of their time is not added to the launch.
+        const int spare = (int)blockIdx.x - ((int)gridDim.x - a.sdy_blocks);
+        if (spare >= 0) {
+            scale_dy_rows(a.dY, a.s0, a.ds, a.z0, a.dz, a.T, a.C, a.sdy_out, a.sdy_crow, spare, reinterpret_cast<float *>(lds));
+            return;
+        }
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int wt = wave & 1, wn = (wave >> 1) & 1, wk = KW == 2 ? wave >> 2 : 0;   // token half, column half, contraction half
@@ -737,6 +747,8 @@ static int halves_per_workgroup(int tiles, bool paired)
     return tiles > cus ? 1 : 2;
 }
 
+bool gemm_four_waves(int tiles) { return halves_per_workgroup(tiles, false) == 1; }
+
 template <int BITS, int MODE, bool GROUPED, int KW>
 static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
 {
@@ -758,7 +770,11 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
     const int grid = ((patches + 7) / 8) * 8 * 32;
     // grouped scale gradient: one pair of scale groups per workgroup along y
     const int gy = GROUPED && MODE == MODE_DDS ? (a.G + 1) / 2 : 1;
-    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW>), dim3(grid, gy), dim3(256 * KW), lds_bytes, stream, a);
+    // spare workgroups (see the kernel) exist in one instantiation only
+    constexpr bool SPARE = MODE == MODE_DDS && !GROUPED && KW == 1;
+    if (!SPARE && a.sdy_blocks != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW>), dim3(grid + (SPARE ? a.sdy_blocks : 0), gy), dim3(256 * KW), lds_bytes,
+                       stream, a);
     return hipGetLastError();
 }
 

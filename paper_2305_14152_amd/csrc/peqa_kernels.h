@@ -19,14 +19,20 @@ struct GemmArgs {
     int K;                    // input features of the layer (fixes the block stride of `packed`)
     int tiles_c, tiles_t;     // ceil(C/256), ceil(T/128)
     int patch_t;              // token tiles per L2 patch (1, 2 or 4; set by launch_gemm)
-    const float *s0;          // [N]            (MODE_Y)
-    const float *ds;          // [N] or NULL    (MODE_Y)
+    const float *s0;          // [N]            (MODE_Y; MODE_DDS with sdy_blocks)
+    const float *ds;          // [N] or NULL    (MODE_Y; MODE_DDS with sdy_blocks)
     const uint8_t *z0;        // [N]            (MODE_Y, MODE_DDS)
     const float *dz;          // [N] or NULL: trained zero-point offset, z = z0 + dz (MODE_Y, MODE_DDS; [N, G] if grouped)
     const float *rs;          // [T, 2] sums of X[t, :] over each contraction half (MODE_Y, MODE_DDS)
     const float *crow;        // [T] sum_i A[t,i] (16 + z_i)                      (MODE_DX)
     const uint16_t *dY;       // [T, N] bf16    (MODE_DDS)
     float *partial;           // [tiles_t, N]   (MODE_DDS) per-token-tile column sums
+    // MODE_DDS, per-channel, four-wave form only: sdy_blocks > 0 adds that many workgroups at the end of the grid,
+    // which do scale_dy_rows on dY (with s0, ds, z0, dz) for the dX contraction of the same backward and fill the
+    // compute units that the last round of tiles leaves half empty
+    int sdy_blocks;
+    uint16_t *sdy_out;        // [T, N] bf16 scaled dY
+    float *sdy_crow;          // [T]
     uint16_t *out;            // [T, C] bf16    (MODE_Y: Y, MODE_DX: dX)
     float *P;                 // [T, N] fp32 or NULL (MODE_Y, per-channel): sum_k X[t,k] (Q[i,k] - z0[i]), kept
     // group-wise layers (gsz > 0; a multiple of 64):
@@ -38,6 +44,8 @@ struct GemmArgs {
 };
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
+// whether a per-channel launch of that many 128 x 256 tiles takes the four-wave form (two workgroups per compute unit)
+bool gemm_four_waves(int tiles);
 
 // Arguments of the token contraction dW = dY^T X with the codes applied in its epilogue (peqa_dw.hip):
 // the scale gradient of group-wise layers.

@@ -112,12 +112,9 @@ __device__ __forceinline__ void reduce_partials_at(const float *__restrict__ par
     out[j] = s;
 }
 
-// dYs[t,i] = bf16(dY[t,i] * (s0+ds)[i]);  crow[t] = sum_i dYs[t,i] * (16 + z0[i] + dz[i])  (per-channel).
-// crow uses the rounded dYs so that it cancels the code offset of the dX contraction exactly.
-// A workgroup takes SDY_ROWS token rows, so that the per-channel parameters are read once per four rows.
-// Workgroups past the last row block do an independent job in the same launch: the fixed-order sum of the
-// scale-gradient partials (n_red = 0: none), which the backward needs between its two contractions too.
-constexpr int SDY_ROWS = 4;
+// scale_dy_rows (peqa_device.h) for every block of SDY_ROWS token rows.  Workgroups past the last row block do an
+// independent job in the same launch: the fixed-order sum of the scale-gradient partials (n_red = 0: none),
+// which the backward needs between its two contractions too.
 __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restrict__ dY, const float *__restrict__ s0,
                                                         const float *__restrict__ ds, const uint8_t *__restrict__ z0,
                                                         const float *__restrict__ dz, int T, int N,
@@ -125,62 +122,13 @@ __global__ __launch_bounds__(256) void scale_dy_kernel(const uint16_t *__restric
                                                         const float *__restrict__ partial, int ntiles, size_t n_red,
                                                         float *__restrict__ red_out)
 {
-    __shared__ float red[SDY_ROWS][4];
-    const int tid = threadIdx.x;
+    __shared__ float red[SDY_ROWS * 4];
     const int row_blocks = (T + SDY_ROWS - 1) / SDY_ROWS;
     if ((int)blockIdx.x >= row_blocks) {
-        reduce_partials_at(partial, ntiles, n_red, (size_t)((int)blockIdx.x - row_blocks) * 256 + tid, red_out);
+        reduce_partials_at(partial, ntiles, n_red, (size_t)((int)blockIdx.x - row_blocks) * 256 + threadIdx.x, red_out);
         return;
     }
-    const int t0 = blockIdx.x * SDY_ROWS, rows = min(SDY_ROWS, T - t0);
-    const int n8s = N >> 3;
-    float acc[SDY_ROWS];
-#pragma unroll
-    for (int r = 0; r < SDY_ROWS; ++r) acc[r] = 0.f;
-    for (int n8 = tid; n8 < n8s; n8 += 256) {
-        u32x4 v[SDY_ROWS];                                 // rows past T re-read the last one and are dropped
-#pragma unroll
-        for (int r = 0; r < SDY_ROWS; ++r)
-            v[r] = reinterpret_cast<const u32x4 *>(dY + (size_t)(t0 + min(r, rows - 1)) * N)[n8];
-        const f32x4 sa = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8);
-        const f32x4 sb = *reinterpret_cast<const f32x4 *>(s0 + 8 * n8 + 4);
-        float s[8] = {sa[0], sa[1], sa[2], sa[3], sb[0], sb[1], sb[2], sb[3]};
-        if (ds) {
-            const f32x4 da = *reinterpret_cast<const f32x4 *>(ds + 8 * n8);
-            const f32x4 db = *reinterpret_cast<const f32x4 *>(ds + 8 * n8 + 4);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { s[i] += da[i]; s[4 + i] += db[i]; }
-        }
-        const u32x2 zz = *reinterpret_cast<const u32x2 *>(z0 + 8 * n8);
-        float zo[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) zo[i] = kCodeOffset + (float)((zz[i >> 2] >> (8 * (i & 3))) & 0xFFu);
-        if (dz) {
-            const f32x4 za = *reinterpret_cast<const f32x4 *>(dz + 8 * n8);
-            const f32x4 zb = *reinterpret_cast<const f32x4 *>(dz + 8 * n8 + 4);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { zo[i] += za[i]; zo[4 + i] += zb[i]; }
-        }
-#pragma unroll
-        for (int r = 0; r < SDY_ROWS; ++r) {
-            u32x4 o;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const uint32_t lo = float_to_bf16_bits(bf16_lo(v[r][p]) * s[2 * p]);
-                const uint32_t hi = float_to_bf16_bits(bf16_hi(v[r][p]) * s[2 * p + 1]);
-                o[p] = lo | (hi << 16);
-                acc[r] += bf16_bits_to_float(lo) * zo[2 * p] + bf16_bits_to_float(hi) * zo[2 * p + 1];
-            }
-            if (r < rows) reinterpret_cast<u32x4 *>(dYs + (size_t)(t0 + r) * N)[n8] = o;
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < SDY_ROWS; ++r) {
-        acc[r] = wave_sum(acc[r]);
-        if ((tid & 63) == 0) red[r][tid >> 6] = acc[r];
-    }
-    __syncthreads();
-    if (tid < rows) crow[t0 + tid] = (red[tid][0] + red[tid][1]) + (red[tid][2] + red[tid][3]);
+    scale_dy_rows(dY, s0, ds, z0, dz, T, N, dYs, crow, (int)blockIdx.x, red);
 }
 
 // Scale gradient from the product P[t,i] = sum_k X[t,k] (Q[i,k] - z0[i]) that the forward kept:

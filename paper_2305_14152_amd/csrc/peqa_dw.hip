@@ -15,16 +15,18 @@
 // arrays every 64-byte piece is half a cache line on its own, 2 Tp bytes from the next, and the loop
 // is bound by the request rate of the L2: measured 1.5 us per step against 0.5 us of matrix work.)
 //
-// dw_kernel: one workgroup = 4 waves = a 256 (features) x 256 (channels) tile of dW; waves 2 x 2, one per
-// SIMD, each a 128 x 128 accumulator (8 x 8 MFMA 16x16x32 tiles in 256 AGPRs).  Both operands come from
-// LDS here, and the LDS port is what bounds this loop: a 128 x 128 wave tile reads 256 B of fragments per
-// matrix instruction, a 64 x 128 one 384 B (measured: twice the matrix pipe's time per step).  A wave's
-// 128 features are two 64-feature chunks, the unit in which the epilogue reports (every group is a
-// whole number of chunks).  Operands go global -> LDS by DMA into a ring of 4 stages of 32 KB (one
-// 32-token step: 256 + 256 rows of 64 B, XOR-swizzled as in the other contraction kernel); fragments
-// for step it + 1 are read from LDS while step it's matrix instructions run.  The epilogue reads each
-// lane's codes straight from the packed array, forms sum dW Q - z sum dW over each chunk with two
-// shuffles, and writes pc[i, chunk]; chunk_reduce_kernel adds the chunks of every group in order.
+// dw_kernel: one workgroup = a 256 (features) x 256 (channels) tile of dW, as 8 waves (4 along the features x
+// 2 along the channels, two per SIMD) of 64 x 128 accumulators each (4 x 8 MFMA 16x16x32 tiles in 128 AGPRs);
+// the template also builds 4 waves of 128 x 128 (one per SIMD), which measured slower (282 against 223 us on
+// the 13B shapes: with one wave per SIMD nothing runs behind a wave's waits).  Both operands come from LDS.
+// A wave's features are 64-feature chunks, the unit in which the epilogue reports (every group is a whole
+// number of chunks).  Operands go global -> LDS by DMA into a ring of 4 stages of 32 KB (one 32-token step:
+// 256 + 256 rows of 64 B, XOR-swizzled as in the other contraction kernel); fragments for step it + 1 are read
+// from LDS while step it's matrix instructions run.  The epilogue reads each lane's codes straight from the
+// packed array, forms sum dW Q - z sum dW over each chunk with two shuffles, and writes pc[i, chunk];
+// chunk_reduce_kernel adds the chunks of every group in order.  The loop runs at about 1.0 us per step
+// against 0.5 us for its matrix instructions and fragment reads alone in a test loop; the 32 KB of DMA per
+// step and compute unit are what is left to suspect, unconfirmed.
 #include "peqa_device.h"
 #include "peqa_kernels.h"
 

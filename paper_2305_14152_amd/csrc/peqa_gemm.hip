@@ -12,6 +12,10 @@
 // bookkeeping of one hide behind the matrix instructions of the other; the contraction split
 // keeps 256 workgroups busy on a 2048 x 4096 output.  The two halves are summed through LDS in
 // the epilogue (or, for MODE_DDS, after the column reduction, which is linear).
+// A second form (KW = 1) runs four waves (2 x 2) over the whole contraction range of the same tile with half
+// the ring, two workgroups per compute unit: launches with more than one tile per compute unit take it (see
+// halves_per_workgroup below).  Its loop is unrolled by the ring depth, and, for the per-channel scale gradient,
+// spare workgroups at the end of its grid make the scaled copy of dY that the dX contraction reads.
 //
 // Operand paths.  Both operands go global -> LDS by DMA (global_load_lds) into a ring of
 // stages, one 32-deep contraction step per stage: the activation operand (X, or the pre-scaled

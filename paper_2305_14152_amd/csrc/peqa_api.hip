@@ -462,11 +462,32 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
             if (peqa::launch_dz_finish(zp, slices, (size_t)N * G, s0, ds, d_dz, s) != hipSuccess) return PEQA_ERR_DEVICE;
         }
         const int Tp = (T + 63) / 64 * 64;
+        uint16_t *xt = reinterpret_cast<uint16_t *>(ws + w.xt), *dyt = reinterpret_cast<uint16_t *>(ws + w.dyt);
+        // When dX is wanted too and its contraction runs two workgroups per compute unit, it goes first and spare
+        // workgroups of its launch write the transposed copies that the token contraction needs.
+        const bool tp_in_dx = d_ds && by_tokens && dX && peqa::gemm_four_waves(tiles_t * ((K + 255) / 256));
+        auto run_dx = [&](bool with_transposes) -> peqa_status {
+            float *sb = reinterpret_cast<float *>(ws + w.table);
+            if (peqa::launch_group_table(s0, ds, z0, dz, N, G, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            peqa::GemmArgs a{};
+            a.packed = packed; a.A = dY; a.T = T; a.KC = N; a.C = K; a.K = K;
+            a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
+            a.N = N; a.gsz = L->group_size; a.G = G; a.sb = sb; a.out = dX;
+            if (with_transposes) {
+                a.tp_blocks = (Tp / 64) * (K / 64 + N / 64); a.tp_Tp = Tp; a.tp_X = X; a.tp_Xt = xt; a.tp_dYt = dyt;
+            }
+            return peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) == hipSuccess ? PEQA_OK : PEQA_ERR_DEVICE;
+        };
+        if (tp_in_dx) {
+            const peqa_status st = run_dx(true);
+            if (st != PEQA_OK) return st;
+        }
         if (d_ds && by_tokens) {
-            uint16_t *xt = reinterpret_cast<uint16_t *>(ws + w.xt), *dyt = reinterpret_cast<uint16_t *>(ws + w.dyt);
             float *pc = reinterpret_cast<float *>(ws + w.pc);
-            if (peqa::launch_transpose_pad(X, T, K, Tp, xt, s) != hipSuccess) return PEQA_ERR_DEVICE;
-            if (peqa::launch_transpose_pad(dY, T, N, Tp, dyt, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (!tp_in_dx) {
+                if (peqa::launch_transpose_pad(X, T, K, Tp, xt, s) != hipSuccess) return PEQA_ERR_DEVICE;
+                if (peqa::launch_transpose_pad(dY, T, N, Tp, dyt, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            }
             peqa::DwArgs a{};
             a.Xt = xt; a.dYt = dyt; a.packed = packed; a.z0 = z0; a.dz = dz; a.pc = pc;
             a.N = N; a.K = K; a.Tp = Tp; a.gsz = L->group_size; a.G = G;
@@ -485,14 +506,9 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
             if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N * G, d_ds, s) != hipSuccess)
                 return PEQA_ERR_DEVICE;
         }
-        if (dX) {
-            float *sb = reinterpret_cast<float *>(ws + w.table);
-            if (peqa::launch_group_table(s0, ds, z0, dz, N, G, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
-            peqa::GemmArgs a{};
-            a.packed = packed; a.A = dY; a.T = T; a.KC = N; a.C = K; a.K = K;
-            a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
-            a.N = N; a.gsz = L->group_size; a.G = G; a.sb = sb; a.out = dX;
-            if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (dX && !tp_in_dx) {
+            const peqa_status st = run_dx(false);
+            if (st != PEQA_OK) return st;
         }
         return PEQA_OK;
     }

@@ -227,6 +227,38 @@ __device__ __forceinline__ void scale_dy_rows(const uint16_t *__restrict__ dY, c
     if (tid < rows) crow[t0 + tid] = (red[tid * 4] + red[tid * 4 + 1]) + (red[tid * 4 + 2] + red[tid * 4 + 3]);
 }
 
+// One 64 x 64 tile of the step-major transposed copy that the token contraction of group-wise layers reads:
+// dst[t / 32][cc][t % 32] = src[t, cc] for t < T, 0 for T <= t < Tp, tile (bt, bc) of 64 tokens x 64 columns,
+// by one workgroup of 256 threads through `tile`, 64 x 66 bf16 of LDS.  C % 64 == 0.
+__device__ __forceinline__ void transpose_pad_tile(const uint16_t *__restrict__ src, int T, int C, uint16_t *__restrict__ dst,
+                                                   int bt, int bc, uint16_t (*tile)[64 + 2])
+{
+    const int t0 = bt * 64, c0 = bc * 64;
+    const int ch = threadIdx.x & 7;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int row = (threadIdx.x >> 3) + 32 * h, t = t0 + row;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (t < T) v = *reinterpret_cast<const u32x4 *>(src + (size_t)t * C + c0 + 8 * ch);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            tile[row][8 * ch + 2 * e] = (uint16_t)(v[e] & 0xFFFFu);
+            tile[row][8 * ch + 2 * e + 1] = (uint16_t)(v[e] >> 16);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int cc = (threadIdx.x >> 3) + 32 * h;
+        u32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = (uint32_t)tile[8 * ch + 2 * e][cc] | ((uint32_t)tile[8 * ch + 2 * e + 1][cc] << 16);
+        const int t = t0 + 8 * ch;                        // 8 tokens of one 32-token step
+        *reinterpret_cast<u32x4 *>(dst + ((size_t)(t >> 5) * C + c0 + cc) * 32 + (t & 31)) = o;
+    }
+}
+
 // s_barrier alone: no implied wait on outstanding LDS or memory operations.
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 

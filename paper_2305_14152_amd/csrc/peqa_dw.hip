@@ -226,35 +226,12 @@ __global__ __launch_bounds__(128 * WM, 1) void dw_kernel(DwArgs a)
     });
 }
 
-// dst[t / 32][cc][t % 32] = src[t, cc] for t < T, 0 for T <= t < Tp.  64 x 64 tiles through LDS; C % 64 == 0.
+// transpose_pad_tile (peqa_device.h) for every 64 x 64 tile of src [T, C] (Tp / 64 x C / 64 workgroups).
 __global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t *__restrict__ src, int T, int C, int Tp,
                                                              uint16_t *__restrict__ dst)
 {
     __shared__ uint16_t tile[64][64 + 2];
-    const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int ch = threadIdx.x & 7;
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int row = (threadIdx.x >> 3) + 32 * h, t = t0 + row;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (t < T) v = *reinterpret_cast<const u32x4 *>(src + (size_t)t * C + c0 + 8 * ch);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            tile[row][8 * ch + 2 * e] = (uint16_t)(v[e] & 0xFFFFu);
-            tile[row][8 * ch + 2 * e + 1] = (uint16_t)(v[e] >> 16);
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int cc = (threadIdx.x >> 3) + 32 * h;
-        u32x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            o[e] = (uint32_t)tile[8 * ch + 2 * e][cc] | ((uint32_t)tile[8 * ch + 2 * e + 1][cc] << 16);
-        const int t = t0 + 8 * ch;                        // 8 tokens of one 32-token step
-        *reinterpret_cast<u32x4 *>(dst + ((size_t)(t >> 5) * C + c0 + cc) * 32 + (t & 31)) = o;
-    }
+    transpose_pad_tile(src, T, C, dst, (int)blockIdx.x, (int)blockIdx.y, tile);
 }
 
 // d_ds[i, g] = sum of pc[i, chunk] over the gsz / 64 chunks of group g, in order.

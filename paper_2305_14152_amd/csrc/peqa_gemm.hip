@@ -82,6 +82,18 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
             return;
         }
     }
+    if constexpr (MODE == MODE_DX && GROUPED && KW == 1) {
+        // Likewise for group-wise layers: the transposed copies of X and dY that the token contraction (the scale
+        // gradient of the same backward, launched next) reads are independent of this contraction.
+        const int spare = (int)blockIdx.x - ((int)gridDim.x - a.tp_blocks);
+        if (spare >= 0) {
+            const int bts = a.tp_Tp >> 6, nx = bts * (a.K >> 6);
+            uint16_t(*tile)[64 + 2] = reinterpret_cast<uint16_t(*)[64 + 2]>(lds);
+            if (spare < nx) transpose_pad_tile(a.tp_X, a.T, a.K, a.tp_Xt, spare % bts, spare / bts, tile);
+            else transpose_pad_tile(a.A, a.T, a.N, a.tp_dYt, (spare - nx) % bts, (spare - nx) / bts, tile);
+            return;
+        }
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int wt = wave & 1, wn = (wave >> 1) & 1, wk = KW == 2 ? wave >> 2 : 0;   // token half, column half, contraction half
@@ -776,8 +788,10 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
     const int gy = GROUPED && MODE == MODE_DDS ? (a.G + 1) / 2 : 1;
     // spare workgroups (see the kernel) exist in one instantiation only
     constexpr bool SPARE = MODE == MODE_DDS && !GROUPED && KW == 1;
-    if (!SPARE && a.sdy_blocks != 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW>), dim3(grid + (SPARE ? a.sdy_blocks : 0), gy), dim3(256 * KW), lds_bytes,
+    constexpr bool SPARE_TP = MODE == MODE_DX && GROUPED && KW == 1;
+    if ((!SPARE && a.sdy_blocks != 0) || (!SPARE_TP && a.tp_blocks != 0)) return hipErrorInvalidValue;
+    const int spare_blocks = SPARE ? a.sdy_blocks : (SPARE_TP ? a.tp_blocks : 0);
+    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW>), dim3(grid + spare_blocks, gy), dim3(256 * KW), lds_bytes,
                        stream, a);
     return hipGetLastError();
 }

@@ -33,6 +33,12 @@ struct GemmArgs {
     int sdy_blocks;
     uint16_t *sdy_out;        // [T, N] bf16 scaled dY
     float *sdy_crow;          // [T]
+    // MODE_DX, group-wise, four-wave form only: tp_blocks > 0 adds that many workgroups at the end of the grid, which
+    // write the step-major transposed copies of X [T, K] and dY [T, N] (transpose_pad_tile) that the token contraction
+    // of the same backward reads afterwards: Tp / 64 x K / 64 tiles of X first, then Tp / 64 x N / 64 of dY
+    int tp_blocks, tp_Tp;
+    const uint16_t *tp_X;
+    uint16_t *tp_Xt, *tp_dYt;
     uint16_t *out;            // [T, C] bf16    (MODE_Y: Y, MODE_DX: dX)
     float *P;                 // [T, N] fp32 or NULL (MODE_Y, per-channel): sum_k X[t,k] (Q[i,k] - z0[i]), kept
     // group-wise layers (gsz > 0; a multiple of 64):

@@ -13,7 +13,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
 # Kernels that queue global -> LDS DMA from inline assembly and count s_waitcnt vmcnt by hand: a
 # register spill would add scratch loads and stores (also counted by vmcnt) that the hand count does
 # not know about, so the build refuses any scratch use in them.
-NO_SCRATCH = ("gemm_kernel", "gemv_kernel", "dw_kernel")
+NO_SCRATCH = ("gemm_kernel", "gemm_bwd_pair_kernel", "gemv_kernel", "dw_kernel")
 
 
 def check_no_scratch(remarks):

@@ -513,50 +513,59 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
         return PEQA_OK;
     }
 
-    // The two gradients are independent, but each contraction fills the machine (one workgroup per compute
-    // unit), so everything stays in order on the caller's stream: running the two chains, or only their
-    // small kernels, beside each other on a second stream measured 2-6 % slower on the 7B block, launched
-    // one by one (the events cost more than they hide) and as a captured graph alike.
-    const bool dys_in_dds = d_ds && dX && peqa::gemm_four_waves(tiles_t * ((N + 255) / 256));
+    // The two gradients are independent.  Everything stays in order on the caller's stream: running the two
+    // chains, or only their small kernels, beside each other on a second stream measured 2-6 % slower on the 7B
+    // block, launched one by one (the events cost more than they hide) and as a captured graph alike.
+    const int tiles_dds = tiles_t * ((N + 255) / 256), tiles_dx = tiles_t * ((K + 255) / 256);
+    // With both gradients wanted and more tiles between them than compute units, the two contractions go out as
+    // one launch of four-wave workgroups, after the scaling of dY and before the sum of the partials
+    // (PEQA_BWD_PAIR=1 / 0 in the environment: whenever both are wanted / never).  Measured against separate
+    // launches: +1 to 2 % on the 7B block, where half the launches have one tile per compute unit and would run
+    // in the eight-wave form, +0.2 to 0.9 % on the 13B and 65B blocks.
+    bool pair = d_ds && dX && peqa::gemm_four_waves(tiles_dds + tiles_dx);
+    if (const char *e = getenv("PEQA_BWD_PAIR")) pair = d_ds && dX && e[0] == '1';
+    peqa::GemmArgs a_dds{}, a_dx{};
     if (d_ds) {
         // row sums of X over the two contraction halves: the caller's (peqa_row_sums), or taken here
         const float *rs = row_sums;
-        float *partial = reinterpret_cast<float *>(ws + w.partial);
-        const int ksplit = split_point(K);
         if (!rs) {
             float *own = reinterpret_cast<float *>(ws + w.rs);
-            if (peqa::launch_rowsum(X, T, K, ksplit, own, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (peqa::launch_rowsum(X, T, K, split_point(K), own, s) != hipSuccess) return PEQA_ERR_DEVICE;
             rs = own;
         }
-        peqa::GemmArgs a{};
+        peqa::GemmArgs &a = a_dds;
         a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K;
         a.tiles_c = (N + 255) / 256; a.tiles_t = tiles_t;
-        a.z0 = z0; a.dz = dz; a.rs = rs; a.dY = dY; a.partial = partial;
-        // When dX is wanted too and this contraction runs two workgroups per compute unit, the scaled copy of dY
-        // for the dX contraction is made by spare workgroups of the same launch; the partials are then summed
-        // by a launch of their own.  Otherwise that sum rides in the scale_dy launch of the dX half.
-        if (dys_in_dds) {
-            a.s0 = s0; a.ds = ds;
-            a.sdy_blocks = (T + 3) / 4;
-            a.sdy_out = reinterpret_cast<uint16_t *>(ws + w.dys);
-            a.sdy_crow = reinterpret_cast<float *>(ws + w.crow);
-        }
-        if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
-        if ((!dX || dys_in_dds) && peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess)
-            return PEQA_ERR_DEVICE;
+        a.z0 = z0; a.dz = dz; a.rs = rs; a.dY = dY; a.partial = reinterpret_cast<float *>(ws + w.partial);
     }
     if (dX) {
-        uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
-        float *crow = reinterpret_cast<float *>(ws + w.crow);
-        if (!dys_in_dds &&
-            peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, reinterpret_cast<const float *>(ws + w.partial),
-                                  tiles_t, d_ds ? (size_t)N : 0, d_ds, s) != hipSuccess)
-            return PEQA_ERR_DEVICE;
-        peqa::GemmArgs a{};
-        a.packed = packed; a.A = dys; a.T = T; a.KC = N; a.C = K; a.K = K;
+        peqa::GemmArgs &a = a_dx;
+        a.packed = packed; a.A = reinterpret_cast<uint16_t *>(ws + w.dys); a.T = T; a.KC = N; a.C = K; a.K = K;
         a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
-        a.crow = crow; a.out = dX;
-        if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        a.crow = reinterpret_cast<float *>(ws + w.crow); a.out = dX;
+    }
+    float *partial = reinterpret_cast<float *>(ws + w.partial);
+    uint16_t *dys = reinterpret_cast<uint16_t *>(ws + w.dys);
+    float *crow = reinterpret_cast<float *>(ws + w.crow);
+    if (pair) {
+        if (peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, nullptr, 0, 0, nullptr, s) != hipSuccess)
+            return PEQA_ERR_DEVICE;
+        if (peqa::launch_gemm_bwd_pair(L->bits, a_dds, a_dx, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    } else {
+        // one after the other; when dX follows the scale gradient, the sum of its partials rides in the launch
+        // that scales dY
+        if (d_ds) {
+            if (peqa::launch_gemm(L->bits, peqa::MODE_DDS, a_dds, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            if (!dX && peqa::launch_reduce_partials(partial, tiles_t, (size_t)N, d_ds, s) != hipSuccess)
+                return PEQA_ERR_DEVICE;
+        }
+        if (dX) {
+            if (peqa::launch_scale_dy(dY, s0, ds, z0, dz, T, N, dys, crow, partial, tiles_t, d_ds ? (size_t)N : 0, d_ds,
+                                      s) != hipSuccess)
+                return PEQA_ERR_DEVICE;
+            if (peqa::launch_gemm(L->bits, peqa::MODE_DX, a_dx, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        }
     }
     if (d_dz) {
         // sums of every row of X (one group spanning K), then the two-stage column reduction
@@ -720,7 +729,7 @@ struct TraceState {
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
-    "gemv_finish", "group_table", "dds_kept", "dz_partial", "dz_finish", "transpose_pad", "gemm_dw"};
+    "gemv_finish", "group_table", "dds_kept", "dz_partial", "dz_finish", "transpose_pad", "gemm_dw", "gemm_bwd"};
 
 }  // namespace
 namespace {

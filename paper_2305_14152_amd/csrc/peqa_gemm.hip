@@ -14,8 +14,10 @@
 // the epilogue (or, for MODE_DDS, after the column reduction, which is linear).
 // A second form (KW = 1) runs four waves (2 x 2) over the whole contraction range of the same tile with half
 // the ring, two workgroups per compute unit: launches with more than one tile per compute unit take it (see
-// halves_per_workgroup below).  Its loop is unrolled by the ring depth, and, for the per-channel scale gradient,
-// spare workgroups at the end of its grid make the scaled copy of dY that the dX contraction reads.
+// halves_per_workgroup below).  Its loop is unrolled by the ring depth.  The scale gradient and dX of one
+// per-channel backward run as four-wave tiles of one launch (gemm_bwd_pair_kernel) when they have more tiles than
+// compute units between them; in the group-wise dX launch, spare workgroups at the end of the grid write the
+// transposed operands of the token contraction.
 //
 // Operand paths.  Both operands go global -> LDS by DMA (global_load_lds) into a ring of
 // stages, one 32-deep contraction step per stage: the activation operand (X, or the pre-scaled
@@ -61,39 +63,17 @@ constexpr int ring_bytes(int kw) { return NSTAGE * stage_bytes(kw); }   // 144 K
 constexpr int tbl_bytes(int kw) { return 2 * kw * 2 * 1024; }           // grouped MODE_Y / MODE_DX: 2 x 1 KB of (s, b) per (column half, contraction half);
                                                                         // twice that for MODE_DX when groups end inside a 128-feature run
 
+// One tile of one contraction: the work of workgroup number `wg` of a launch of this contraction alone.
 template <int BITS, int MODE, bool GROUPED, int KW>
-__global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
+__device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8_t *lds)
 {
     constexpr int STAGE_BYTES = stage_bytes(KW);
-    extern __shared__ __align__(16) uint8_t lds[];
     constexpr int WPB = 2 * BITS;                          // words per 8x8 block
     constexpr bool ALONG_CH = (MODE == MODE_DX);           // contraction over output channels
     constexpr bool SCALED = GROUPED && MODE != MODE_DDS;   // weights enter the MFMA already scaled
     constexpr bool PAIRED = GROUPED && MODE == MODE_DDS;   // one scale group per contraction half
     static_assert(KW == 2 || (KW == 1 && !PAIRED), "the paired scale gradient needs both contraction halves");
 
-    if constexpr (MODE == MODE_DDS && !GROUPED && KW == 1) {
-        // Workgroups past the tiles: an independent, bandwidth-bound job of the same backward (the scaled copy of
-        // dY that the dX contraction reads).  They are dispatched last and take the places that the last tiles
-        // leave free on the compute units, so most of their time is not added to the launch.
-        const int spare = (int)blockIdx.x - ((int)gridDim.x - a.sdy_blocks);
-        if (spare >= 0) {
-            scale_dy_rows(a.dY, a.s0, a.ds, a.z0, a.dz, a.T, a.C, a.sdy_out, a.sdy_crow, spare, reinterpret_cast<float *>(lds));
-            return;
-        }
-    }
-    if constexpr (MODE == MODE_DX && GROUPED && KW == 1) {
-        // Likewise for group-wise layers: the transposed copies of X and dY that the token contraction (the scale
-        // gradient of the same backward, launched next) reads are independent of this contraction.
-        const int spare = (int)blockIdx.x - ((int)gridDim.x - a.tp_blocks);
-        if (spare >= 0) {
-            const int bts = a.tp_Tp >> 6, nx = bts * (a.K >> 6);
-            uint16_t(*tile)[64 + 2] = reinterpret_cast<uint16_t(*)[64 + 2]>(lds);
-            if (spare < nx) transpose_pad_tile(a.tp_X, a.T, a.K, a.tp_Xt, spare % bts, spare / bts, tile);
-            else transpose_pad_tile(a.A, a.T, a.N, a.tp_dYt, (spare - nx) % bts, (spare - nx) / bts, tile);
-            return;
-        }
-    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in an SGPR
     const int wt = wave & 1, wn = (wave >> 1) & 1, wk = KW == 2 ? wave >> 2 : 0;   // token half, column half, contraction half
@@ -105,7 +85,6 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
     // through that XCD's L2 instead of each pulling its own from the fabric.
     int tile_t, tile_c;
     {
-        const int wg = blockIdx.x;
         const int xcd = wg & 7, local = wg >> 3;
         const int g = (local >> 5) * 8 + xcd;              // patch number
         const int r = local & 31;                          // position in the patch
@@ -454,10 +433,13 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         wait_vmcnt<DMA_PER_ITER *(NSTAGE - 4) + 1>();
         bare_barrier();
     };
-    // The eight-wave form (and one grouped instantiation of the four-wave form) does not fit into its registers
-    // when unrolled that far -- the compiler spills, which the hand-counted DMA queue cannot take -- and keeps
-    // the stage in a register, two steps per trip (the register buffers alternate).
-    constexpr bool RING_UNROLL = KW == 1 && !(SCALED && ALONG_CH && BITS == 4);
+    // The grouped forward / dX (scaled fragments) in its eight-wave form, and one instantiation of its four-wave
+    // form, do not fit into their registers when unrolled that far -- the compiler spills inside the loop, which
+    // the hand-counted DMA queue cannot take -- and keep the stage in a register, two steps per trip (the
+    // register buffers alternate).  For the eight-wave per-channel kernels the unrolled loop measures the same
+    // as the other (within 0.3 %): their loss against the four-wave form is ring fill, exchange and epilogue,
+    // which nothing overlaps with one workgroup per compute unit.
+    constexpr bool RING_UNROLL = !SCALED || (KW == 1 && !(ALONG_CH && BITS == 4));
     if constexpr (RING_UNROLL) {
         int it = 0;
         for (; it + NSTAGE <= nit; it += NSTAGE)
@@ -517,6 +499,12 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         step2(it + 1, std::integral_constant<int, 1>{});
     }
     }
+    // The loop's exits meet here; this keeps the accumulators in their AGPRs past that point (the compiler would
+    // otherwise copy all 128 of them into VGPRs at once, more than there are)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));
     // The epilogue works out its lane indices afresh (from a copy of the thread index that the compiler cannot
     // connect to the first one), so that none of them has to be held in a register through the loop.
     {
@@ -732,7 +720,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
             for (int rtl = 0; rtl < 2; ++rtl) {
                 f32x4 sum[8];
 #pragma unroll
-                for (int ct = 0; ct < 8; ++ct) sum[ct] = acc[KEEP + rtl][ct] + theirs[(rtl * 8 + ct) * 64];
+                for (int ct = 0; ct < 8; ++ct) sum[ct] = read_acc(acc[KEEP + rtl][ct]) + theirs[(rtl * 8 + ct) * 64];
                 store_rows(KEEP + rtl, sum, ep_row + 4 * rtl);
             }
         };
@@ -741,6 +729,43 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
         }
     }
     }
+}
+
+template <int BITS, int MODE, bool GROUPED, int KW>
+__global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    if constexpr (MODE == MODE_DX && GROUPED && KW == 1) {
+        // Workgroups past the tiles: an independent, bandwidth-bound job of the same backward -- the transposed
+        // copies of X and dY that the token contraction (the scale gradient, launched next) reads.  They are
+        // dispatched last and take the places that the last tiles leave free on the compute units, so most of
+        // their time is not added to the launch.
+        const int spare = (int)blockIdx.x - ((int)gridDim.x - a.tp_blocks);
+        if (spare >= 0) {
+            const int bts = a.tp_Tp >> 6, nx = bts * (a.K >> 6);
+            uint16_t(*tile)[64 + 2] = reinterpret_cast<uint16_t(*)[64 + 2]>(lds);
+            if (spare < nx) transpose_pad_tile(a.tp_X, a.T, a.K, a.tp_Xt, spare % bts, spare / bts, tile);
+            else transpose_pad_tile(a.A, a.T, a.N, a.tp_dYt, (spare - nx) % bts, (spare - nx) / bts, tile);
+            return;
+        }
+    }
+    gemm_tile<BITS, MODE, GROUPED, KW>(a, (int)blockIdx.x, lds);
+}
+
+// Both contractions of a per-channel backward in one launch of four-wave workgroups: the first n_first
+// workgroups are the tiles of one of them (the one with the longer contraction), the rest the tiles of the
+// other.  Neither reads what the other writes.  Two launches of at most one tile per compute unit each -- which
+// would run in the eight-wave form, ring fill and epilogue exposed -- become one launch with two workgroups per
+// compute unit, and the last round of the first contraction is filled with tiles of the second.
+template <int BITS>
+__global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmArgs a_dds, GemmArgs a_dx, int n_first, int dx_first)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    const int b = (int)blockIdx.x;
+    const bool first = b < n_first;
+    const int wg = first ? b : b - n_first;
+    if (first == (dx_first != 0)) gemm_tile<BITS, MODE_DX, false, 1>(a_dx, wg, lds);
+    else gemm_tile<BITS, MODE_DDS, false, 1>(a_dds, wg, lds);
 }
 
 }  // namespace
@@ -787,10 +812,9 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
     // grouped scale gradient: one pair of scale groups per workgroup along y
     const int gy = GROUPED && MODE == MODE_DDS ? (a.G + 1) / 2 : 1;
     // spare workgroups (see the kernel) exist in one instantiation only
-    constexpr bool SPARE = MODE == MODE_DDS && !GROUPED && KW == 1;
     constexpr bool SPARE_TP = MODE == MODE_DX && GROUPED && KW == 1;
-    if ((!SPARE && a.sdy_blocks != 0) || (!SPARE_TP && a.tp_blocks != 0)) return hipErrorInvalidValue;
-    const int spare_blocks = SPARE ? a.sdy_blocks : (SPARE_TP ? a.tp_blocks : 0);
+    if (!SPARE_TP && a.tp_blocks != 0) return hipErrorInvalidValue;
+    const int spare_blocks = SPARE_TP ? a.tp_blocks : 0;
     hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW>), dim3(grid + spare_blocks, gy), dim3(256 * KW), lds_bytes,
                        stream, a);
     return hipGetLastError();
@@ -831,6 +855,46 @@ hipError_t launch_gemm(int bits, int mode, const GemmArgs &a_in, hipStream_t str
     trace_before(kid, stream);
     const hipError_t e = dispatch(bits, mode, a, stream);
     trace_after(kid, stream);
+    return e;
+}
+
+// Scale gradient and dX of one per-channel layer in one launch (see gemm_bwd_pair_kernel).  The caller has checked
+// gemm_four_waves(tiles of both).
+template <int BITS>
+static hipError_t launch_pair(const GemmArgs &a_dds, const GemmArgs &a_dx, hipStream_t stream)
+{
+    const int lds_bytes = ring_bytes(1);
+    static int attr_bytes[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (attr_bytes[dev] < lds_bytes) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bwd_pair_kernel<BITS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_bytes[dev] = lds_bytes;
+    }
+    auto grid_of = [](const GemmArgs &a) {
+        const int pt = a.patch_t, pc = 32 / pt;
+        const int patches = ((a.tiles_t + pt - 1) / pt) * ((a.tiles_c + pc - 1) / pc);
+        return ((patches + 7) / 8) * 8 * 32;               // a multiple of 8: both parts keep workgroup id % 8 = XCD
+    };
+    // the tiles that take longer go first: the short ones fill the last round better
+    const int dx_first = a_dx.KC >= a_dds.KC;
+    const int n_first = grid_of(dx_first ? a_dx : a_dds), n_second = grid_of(dx_first ? a_dds : a_dx);
+    hipLaunchKernelGGL((gemm_bwd_pair_kernel<BITS>), dim3(n_first + n_second), dim3(256), lds_bytes, stream, a_dds, a_dx,
+                       n_first, dx_first);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_bwd_pair(int bits, const GemmArgs &dds_in, const GemmArgs &dx_in, hipStream_t stream)
+{
+    GemmArgs a_dds = dds_in, a_dx = dx_in;
+    if (a_dds.gsz > 0 || a_dx.gsz > 0 || a_dds.tp_blocks || a_dx.tp_blocks || a_dds.tiles_t != a_dx.tiles_t)
+        return hipErrorInvalidValue;
+    a_dds.patch_t = a_dx.patch_t = a_dds.tiles_t >= 4 ? 4 : (a_dds.tiles_t >= 2 ? 2 : 1);
+    trace_before(KID_GEMM_BWD, stream);
+    const hipError_t e = bits == 4 ? launch_pair<4>(a_dds, a_dx, stream) : launch_pair<3>(a_dds, a_dx, stream);
+    trace_after(KID_GEMM_BWD, stream);
     return e;
 }
 

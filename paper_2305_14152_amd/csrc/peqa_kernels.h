@@ -19,20 +19,14 @@ struct GemmArgs {
     int K;                    // input features of the layer (fixes the block stride of `packed`)
     int tiles_c, tiles_t;     // ceil(C/256), ceil(T/128)
     int patch_t;              // token tiles per L2 patch (1, 2 or 4; set by launch_gemm)
-    const float *s0;          // [N]            (MODE_Y; MODE_DDS with sdy_blocks)
-    const float *ds;          // [N] or NULL    (MODE_Y; MODE_DDS with sdy_blocks)
+    const float *s0;          // [N]            (MODE_Y)
+    const float *ds;          // [N] or NULL    (MODE_Y)
     const uint8_t *z0;        // [N]            (MODE_Y, MODE_DDS)
     const float *dz;          // [N] or NULL: trained zero-point offset, z = z0 + dz (MODE_Y, MODE_DDS; [N, G] if grouped)
     const float *rs;          // [T, 2] sums of X[t, :] over each contraction half (MODE_Y, MODE_DDS)
     const float *crow;        // [T] sum_i A[t,i] (16 + z_i)                      (MODE_DX)
     const uint16_t *dY;       // [T, N] bf16    (MODE_DDS)
     float *partial;           // [tiles_t, N]   (MODE_DDS) per-token-tile column sums
-    // MODE_DDS, per-channel, four-wave form only: sdy_blocks > 0 adds that many workgroups at the end of the grid,
-    // which do scale_dy_rows on dY (with s0, ds, z0, dz) for the dX contraction of the same backward and fill the
-    // compute units that the last round of tiles leaves half empty
-    int sdy_blocks;
-    uint16_t *sdy_out;        // [T, N] bf16 scaled dY
-    float *sdy_crow;          // [T]
     // MODE_DX, group-wise, four-wave form only: tp_blocks > 0 adds that many workgroups at the end of the grid, which
     // write the step-major transposed copies of X [T, K] and dY [T, N] (transpose_pad_tile) that the token contraction
     // of the same backward reads afterwards: Tp / 64 x K / 64 tiles of X first, then Tp / 64 x N / 64 of dY
@@ -52,6 +46,9 @@ struct GemmArgs {
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
 // whether a per-channel launch of that many 128 x 256 tiles takes the four-wave form (two workgroups per compute unit)
 bool gemm_four_waves(int tiles);
+// Per-channel layers: the MODE_DDS and the MODE_DX contraction of one backward (arguments as for launch_gemm) as one
+// launch of four-wave workgroups, which pays when the two have more tiles than compute units between them.  The dX arguments' input (the scaled dY) must be complete before the launch.
+hipError_t launch_gemm_bwd_pair(int bits, const GemmArgs &a_dds, const GemmArgs &a_dx, hipStream_t stream);
 
 // Arguments of the token contraction dW = dY^T X with the codes applied in its epilogue (peqa_dw.hip):
 // the scale gradient of group-wise layers.
@@ -147,7 +144,7 @@ void trace_after(int kernel_id, hipStream_t stream);
 
 enum {
     KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
-    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_DZ_PARTIAL, KID_DZ_FINISH, KID_TRANSPOSE, KID_GEMM_DW, KID_COUNT
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_DZ_PARTIAL, KID_DZ_FINISH, KID_TRANSPOSE, KID_GEMM_DW, KID_GEMM_BWD, KID_COUNT
 };
 
 }  // namespace peqa

@@ -148,6 +148,14 @@ def test_four_wave_contraction_parity(gpu, oracle, monkeypatch, bits, N, K, T, g
     assert np.abs(gpu.bf16_dev_to_f64(dX4) - gpu.bf16_dev_to_f64(dX8)).max() <= 2.0 ** -7 * np.abs(gpu.bf16_dev_to_f64(dX8)).max()
     g4h, g8h = gpu.to_host(g4).astype(np.float64), gpu.to_host(g8).astype(np.float64)
     assert np.linalg.norm(g4h - g8h) <= 1e-5 * np.linalg.norm(g8h)
+    if group == 0:
+        # both contractions of the backward as one launch (taken by itself when they have more tiles than compute
+        # units between them and one of them has fewer): the same products in the same order as the four-wave form
+        monkeypatch.setenv("PEQA_BWD_PAIR", "1")
+        _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, ds, group)
+        dXp, gp = layer.bwd(X, dY, ds)
+        assert np.array_equal(gpu.to_host(dXp), gpu.to_host(dX4))
+        assert np.array_equal(gpu.to_host(gp), gpu.to_host(g4))
 
 
 @pytest.mark.parametrize("bits,N,K,T,group", [(4, 1152, 512, 9000, 0), (3, 640, 768, 16500, 128)])

@@ -289,10 +289,10 @@ def kept_product(torch, peqa, layers, cfg, stream, steps):
 def backward_launch_flops(T, N, K, cus):
     """Flops of the contraction launches of one per-channel layer's backward, by kernel name.  The library sends
     the scale gradient and dX out as one launch (gemm_bwd) when they have more 128 x 256 tiles than compute units
-    between them and one of them has fewer."""
+    between them."""
     tt, tcd, tcx = -(-T // 128), -(-N // 256), -(-K // 256)
     td, tx, full = tt * tcd, tt * tcx, 2.0 * T * N * K
-    if td + tx > cus and not (td > cus and tx > cus):
+    if td + tx > cus:
         return {"gemm_bwd": 2.0 * full}
     return {"gemm_dds": full, "gemm_dx": full}
 

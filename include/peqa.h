@@ -24,11 +24,14 @@
  * Shape limits: N % 128 == 0, K % 128 == 0 (every LLaMA-family linear satisfies
  * this).  group_size is 0 or a multiple of 64 that divides K.
  *
- * Environment.  Two variables are read at every call, for tests and comparisons; neither is needed:
+ * Environment.  Three variables are read at every call, for tests and comparisons; none is needed:
  * PEQA_GEMM_WAVES=4|8 forces one of the two forms of the tiled contraction kernel (by default a
  * launch with more than one 128 x 256 tile per compute unit runs four-wave workgroups, two per
- * compute unit, any other launch eight-wave ones); PEQA_GROUPED_DDS=pairs selects the older of
- * two routes to the scale gradient of group-wise layers.  Results agree within rounding.
+ * compute unit, any other launch eight-wave ones); PEQA_BWD_PAIR=1|0 makes a per-channel backward
+ * that is asked for both gradients always / never run its two contractions as one launch (by
+ * default it does when they have more tiles than compute units between them);
+ * PEQA_GROUPED_DDS=pairs selects the older of two routes to the scale gradient of group-wise
+ * layers.  Results agree within rounding.
  *
  * Stacking.  The packed array is stored by rows of 128-channel tiles and the scale-shaped
  * arrays by channel, so layers with equal K, bits and group_size that read the same input

@@ -138,6 +138,7 @@ def test_four_wave_contraction_parity(gpu, oracle, monkeypatch, bits, N, K, T, g
     Y8 = gpu.bf16_dev_to_f64(layer.fwd(X, ds))
     dX8, g8 = layer.bwd(X, dY, ds)
     monkeypatch.setenv("PEQA_GEMM_WAVES", "4")
+    monkeypatch.setenv("PEQA_BWD_PAIR", "0")               # the backward's two contractions as launches of their own
     e = _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, ds, group)
     _log("  errors: %.2e %.2e" % e)
     _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, None, group)
@@ -149,8 +150,8 @@ def test_four_wave_contraction_parity(gpu, oracle, monkeypatch, bits, N, K, T, g
     g4h, g8h = gpu.to_host(g4).astype(np.float64), gpu.to_host(g8).astype(np.float64)
     assert np.linalg.norm(g4h - g8h) <= 1e-5 * np.linalg.norm(g8h)
     if group == 0:
-        # both contractions of the backward as one launch (taken by itself when they have more tiles than compute
-        # units between them and one of them has fewer): the same products in the same order as the four-wave form
+        # both contractions of the backward as one launch of four-wave workgroups (taken by itself when they have
+        # more tiles than compute units between them): the same products in the same order
         monkeypatch.setenv("PEQA_BWD_PAIR", "1")
         _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, ds, group)
         dXp, gp = layer.bwd(X, dY, ds)

@@ -286,17 +286,6 @@ def kept_product(torch, peqa, layers, cfg, stream, steps):
             "kept_bytes": int(sum(P.numel() * 4 for P in Ps))}
 
 
-def backward_launch_flops(T, N, K, cus):
-    """Flops of the contraction launches of one per-channel layer's backward, by kernel name.  The library sends
-    the scale gradient and dX out as one launch (gemm_bwd) when they have more 128 x 256 tiles than compute units
-    between them."""
-    tt, tcd, tcx = -(-T // 128), -(-N // 256), -(-K // 256)
-    td, tx, full = tt * tcd, tt * tcx, 2.0 * T * N * K
-    if td + tx > cus:
-        return {"gemm_bwd": 2.0 * full}
-    return {"gemm_dds": full, "gemm_dx": full}
-
-
 def device_info(torch, peqa):
     """What the run saw of the device, and the denominators the fractions above use."""
     p = torch.cuda.get_device_properties(0)
@@ -446,7 +435,6 @@ def main():
     trace = peqa.trace_end(16)
     # gemm_dw: the scale gradient of group-wise layers (contraction over tokens), same 2 T N K flops
     gemm_flops = {"gemm_y": 0.0, "gemm_dds": 0.0, "gemm_dx": 0.0, "gemm_dw": 0.0, "gemm_bwd": 0.0}
-    cus = peqa.device_info()[0]
     for l in block:
         full = 2.0 * T * l.N * l.K * args.steps
         gemm_flops["gemm_y"] += full
@@ -454,8 +442,8 @@ def main():
             for k in ("gemm_dds", "gemm_dx", "gemm_dw"):
                 gemm_flops[k] += full
         else:
-            for k, f in backward_launch_flops(T, l.N, l.K, cus).items():
-                gemm_flops[k] += f * args.steps
+            # per-channel layers: the scale gradient and dX of one backward are one launch
+            gemm_flops["gemm_bwd"] += 2.0 * full
     dom = max((k for k in gemm_flops if k in trace), key=lambda k: trace[k][1])
     # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc summary (default workload only)
     traffic = None

@@ -27,9 +27,9 @@
  * Environment.  Three variables are read at every call, for tests and comparisons; none is needed:
  * PEQA_GEMM_WAVES=4|8 forces one of the two forms of the tiled contraction kernel (by default a
  * launch with more than one 128 x 256 tile per compute unit runs four-wave workgroups, two per
- * compute unit, any other launch eight-wave ones); PEQA_BWD_PAIR=1|0 makes a per-channel backward
- * that is asked for both gradients always / never run its two contractions as one launch (by
- * default it does when they have more tiles than compute units between them);
+ * compute unit, any other launch eight-wave ones); PEQA_BWD_PAIR=0 makes a per-channel backward
+ * that is asked for both gradients run its two contractions as launches of their own (by default
+ * they are one launch of four-wave workgroups, unless PEQA_GEMM_WAVES=8);
  * PEQA_GROUPED_DDS=pairs selects the older of two routes to the scale gradient of group-wise
  * layers.  Results agree within rounding.
  *
@@ -40,7 +40,9 @@
  * and then run as ONE layer with N = the sum of theirs: Y and dY are [T, sum N] with every
  * member a column range, d_ds is the members' gradients one after the other, and dX is the
  * gradient of the shared input (the sum of the members' dX) from a single contraction.
- * Results per member are bit-identical to running it alone; only dX, a sum, is new.
+ * Results per member are those of running it alone -- bit for bit when both runs take the same
+ * form of the contraction kernel (see Environment; the forms add the same products in a different
+ * order), else to the last bf16 bit; only dX, a sum, is new.
  */
 #ifndef PEQA_H
 #define PEQA_H
@@ -177,7 +179,10 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
  *   d_ds[i,g] = sum_t dY[t,i] * sum_{k in g} X[t,k] * (Q[i,k] - z0[i,g])
  *   dX [T, K] bf16 out, or NULL to skip; d_ds [N, G] fp32 out (overwritten, not
  *   accumulated), or NULL to skip.  X may be NULL when d_ds is NULL.
- *   The result is deterministic (fixed reduction order, no atomics).
+ *   The result is deterministic (fixed reduction order, no atomics): the same call gives the
+ *   same bits.  A call that skips one gradient may run the other's contraction in another form of
+ *   the kernel than a call that asks for both (see Environment): the same products added in
+ *   another order, so the two agree to the last bf16 bit of dX / 1e-5 of |d_ds|, not bit for bit.
  *   Group-wise layers take d_ds by the other order of the two sums,
  *   d_ds[i,g] = sum_{k in g} (sum_t dY[t,i] X[t,k]) (Q[i,k] - z0[i,g]); their backward workspace
  *   therefore also holds transposed copies of X and dY (2 (K + N) T' bytes, T' = T rounded up to 64).

@@ -516,13 +516,13 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     // The two gradients are independent.  Everything stays in order on the caller's stream: running the two
     // chains, or only their small kernels, beside each other on a second stream measured 2-6 % slower on the 7B
     // block, launched one by one (the events cost more than they hide) and as a captured graph alike.
-    const int tiles_dds = tiles_t * ((N + 255) / 256), tiles_dx = tiles_t * ((K + 255) / 256);
-    // With both gradients wanted and more tiles between them than compute units, the two contractions go out as
-    // one launch of four-wave workgroups, after the scaling of dY and before the sum of the partials
-    // (PEQA_BWD_PAIR=1 / 0 in the environment: whenever both are wanted / never).  Measured against separate
-    // launches: +1 to 2 % on the 7B block, where half the launches have one tile per compute unit and would run
-    // in the eight-wave form, +0.2 to 0.9 % on the 13B and 65B blocks.
-    bool pair = d_ds && dX && peqa::gemm_four_waves(tiles_dds + tiles_dx);
+    // With both gradients wanted, the two contractions go out as one launch of four-wave workgroups, after the
+    // scaling of dY and before the sum of the partials (PEQA_BWD_PAIR=0 in the environment, or PEQA_GEMM_WAVES=8:
+    // as launches of their own).  Measured against separate launches: +1 to 2 % on the 7B block at T = 2048, where
+    // half the launches have one tile per compute unit and would run in the eight-wave form, +0.2 to 0.9 % on the
+    // 13B and 65B blocks; 8 to 18 % less time per backward at T = 16 to 1024 on 4096 x 4096 and 4096 x 11008
+    // layers, where each contraction alone fills a fraction of the machine.
+    bool pair = d_ds && dX && peqa::gemm_four_waves(1 << 30);
     if (const char *e = getenv("PEQA_BWD_PAIR")) pair = d_ds && dX && e[0] == '1';
     peqa::GemmArgs a_dds{}, a_dx{};
     if (d_ds) {

@@ -15,8 +15,7 @@
 // A second form (KW = 1) runs four waves (2 x 2) over the whole contraction range of the same tile with half
 // the ring, two workgroups per compute unit: launches with more than one tile per compute unit take it (see
 // halves_per_workgroup below).  Its loop is unrolled by the ring depth.  The scale gradient and dX of one
-// per-channel backward run as four-wave tiles of one launch (gemm_bwd_pair_kernel) when they have more tiles than
-// compute units between them; in the group-wise dX launch, spare workgroups at the end of the grid write the
+// per-channel backward run as four-wave tiles of one launch (gemm_bwd_pair_kernel); in the group-wise dX launch, spare workgroups at the end of the grid write the
 // transposed operands of the token contraction.
 //
 // Operand paths.  Both operands go global -> LDS by DMA (global_load_lds) into a ring of
@@ -755,8 +754,9 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
 // Both contractions of a per-channel backward in one launch of four-wave workgroups: the first n_first
 // workgroups are the tiles of one of them (the one with the longer contraction), the rest the tiles of the
 // other.  Neither reads what the other writes.  Two launches of at most one tile per compute unit each -- which
-// would run in the eight-wave form, ring fill and epilogue exposed -- become one launch with two workgroups per
-// compute unit, and the last round of the first contraction is filled with tiles of the second.
+// would run in the eight-wave form, ring fill and epilogue exposed, or leave most of the machine idle at small T --
+// become one launch with up to two workgroups per compute unit, and the last round of the first contraction is
+// filled with tiles of the second.
 template <int BITS>
 __global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmArgs a_dds, GemmArgs a_dx, int n_first, int dx_first)
 {

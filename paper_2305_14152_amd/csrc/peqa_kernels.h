@@ -44,10 +44,11 @@ struct GemmArgs {
 };
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
-// whether a per-channel launch of that many 128 x 256 tiles takes the four-wave form (two workgroups per compute unit)
+// whether a per-channel launch of that many 128 x 256 tiles takes the four-wave form (two workgroups per compute unit);
+// for a huge count: whether the four-wave form is allowed at all (PEQA_GEMM_WAVES=8 forbids it)
 bool gemm_four_waves(int tiles);
 // Per-channel layers: the MODE_DDS and the MODE_DX contraction of one backward (arguments as for launch_gemm) as one
-// launch of four-wave workgroups, which pays when the two have more tiles than compute units between them.  The dX arguments' input (the scaled dY) must be complete before the launch.
+// launch of four-wave workgroups (measured faster than two launches at every T).  The dX arguments' input (the scaled dY) must be complete before the launch.
 hipError_t launch_gemm_bwd_pair(int bits, const GemmArgs &a_dds, const GemmArgs &a_dx, hipStream_t stream);
 
 // Arguments of the token contraction dW = dY^T X with the codes applied in its epilogue (peqa_dw.hip):

@@ -150,8 +150,8 @@ def test_four_wave_contraction_parity(gpu, oracle, monkeypatch, bits, N, K, T, g
     g4h, g8h = gpu.to_host(g4).astype(np.float64), gpu.to_host(g8).astype(np.float64)
     assert np.linalg.norm(g4h - g8h) <= 1e-5 * np.linalg.norm(g8h)
     if group == 0:
-        # both contractions of the backward as one launch of four-wave workgroups (taken by itself when they have
-        # more tiles than compute units between them): the same products in the same order
+        # both contractions of the backward as one launch of four-wave workgroups (the default when both gradients
+        # are asked for): the same products in the same order
         monkeypatch.setenv("PEQA_BWD_PAIR", "1")
         _check_fwd_bwd(gpu, oracle, layer, codes, s0, z0, X, dY, ds, group)
         dXp, gp = layer.bwd(X, dY, ds)

@@ -15,8 +15,8 @@
 // A second form (KW = 1) runs four waves (2 x 2) over the whole contraction range of the same tile with half
 // the ring, two workgroups per compute unit: launches with more than one tile per compute unit take it (see
 // halves_per_workgroup below).  Its loop is unrolled by the ring depth.  The scale gradient and dX of one
-// per-channel backward run as four-wave tiles of one launch (gemm_bwd_pair_kernel); in the group-wise dX launch, spare workgroups at the end of the grid write the
-// transposed operands of the token contraction.
+// per-channel backward run as four-wave tiles of one launch (gemm_bwd_pair_kernel); in the group-wise dX
+// launch, spare workgroups at the end of the grid write the transposed operands of the token contraction.
 //
 // Operand paths.  Both operands go global -> LDS by DMA (global_load_lds) into a ring of
 // stages, one 32-deep contraction step per stage: the activation operand (X, or the pre-scaled
@@ -858,8 +858,7 @@ hipError_t launch_gemm(int bits, int mode, const GemmArgs &a_in, hipStream_t str
     return e;
 }
 
-// Scale gradient and dX of one per-channel layer in one launch (see gemm_bwd_pair_kernel).  The caller has checked
-// gemm_four_waves(tiles of both).
+// Scale gradient and dX of one per-channel layer in one launch (see gemm_bwd_pair_kernel).
 template <int BITS>
 static hipError_t launch_pair(const GemmArgs &a_dds, const GemmArgs &a_dx, hipStream_t stream)
 {

@@ -24,14 +24,15 @@
  * Shape limits: N % 128 == 0, K % 128 == 0 (every LLaMA-family linear satisfies
  * this).  group_size is 0 or a multiple of 64 that divides K.
  *
- * Environment.  Three variables are read at every call, for tests and comparisons; none is needed:
- * PEQA_GEMM_WAVES=4|8 forces one of the two forms of the tiled contraction kernel (by default a
- * launch with more than one 128 x 256 tile per compute unit runs four-wave workgroups, two per
- * compute unit, any other launch eight-wave ones); PEQA_BWD_PAIR=0 makes a per-channel backward
- * that is asked for both gradients run its two contractions as launches of their own (by default
- * they are one launch of four-wave workgroups, unless PEQA_GEMM_WAVES=8);
- * PEQA_GROUPED_DDS=pairs selects the older of two routes to the scale gradient of group-wise
- * layers.  Results agree within rounding.
+ * Options.  The library reads nothing from the process environment.  Three switches exist for tests and
+ * comparisons, set explicitly with peqa_set_option (process-wide, not thread-safe; none is needed):
+ * PEQA_OPT_GEMM_WAVES = 4 | 8 forces one of the two forms of the tiled contraction kernel (0, the default:
+ * a launch with more than one 128 x 256 tile per compute unit runs four-wave workgroups, two per
+ * compute unit, any other launch eight-wave ones); PEQA_OPT_BWD_PAIR = 0 makes a per-channel backward
+ * that is asked for both gradients run its two contractions as launches of their own, 1 as one launch of
+ * four-wave workgroups (-1, the default: one launch unless PEQA_OPT_GEMM_WAVES is 8);
+ * PEQA_OPT_GROUPED_DDS = 1 selects the older of two routes to the scale gradient of group-wise
+ * layers (0, the default: the contraction over tokens).  Results agree within rounding.
  *
  * Stacking.  The packed array is stored by rows of 128-channel tiles and the scale-shaped
  * arrays by channel, so layers with equal K, bits and group_size that read the same input
@@ -41,7 +42,7 @@
  * member a column range, d_ds is the members' gradients one after the other, and dX is the
  * gradient of the shared input (the sum of the members' dX) from a single contraction.
  * Results per member are those of running it alone -- bit for bit when both runs take the same
- * form of the contraction kernel (see Environment; the forms add the same products in a different
+ * form of the contraction kernel (see Options; the forms add the same products in a different
  * order), else to the last bf16 bit; only dX, a sum, is new.
  */
 #ifndef PEQA_H
@@ -90,6 +91,16 @@ size_t peqa_num_scales(const peqa_layout *L);     /* N*G; 0 if invalid          
 size_t peqa_workspace_bytes(const peqa_layout *L, int32_t T, int32_t op);
 const char *peqa_status_string(int32_t status);
 
+/* Test and comparison switches (see Options above).  peqa_set_option returns PEQA_ERR_PARAM for an unknown
+ * option or a value outside those listed; peqa_get_option returns the current value (INT32_MIN if unknown). */
+typedef enum {
+    PEQA_OPT_GEMM_WAVES = 0,   /* 0 (default), 4, 8 */
+    PEQA_OPT_BWD_PAIR = 1,     /* -1 (default), 0, 1 */
+    PEQA_OPT_GROUPED_DDS = 2   /* 0 (default), 1 */
+} peqa_option;
+peqa_status peqa_set_option(int32_t option, int32_t value);
+int32_t peqa_get_option(int32_t option);
+
 /*
  * Word and bit (0..31) that hold bit `t` of the code of channel i, feature k in the
  * packed array.  The paper fixes only the density (exactly b bits per weight,
@@ -121,8 +132,9 @@ peqa_status peqa_quantize(const peqa_layout *L, const float *W0, uint32_t *packe
                           float *s0, uint8_t *z0, void *stream);
 
 /*
- * Error-minimising initialisation.  Sec. 3.2 asks for s0, z0 "to minimize ||W0 - What0||_F" without a
- * procedure (the experiments use the plain range of Eq. 1); this is the usual grid over clipped ranges.
+ * Error-minimising initialisation.  Sec. 3.2 wants s0, z0 chosen so that the Frobenius norm of W0 - What0 is
+ * smallest, and gives no procedure (the experiments use the plain range of Eq. 1); this is the usual grid
+ * over clipped ranges.
  * For j = 0 .. n_ratios-1 with r_j = 1 - j * (1 - min_ratio) / (n_ratios - 1)  (r_0 = 1: Eq. 1 itself),
  * every (channel, group) is quantized with the range [r_j xmin, r_j xmax] exactly as in peqa_quantize,
  * and the candidate with the smallest sum_k (w - s (Q - z))^2 is kept (the first of equal ones).
@@ -181,7 +193,7 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
  *   accumulated), or NULL to skip.  X may be NULL when d_ds is NULL.
  *   The result is deterministic (fixed reduction order, no atomics): the same call gives the
  *   same bits.  A call that skips one gradient may run the other's contraction in another form of
- *   the kernel than a call that asks for both (see Environment): the same products added in
+ *   the kernel than a call that asks for both (see Options): the same products added in
  *   another order, so the two agree to the last bf16 bit of dX / 1e-5 of |d_ds|, not bit for bit.
  *   Group-wise layers take d_ds by the other order of the two sums,
  *   d_ds[i,g] = sum_{k in g} (sum_t dY[t,i] X[t,k]) (Q[i,k] - z0[i,g]); their backward workspace

@@ -119,8 +119,8 @@ int oracle_quantize(const float *W0, int N, int K, int bits, int group,
     return 0;
 }
 
-/* Sec. 3.2 initialises s0, z0 "to minimize ||W0 - What0||_F" but gives no procedure
- * (the experiments use plain round-to-nearest).  The usual procedure is a grid search over
+/* Sec. 3.2 wants s0, z0 initialised so that the Frobenius norm of W0 - What0 is smallest, but gives
+ * no procedure (the experiments use plain round-to-nearest).  The usual procedure is a grid search over
  * clipped ranges, which is what this function states: for every (channel, group) and every
  * ratio r_j = 1 - j * step, step = (1 - min_ratio) / (n_ratios - 1), j = 0 .. n_ratios - 1
  * (r_0 = 1 is Eq. 1 as it stands):

@@ -2,18 +2,21 @@
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpeqa_hip.so")
-SOURCES = ["peqa_api.hip", "peqa_quantize.hip", "peqa_small.hip", "peqa_gemm.hip", "peqa_gemv.hip", "peqa_dw.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+SOURCES = ["peqa_api.hip", "peqa_quantize.hip", "peqa_small.hip", "peqa_gemm.hip", "peqa_gemv.hip", "peqa_dw.hip",
+           "peqa_block.hip"]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage"]
 # Kernels that queue global -> LDS DMA from inline assembly and count s_waitcnt vmcnt by hand: a
 # register spill would add scratch loads and stores (also counted by vmcnt) that the hand count does
 # not know about, so the build refuses any scratch use in them.
-NO_SCRATCH = ("gemm_kernel", "gemm_bwd_pair_kernel", "gemv_kernel", "dw_kernel")
+NO_SCRATCH = ("gemm_kernel", "gemm_bwd_pair_kernel", "gemm_multi_kernel", "gemv_kernel", "dw_kernel")
 
 
 def check_no_scratch(remarks):
@@ -29,19 +32,44 @@ def check_no_scratch(remarks):
     return bad
 
 
-def build(verbose=False, extra=()):
+def _quiet(text):
+    return "\n".join(l for l in text.splitlines() if "packed-fp32-ops" not in l and "remark:" not in l)
+
+
+def build(verbose=False, extra=(), jobs=None):
+    """Every source is compiled (always: no time stamps are consulted) to an object of its own, in
+    parallel, then the objects are linked into the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + list(extra) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and "remark:" not in l)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    bad = check_no_scratch(r.stdout)
-    if bad:
+    os.makedirs(OBJ, exist_ok=True)
+    if os.path.exists(LIB):
         os.remove(LIB)
+
+    def compile_one(src):
+        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+        cmd = [hipcc] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        return src, obj, r
+
+    jobs = jobs or min(len(SOURCES), int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        results = list(pool.map(compile_one, SOURCES))
+    remarks = ""
+    for src, _, r in results:
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (src, _quiet(r.stdout)))
+        remarks += r.stdout
+    bad = check_no_scratch(remarks)
+    if bad:
         raise RuntimeError("register spills in kernels that count vmcnt by hand:\n" + "\n".join(bad))
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + [obj for _, obj, _ in results] + ["-o", LIB]
+    if verbose:
+        print(" ".join(link), flush=True)
+    r = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link failed:\n" + _quiet(r.stdout))
+    out = _quiet(remarks)
     if verbose and out.strip():
         print(out)
     return LIB

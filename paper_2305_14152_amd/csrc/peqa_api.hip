@@ -3,9 +3,8 @@
 // the benchmark tracing hooks at the bottom.
 #include "../../include/peqa.h"
 
+#include <limits.h>
 #include <math.h>
-#include <stdlib.h>
-#include <string.h>
 
 #include "peqa_kernels.h"
 
@@ -128,14 +127,10 @@ peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const 
                             const uint8_t *z0, const float *dz, const uint16_t *X, int32_t T, uint16_t *Y, float *P,
                             const float *rs, hipStream_t s);
 
-// Scale gradient of group-wise layers: by the contraction over tokens (default), or, with
-// PEQA_GROUPED_DDS=pairs in the environment (read at every call), by the contraction over features, one
-// pair of scale groups per workgroup: the older, slower route, kept for comparison.
-bool grouped_dds_by_tokens()
-{
-    const char *e = getenv("PEQA_GROUPED_DDS");
-    return !(e && strcmp(e, "pairs") == 0);
-}
+// Scale gradient of group-wise layers: by the contraction over tokens (default), or, with the option
+// grouped_dds = 1, by the contraction over features, one pair of scale groups per workgroup: the older,
+// slower route, kept for comparison.
+bool grouped_dds_by_tokens() { return peqa::options().grouped_dds == 0; }
 
 }  // namespace
 
@@ -174,6 +169,38 @@ size_t peqa_workspace_bytes(const peqa_layout *L, int32_t T, int32_t op)
         return 0;
     }
     return carve(L, T, op).total;
+}
+
+peqa_status peqa_set_option(int32_t option, int32_t value)
+{
+    peqa::Options &o = peqa::options();
+    switch (option) {
+    case PEQA_OPT_GEMM_WAVES:
+        if (value != 0 && value != 4 && value != 8) return PEQA_ERR_PARAM;
+        o.gemm_waves = value;
+        return PEQA_OK;
+    case PEQA_OPT_BWD_PAIR:
+        if (value < -1 || value > 1) return PEQA_ERR_PARAM;
+        o.bwd_pair = value;
+        return PEQA_OK;
+    case PEQA_OPT_GROUPED_DDS:
+        if (value != 0 && value != 1) return PEQA_ERR_PARAM;
+        o.grouped_dds = value;
+        return PEQA_OK;
+    default:
+        return PEQA_ERR_PARAM;
+    }
+}
+
+int32_t peqa_get_option(int32_t option)
+{
+    const peqa::Options &o = peqa::options();
+    switch (option) {
+    case PEQA_OPT_GEMM_WAVES: return o.gemm_waves;
+    case PEQA_OPT_BWD_PAIR: return o.bwd_pair;
+    case PEQA_OPT_GROUPED_DDS: return o.grouped_dds;
+    default: return INT32_MIN;
+    }
 }
 
 const char *peqa_status_string(int32_t status)
@@ -517,13 +544,13 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     // chains, or only their small kernels, beside each other on a second stream measured 2-6 % slower on the 7B
     // block, launched one by one (the events cost more than they hide) and as a captured graph alike.
     // With both gradients wanted, the two contractions go out as one launch of four-wave workgroups, after the
-    // scaling of dY and before the sum of the partials (PEQA_BWD_PAIR=0 in the environment, or PEQA_GEMM_WAVES=8:
-    // as launches of their own).  Measured against separate launches: +1 to 2 % on the 7B block at T = 2048, where
+    // scaling of dY and before the sum of the partials (option bwd_pair = 0, or gemm_waves = 8: as launches of
+    // their own).  Measured against separate launches: +1 to 2 % on the 7B block at T = 2048, where
     // half the launches have one tile per compute unit and would run in the eight-wave form, +0.2 to 0.9 % on the
     // 13B and 65B blocks; 8 to 18 % less time per backward at T = 16 to 1024 on 4096 x 4096 and 4096 x 11008
     // layers, where each contraction alone fills a fraction of the machine.
     bool pair = d_ds && dX && peqa::gemm_four_waves(1 << 30);
-    if (const char *e = getenv("PEQA_BWD_PAIR")) pair = d_ds && dX && e[0] == '1';
+    if (peqa::options().bwd_pair >= 0) pair = d_ds && dX && peqa::options().bwd_pair == 1;
     peqa::GemmArgs a_dds{}, a_dx{};
     if (d_ds) {
         // row sums of X over the two contraction halves: the caller's (peqa_row_sums), or taken here
@@ -718,6 +745,14 @@ peqa_status peqa_scale_update_multi(int32_t n, const peqa_update_item *items, co
 // ---------------------------------------------------------------------------------------
 // Benchmark tracing: HIP events around every launch while enabled.
 // ---------------------------------------------------------------------------------------
+namespace peqa {
+Options &options()
+{
+    static Options o;
+    return o;
+}
+}  // namespace peqa
+
 namespace {
 
 struct TraceState {

@@ -40,10 +40,7 @@ constexpr int DW_NST = 4;                        // ring depth
 constexpr int DW_A_BYTES = DW_TF * 64;           // 16 KB: 256 feature rows x 32 tokens
 constexpr int DW_STAGE = (DW_TF + DW_TC) * 64;   // 32 KB
 constexpr int DW_LDS = DW_NST * DW_STAGE;        // 128 KB
-#ifndef PEQA_DW_WM
-#define PEQA_DW_WM 4
-#endif
-constexpr int DW_WM = PEQA_DW_WM;                // waves along the features: see dw_kernel
+constexpr int DW_WM = 4;                         // waves along the features: see dw_kernel
 
 // Code of (channel row r, feature column cc) of one packed 8x8 block (the layout of peqa.h).
 template <int BITS>

@@ -36,9 +36,7 @@
 //                     contraction half one group, and the column-reduced epilogue writes one
 //                     partial per (token tile, channel, group).  This is the older of two routes to
 //                     the grouped scale gradient (the default contracts over tokens, peqa_dw.hip)
-//                     and runs only on request (PEQA_GROUPED_DDS=pairs).
-#include <stdlib.h>
-
+//                     and runs only on request (option grouped_dds = 1).
 #include <type_traits>
 
 #include "peqa_device.h"
@@ -774,15 +772,13 @@ __global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmArgs a_dds, G
 // has at most one tile per compute unit (a lone four-wave workgroup leaves every SIMD a single wave, which
 // measures 7-10 % slower); otherwise four waves with the whole range and two workgroups per compute unit
 // (72 KB of LDS each), which fill the same four SIMDs with two waves each, need no exchange of partial sums,
-// and hide one workgroup's ring fill and epilogue behind the other's loop.  PEQA_GEMM_WAVES=4 or 8 in the
-// environment (read at every launch) forces one of them, for tests and comparisons.
+// and hide one workgroup's ring fill and epilogue behind the other's loop.  The option gemm_waves = 4 or 8
+// (peqa_set_option) forces one of them, for tests and comparisons.
 static int halves_per_workgroup(int tiles, bool paired)
 {
     if (paired) return 2;
-    if (const char *e = getenv("PEQA_GEMM_WAVES")) {
-        if (e[0] == '4') return 1;
-        if (e[0] == '8') return 2;
-    }
+    if (options().gemm_waves == 4) return 1;
+    if (options().gemm_waves == 8) return 2;
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     return tiles > cus ? 1 : 2;

@@ -9,6 +9,14 @@ namespace peqa {
 
 enum { MODE_Y = 0, MODE_DDS = 1, MODE_DX = 2 };
 
+// Test and comparison switches, set through peqa_set_option (peqa_api.hip); the defaults select by launch size.
+struct Options {
+    int gemm_waves = 0;     // 0 = by launch size, 4 or 8 = that form of the tiled contraction
+    int bwd_pair = -1;      // -1 = pair the two contractions of a per-channel backward unless gemm_waves is 8; 0, 1 = never, always
+    int grouped_dds = 0;    // 0 = group-wise scale gradient by the contraction over tokens, 1 = over features (older route)
+};
+Options &options();
+
 // Arguments of the tiled MFMA contraction (peqa_gemm.hip).
 struct GemmArgs {
     const uint32_t *packed;   // packed codes of the whole layer
@@ -45,7 +53,7 @@ struct GemmArgs {
 
 hipError_t launch_gemm(int bits, int mode, const GemmArgs &a, hipStream_t stream);
 // whether a per-channel launch of that many 128 x 256 tiles takes the four-wave form (two workgroups per compute unit);
-// for a huge count: whether the four-wave form is allowed at all (PEQA_GEMM_WAVES=8 forbids it)
+// for a huge count: whether the four-wave form is allowed at all (the option gemm_waves = 8 forbids it)
 bool gemm_four_waves(int tiles);
 // Per-channel layers: the MODE_DDS and the MODE_DX contraction of one backward (arguments as for launch_gemm) as one
 // launch of four-wave workgroups (measured faster than two launches at every T).  The dX arguments' input (the scaled dY) must be complete before the launch.

@@ -11,6 +11,7 @@ PEQA_OK = 0
 PEQA_ERR_NULL, PEQA_ERR_SHAPE, PEQA_ERR_BITS, PEQA_ERR_GROUP = 1, 2, 3, 4
 PEQA_ERR_ALIGN, PEQA_ERR_WORKSPACE, PEQA_ERR_DEVICE, PEQA_ERR_PARAM = 5, 6, 7, 8
 PEQA_OP_FWD, PEQA_OP_BWD, PEQA_OP_FWD_KEEP, PEQA_OP_BWD_KEPT, PEQA_OP_FWD_Z, PEQA_OP_BWD_Z = 0, 1, 2, 3, 4, 5
+PEQA_OPT_GEMM_WAVES, PEQA_OPT_BWD_PAIR, PEQA_OPT_GROUPED_DDS = 0, 1, 2
 
 EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_workspace_bytes",
            "peqa_status_string", "peqa_bit_location", "peqa_quantize", "peqa_linear_fwd",
@@ -18,7 +19,8 @@ EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_wo
            "peqa_workspace_bytes_fused", "peqa_linear_fwd_fused", "peqa_linear_fwd_keep", "peqa_linear_bwd_kept",
            "peqa_linear_fwd_z", "peqa_linear_bwd_z", "peqa_quantize_search",
            "peqa_scale_update_multi", "peqa_device_info",
-           "peqa_row_sums", "peqa_linear_fwd_fused_rs", "peqa_linear_bwd_rs"]
+           "peqa_row_sums", "peqa_linear_fwd_fused_rs", "peqa_linear_bwd_rs",
+           "peqa_set_option", "peqa_get_option"]
 
 
 class Layout(ctypes.Structure):
@@ -96,6 +98,10 @@ def lib():
         L.peqa_workspace_bytes_fused.restype = sz
         L.peqa_linear_fwd_fused.argtypes = [i32, vp, vp, i32, vp, sz, vp]
         L.peqa_linear_fwd_fused.restype = i32
+        L.peqa_set_option.argtypes = [i32, i32]
+        L.peqa_set_option.restype = i32
+        L.peqa_get_option.argtypes = [i32]
+        L.peqa_get_option.restype = i32
         L.peqa_trace_begin.argtypes = [i32]
         L.peqa_trace_begin.restype = i32
         L.peqa_trace_end.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32),
@@ -276,11 +282,19 @@ def scale_update(n_scales, ds, d_ds, m, v, s0, lr, beta1=0.9, beta2=0.999, eps=1
                                    ctypes.byref(opt), _stream(stream)), "peqa_scale_update")
 
 
+def set_option(option, value):
+    _check(lib().peqa_set_option(int(option), int(value)), "peqa_set_option")
+
+
+def get_option(option):
+    return int(lib().peqa_get_option(int(option)))
+
+
 def trace_begin(max_launches):
     _check(lib().peqa_trace_begin(int(max_launches)), "peqa_trace_begin")
 
 
-def trace_end(max_kernels=16):
+def trace_end(max_kernels=32):
     names = (ctypes.c_char_p * max_kernels)()
     launches = (ctypes.c_int32 * max_kernels)()
     total_ms = (ctypes.c_float * max_kernels)()

@@ -131,6 +131,26 @@ class GpuLayer:
         return dX, dds, ddz
 
 
+def assert_scale_grad_close(g, gref, what="d_ds"):
+    """The two bounds every scale (or zero-point) gradient is held to: relative L2 error at most 1e-3 (the stated
+    tolerance), and, element by element, |g - ref| <= 1e-3 |ref| + 5e-5 rms(ref), so that a single wrong channel
+    or group of small magnitude cannot hide under the norm.  Returns (relative L2 error, worst element's share of
+    its bound)."""
+    g = np.asarray(g, np.float64)
+    gref = np.asarray(gref, np.float64)
+    assert g.shape == gref.shape, (what, g.shape, gref.shape)
+    nref = np.linalg.norm(gref)
+    l2 = np.linalg.norm(g - gref) / nref if nref > 0 else float(np.abs(g).max())
+    assert l2 <= 1e-3, "%s: relative L2 error %.3e" % (what, l2)
+    bound = 1e-3 * np.abs(gref) + 5e-5 * nref / np.sqrt(gref.size)
+    ratio = np.abs(g - gref) / np.maximum(bound, 1e-300)
+    worst = float(ratio.max())
+    assert worst <= 1.0, "%s: element %s off by %.3e (bound %.3e)" % (
+        what, np.unravel_index(int(ratio.argmax()), ratio.shape), float(np.abs(g - gref).ravel()[ratio.argmax()]),
+        float(bound.ravel()[ratio.argmax()]))
+    return l2, worst
+
+
 def bf16_dev_to_f64(t):
     from paper_2305_14152_amd import synth
     return synth.bf16_bits_to_f32(to_host(t).view(np.uint16)).astype(np.float64)

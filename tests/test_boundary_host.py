@@ -240,3 +240,23 @@ def test_fp64_reciprocal_product_is_the_correctly_rounded_fp32_quotient():
         w = (m * s).astype(np.float32)
         w = (w.view(np.int32) + nudge).view(np.float32)
         check(w, s)
+
+
+def test_options_are_explicit_and_validated(peqa):
+    """The test switches are set through peqa_set_option only (nothing is read from the environment); unknown
+    options and values are refused and change nothing."""
+    assert peqa.get_option(peqa.PEQA_OPT_GEMM_WAVES) == 0
+    assert peqa.get_option(peqa.PEQA_OPT_BWD_PAIR) == -1
+    assert peqa.get_option(peqa.PEQA_OPT_GROUPED_DDS) == 0
+    lib = peqa.lib()
+    for opt, bad in ((peqa.PEQA_OPT_GEMM_WAVES, 2), (peqa.PEQA_OPT_BWD_PAIR, 2), (peqa.PEQA_OPT_GROUPED_DDS, -1), (99, 0)):
+        assert lib.peqa_set_option(opt, bad) == peqa.PEQA_ERR_PARAM
+    assert peqa.get_option(99) == -2 ** 31
+    try:
+        peqa.set_option(peqa.PEQA_OPT_GEMM_WAVES, 8)
+        assert peqa.get_option(peqa.PEQA_OPT_GEMM_WAVES) == 8
+    finally:
+        peqa.set_option(peqa.PEQA_OPT_GEMM_WAVES, 0)
+    src = "".join(open(os.path.join(ROOT, "paper_2305_14152_amd", "csrc", f)).read()
+                  for f in os.listdir(os.path.join(ROOT, "paper_2305_14152_amd", "csrc")))
+    assert "getenv" not in src

@@ -10,7 +10,6 @@ from paper_2305_14152_amd import synth
 pytestmark = pytest.mark.gpu
 
 Y_TOL = 2e-2
-G_TOL = 1e-3
 
 
 @pytest.fixture(scope="module")
@@ -31,6 +30,19 @@ def _sample(n, edges, rng, count):
             if 0 <= e + d < n:
                 picks.add(e + d)
     picks.update(int(v) for v in rng.integers(0, n, size=count))
+    return np.array(sorted(picks))
+
+
+def _one_per_tile(n, tile, edges, rng):
+    """One index in every run of `tile` (a random position in it), both ends of the range, and both sides of
+    the given boundaries: every tile of a launch is touched, whatever workgroup ran it."""
+    picks = {0, n - 1}
+    for b in range(0, n, tile):
+        picks.add(b + int(rng.integers(0, min(tile, n - b))))
+    for e in edges:
+        for d in (-1, 0):
+            if 0 <= e + d < n:
+                picks.add(e + d)
     return np.array(sorted(picks))
 
 
@@ -73,22 +85,33 @@ def _full_size_layer(gpu, oracle, cfg, li, count):
     X = synth.activations(cfg, li)
     dY = synth.output_grads(cfg, li, N=N)
     ds = synth.normal_f32(77 + cfg, s0.shape, 1e-3 * float(np.mean(s0)))
-    ts = _sample(T, (128, 1024), rng, 3)
-    ns = _sample(N, (128, 256, N // 2, N // count), rng, 8)
+    # token rows: one in every 128-row tile (and the edges of some); channels: one in every 128-channel half of a
+    # 256-column tile (and the edges of some, and of the stacked members)
+    ts = _one_per_tile(T, 128, (128, 1024, T - 128), rng)
+    ns = _one_per_tile(N, 128, (128, 256, N // 2, N // count), rng)
+    ks = _one_per_tile(K, 128, (128, 256, K // 2), rng)
+    assert len(ts) >= T // 128 and len(ns) >= N // 128
 
-    # forward: sampled rows x sampled channels
+    # forward: the sampled rows against every channel
     Y = gpu.bf16_dev_to_f64(layer.fwd(X, ds))
-    Yref = oracle.fwd(codes[ns], s0[ns], ds[ns], z0[ns], X[ts], group)
-    assert np.abs(Y[np.ix_(ts, ns)] - Yref).max() <= Y_TOL * np.abs(Yref).max()
+    Yref = oracle.fwd(codes, s0, ds, z0, X[ts], group)
+    assert np.abs(Y[ts] - Yref).max() <= Y_TOL * np.abs(Yref).max()
+    # every output tile is non-trivial: no 128 x 128 block of Y was left unwritten or zero
+    blocks = np.abs(Y).reshape(T // 128, 128, N // 128, 128).max(axis=(1, 3))
+    assert (blocks > 0).all()
 
     # backward: whole rows of dX for the sampled tokens, d_ds of the sampled channels
     dX, dds = layer.bwd(X, dY, ds)
-    dXref, _, _ = oracle.bwd(codes, s0, ds, z0, X[ts], dY[ts], group)
-    got = gpu.bf16_dev_to_f64(dX)[ts]
-    assert np.abs(got - dXref).max() <= Y_TOL * np.abs(dXref).max()
-    _, gref, _ = oracle.bwd(codes[ns], s0[ns], ds[ns], z0[ns], X, np.ascontiguousarray(dY[:, ns]), group)
+    dXref, _, _ = oracle.bwd(codes, s0, ds, z0, X[ts], dY[ts], group, want_P=False)
+    got = gpu.bf16_dev_to_f64(dX)
+    assert np.abs(got[ts] - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    blocks = np.abs(got).reshape(T // 128, 128, K // 128, 128).max(axis=(1, 3))
+    assert (blocks > 0).all()
+    del got, ks
+    _, gref, _ = oracle.bwd(codes[ns], s0[ns], ds[ns], z0[ns], X, np.ascontiguousarray(dY[:, ns]), group, want_dX=False)
     g = gpu.to_host(dds).astype(np.float64)[ns]
-    assert np.linalg.norm(g - gref) <= G_TOL * np.linalg.norm(gref)
+    gpu.assert_scale_grad_close(g, gref)
+    assert np.isfinite(gpu.to_host(dds)).all() and (np.abs(gpu.to_host(dds)).reshape(N // 128, -1).max(axis=1) > 0).all()
 
     if cfg == 4:
         # deployment forward of the same layer: T = 1 and T = 16, every channel
@@ -131,8 +154,8 @@ def test_full_size_variants(gpu, oracle, cfg, li):
     _, gs_ref, gz_ref = oracle.bwd_z(codes[ns], s0[ns], ds[ns], z0[ns], dz[ns], X, dYn, group, want_dX=False)
     gs = gpu.to_host(dds).astype(np.float64)[ns]
     gz = gpu.to_host(ddz).astype(np.float64)[ns]
-    assert np.linalg.norm(gs - gs_ref) <= G_TOL * np.linalg.norm(gs_ref)
-    assert np.linalg.norm(gz - gz_ref) <= G_TOL * np.linalg.norm(gz_ref)
+    gpu.assert_scale_grad_close(gs, gs_ref, "d_ds")
+    gpu.assert_scale_grad_close(gz, gz_ref, "d_dz")
 
     if group == 0:
         # kept product: P on the sampled entries, the scale gradient of the sampled channels from it
@@ -143,7 +166,7 @@ def test_full_size_variants(gpu, oracle, cfg, li):
         _, ddsk = layer.bwd_kept(P, dY, ds, want_dX=False)
         _, gref, _ = oracle.bwd(codes[ns], s0[ns], ds[ns], z0[ns], X, dYn, 0, want_dX=False)
         gk = gpu.to_host(ddsk).astype(np.float64)[ns]
-        assert np.linalg.norm(gk - gref) <= G_TOL * np.linalg.norm(gref)
+        gpu.assert_scale_grad_close(gk, gref)
 
 
 def test_full_size_quantize_search(gpu, oracle):
@@ -168,8 +191,15 @@ def test_full_size_quantize_search(gpu, oracle):
     same = (gpu.to_host(s0).view(np.uint32) == rs0.view(np.uint32)) & (gpu.to_host(z0) == rz0)
     print("  candidates kept beyond the plain range: %d of %d; rows differing: %d"
           % (int((choice > 0).sum()), choice.size, int((~same).sum())), flush=True)
-    assert (~same).sum() <= 2                                       # only exact-to-rounding ties may differ
-    rows = same[:, 0]
     words = gpu.to_host(packed, np.uint32)
     got = oracle.unpack(words, N, K, bits)
+    rows = same[:, 0]
     assert (got[rows] == codes[rows]).all()
+    if not rows.all():
+        # another candidate is right only as a tie: the two reconstruction errors (fp64) agree to 1e-12
+        bad = np.nonzero(~rows)[0]
+        Wb = W[bad].astype(np.float64)
+        gs0, gz0 = gpu.to_host(s0)[bad], gpu.to_host(z0)[bad]
+        e_ref = ((Wb - oracle.dequant(codes[bad], rs0[bad], None, rz0[bad], group)) ** 2).sum(axis=1)
+        e_gpu = ((Wb - oracle.dequant(got[bad], gs0, None, gz0, group)) ** 2).sum(axis=1)
+        assert (np.abs(e_gpu - e_ref) <= 1e-12 * e_ref).all()

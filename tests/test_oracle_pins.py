@@ -389,7 +389,7 @@ def test_scale_gradient_fd_two_routes_euler_and_independence(oracle, bits, group
 
 
 # ----------------------------------------------------------------------------
-# Error-minimising initialisation (Sec. 3.2: s0, z0 "to minimize ||W0 - What0||_F")
+# Error-minimising initialisation (Sec. 3.2: s0, z0 with the smallest Frobenius norm of W0 - What0)
 # ----------------------------------------------------------------------------
 def _recon_error(oracle, W, codes, s0, z0, group):
     """sum_k (w - s (Q - z))^2 per (channel, group), in fp64 from the returned parameters."""

@@ -163,6 +163,24 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
                             uint16_t *Y, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * peqa_linear_fwd for callers that cannot allocate device memory and have no workspace to pass: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * result bit for bit as peqa_linear_fwd; the scratch a forward needs (row sums of X, the group table, or the
+ * partial sums of the T <= 16 path) lives in an array of PEQA_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends).  The call allocates
+ * nothing and frees nothing.  A forward that needs more scratch than that (peqa_workspace_bytes(L, T,
+ * PEQA_OP_FWD) > PEQA_STATIC_SCRATCH_BYTES) is refused with PEQA_ERR_WORKSPACE before anything is enqueued.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it; calls on one stream are ordered and safe.  Nothing in the array needs to start at zero.
+ * The array's device address is looked up once per device, at the first call on that device (not a stream
+ * operation: make that first call outside a capture).
+ */
+#define PEQA_STATIC_SCRATCH_BYTES (16u << 20)
+peqa_status peqa_linear_fwd_static(const peqa_layout *L, const uint32_t *packed, const float *s0,
+                                   const float *ds, const uint8_t *z0, const uint16_t *X, int32_t T,
+                                   uint16_t *Y, void *stream);
+
+/*
  * The same forward for 1..PEQA_MAX_FUSED layers that read the same X (the query / key / value
  * projections of an attention block; the gate and up projections of its MLP): equal to calling
  * peqa_linear_fwd once per item, every item writing its own Y.  All items must share k_in, bits

@@ -314,6 +314,47 @@ peqa_status peqa_linear_fwd(const peqa_layout *L, const uint32_t *packed, const 
     return fwd_impl(L, packed, s0, ds, z0, nullptr, X, T, Y, workspace, workspace_bytes, stream);
 }
 
+// ---- forward without a caller workspace: the scratch is an array in the library's own device image.
+// In host code the array's name is only a handle for the runtime's symbol lookup, never an address: every use of
+// its memory goes through the pointer that hipGetSymbolAddress returned for the current device.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[PEQA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];     // device address of `scratch` on each device, looked up at first use
+
+peqa_status static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PEQA_ERR_DEVICE;
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PEQA_ERR_DEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PEQA_OK;
+}
+}  // namespace
+
+extern "C" {
+
+peqa_status peqa_linear_fwd_static(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
+                                   const uint8_t *z0, const uint16_t *X, int32_t T, uint16_t *Y, void *stream)
+{
+    peqa_status st = peqa_check_layout(L);
+    if (st != PEQA_OK) return st;
+    if (T < 1 || T > (1 << 24)) return PEQA_ERR_SHAPE;
+    if (carve(L, T, PEQA_OP_FWD).total > (size_t)PEQA_STATIC_SCRATCH_BYTES) return PEQA_ERR_WORKSPACE;
+    if (!packed || !s0 || !z0 || !X || !Y) return PEQA_ERR_NULL;    // before the device is touched
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != PEQA_OK) return st;
+    return fwd_impl(L, packed, s0, ds, z0, nullptr, X, T, Y, ws, (size_t)PEQA_STATIC_SCRATCH_BYTES, stream);
+}
+
 peqa_status peqa_linear_fwd_z(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
                               const uint8_t *z0, const float *dz, const uint16_t *X, int32_t T, uint16_t *Y,
                               void *workspace, size_t workspace_bytes, void *stream)

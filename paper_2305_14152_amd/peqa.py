@@ -20,7 +20,7 @@ EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_wo
            "peqa_linear_fwd_z", "peqa_linear_bwd_z", "peqa_quantize_search",
            "peqa_scale_update_multi", "peqa_device_info",
            "peqa_row_sums", "peqa_linear_fwd_fused_rs", "peqa_linear_bwd_rs",
-           "peqa_set_option", "peqa_get_option"]
+           "peqa_set_option", "peqa_get_option", "peqa_linear_fwd_static"]
 
 
 class Layout(ctypes.Structure):
@@ -74,6 +74,8 @@ def lib():
         L.peqa_quantize_search.restype = i32
         L.peqa_linear_fwd.argtypes = [LP, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.peqa_linear_fwd.restype = i32
+        L.peqa_linear_fwd_static.argtypes = [LP, vp, vp, vp, vp, vp, i32, vp, vp]
+        L.peqa_linear_fwd_static.restype = i32
         L.peqa_linear_bwd.argtypes = [LP, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
         L.peqa_linear_bwd.restype = i32
         L.peqa_linear_fwd_keep.argtypes = [LP, vp, vp, vp, vp, vp, i32, vp, vp, vp, sz, vp]
@@ -219,6 +221,14 @@ def linear_fwd(L, packed, s0, ds, z0, X, T, Y, workspace, workspace_bytes_, stre
     _check(lib().peqa_linear_fwd(ctypes.byref(L), _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(X), int(T),
                                  _ptr(Y), _ptr(workspace), int(workspace_bytes_), _stream(stream)),
            "peqa_linear_fwd")
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def linear_fwd_static(L, packed, s0, ds, z0, X, T, Y, stream=None):
+    _check(lib().peqa_linear_fwd_static(ctypes.byref(L), _ptr(packed), _ptr(s0), _ptr(ds), _ptr(z0), _ptr(X), int(T),
+                                        _ptr(Y), _stream(stream)), "peqa_linear_fwd_static")
 
 
 class FwdItem(ctypes.Structure):

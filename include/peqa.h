@@ -204,6 +204,50 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
                                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The linears of a decoder block behind one call (Sec. 3.1 motivates PEQA by the cost of the fully-connected
+ * layers of a block: the query / key / value / output projections and the gate / up / down projections of
+ * LLaMA; Eq. 2 is applied to each).  An item is one layer with its own input: peqa_block_fwd equals
+ * peqa_linear_fwd per item, peqa_block_bwd equals peqa_linear_bwd per item, up to the order of floating-point
+ * additions.  Items are independent of each other: no item's input may be another item's output of the same
+ * call.  Layers that read one input are best passed stacked as one item (see Stacking); items may also
+ * simply share an X pointer.  All items share T and the bit width (PEQA_ERR_PARAM otherwise); shapes and
+ * group sizes may differ.
+ *   T <= 16 (the deployment path of Sec. 3.1): every layer of the call runs in ONE launch, whose workgroups
+ *     get equal shares of the packed bytes, plus one short launch that adds up the feature slices of the
+ *     layers that were sliced.
+ *   T > 16, per-channel layers: forward = the row sums of all distinct inputs in one launch, then all
+ *     items' contractions in one launch of four-wave tiles, longest contraction first.  Backward = all scale-gradient
+ *     contractions in one launch whose grid also carries the scaling of dY for every item, then all dX
+ *     contractions in one launch whose grid also carries the fixed-order sums of the scale-gradient partials.
+ *     Group-wise layers run item by item as peqa_linear_fwd / peqa_linear_bwd do.
+ *   row_sums (optional, [T, 2] fp32 per distinct X, caller-owned): when not NULL, peqa_block_fwd stores the row
+ *     sums of the item's X there (see peqa_row_sums) and peqa_block_bwd reads them instead of taking them again;
+ *     items that share X may share the array.  Ignored by T <= 16 and by group-wise layers.
+ *   `items` is a HOST array of 1..PEQA_MAX_BLOCK entries; workspace: peqa_block_workspace_bytes(n, items, T, op)
+ *   with op = PEQA_OP_FWD or PEQA_OP_BWD, contents undefined on return.  dX and d_ds may be NULL per item (skipped).
+ */
+#define PEQA_MAX_BLOCK 8
+typedef struct {
+    peqa_layout layout;
+    const uint32_t *packed;
+    const float *s0;
+    const float *ds;       /* may be NULL */
+    const uint8_t *z0;
+    const uint16_t *X;     /* [T, layout.k_in] bf16, in (both calls; may be NULL in the backward when d_ds is) */
+    uint16_t *Y;           /* [T, layout.n_out] bf16, out of peqa_block_fwd (unused by the backward)           */
+    const uint16_t *dY;    /* [T, layout.n_out] bf16, in of peqa_block_bwd (unused by the forward)             */
+    uint16_t *dX;          /* [T, layout.k_in] bf16, out of peqa_block_bwd, or NULL                            */
+    float *d_ds;           /* [N, G] fp32, out of peqa_block_bwd (overwritten), or NULL                        */
+    float *row_sums;       /* optional, see above                                                              */
+} peqa_block_item;
+
+size_t peqa_block_workspace_bytes(int32_t n, const peqa_block_item *items, int32_t T, int32_t op);
+peqa_status peqa_block_fwd(int32_t n, const peqa_block_item *items, int32_t T, void *workspace,
+                           size_t workspace_bytes, void *stream);
+peqa_status peqa_block_bwd(int32_t n, const peqa_block_item *items, int32_t T, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/*
  * Backward of Eq. 2 by the chain rule (only the scales are trained, Sec. 3.2):
  *   dX[t,k]   = sum_i dY[t,i] * (s0+ds)[i,g(k)] * (Q[i,k] - z0[i,g(k)])
  *   d_ds[i,g] = sum_t dY[t,i] * sum_{k in g} X[t,k] * (Q[i,k] - z0[i,g])

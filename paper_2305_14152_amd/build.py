@@ -60,6 +60,8 @@ def build(verbose=False, extra=(), jobs=None):
         if r.returncode != 0:
             raise RuntimeError("hipcc failed on %s:\n%s" % (src, _quiet(r.stdout)))
         remarks += r.stdout
+    with open(os.path.join(OBJ, "remarks.txt"), "w") as f:     # registers, LDS and occupancy of every kernel
+        f.write(remarks)
     bad = check_no_scratch(remarks)
     if bad:
         raise RuntimeError("register spills in kernels that count vmcnt by hand:\n" + "\n".join(bad))

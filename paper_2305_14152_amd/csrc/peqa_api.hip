@@ -6,34 +6,17 @@
 #include <limits.h>
 #include <math.h>
 
-#include "peqa_kernels.h"
+#include "peqa_host.h"
+
+using namespace peqa::host;
 
 namespace {
 
-inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
-inline int groups(const peqa_layout *L) { return L->group_size > 0 ? L->k_in / L->group_size : 1; }
-// A single group per channel is the per-channel layer, and takes its kernels.
-inline bool grouped(const peqa_layout *L) { return groups(L) > 1; }
-
-// Contraction index at which the second half of a contraction of length n starts: the contraction
-// kernels give each of their two wave groups one half (n % 128 == 0, so both are whole steps of 64),
-// and the row sums their epilogues use are taken over the same halves.
-inline int split_point(int n) { return n / 2; }
-
-constexpr int PEQA_GEMV_MAX_T = 16;   // forward calls with at most this many tokens take the matrix-vector path
+constexpr int PEQA_GEMV_MAX_T = GEMV_MAX_T;
 
 struct Workspace {
     size_t rs, dys, crow, partial, table, rsz, zpartial, xt, dyt, pc, total;
 };
-
-// matrix-vector path: fp32 partials of the feature slices, for n_total output channels side by side
-size_t gemv_partial_bytes(const peqa_layout *L, size_t n_total, int32_t T)
-{
-    const int chunk = L->group_size > 0 ? L->group_size : L->k_in;
-    const size_t S = (size_t)peqa::gemv_slices((int)n_total, L->k_in, T, chunk);
-    return round256(S * (size_t)T * n_total * sizeof(float));
-}
 
 Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
 {
@@ -65,7 +48,9 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
         return w;
     }
     if (op == PEQA_OP_FWD && T <= PEQA_GEMV_MAX_T) {
-        w.partial = off; off += gemv_partial_bytes(L, L->n_out, T);
+        const GemvItem one{L, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+        w.partial = off; off += round256(gemv_partial_bytes(1, &one, T, false));
+        if (off == 0) off = 256;                               // a single slice needs none; 0 would read as "invalid"
         w.total = off;
         return w;
     }
@@ -93,34 +78,6 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
     }
     w.total = off;
     return w;
-}
-
-peqa_status dev_status(hipError_t e) { return e == hipSuccess ? PEQA_OK : PEQA_ERR_DEVICE; }
-
-// One matrix-vector launch for n <= GEMV_MAX_LAYERS validated layers that share X, K, bits and group size.
-peqa_status gemv_forward(int n, const peqa_fwd_item *items, const float *dz, const uint16_t *X, int32_t T,
-                         float *partial, hipStream_t s)
-{
-    const peqa_layout *L = &items[0].layout;
-    peqa::GemvArgs g{};
-    int tiles = 0;
-    for (int j = 0; j < peqa::GEMV_MAX_LAYERS; ++j) {
-        if (j < n) {
-            tiles += items[j].layout.n_out / 128;
-            // dz (a trained zero-point offset) is only ever passed with a single layer
-            g.layer[j] = peqa::GemvLayer{items[j].packed, items[j].s0, items[j].ds, items[j].z0, dz, items[j].Y,
-                                         items[j].layout.n_out, tiles};
-        } else {
-            g.layer[j] = g.layer[n - 1];                   // never selected: its tile_end is the total
-        }
-    }
-    if ((uint64_t)T * (uint64_t)tiles * 128u >= ((uint64_t)1 << 31)) return PEQA_ERR_SHAPE;   // 32-bit indexing in there
-    g.n_layers = n;
-    g.X = X; g.partial = partial;
-    g.K = L->k_in; g.G = groups(L); g.T = T;
-    g.chunk = L->group_size > 0 ? L->group_size : L->k_in;
-    g.S = peqa::gemv_slices(tiles * 128, L->k_in, T, g.chunk);
-    return dev_status(peqa::launch_gemv(L->bits, g, s));
 }
 
 peqa_status fwd_per_channel(const peqa_layout *L, const uint32_t *packed, const float *s0, const float *ds,
@@ -274,8 +231,8 @@ static peqa_status fwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     uint8_t *ws = static_cast<uint8_t *>(workspace);
     const int N = L->n_out, K = L->k_in, ksplit = split_point(K);
     if (T <= PEQA_GEMV_MAX_T) {
-        peqa_fwd_item item{*L, packed, s0, ds, z0, Y};
-        return gemv_forward(1, &item, dz, X, T, reinterpret_cast<float *>(ws + w.partial), s);
+        const GemvItem item{L, packed, s0, ds, z0, dz, X, Y};
+        return gemv_forward(1, &item, T, false, reinterpret_cast<float *>(ws + w.partial), s);
     }
     if (grouped(L)) {
         float *sb = reinterpret_cast<float *>(ws + w.table);
@@ -422,9 +379,10 @@ size_t peqa_workspace_bytes_fused(int32_t n, const peqa_fwd_item *items, int32_t
 {
     if (check_fused(n, items, T) != PEQA_OK) return 0;
     if (T <= PEQA_GEMV_MAX_T) {
-        size_t n_total = 0;
-        for (int j = 0; j < n; ++j) n_total += (size_t)items[j].layout.n_out;
-        return gemv_partial_bytes(&items[0].layout, n_total, T);
+        GemvItem gi[PEQA_MAX_FUSED];
+        for (int j = 0; j < n; ++j) gi[j] = GemvItem{&items[j].layout, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+        const size_t b = round256(gemv_partial_bytes(n, gi, T, false));
+        return b ? b : 256;
     }
     size_t need = 0;                                       // layer by layer: the largest single need
     for (int j = 0; j < n; ++j) {
@@ -452,8 +410,12 @@ static peqa_status fwd_fused_impl(int32_t n, const peqa_fwd_item *items, const u
     const size_t need = peqa_workspace_bytes_fused(n, items, T);
     if (!workspace || workspace_bytes < need) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
-    if (T <= PEQA_GEMV_MAX_T)
-        return gemv_forward(n, items, nullptr, X, T, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+    if (T <= PEQA_GEMV_MAX_T) {
+        GemvItem gi[PEQA_MAX_FUSED];
+        for (int j = 0; j < n; ++j)
+            gi[j] = GemvItem{&items[j].layout, items[j].packed, items[j].s0, items[j].ds, items[j].z0, nullptr, X, items[j].Y};
+        return gemv_forward(n, gi, T, false, static_cast<float *>(workspace), static_cast<hipStream_t>(stream));
+    }
     // the tiled contraction runs the layers one by one; per-channel layers share the row sums of X
     if (!grouped(&items[0].layout)) {
         hipStream_t s = static_cast<hipStream_t>(stream);
@@ -787,6 +749,69 @@ peqa_status peqa_scale_update_multi(int32_t n, const peqa_update_item *items, co
 // Benchmark tracing: HIP events around every launch while enabled.
 // ---------------------------------------------------------------------------------------
 namespace peqa {
+namespace host {
+
+void gemv_slicing(int n, const GemvItem *items, int32_t T, bool block_plan, int *S)
+{
+    if (block_plan) {
+        int N[GEMV_MAX_LAYERS], K[GEMV_MAX_LAYERS], chunk[GEMV_MAX_LAYERS];
+        for (int j = 0; j < n; ++j) {
+            N[j] = items[j].L->n_out;
+            K[j] = items[j].L->k_in;
+            chunk[j] = items[j].L->group_size > 0 ? items[j].L->group_size : items[j].L->k_in;
+        }
+        gemv_plan(n, N, K, chunk, items[0].L->bits, T, S);
+        return;
+    }
+    const peqa_layout *L = items[0].L;
+    int n_total = 0;
+    for (int j = 0; j < n; ++j) n_total += items[j].L->n_out;
+    const int s = gemv_slices(n_total, L->k_in, T, L->group_size > 0 ? L->group_size : L->k_in);
+    for (int j = 0; j < n; ++j) S[j] = s;
+}
+
+size_t gemv_partial_bytes(int n, const GemvItem *items, int32_t T, bool block_plan)
+{
+    int S[GEMV_MAX_LAYERS];
+    gemv_slicing(n, items, T, block_plan, S);
+    size_t bytes = 0;
+    for (int j = 0; j < n; ++j)
+        if (S[j] > 1) bytes += (size_t)S[j] * (size_t)T * (size_t)items[j].L->n_out * sizeof(float);
+    return bytes;
+}
+
+peqa_status gemv_forward(int n, const GemvItem *items, int32_t T, bool block_plan, float *partial, hipStream_t s)
+{
+    int S[GEMV_MAX_LAYERS];
+    gemv_slicing(n, items, T, block_plan, S);
+    GemvArgs g{};
+    int wgs = 0;
+    size_t poff = 0;                                           // in floats
+    for (int j = 0; j < GEMV_MAX_LAYERS; ++j) {
+        if (j < n) {
+            const peqa_layout *L = items[j].L;
+            if ((uint64_t)T * (uint64_t)L->n_out >= ((uint64_t)1 << 31)) return PEQA_ERR_SHAPE;   // 32-bit indexing in there
+            GemvLayer &l = g.layer[j];
+            l.packed = items[j].packed; l.s0 = items[j].s0; l.ds = items[j].ds; l.z0 = items[j].z0; l.dz = items[j].dz;
+            l.X = items[j].X; l.Y = items[j].Y;
+            l.N = L->n_out; l.K = L->k_in; l.G = groups(L);
+            l.chunk = L->group_size > 0 ? L->group_size : L->k_in;
+            l.S = S[j];
+            l.partial = partial + poff;
+            if (S[j] > 1) poff += (size_t)S[j] * (size_t)T * (size_t)L->n_out;
+            wgs += (L->n_out / 128) * S[j];
+            l.wg_end = wgs;
+        } else {
+            g.layer[j] = g.layer[n - 1];                       // never selected: its wg_end is the total
+        }
+    }
+    g.n_layers = n;
+    g.T = T;
+    return dev_status(launch_gemv(items[0].L->bits, g, s));
+}
+
+}  // namespace host
+
 Options &options()
 {
     static Options o;

@@ -259,6 +259,23 @@ __device__ __forceinline__ void transpose_pad_tile(const uint16_t *__restrict__ 
     }
 }
 
+// A piece of the kernel's argument block read at a run-time (wavefront-uniform) byte offset: scalar loads from the
+// kernarg segment.  Indexing an array inside a by-value kernel argument with a run-time index would make the
+// compiler keep a private copy of the whole argument in scratch memory; this reads the segment itself.
+typedef uint32_t __attribute__((may_alias)) u32_alias;
+template <class T>
+__device__ __forceinline__ T kernarg_load(uint32_t byte_offset)
+{
+    static_assert(sizeof(T) % 4 == 0, "whole dwords");
+    typedef const __attribute__((address_space(4))) u32_alias *cptr;
+    const cptr p = (cptr)((const __attribute__((address_space(4))) char *)__builtin_amdgcn_kernarg_segment_ptr() + byte_offset);
+    T out;
+    u32_alias *o = reinterpret_cast<u32_alias *>(&out);
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) / 4); ++i) o[i] = p[i];
+    return out;
+}
+
 // s_barrier alone: no implied wait on outstanding LDS or memory operations.
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 

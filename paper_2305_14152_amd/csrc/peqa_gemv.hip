@@ -9,9 +9,11 @@
 // and at the end of every scale group   y += s * (acc - (16 + z) * rowsum)   folds offset, zero-point
 // and scale in fp32.  Per-channel layers are one group spanning the whole slice.
 //
-// Grid: (N / 128 channel tiles) x (S feature slices).  The K / 64 rounds of 64 features are dealt
-// evenly to the slices and, inside a slice, to the waves of the workgroup (a wave may start or
-// stop in the middle of a scale group: the fold above is linear in the features, so it is applied
+// Grid: one workgroup per (layer, channel tile of 128, feature slice); up to GEMV_MAX_LAYERS layers of different
+// shapes and inputs share a launch (a decoder block's linears: a single LLaMA-size layer at such T is too short
+// to fill the machine, and a launch costs as much as streaming several megabytes).  The K / 64 rounds of 64
+// features of a tile are dealt evenly to its S slices and, inside a slice, to the waves of the workgroup (a wave
+// may start or stop in the middle of a scale group: the fold above is linear in the features, so it is applied
 // to whatever part of a group the wave has seen); the waves are summed through LDS at the end.
 // S > 1 leaves fp32 partials [S, T, N] in the workspace for gemv_finish_kernel to add up in a fixed
 // order.  Two shapes of workgroup: 4 waves (two or three workgroups per compute unit, S chosen so that
@@ -27,6 +29,8 @@
 // 16-byte block halves sit at 16 * lane of two 1 KB planes per step; at 3 bits the 96 16-byte
 // chunks of a step lie in address order (rows of 96 B).  No barrier is involved: a wave waits for
 // its own DMA only.
+#include <stddef.h>
+
 #include <type_traits>
 
 #include "peqa_device.h"
@@ -70,25 +74,27 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, q = lane >> 4;
-    // which layer this channel tile belongs to (uniform; selects instead of indexing, so that the
-    // argument block stays in scalar registers)
+    // which layer this workgroup belongs to, and that layer's descriptor: scalar loads from the argument block
     const int bx = blockIdx.x;
-    const int li = (bx >= a.layer[0].tile_end) + (bx >= a.layer[1].tile_end) + (bx >= a.layer[2].tile_end);
-    auto pick = [&](auto f) { return li == 0 ? f(a.layer[0]) : li == 1 ? f(a.layer[1]) : li == 2 ? f(a.layer[2]) : f(a.layer[3]); };
-    const uint32_t *l_packed = pick([](const GemvLayer &l) { return l.packed; });
-    const float *l_s0 = pick([](const GemvLayer &l) { return l.s0; });
-    const float *l_ds = pick([](const GemvLayer &l) { return l.ds; });
-    const uint8_t *l_z0 = pick([](const GemvLayer &l) { return l.z0; });
-    const float *l_dz = pick([](const GemvLayer &l) { return l.dz; });
-    uint16_t *l_Y = pick([](const GemvLayer &l) { return l.Y; });
-    const int l_N = pick([](const GemvLayer &l) { return l.N; });
-    const int tile0 = li == 0 ? 0 : li == 1 ? a.layer[0].tile_end : li == 2 ? a.layer[1].tile_end : a.layer[2].tile_end;
-    const int n0 = (bx - tile0) * 128;                           // first channel, within its layer
-    const int K = a.K, G = a.G;
-    const int chunk_rounds = a.chunk >> 6;                        // 64-feature rounds per scale group
+    int li = 0, wg0 = 0;
+#pragma unroll
+    for (int i = 0; i < GEMV_MAX_LAYERS - 1; ++i) {
+        const int e = kernarg_load<int>((uint32_t)(i * sizeof(GemvLayer) + offsetof(GemvLayer, wg_end)));
+        if (bx >= e) { li = i + 1; wg0 = e; }
+    }
+    const GemvLayer L = kernarg_load<GemvLayer>((uint32_t)(li * sizeof(GemvLayer)));
+    const uint32_t *l_packed = L.packed;
+    const float *l_s0 = L.s0, *l_ds = L.ds, *l_dz = L.dz;
+    const uint8_t *l_z0 = L.z0;
+    uint16_t *l_Y = L.Y;
+    const int l_N = L.N, l_S = L.S;
+    const int tile = (int)((uint32_t)(bx - wg0) / (uint32_t)l_S), slice = (bx - wg0) - tile * l_S;
+    const int n0 = tile * 128;                                   // first channel, within its layer
+    const int K = L.K, G = L.G;
+    const int chunk_rounds = L.chunk >> 6;                        // 64-feature rounds per scale group
     // this workgroup's rounds [rbeg, rend); wave w takes the w-th of WAVES equal parts of them
     const uint32_t R = (uint32_t)K >> 6;
-    const int rbeg = (int)(blockIdx.y * R / (uint32_t)a.S), rend = (int)((blockIdx.y + 1) * R / (uint32_t)a.S);
+    const int rbeg = (int)((uint32_t)slice * R / (uint32_t)l_S), rend = (int)((uint32_t)(slice + 1) * R / (uint32_t)l_S);
     const int wr0 = rbeg + (int)((uint32_t)(wave * (rend - rbeg)) / (uint32_t)WAVES);
     const int nrounds = rbeg + (int)((uint32_t)((wave + 1) * (rend - rbeg)) / (uint32_t)WAVES) - wr0;
     const int k0 = wr0 << 6;                                      // first feature of this wave
@@ -99,8 +105,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
     // the wave's tiles (128 channels x 32 features, TILE bytes each) are contiguous along the features
     constexpr uint32_t TILE = 64 * WPB * 4;
     const uint8_t *bbase = reinterpret_cast<const uint8_t *>(l_packed) +
-                           ((size_t)(bx - tile0) * (K >> 5) + (k0 >> 5)) * TILE;
-    const uint8_t *xbase = reinterpret_cast<const uint8_t *>(a.X + k0);
+                           ((size_t)tile * (K >> 5) + (k0 >> 5)) * TILE;
+    const uint8_t *xbase = reinterpret_cast<const uint8_t *>(L.X + k0);
     const uint32_t lds_stage = (uint32_t)(uintptr_t)stage + wave * 2 * GV_ROUND_BYTES;
     uint32_t b_voff[NDMA_B], x_voff[2];
     if constexpr (BITS == 4) {
@@ -255,31 +261,25 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
         for (int w = 0; w < WAVES; ++w) v += red[((w * 8 + ct) * 4 + j) * 64 + ln];
         const int t = 4 * (ln >> 4) + j, n = n0 + 8 * (ln & 15) + ct;
         if (t < a.T) {
-            if (a.S == 1) l_Y[(size_t)t * l_N + n] = (uint16_t)float_to_bf16_bits(v);
-            else a.partial[((size_t)blockIdx.y * a.T + t) * (gridDim.x * 128) + bx * 128 + 8 * (ln & 15) + ct] = v;
+            if (l_S == 1) l_Y[(size_t)t * l_N + n] = (uint16_t)float_to_bf16_bits(v);
+            else L.partial[((size_t)slice * a.T + t) * l_N + n] = v;
         }
     }
 }
 
-// Y[t,n] = bf16( partial[0][t,n] + partial[1][t,n] + ... ), fixed order; column n of the side-by-side
-// layers goes to its own layer's Y.
+// Y[t,n] = bf16( partial[0][t,n] + partial[1][t,n] + ... ), fixed order, for every sliced layer of the launch
+// (blockIdx.y = layer; layers with a single slice wrote their Y themselves).
 __global__ __launch_bounds__(256) void gemv_finish_kernel(GemvArgs a)
 {
+    const GemvLayer L = kernarg_load<GemvLayer>((uint32_t)(blockIdx.y * sizeof(GemvLayer)));
+    if (L.S == 1) return;
     // T <= 16 and at most 2^24 channels: everything fits 32-bit arithmetic
-    const uint32_t ntot = (uint32_t)a.layer[a.n_layers - 1].tile_end * 128u;
-    const uint32_t tn = (uint32_t)a.T * ntot;
+    const uint32_t tn = (uint32_t)a.T * (uint32_t)L.N;
     const uint32_t e = blockIdx.x * 256u + threadIdx.x;
     if (e >= tn) return;
-    const int t = (int)(e / ntot), n = (int)(e - (uint32_t)t * ntot);
     float v = 0.f;
-    for (int sl = 0; sl < a.S; ++sl) v += a.partial[(size_t)sl * tn + e];
-    const int tile = n >> 7;
-    const int li = (tile >= a.layer[0].tile_end) + (tile >= a.layer[1].tile_end) + (tile >= a.layer[2].tile_end);
-    auto pick = [&](auto f) { return li == 0 ? f(a.layer[0]) : li == 1 ? f(a.layer[1]) : li == 2 ? f(a.layer[2]) : f(a.layer[3]); };
-    uint16_t *y = pick([](const GemvLayer &l) { return l.Y; });
-    const int ln = pick([](const GemvLayer &l) { return l.N; });
-    const int tile0 = li == 0 ? 0 : li == 1 ? a.layer[0].tile_end : li == 2 ? a.layer[1].tile_end : a.layer[2].tile_end;
-    y[(size_t)t * ln + (n - tile0 * 128)] = (uint16_t)float_to_bf16_bits(v);
+    for (int sl = 0; sl < L.S; ++sl) v += L.partial[(size_t)sl * tn + e];
+    L.Y[e] = (uint16_t)float_to_bf16_bits(v);
 }
 
 }  // namespace
@@ -306,12 +306,49 @@ int gemv_slices(int Ntot, int K, int T, int chunk)
     return S;
 }
 
+bool gemv_whole(int tiles, bool per_channel, int S)
+{
+    return per_channel && S == 1 && tiles >= GV_WHOLE_MIN_TILES && tiles <= GV_WHOLE_MAX_TILES;
+}
+
+void gemv_plan(int n, const int *N, const int *K, const int *chunk, int bits, int T, int *S)
+{
+    // target: all workgroups resident at once (two per compute unit) with equal shares of the packed bytes
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    double total = 0.0;
+    for (int j = 0; j < n; ++j) total += (double)N[j] * K[j] * bits / 8.0;
+    const double target = total / (2.0 * cus);
+    const int by_bytes = T > 4 ? 6 : 16;                         // partials stay small next to the weight bytes
+    for (int j = 0; j < n; ++j) {
+        const int R = K[j] / 64, chunk_rounds = chunk[j] / 64;
+        const double tile_bytes = 128.0 * K[j] * bits / 8.0;
+        int s = (int)(tile_bytes / target + 0.5);
+        if (s > R / (2 * GV_WAVES)) s = R / (2 * GV_WAVES);      // every wave at least two rounds
+        if (s > by_bytes) s = by_bytes;
+        if (s < 1) s = 1;
+        // the scale tile in LDS holds at most GV_MAX_PER groups per slice
+        if (chunk[j] != K[j])
+            while (((R + s - 1) / s + chunk_rounds - 1) / chunk_rounds + 1 > GV_MAX_PER) ++s;
+        S[j] = s;
+    }
+}
+
 hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
 {
-    const int tiles = a.layer[a.n_layers - 1].tile_end;
-    const dim3 grid(tiles, a.S);
+    const int wgs = a.layer[a.n_layers - 1].wg_end;
+    bool per_channel_all = true, sliced = false;
+    unsigned max_tn = 0;
+    for (int j = 0; j < a.n_layers; ++j) {
+        per_channel_all = per_channel_all && a.layer[j].chunk == a.layer[j].K;
+        sliced = sliced || a.layer[j].S > 1;
+        if (a.layer[j].S > 1 && (unsigned)a.T * (unsigned)a.layer[j].N > max_tn) max_tn = (unsigned)a.T * (unsigned)a.layer[j].N;
+    }
+    const dim3 grid(wgs);
     constexpr int SLICED_LDS = GV_WAVES * 2 * GV_ROUND_BYTES, WHOLE_LDS = GV_WAVES_WHOLE * 2 * GV_ROUND_BYTES;
-    const bool whole = a.chunk == a.K && a.S == 1 && tiles >= GV_WHOLE_MIN_TILES && tiles <= GV_WHOLE_MAX_TILES;
+    // the 12-wave form: layers of equal K in one launch (one layer, or layers that read one X), a single slice each
+    bool whole = !sliced && gemv_whole(wgs, per_channel_all, 1);
+    for (int j = 1; j < a.n_layers; ++j) whole = whole && a.layer[j].K == a.layer[0].K;
     if (whole) {
         // 144 KB of dynamic LDS: allowed once per device and instantiation
         static bool allowed[2][64];
@@ -331,7 +368,7 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
     // Per-channel layers fit three workgroups per compute unit (1 KB scale tile).  That pays only when
     // there are more workgroups than two per unit: below, the dispatcher would stack three on some
     // units and leave others with one, so such launches take the 16 KB instantiation (two per unit).
-    const bool per_channel = a.chunk == a.K && tiles * a.S > 512;
+    const bool per_channel = per_channel_all && wgs > 512;
     if (whole) {
         if (bits == 4) hipLaunchKernelGGL((gemv_kernel<4, 1, GV_WAVES_WHOLE>), grid, dim3(GV_WAVES_WHOLE * 64), WHOLE_LDS, stream, a);
         else hipLaunchKernelGGL((gemv_kernel<3, 1, GV_WAVES_WHOLE>), grid, dim3(GV_WAVES_WHOLE * 64), WHOLE_LDS, stream, a);
@@ -344,10 +381,9 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
     }
     trace_after(KID_GEMV, stream);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.S == 1) return e;
+    if (e != hipSuccess || !sliced) return e;
     trace_before(KID_GEMV_FINISH, stream);
-    const size_t tn = (size_t)a.T * tiles * 128;
-    hipLaunchKernelGGL(gemv_finish_kernel, dim3((unsigned)((tn + 255) / 256)), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(gemv_finish_kernel, dim3((max_tn + 255) / 256, a.n_layers), dim3(256), 0, stream, a);
     trace_after(KID_GEMV_FINISH, stream);
     return hipGetLastError();
 }

@@ -76,28 +76,34 @@ hipError_t launch_transpose_pad(const uint16_t *src, int T, int C, int Tp, uint1
 hipError_t launch_dw(int bits, const DwArgs &a, hipStream_t stream);
 hipError_t launch_chunk_reduce(const float *pc, size_t n, int per, float *d_ds, hipStream_t stream);
 
-// Arguments of the T <= 16 forward (peqa_gemv.hip): up to GEMV_MAX_LAYERS layers that share X
-// (same K, bit width and group size), laid side by side along the output channels.
-constexpr int GEMV_MAX_LAYERS = 4;
+// Arguments of the T <= 16 forward (peqa_gemv.hip): up to GEMV_MAX_LAYERS layers in one launch, laid side by
+// side along the workgroup index.  Every layer has its own shape, input and slicing, so that the linears of a
+// whole decoder block (different K, different X) can share one launch; the bit width is the launch's.
+constexpr int GEMV_MAX_LAYERS = 8;
 struct GemvLayer {
     const uint32_t *packed;
     const float *s0, *ds;     // [N, G]; ds may be NULL
     const uint8_t *z0;        // [N, G]
     const float *dz;          // [N, G] or NULL: trained zero-point offset
+    const uint16_t *X;        // [T, K] bf16
     uint16_t *Y;              // [T, N] bf16
-    int N;
-    int tile_end;             // channel tiles (of 128) of this layer and all before it
+    float *partial;           // [S, T, N] fp32 slice partials of this layer (S > 1)
+    int N, K, G;
+    int chunk;                // features per scale group (K for per-channel layers)
+    int S;                    // feature slices: a channel tile is S workgroups
+    int wg_end;               // workgroups of this layer and all before it (unused entries: the total)
 };
 struct GemvArgs {
-    GemvLayer layer[GEMV_MAX_LAYERS];
+    GemvLayer layer[GEMV_MAX_LAYERS];   // must stay the first member: the kernels index it in the argument block
     int n_layers;
-    const uint16_t *X;        // [T, K] bf16
-    float *partial;           // [S, T, Ntot] fp32 (S > 1), Ntot = 128 * layer[n_layers - 1].tile_end
-    int K, G, T;
-    int S;                    // feature slices (gemv_slices)
-    int chunk;                // features per scale group (K for per-channel layers)
+    int T;
 };
 int gemv_slices(int Ntot, int K, int T, int chunk);
+// Slices per layer for a launch of several layers of different shapes: every workgroup gets about the same
+// number of packed bytes, and all of them are resident at once.  Fills S[0..n).
+void gemv_plan(int n, const int *N, const int *K, const int *chunk, int bits, int T, int *S);
+// whether a per-channel launch of that many channel tiles with a single slice takes the 12-wave workgroups
+bool gemv_whole(int tiles, bool per_channel, int S);
 hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 
 // peqa_small.hip

@@ -20,7 +20,8 @@ EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_wo
            "peqa_linear_fwd_z", "peqa_linear_bwd_z", "peqa_quantize_search",
            "peqa_scale_update_multi", "peqa_device_info",
            "peqa_row_sums", "peqa_linear_fwd_fused_rs", "peqa_linear_bwd_rs",
-           "peqa_set_option", "peqa_get_option", "peqa_linear_fwd_static"]
+           "peqa_set_option", "peqa_get_option", "peqa_linear_fwd_static",
+           "peqa_block_workspace_bytes", "peqa_block_fwd", "peqa_block_bwd"]
 
 
 class Layout(ctypes.Structure):
@@ -104,6 +105,12 @@ def lib():
         L.peqa_set_option.restype = i32
         L.peqa_get_option.argtypes = [i32]
         L.peqa_get_option.restype = i32
+        L.peqa_block_workspace_bytes.argtypes = [i32, vp, i32, i32]
+        L.peqa_block_workspace_bytes.restype = sz
+        L.peqa_block_fwd.argtypes = [i32, vp, i32, vp, sz, vp]
+        L.peqa_block_fwd.restype = i32
+        L.peqa_block_bwd.argtypes = [i32, vp, i32, vp, sz, vp]
+        L.peqa_block_bwd.restype = i32
         L.peqa_trace_begin.argtypes = [i32]
         L.peqa_trace_begin.restype = i32
         L.peqa_trace_end.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32),
@@ -290,6 +297,36 @@ def scale_update(n_scales, ds, d_ds, m, v, s0, lr, beta1=0.9, beta2=0.999, eps=1
     opt = AdamW(lr, beta1, beta2, eps, weight_decay, int(step))
     _check(lib().peqa_scale_update(int(n_scales), _ptr(ds), _ptr(d_ds), _ptr(m), _ptr(v), _ptr(s0),
                                    ctypes.byref(opt), _stream(stream)), "peqa_scale_update")
+
+
+class BlockItem(ctypes.Structure):
+    _fields_ = [("layout", Layout), ("packed", ctypes.c_void_p), ("s0", ctypes.c_void_p), ("ds", ctypes.c_void_p),
+                ("z0", ctypes.c_void_p), ("X", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("dY", ctypes.c_void_p),
+                ("dX", ctypes.c_void_p), ("d_ds", ctypes.c_void_p), ("row_sums", ctypes.c_void_p)]
+
+
+def block_items(layers):
+    """layers: sequence of dicts with keys L, packed, s0, z0 and optionally ds, X, Y, dY, dX, d_ds, row_sums."""
+    arr = (BlockItem * len(layers))()
+    for i, d in enumerate(layers):
+        arr[i] = BlockItem(d["L"], _ptr(d["packed"]), _ptr(d["s0"]), _ptr(d.get("ds")), _ptr(d["z0"]), _ptr(d.get("X")),
+                           _ptr(d.get("Y")), _ptr(d.get("dY")), _ptr(d.get("dX")), _ptr(d.get("d_ds")),
+                           _ptr(d.get("row_sums")))
+    return arr
+
+
+def block_workspace_bytes(items, T, op):
+    return int(lib().peqa_block_workspace_bytes(len(items), ctypes.addressof(items), int(T), int(op)))
+
+
+def block_fwd(items, T, workspace, workspace_bytes_, stream=None):
+    _check(lib().peqa_block_fwd(len(items), ctypes.addressof(items), int(T), _ptr(workspace), int(workspace_bytes_),
+                                _stream(stream)), "peqa_block_fwd")
+
+
+def block_bwd(items, T, workspace, workspace_bytes_, stream=None):
+    _check(lib().peqa_block_bwd(len(items), ctypes.addressof(items), int(T), _ptr(workspace), int(workspace_bytes_),
+                                _stream(stream)), "peqa_block_bwd")
 
 
 def set_option(option, value):

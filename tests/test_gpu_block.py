@@ -1,0 +1,147 @@
+"""GPU parity of the block-level calls (peqa_block_fwd / peqa_block_bwd): several layers of different shapes and
+inputs behind one call, every member against the oracle and against the single-layer calls."""
+import numpy as np
+import pytest
+
+from paper_2305_14152_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+Y_TOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2305_14152_amd import peqa
+    peqa.lib()
+    import gpu_util
+    return gpu_util
+
+
+class Member:
+    """One layer of a block with its own input, on both sides."""
+
+    def __init__(self, gpu, oracle, seed, bits, N, K, group, T, X=None, with_ds=True):
+        self.N, self.K, self.group = N, K, group
+        W = synth.normal_f32(seed, (N, K), 0.02)
+        self.layer = gpu.GpuLayer(W, bits, group)
+        self.codes, self.s0, self.z0 = oracle.quantize(W, bits, group)
+        self.ds = synth.normal_f32(seed + 1, self.s0.shape, 1e-3) if with_ds else None
+        self.dsd = gpu.to_dev(self.ds) if with_ds else None
+        self.X = X if X is not None else synth.normal_bf16(seed + 2, (T, K), 1.0)
+        self.dY = synth.normal_bf16(seed + 3, (T, N), 1.0)
+
+
+def _run_block(gpu, members, T, backward, share_row_sums=False):
+    import torch
+    from paper_2305_14152_amd import peqa
+    xdev = {}
+    dicts = []
+    for m in members:
+        if id(m.X) not in xdev:
+            xdev[id(m.X)] = (gpu.to_dev(m.X), torch.zeros((T, 2), dtype=torch.float32, device="cuda"))
+        Xd, rs = xdev[id(m.X)]
+        d = dict(L=m.layer.L, packed=m.layer.packed, s0=m.layer.s0, z0=m.layer.z0, ds=m.dsd, X=Xd,
+                 Y=torch.zeros((T, m.N), dtype=torch.int16, device="cuda"), dY=gpu.to_dev(m.dY),
+                 dX=torch.zeros((T, m.K), dtype=torch.int16, device="cuda"),
+                 d_ds=torch.zeros(m.s0.shape, dtype=torch.float32, device="cuda"),
+                 row_sums=rs if share_row_sums else None)
+        dicts.append(d)
+    items = peqa.block_items(dicts)
+    nb = peqa.block_workspace_bytes(items, T, peqa.PEQA_OP_FWD)
+    assert nb > 0
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    peqa.block_fwd(items, T, ws, nb)
+    if backward:
+        nbb = peqa.block_workspace_bytes(items, T, peqa.PEQA_OP_BWD)
+        assert nbb > 0
+        wsb = torch.empty(nbb, dtype=torch.uint8, device="cuda")
+        peqa.block_bwd(items, T, wsb, nbb)
+    torch.cuda.synchronize()
+    return dicts
+
+
+BLOCKS = [
+    # (bits, group, [(N, K, input index)]): members with equal input index read one X
+    (4, 0, [(256, 512, 0), (384, 512, 0), (128, 512, 1), (512, 1152, 2)]),
+    (3, 128, [(256, 512, 0), (256, 512, 0), (256, 512, 1), (384, 512, 2), (512, 1408, 3)]),
+    (3, 0, [(1280, 640, 0), (640, 1280, 1)]),
+    (4, 64, [(128, 256, 0), (256, 768, 1), (128, 128, 2)]),
+    (4, 0, [(128, 128, 0)] * 8),
+]
+
+
+@pytest.mark.parametrize("bits,group,shapes", BLOCKS)
+@pytest.mark.parametrize("T", [1, 7, 16, 40, 200])
+def test_block_forward_parity(gpu, oracle, bits, group, shapes, T):
+    print("block forward bits=%d g=%d T=%d shapes=%s" % (bits, group, T, shapes), flush=True)
+    seed = 31000 + 100 * bits + group + T
+    inputs = {}
+    members = []
+    for j, (N, K, xi) in enumerate(shapes):
+        if xi not in inputs:
+            inputs[xi] = synth.normal_bf16(seed + 7 * xi, (T, K), 1.0)
+        members.append(Member(gpu, oracle, seed + 50 * j, bits, N, K, group, T, X=inputs[xi], with_ds=(j % 2 == 0)))
+    dicts = _run_block(gpu, members, T, backward=False, share_row_sums=(T % 2 == 0))
+    for m, d in zip(members, dicts):
+        Yref = oracle.fwd(m.codes, m.s0, m.ds, m.z0, m.X, group)
+        Y = gpu.bf16_dev_to_f64(d["Y"])
+        assert np.abs(Y - Yref).max() <= Y_TOL * np.abs(Yref).max(), (m.N, m.K)
+        single = gpu.bf16_dev_to_f64(m.layer.fwd(d["X"], m.dsd))
+        # the same products, possibly added in another order (other slicing or kernel form): a last bf16 bit
+        assert np.abs(Y - single).max() <= 2.0 ** -7 * np.abs(Yref).max()
+
+
+@pytest.mark.parametrize("bits,group,shapes", BLOCKS[:4])
+@pytest.mark.parametrize("T", [40, 200, 300])
+def test_block_backward_parity(gpu, oracle, bits, group, shapes, T):
+    print("block backward bits=%d g=%d T=%d shapes=%s" % (bits, group, T, shapes), flush=True)
+    seed = 33000 + 100 * bits + group + T
+    inputs = {}
+    members = []
+    for j, (N, K, xi) in enumerate(shapes):
+        if xi not in inputs:
+            inputs[xi] = synth.normal_bf16(seed + 7 * xi, (T, K), 1.0)
+        members.append(Member(gpu, oracle, seed + 50 * j, bits, N, K, group, T, X=inputs[xi], with_ds=(j % 2 == 1)))
+    for share in (False, True):
+        dicts = _run_block(gpu, members, T, backward=True, share_row_sums=share)
+        for m, d in zip(members, dicts):
+            dXref, gref, _ = oracle.bwd(m.codes, m.s0, m.ds, m.z0, m.X, m.dY, group)
+            dX = gpu.bf16_dev_to_f64(d["dX"])
+            assert np.abs(dX - dXref).max() <= Y_TOL * np.abs(dXref).max(), (m.N, m.K)
+            gpu.assert_scale_grad_close(gpu.to_host(d["d_ds"]), gref)
+
+
+def test_block_skips_and_errors(gpu, oracle):
+    """NULL dX / d_ds per item are skipped; mixed bit widths and missing workspace are refused."""
+    import ctypes
+    import torch
+    from paper_2305_14152_amd import peqa
+    T = 150
+    a = Member(gpu, oracle, 35000, 4, 256, 512, 0, T)
+    b = Member(gpu, oracle, 35100, 4, 384, 256, 0, T)
+    dicts = []
+    for m, (want_dx, want_g) in zip((a, b), ((True, False), (False, True))):
+        dicts.append(dict(L=m.layer.L, packed=m.layer.packed, s0=m.layer.s0, z0=m.layer.z0, ds=None, X=gpu.to_dev(m.X),
+                          dY=gpu.to_dev(m.dY), Y=None,
+                          dX=torch.full((T, m.K), 7, dtype=torch.int16, device="cuda") if want_dx else None,
+                          d_ds=torch.full(m.s0.shape, 7.0, dtype=torch.float32, device="cuda") if want_g else None))
+    items = peqa.block_items(dicts)
+    nb = peqa.block_workspace_bytes(items, T, peqa.PEQA_OP_BWD)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    peqa.block_bwd(items, T, ws, nb)
+    torch.cuda.synchronize()
+    dXref, _, _ = oracle.bwd(a.codes, a.s0, None, a.z0, a.X, a.dY, 0, want_P=False)
+    assert np.abs(gpu.bf16_dev_to_f64(dicts[0]["dX"]) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+    _, gref, _ = oracle.bwd(b.codes, b.s0, None, b.z0, b.X, b.dY, 0, want_dX=False)
+    gpu.assert_scale_grad_close(gpu.to_host(dicts[1]["d_ds"]), gref)
+    lib = peqa.lib()
+    assert lib.peqa_block_bwd(2, ctypes.addressof(items), T, None, 0, None) == peqa.PEQA_ERR_WORKSPACE
+    c = Member(gpu, oracle, 35200, 3, 128, 128, 0, T)
+    mixed = peqa.block_items([dicts[0], dict(L=c.layer.L, packed=c.layer.packed, s0=c.layer.s0, z0=c.layer.z0,
+                                             X=gpu.to_dev(c.X), dY=gpu.to_dev(c.dY))])
+    assert peqa.block_workspace_bytes(mixed, T, peqa.PEQA_OP_BWD) == 0
+    assert lib.peqa_block_bwd(2, ctypes.addressof(mixed), T, ws.data_ptr(), nb, None) == peqa.PEQA_ERR_PARAM
+    assert lib.peqa_block_fwd(9, ctypes.addressof(items), T, ws.data_ptr(), nb, None) == peqa.PEQA_ERR_PARAM

@@ -20,7 +20,7 @@ struct Workspace {
 
 Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
 {
-    if (op == PEQA_OP_FWD_Z) return carve(L, T, PEQA_OP_FWD);
+    if (op == PEQA_OP_FWD_Z && T > PEQA_GEMV_MAX_T) return carve(L, T, PEQA_OP_FWD);
     if (op == PEQA_OP_BWD_Z) {
         // the plain backward's needs, then the group sums of X and the partials of the zero-point gradient
         Workspace w = carve(L, T, PEQA_OP_BWD);
@@ -47,9 +47,10 @@ Workspace carve(const peqa_layout *L, int32_t T, int32_t op)
         w.total = off;
         return w;
     }
-    if (op == PEQA_OP_FWD && T <= PEQA_GEMV_MAX_T) {
+    if ((op == PEQA_OP_FWD || op == PEQA_OP_FWD_Z) && T <= PEQA_GEMV_MAX_T) {
+        // with a trained zero-point offset a slice of a group-wise layer spans fewer groups: more slices
         const GemvItem one{L, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-        w.partial = off; off += round256(gemv_partial_bytes(1, &one, T, false));
+        w.partial = off; off += round256(gemv_partial_bytes(1, &one, T, false, op == PEQA_OP_FWD));
         if (off == 0) off = 256;                               // a single slice needs none; 0 would read as "invalid"
         w.total = off;
         return w;
@@ -223,7 +224,7 @@ static peqa_status fwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     if (!aligned16(packed) || !aligned16(s0) || !aligned16(z0) || !aligned16(X) || !aligned16(Y) ||
         (ds && !aligned16(ds)) || (dz && !aligned16(dz)))
         return PEQA_ERR_ALIGN;
-    const Workspace w = carve(L, T, PEQA_OP_FWD);
+    const Workspace w = carve(L, T, dz ? PEQA_OP_FWD_Z : PEQA_OP_FWD);
     if (!workspace || workspace_bytes < w.total) return PEQA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PEQA_ERR_ALIGN;
 
@@ -381,7 +382,7 @@ size_t peqa_workspace_bytes_fused(int32_t n, const peqa_fwd_item *items, int32_t
     if (T <= PEQA_GEMV_MAX_T) {
         GemvItem gi[PEQA_MAX_FUSED];
         for (int j = 0; j < n; ++j) gi[j] = GemvItem{&items[j].layout, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-        const size_t b = round256(gemv_partial_bytes(n, gi, T, false));
+        const size_t b = round256(gemv_partial_bytes(n, gi, T, false, true));
         return b ? b : 256;
     }
     size_t need = 0;                                       // layer by layer: the largest single need
@@ -751,7 +752,7 @@ peqa_status peqa_scale_update_multi(int32_t n, const peqa_update_item *items, co
 namespace peqa {
 namespace host {
 
-void gemv_slicing(int n, const GemvItem *items, int32_t T, bool block_plan, int *S)
+void gemv_slicing(int n, const GemvItem *items, int32_t T, bool block_plan, bool zbyte, int *S)
 {
     if (block_plan) {
         int N[GEMV_MAX_LAYERS], K[GEMV_MAX_LAYERS], chunk[GEMV_MAX_LAYERS];
@@ -760,20 +761,20 @@ void gemv_slicing(int n, const GemvItem *items, int32_t T, bool block_plan, int 
             K[j] = items[j].L->k_in;
             chunk[j] = items[j].L->group_size > 0 ? items[j].L->group_size : items[j].L->k_in;
         }
-        gemv_plan(n, N, K, chunk, items[0].L->bits, T, S);
+        gemv_plan(n, N, K, chunk, items[0].L->bits, T, zbyte, S);
         return;
     }
     const peqa_layout *L = items[0].L;
     int n_total = 0;
     for (int j = 0; j < n; ++j) n_total += items[j].L->n_out;
-    const int s = gemv_slices(n_total, L->k_in, T, L->group_size > 0 ? L->group_size : L->k_in);
+    const int s = gemv_slices(n_total, L->k_in, T, L->group_size > 0 ? L->group_size : L->k_in, zbyte);
     for (int j = 0; j < n; ++j) S[j] = s;
 }
 
-size_t gemv_partial_bytes(int n, const GemvItem *items, int32_t T, bool block_plan)
+size_t gemv_partial_bytes(int n, const GemvItem *items, int32_t T, bool block_plan, bool zbyte)
 {
     int S[GEMV_MAX_LAYERS];
-    gemv_slicing(n, items, T, block_plan, S);
+    gemv_slicing(n, items, T, block_plan, zbyte, S);
     size_t bytes = 0;
     for (int j = 0; j < n; ++j)
         if (S[j] > 1) bytes += (size_t)S[j] * (size_t)T * (size_t)items[j].L->n_out * sizeof(float);
@@ -783,7 +784,9 @@ size_t gemv_partial_bytes(int n, const GemvItem *items, int32_t T, bool block_pl
 peqa_status gemv_forward(int n, const GemvItem *items, int32_t T, bool block_plan, float *partial, hipStream_t s)
 {
     int S[GEMV_MAX_LAYERS];
-    gemv_slicing(n, items, T, block_plan, S);
+    bool zbyte = true;                                         // the kernel takes the same decision from the same pointers
+    for (int j = 0; j < n; ++j) zbyte = zbyte && items[j].dz == nullptr;
+    gemv_slicing(n, items, T, block_plan, zbyte, S);
     GemvArgs g{};
     int wgs = 0;
     size_t poff = 0;                                           // in floats

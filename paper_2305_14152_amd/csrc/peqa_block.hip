@@ -72,7 +72,7 @@ size_t peqa_block_workspace_bytes(int32_t n, const peqa_block_item *items, int32
     if (op == PEQA_OP_FWD && T <= GEMV_MAX_T) {
         GemvItem gi[PEQA_MAX_BLOCK];
         for (int j = 0; j < n; ++j) gi[j] = GemvItem{&items[j].layout, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
-        const size_t b = round256(gemv_partial_bytes(n, gi, T, true));
+        const size_t b = round256(gemv_partial_bytes(n, gi, T, true, true));
         return b ? b : 256;
     }
     return carve_block(n, items, T, op).total;

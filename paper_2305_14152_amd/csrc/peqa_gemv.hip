@@ -43,11 +43,13 @@ namespace {
 constexpr int GV_WAVES = 4;          // waves of the sliced workgroup
 constexpr int GV_WAVES_WHOLE = 12;   // waves of the workgroup that takes all of K
 constexpr int GV_WHOLE_MIN_TILES = 128, GV_WHOLE_MAX_TILES = 256;
-constexpr int GV_MAX_PER = 16;       // most scale groups a slice may touch (bounds the scale tile in LDS)
-constexpr int GV_B_BYTES = 4096;     // packed blocks of one round of one wave (4 KB at 4 bits, 3 KB at 3 bits)
-constexpr int GV_ROUND_BYTES = GV_B_BYTES + 2048;   // + 16 token rows x 128 B
+constexpr int GV_MAX_PER = 16;       // most scale groups a slice may touch (bounds the scale tile in LDS): trained zero-points
+constexpr int GV_MAX_PER_Z8 = 48;    // the same with integer zero-points, kept as bytes (5 instead of 8 bytes per entry)
+// One round of one wave in LDS: its packed blocks (4 KB at 4 bits, 3 KB at 3 bits), then NX KB of token rows
+// (8 rows x 128 B per KB: one DMA when T <= 8, two otherwise).
+constexpr int gv_b_bytes(int bits) { return bits == 4 ? 4096 : 3072; }
+constexpr int gv_round_bytes(int bits, int nx) { return gv_b_bytes(bits) + nx * 1024; }
 
-struct ScaleZero { float s, zoff; };  // s0 + ds and 16 + z0 + dz
 
 __device__ __forceinline__ void gv_dma16(uint32_t voff, const void *sbase, uint32_t lds_dst)
 {
@@ -60,17 +62,24 @@ __device__ __forceinline__ void gv_wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
-// GROUPS_MAX: most scale groups a workgroup may touch: 1 for per-channel layers (1 KB scale tile, three
-// workgroups per compute unit), GV_MAX_PER for group-wise ones (16 KB, two workgroups).
-template <int BITS, int GROUPS_MAX, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 2)) void gemv_kernel(GemvArgs a)
+// GROUPS_MAX: most scale groups a workgroup may touch: 1 for per-channel layers (1 KB scale tile),
+// GV_MAX_PER for group-wise ones (16 KB).  NBUF: rounds a wave keeps in flight (its private ring in LDS).
+// NX: KB of token rows per round (1: T <= 8, 2: T <= 16).
+// ZBYTE: zero-points are the stored integers (no trained offset dz): they stay bytes in LDS, which lets a
+// workgroup hold the scales of GV_MAX_PER_Z8 groups -- a whole row of LLaMA-13B's 40 -- and take all of K.
+template <int BITS, int GROUPS_MAX, int WAVES, int NBUF, int NX, bool ZBYTE>
+__global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : 2) void gemv_kernel(GemvArgs a)
 {
-    // [wave][2 rounds][6 KB]; reused as [wave][column tile][row][lane] fp32 (8 KB per wave) for the final sum
+    // [wave][NBUF rounds][round]; reused as [wave][column tile][row][lane] fp32 (8 KB per wave) for the final sum
     extern __shared__ __align__(16) uint8_t stage[];
-    __shared__ __align__(16) ScaleZero sz[GROUPS_MAX][128];      // [group of the slice][channel]
+    // scale s0 + ds and zero-point (16 + z0 + dz as fp32, or z0 as stored) of [group of the slice][channel]
+    __shared__ __align__(16) float sS[GROUPS_MAX][128];
+    __shared__ __align__(16) typename std::conditional<ZBYTE, uint8_t, float>::type sZ[GROUPS_MAX][128];
     constexpr int WPB = 2 * BITS;
+    constexpr int GV_B_BYTES = gv_b_bytes(BITS), GV_ROUND_BYTES = gv_round_bytes(BITS, NX);
+    static_assert(NBUF * GV_ROUND_BYTES >= 8192, "the final sum reuses a wave's ring");
     constexpr int NDMA_B = 2 * 64 * WPB * 4 / 1024;               // 1 KB DMAs for the blocks of a round: 4 / 3
-    constexpr int NDMA = NDMA_B + 2;                              // + 2 for the token rows
+    constexpr int NDMA = NDMA_B + NX;                             // + the token rows
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, q = lane >> 4;
@@ -107,8 +116,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
     const uint8_t *bbase = reinterpret_cast<const uint8_t *>(l_packed) +
                            ((size_t)tile * (K >> 5) + (k0 >> 5)) * TILE;
     const uint8_t *xbase = reinterpret_cast<const uint8_t *>(L.X + k0);
-    const uint32_t lds_stage = (uint32_t)(uintptr_t)stage + wave * 2 * GV_ROUND_BYTES;
-    uint32_t b_voff[NDMA_B], x_voff[2];
+    const uint32_t lds_stage = (uint32_t)(uintptr_t)stage + wave * NBUF * GV_ROUND_BYTES;
+    uint32_t b_voff[NDMA_B], x_voff[NX];
     if constexpr (BITS == 4) {
         // DMA (step s, half h): lane (c, q) fetches half h of its own block (c * 4 + q of tile s)
 #pragma unroll
@@ -120,22 +129,27 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
         for (int i = 0; i < NDMA_B; ++i) b_voff[i] = (uint32_t)(64 * i + lane) * 16u;
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NX; ++i) {
         const int x = 64 * i + lane;                              // chunk x: token row x / 8, 16 bytes x % 8
         const int t = (x >> 3) < a.T ? (x >> 3) : a.T - 1;        // rows beyond T repeat the last one (never stored)
         x_voff[i] = (uint32_t)t * (uint32_t)K * 2u + (uint32_t)(x & 7) * 16u;
     }
-    auto issue_round = [&](int r) {
-        const uint32_t dst = lds_stage + (r & 1) * GV_ROUND_BYTES;
-        const uint8_t *bsrc = bbase + (size_t)r * 2 * TILE;       // two tiles per round
+    // round r lives in ring slot r % NBUF; `slot` is the slot of the next round to be issued
+    int next_round = 0, slot = 0;
+    auto issue_round = [&]() {
+        const uint32_t dst = lds_stage + slot * GV_ROUND_BYTES;
+        const uint8_t *bsrc = bbase + (size_t)next_round * 2 * TILE;   // two tiles per round
 #pragma unroll
         for (int i = 0; i < NDMA_B; ++i) gv_dma16(b_voff[i], bsrc, dst + i * 1024);
-        const uint8_t *xsrc = xbase + (size_t)r * 128;
-        gv_dma16(x_voff[0], xsrc, dst + GV_B_BYTES);
-        gv_dma16(x_voff[1], xsrc, dst + GV_B_BYTES + 1024);
+        const uint8_t *xsrc = xbase + (size_t)next_round * 128;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) gv_dma16(x_voff[i], xsrc, dst + GV_B_BYTES + i * 1024);
+        ++next_round;
+        slot = slot + 1 == NBUF ? 0 : slot + 1;
     };
-    if (nrounds > 0) issue_round(0);
-    if (nrounds > 1) issue_round(1);
+#pragma unroll
+    for (int i = 0; i < NBUF; ++i)
+        if (i < nrounds) issue_round();
 
     // scale / zero-point tile of the slice: [groups touched][128 channels].  All its loads are issued
     // together (indices clamped instead of branching, so that the compiler batches them behind a
@@ -160,12 +174,25 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            if (tid + i * WAVES * 64 < 128 * cols) sz[jj[i]][ch[i]] = ScaleZero{ts[i] + td[i], kCodeOffset + (float)tz[i] + tdz[i]};
+            if (tid + i * WAVES * 64 < 128 * cols) {
+                sS[jj[i]][ch[i]] = ts[i] + td[i];
+                if constexpr (ZBYTE) sZ[jj[i]][ch[i]] = tz[i];
+                else sZ[jj[i]][ch[i]] = kCodeOffset + (float)tz[i] + tdz[i];
+            }
     };
-    if (GROUPS_MAX == 1 || cols <= 2) load_tile(std::integral_constant<int, 1>{});
-    else if (cols <= 4) load_tile(std::integral_constant<int, 2>{});
-    else if (cols <= 8) load_tile(std::integral_constant<int, 4>{});
-    else load_tile(std::integral_constant<int, 8>{});
+    constexpr int PER_BATCH = WAVES * 64 / 128;                   // groups of 128 channels per batch of loads
+    if constexpr (GROUPS_MAX == 1) {
+        load_tile(std::integral_constant<int, 1>{});
+    } else {
+        if (cols <= PER_BATCH) load_tile(std::integral_constant<int, 1>{});
+        else if (cols <= 2 * PER_BATCH) load_tile(std::integral_constant<int, 2>{});
+        else if (cols <= 4 * PER_BATCH) load_tile(std::integral_constant<int, 4>{});
+        else if (cols <= 8 * PER_BATCH) load_tile(std::integral_constant<int, 8>{});
+        else if constexpr (GROUPS_MAX > 8 * PER_BATCH) {
+            if (cols <= 16 * PER_BATCH) load_tile(std::integral_constant<int, 16>{});
+            else load_tile(std::integral_constant<int, (GROUPS_MAX + PER_BATCH - 1) / PER_BATCH>{});
+        }
+    }
     __syncthreads();
 
     f32x4 y[8], acc[8], accrs = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -175,7 +202,8 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
     // this lane's block and activation fragment of step 0 within a round
     constexpr int STEP_B = BITS == 4 ? 2048 : 1536;               // packed bytes of one step in a round buffer
     const int b_off = BITS == 4 ? lane * 16 : c * 96 + q * 24;
-    const int x_off = GV_B_BYTES + c * 128 + q * 16;
+    // token row of this lane's activation fragment; with 8 rows staged, rows 8..15 (beyond T, never stored) read rows 0..7
+    const int x_off = GV_B_BYTES + (NX == 2 ? c : (c & 7)) * 128 + q * 16;
     int group_left = chunk_rounds - (int)((uint32_t)wr0 % (uint32_t)chunk_rounds);   // rounds to the end of the scale group
     int gj = (int)((uint32_t)wr0 / (uint32_t)chunk_rounds) - g_lo;                    // its column of the tile
 
@@ -183,15 +211,20 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
     // code (a workgroup runs only a few steps, so instruction fetch of an unrolled pipeline would
     // cost more than it hides).
     const int nsteps = 2 * nrounds;
+    int rslot = 0;                                                // ring slot of the round being consumed
 #pragma unroll 1
     for (int step = 0; step < nsteps; ++step) {
         const int r = step >> 1, s2 = step & 1;
         if (s2 == 0) {
-            // rounds r and (if any) r + 1 are in flight: wait for r only
-            if (r + 1 < nrounds) gv_wait_vmcnt<NDMA>(); else gv_wait_vmcnt<0>();
+            // rounds r .. min(r + NBUF, nrounds) - 1 are in flight, issued in order: wait for r only
+            const int after = next_round - 1 - r;                 // rounds issued after r
+            if (NBUF > 3 && after >= 3) gv_wait_vmcnt<3 * NDMA>();
+            else if (NBUF > 2 && after == 2) gv_wait_vmcnt<2 * NDMA>();
+            else if (after == 1) gv_wait_vmcnt<NDMA>();
+            else gv_wait_vmcnt<0>();
             asm volatile("" ::: "memory");
         }
-        const uint8_t *rb = stage + (wave * 2 + (r & 1)) * GV_ROUND_BYTES;
+        const uint8_t *rb = stage + (wave * NBUF + rslot) * GV_ROUND_BYTES;
         {
             const uint8_t *sb = rb + s2 * STEP_B + b_off;
             uint32_t bw[WPB];
@@ -222,21 +255,30 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : (GROUPS_MAX == 1 ? 3 : 
         }
         if (s2 == 1) {
             // this buffer is free again (its LDS reads have returned: the MFMAs consumed them): refill it
-            if (r + 2 < nrounds) issue_round(r + 2);
+            if (next_round < nrounds) issue_round();
+            rslot = rslot + 1 == NBUF ? 0 : rslot + 1;
             if (--group_left == 0 || r + 1 == nrounds) {
                 // end of a scale group, or of this wave's share: fold offset, zero-point and scale
                 // of the group into y, restart the sums
-                const f32x4 *szp = reinterpret_cast<const f32x4 *>(&sz[gj][8 * c]);
+                const f32x4 s_lo = *reinterpret_cast<const f32x4 *>(&sS[gj][8 * c]);
+                const f32x4 s_hi = *reinterpret_cast<const f32x4 *>(&sS[gj][8 * c + 4]);
+                float zo[8];                                      // 16 + z of channels 8c .. 8c + 7
+                if constexpr (ZBYTE) {
+                    const u32x2 zz = *reinterpret_cast<const u32x2 *>(&sZ[gj][8 * c]);
 #pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    const f32x4 v = szp[h];                       // (s, 16 + z) of channels 8c + 2h, 8c + 2h + 1
+                    for (int i = 0; i < 8; ++i) zo[i] = kCodeOffset + (float)((zz[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+                } else {
+                    const f32x4 z_lo = *reinterpret_cast<const f32x4 *>(&sZ[gj][8 * c]);
+                    const f32x4 z_hi = *reinterpret_cast<const f32x4 *>(&sZ[gj][8 * c + 4]);
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int ct = 2 * h + e;
+                    for (int i = 0; i < 4; ++i) { zo[i] = z_lo[i]; zo[4 + i] = z_hi[i]; }
+                }
 #pragma unroll
-                        for (int jj = 0; jj < 4; ++jj) y[ct][jj] += v[2 * e] * (acc[ct][jj] - v[2 * e + 1] * accrs[jj]);
-                        acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    }
+                for (int ct = 0; ct < 8; ++ct) {
+                    const float sc = ct < 4 ? s_lo[ct & 3] : s_hi[ct & 3];
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) y[ct][jj] += sc * (acc[ct][jj] - zo[ct] * accrs[jj]);
+                    acc[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
                 }
                 accrs = f32x4{0.f, 0.f, 0.f, 0.f};
                 ++gj;
@@ -284,7 +326,7 @@ __global__ __launch_bounds__(256) void gemv_finish_kernel(GemvArgs a)
 
 }  // namespace
 
-int gemv_slices(int Ntot, int K, int T, int chunk)
+int gemv_slices(int Ntot, int K, int T, int chunk, bool zbyte)
 {
     // as many slices as give two workgroups per compute unit (measured: more, up to the three that fit
     // for per-channel layers, only adds partials), every wave at least two rounds long, and the
@@ -301,8 +343,10 @@ int gemv_slices(int Ntot, int K, int T, int chunk)
     const int by_bytes = T > 4 ? 6 : 16;
     if (S > by_bytes) S = by_bytes;
     if (S < 1) S = 1;
-    // the scale tile in LDS holds at most GV_MAX_PER groups per slice
-    while (((R + S - 1) / S + chunk_rounds - 1) / chunk_rounds + 1 > GV_MAX_PER) ++S;
+    // the scale tile in LDS holds a bounded number of groups per slice
+    const int gmax = zbyte ? GV_MAX_PER_Z8 : GV_MAX_PER;
+    if (chunk != K)
+        while (((R + S - 1) / S + chunk_rounds - 1) / chunk_rounds + 1 > gmax) ++S;
     return S;
 }
 
@@ -311,7 +355,7 @@ bool gemv_whole(int tiles, bool per_channel, int S)
     return per_channel && S == 1 && tiles >= GV_WHOLE_MIN_TILES && tiles <= GV_WHOLE_MAX_TILES;
 }
 
-void gemv_plan(int n, const int *N, const int *K, const int *chunk, int bits, int T, int *S)
+void gemv_plan(int n, const int *N, const int *K, const int *chunk, int bits, int T, bool zbyte, int *S)
 {
     // target: all workgroups resident at once (two per compute unit) with equal shares of the packed bytes
     int dev = 0, cus = 256;
@@ -327,9 +371,10 @@ void gemv_plan(int n, const int *N, const int *K, const int *chunk, int bits, in
         if (s > R / (2 * GV_WAVES)) s = R / (2 * GV_WAVES);      // every wave at least two rounds
         if (s > by_bytes) s = by_bytes;
         if (s < 1) s = 1;
-        // the scale tile in LDS holds at most GV_MAX_PER groups per slice
+        // the scale tile in LDS holds a bounded number of groups per slice
+        const int gmax = zbyte ? GV_MAX_PER_Z8 : GV_MAX_PER;
         if (chunk[j] != K[j])
-            while (((R + s - 1) / s + chunk_rounds - 1) / chunk_rounds + 1 > GV_MAX_PER) ++s;
+            while (((R + s - 1) / s + chunk_rounds - 1) / chunk_rounds + 1 > gmax) ++s;
         S[j] = s;
     }
 }
@@ -345,42 +390,49 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
         if (a.layer[j].S > 1 && (unsigned)a.T * (unsigned)a.layer[j].N > max_tn) max_tn = (unsigned)a.T * (unsigned)a.layer[j].N;
     }
     const dim3 grid(wgs);
-    constexpr int SLICED_LDS = GV_WAVES * 2 * GV_ROUND_BYTES, WHOLE_LDS = GV_WAVES_WHOLE * 2 * GV_ROUND_BYTES;
     // the 12-wave form: layers of equal K in one launch (one layer, or layers that read one X), a single slice each
     bool whole = !sliced && gemv_whole(wgs, per_channel_all, 1);
     for (int j = 1; j < a.n_layers; ++j) whole = whole && a.layer[j].K == a.layer[0].K;
-    if (whole) {
-        // 144 KB of dynamic LDS: allowed once per device and instantiation
-        static bool allowed[2][64];
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-        if (!allowed[bits == 4][dev]) {
-            const void *f = bits == 4 ? reinterpret_cast<const void *>(gemv_kernel<4, 1, GV_WAVES_WHOLE>)
-                                      : reinterpret_cast<const void *>(gemv_kernel<3, 1, GV_WAVES_WHOLE>);
-            e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, WHOLE_LDS);
-            if (e != hipSuccess) return e;
-            allowed[bits == 4][dev] = true;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    // One instantiation: its dynamic LDS (more than the default limit: allowed once per device), then the launch.
+    auto go = [&](auto kern, int waves, int lds_bytes, bool *allowed) -> hipError_t {
+        if (!allowed[dev]) {
+            const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (e2 != hipSuccess) return e2;
+            allowed[dev] = true;
         }
-    }
-    trace_before(KID_GEMV, stream);
-    // Per-channel layers fit three workgroups per compute unit (1 KB scale tile).  That pays only when
-    // there are more workgroups than two per unit: below, the dispatcher would stack three on some
-    // units and leave others with one, so such launches take the 16 KB instantiation (two per unit).
-    const bool per_channel = per_channel_all && wgs > 512;
+        trace_before(KID_GEMV, stream);
+        hipLaunchKernelGGL(kern, grid, dim3(waves * 64), lds_bytes, stream, a);
+        trace_after(KID_GEMV, stream);
+        return hipGetLastError();
+    };
+#define PEQA_GEMV_GO(BITS, GROUPS, WAVES, NX, ZBYTE)                                                      \
+    do {                                                                                                   \
+        static bool allowed[64];                                                                           \
+        e = go(gemv_kernel<BITS, GROUPS, WAVES, 2, NX, ZBYTE>, WAVES, WAVES * 2 * gv_round_bytes(BITS, NX), allowed); \
+    } while (0)
+    // Two rounds per wave in flight everywhere: a third (which fits beside the scale tile for most
+    // instantiations) measured no faster on the LLaMA-7B and 13B blocks.
+    const bool nx2 = a.T > 8;
+    bool zbyte = true;
+    for (int j = 0; j < a.n_layers; ++j) zbyte = zbyte && a.layer[j].dz == nullptr;
     if (whole) {
-        if (bits == 4) hipLaunchKernelGGL((gemv_kernel<4, 1, GV_WAVES_WHOLE>), grid, dim3(GV_WAVES_WHOLE * 64), WHOLE_LDS, stream, a);
-        else hipLaunchKernelGGL((gemv_kernel<3, 1, GV_WAVES_WHOLE>), grid, dim3(GV_WAVES_WHOLE * 64), WHOLE_LDS, stream, a);
-    } else if (bits == 4) {
-        if (per_channel) hipLaunchKernelGGL((gemv_kernel<4, 1, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
-        else hipLaunchKernelGGL((gemv_kernel<4, GV_MAX_PER, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
+        if (bits == 4) PEQA_GEMV_GO(4, 1, GV_WAVES_WHOLE, 2, false); else PEQA_GEMV_GO(3, 1, GV_WAVES_WHOLE, 2, false);
+    } else if (per_channel_all) {
+        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, 1, GV_WAVES, 2, false); else PEQA_GEMV_GO(4, 1, GV_WAVES, 1, false); }
+        else { if (nx2) PEQA_GEMV_GO(3, 1, GV_WAVES, 2, false); else PEQA_GEMV_GO(3, 1, GV_WAVES, 1, false); }
+    } else if (zbyte) {
+        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, GV_MAX_PER_Z8, GV_WAVES, 2, true); else PEQA_GEMV_GO(4, GV_MAX_PER_Z8, GV_WAVES, 1, true); }
+        else { if (nx2) PEQA_GEMV_GO(3, GV_MAX_PER_Z8, GV_WAVES, 2, true); else PEQA_GEMV_GO(3, GV_MAX_PER_Z8, GV_WAVES, 1, true); }
     } else {
-        if (per_channel) hipLaunchKernelGGL((gemv_kernel<3, 1, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
-        else hipLaunchKernelGGL((gemv_kernel<3, GV_MAX_PER, GV_WAVES>), grid, dim3(GV_WAVES * 64), SLICED_LDS, stream, a);
+        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, GV_MAX_PER, GV_WAVES, 2, false); else PEQA_GEMV_GO(4, GV_MAX_PER, GV_WAVES, 1, false); }
+        else { if (nx2) PEQA_GEMV_GO(3, GV_MAX_PER, GV_WAVES, 2, false); else PEQA_GEMV_GO(3, GV_MAX_PER, GV_WAVES, 1, false); }
     }
-    trace_after(KID_GEMV, stream);
-    hipError_t e = hipGetLastError();
+#undef PEQA_GEMV_GO
     if (e != hipSuccess || !sliced) return e;
     trace_before(KID_GEMV_FINISH, stream);
     hipLaunchKernelGGL(gemv_finish_kernel, dim3((max_tn + 255) / 256, a.n_layers), dim3(256), 0, stream, a);

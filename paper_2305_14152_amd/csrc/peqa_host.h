@@ -33,9 +33,10 @@ struct GemvItem {
 };
 // Slices per layer: `block_plan` balances layers of different shapes against each other (peqa_block_fwd);
 // otherwise all layers share K and take the slicing of one layer of their summed channels.
-void gemv_slicing(int n, const GemvItem *items, int32_t T, bool block_plan, int *S);
+// `zbyte`: no item has a trained zero-point offset (dz), which allows longer slices of group-wise layers.
+void gemv_slicing(int n, const GemvItem *items, int32_t T, bool block_plan, bool zbyte, int *S);
 // fp32 partials of the sliced layers of such a launch
-size_t gemv_partial_bytes(int n, const GemvItem *items, int32_t T, bool block_plan);
+size_t gemv_partial_bytes(int n, const GemvItem *items, int32_t T, bool block_plan, bool zbyte);
 // One matrix-vector launch (plus the sum of the slices, if any) for n <= GEMV_MAX_LAYERS layers of one bit width.
 peqa_status gemv_forward(int n, const GemvItem *items, int32_t T, bool block_plan, float *partial, hipStream_t s);
 

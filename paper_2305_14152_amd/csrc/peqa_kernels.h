@@ -98,10 +98,12 @@ struct GemvArgs {
     int n_layers;
     int T;
 };
-int gemv_slices(int Ntot, int K, int T, int chunk);
+// zbyte: no layer of the launch has a trained zero-point offset, so zero-points stay bytes in LDS and a slice may
+// span more scale groups
+int gemv_slices(int Ntot, int K, int T, int chunk, bool zbyte);
 // Slices per layer for a launch of several layers of different shapes: every workgroup gets about the same
 // number of packed bytes, and all of them are resident at once.  Fills S[0..n).
-void gemv_plan(int n, const int *N, const int *K, const int *chunk, int bits, int T, int *S);
+void gemv_plan(int n, const int *N, const int *K, const int *chunk, int bits, int T, bool zbyte, int *S);
 // whether a per-channel launch of that many channel tiles with a single slice takes the 12-wave workgroups
 bool gemv_whole(int tiles, bool per_channel, int S);
 hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);

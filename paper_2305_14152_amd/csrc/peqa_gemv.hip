@@ -44,6 +44,7 @@ constexpr int GV_WAVES = 4;          // waves of the sliced workgroup
 constexpr int GV_WAVES_WHOLE = 12;   // waves of the workgroup that takes all of K
 constexpr int GV_WHOLE_MIN_TILES = 128, GV_WHOLE_MAX_TILES = 256;
 constexpr int GV_MAX_PER = 16;       // most scale groups a slice may touch (bounds the scale tile in LDS): trained zero-points
+constexpr int NB_PC = 2, NB_G31 = 2; // ring depth of the per-channel instantiations / of the 3-bit group-wise one for T <= 8
 constexpr int GV_MAX_PER_Z8 = 48;    // the same with integer zero-points, kept as bytes (5 instead of 8 bytes per entry)
 // One round of one wave in LDS: its packed blocks (4 KB at 4 bits, 3 KB at 3 bits), then NX KB of token rows
 // (8 rows x 128 B per KB: one DMA when T <= 8, two otherwise).
@@ -73,8 +74,9 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : 2) void gemv_kernel(Gem
     // [wave][NBUF rounds][round]; reused as [wave][column tile][row][lane] fp32 (8 KB per wave) for the final sum
     extern __shared__ __align__(16) uint8_t stage[];
     // scale s0 + ds and zero-point (16 + z0 + dz as fp32, or z0 as stored) of [group of the slice][channel]
-    __shared__ __align__(16) float sS[GROUPS_MAX][128];
-    __shared__ __align__(16) typename std::conditional<ZBYTE, uint8_t, float>::type sZ[GROUPS_MAX][128];
+    // (rows padded: the transposing writes of consecutive groups of one channel then fall into different banks)
+    __shared__ __align__(16) float sS[GROUPS_MAX][128 + 4];
+    __shared__ __align__(16) typename std::conditional<ZBYTE, uint8_t, float>::type sZ[GROUPS_MAX][128 + (ZBYTE ? 8 : 4)];
     constexpr int WPB = 2 * BITS;
     constexpr int GV_B_BYTES = gv_b_bytes(BITS), GV_ROUND_BYTES = gv_round_bytes(BITS, NX);
     static_assert(NBUF * GV_ROUND_BYTES >= 8192, "the final sum reuses a wave's ring");
@@ -151,12 +153,19 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : 2) void gemv_kernel(Gem
     for (int i = 0; i < NBUF; ++i)
         if (i < nrounds) issue_round();
 
-    // scale / zero-point tile of the slice: [groups touched][128 channels].  All its loads are issued
-    // together (indices clamped instead of branching, so that the compiler batches them behind a
-    // single wait); that wait also covers the two rounds above, which every wave needs next anyway.
+    // scale / zero-point tile of the slice: [groups touched][128 channels], transposed on the way into LDS (memory
+    // has a channel's groups next to each other).  All loads of a thread are issued together (indices clamped
+    // instead of branching, so that the compiler batches them behind a single wait); that wait also covers the
+    // rounds above, which every wave needs next anyway.  idx / cols is taken in fp32 (exact: idx < 2^13).
     const int cols = (GROUPS_MAX > 1 && rend > rbeg) ? (int)((uint32_t)(rend - 1) / (uint32_t)chunk_rounds) - g_lo + 1 : 1;
+    const float inv_cols = 1.0f / (float)cols;
+    auto store_entry = [&](int jj, int ch, float sv, uint32_t zv, float dzv) {
+        sS[jj][ch] = sv;
+        if constexpr (ZBYTE) sZ[jj][ch] = (uint8_t)zv;
+        else sZ[jj][ch] = kCodeOffset + (float)zv + dzv;
+    };
     auto load_tile = [&](auto nb_c) {
-        constexpr int NB = decltype(nb_c)::value;                 // batches of 256 entries
+        constexpr int NB = decltype(nb_c)::value;                 // batches of one entry per thread
         float ts[NB], td[NB], tdz[NB];
         uint8_t tz[NB];
         int ch[NB], jj[NB];
@@ -164,7 +173,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : 2) void gemv_kernel(Gem
         for (int i = 0; i < NB; ++i) {
             const int idx = tid + i * WAVES * 64;
             const bool on = idx < 128 * cols;
-            ch[i] = on ? (int)((uint32_t)idx / (uint32_t)cols) : 0;
+            ch[i] = on ? (int)(((float)idx + 0.5f) * inv_cols) : 0;
             jj[i] = on ? idx - ch[i] * cols : 0;
             const size_t si = (size_t)(n0 + ch[i]) * G + g_lo + jj[i];
             ts[i] = l_s0[si];
@@ -174,16 +183,49 @@ __global__ __launch_bounds__(WAVES * 64, WAVES > 4 ? 1 : 2) void gemv_kernel(Gem
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i)
-            if (tid + i * WAVES * 64 < 128 * cols) {
-                sS[jj[i]][ch[i]] = ts[i] + td[i];
-                if constexpr (ZBYTE) sZ[jj[i]][ch[i]] = tz[i];
-                else sZ[jj[i]][ch[i]] = kCodeOffset + (float)tz[i] + tdz[i];
-            }
+            if (tid + i * WAVES * 64 < 128 * cols) store_entry(jj[i], ch[i], ts[i] + td[i], tz[i], tdz[i]);
     };
-    constexpr int PER_BATCH = WAVES * 64 / 128;                   // groups of 128 channels per batch of loads
+    // A slice that spans all groups reads whole rows: the tile's entries are one contiguous run of 128 G, taken
+    // four at a time (16 bytes of s0 and of ds, 4 bytes of z0 per thread and batch).
+    auto load_rows = [&](auto nb_c) {
+        constexpr int NB = decltype(nb_c)::value;                 // batches of four entries per thread
+        f32x4 ts[NB], td[NB], tdz[NB];
+        uint32_t tz[NB];
+        const size_t base = (size_t)n0 * G;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            int e = 4 * (tid + i * WAVES * 64);
+            e = e < 128 * cols ? e : 0;
+            ts[i] = *reinterpret_cast<const f32x4 *>(l_s0 + base + e);
+            tz[i] = *reinterpret_cast<const uint32_t *>(l_z0 + base + e);
+            td[i] = l_ds ? *reinterpret_cast<const f32x4 *>(l_ds + base + e) : f32x4{0.f, 0.f, 0.f, 0.f};
+            tdz[i] = l_dz ? *reinterpret_cast<const f32x4 *>(l_dz + base + e) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int e = 4 * (tid + i * WAVES * 64);
+            if (e < 128 * cols) {
+                int chn = (int)(((float)e + 0.5f) * inv_cols), jn = e - chn * cols;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    store_entry(jn, chn, ts[i][u] + td[i][u], (tz[i] >> (8 * u)) & 0xFFu, tdz[i][u]);
+                    if (++jn == cols) { jn = 0; ++chn; }
+                }
+            }
+        }
+    };
+    constexpr int THREADS = WAVES * 64;
     if constexpr (GROUPS_MAX == 1) {
         load_tile(std::integral_constant<int, 1>{});
+    } else if (cols == G) {
+        // 128 cols / (4 THREADS) batches, at most GROUPS_MAX / 8 with 256 threads
+        constexpr int NBMAX = (128 * GROUPS_MAX + 4 * THREADS - 1) / (4 * THREADS);
+        if (128 * cols <= 4 * THREADS) load_rows(std::integral_constant<int, 1>{});
+        else if (128 * cols <= 8 * THREADS || NBMAX <= 2) load_rows(std::integral_constant<int, NBMAX < 2 ? NBMAX : 2>{});
+        else if (128 * cols <= 16 * THREADS || NBMAX <= 4) load_rows(std::integral_constant<int, NBMAX < 4 ? NBMAX : 4>{});
+        else load_rows(std::integral_constant<int, NBMAX>{});
     } else {
+        constexpr int PER_BATCH = THREADS / 128;                  // groups of 128 channels per batch of loads
         if (cols <= PER_BATCH) load_tile(std::integral_constant<int, 1>{});
         else if (cols <= 2 * PER_BATCH) load_tile(std::integral_constant<int, 2>{});
         else if (cols <= 4 * PER_BATCH) load_tile(std::integral_constant<int, 4>{});
@@ -410,27 +452,25 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream)
         trace_after(KID_GEMV, stream);
         return hipGetLastError();
     };
-#define PEQA_GEMV_GO(BITS, GROUPS, WAVES, NX, ZBYTE)                                                      \
+#define PEQA_GEMV_GO(BITS, GROUPS, WAVES, NBUF, NX, ZBYTE)                                                \
     do {                                                                                                   \
         static bool allowed[64];                                                                           \
-        e = go(gemv_kernel<BITS, GROUPS, WAVES, 2, NX, ZBYTE>, WAVES, WAVES * 2 * gv_round_bytes(BITS, NX), allowed); \
+        e = go(gemv_kernel<BITS, GROUPS, WAVES, NBUF, NX, ZBYTE>, WAVES, WAVES * NBUF * gv_round_bytes(BITS, NX), allowed); \
     } while (0)
-    // Two rounds per wave in flight everywhere: a third (which fits beside the scale tile for most
-    // instantiations) measured no faster on the LLaMA-7B and 13B blocks.
     const bool nx2 = a.T > 8;
     bool zbyte = true;
     for (int j = 0; j < a.n_layers; ++j) zbyte = zbyte && a.layer[j].dz == nullptr;
     if (whole) {
-        if (bits == 4) PEQA_GEMV_GO(4, 1, GV_WAVES_WHOLE, 2, false); else PEQA_GEMV_GO(3, 1, GV_WAVES_WHOLE, 2, false);
+        if (bits == 4) PEQA_GEMV_GO(4, 1, GV_WAVES_WHOLE, 2, 2, false); else PEQA_GEMV_GO(3, 1, GV_WAVES_WHOLE, 2, 2, false);
     } else if (per_channel_all) {
-        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, 1, GV_WAVES, 2, false); else PEQA_GEMV_GO(4, 1, GV_WAVES, 1, false); }
-        else { if (nx2) PEQA_GEMV_GO(3, 1, GV_WAVES, 2, false); else PEQA_GEMV_GO(3, 1, GV_WAVES, 1, false); }
+        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, 1, GV_WAVES, NB_PC, 2, false); else PEQA_GEMV_GO(4, 1, GV_WAVES, NB_PC, 1, false); }
+        else { if (nx2) PEQA_GEMV_GO(3, 1, GV_WAVES, NB_PC, 2, false); else PEQA_GEMV_GO(3, 1, GV_WAVES, NB_PC, 1, false); }
     } else if (zbyte) {
-        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, GV_MAX_PER_Z8, GV_WAVES, 2, true); else PEQA_GEMV_GO(4, GV_MAX_PER_Z8, GV_WAVES, 1, true); }
-        else { if (nx2) PEQA_GEMV_GO(3, GV_MAX_PER_Z8, GV_WAVES, 2, true); else PEQA_GEMV_GO(3, GV_MAX_PER_Z8, GV_WAVES, 1, true); }
+        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, GV_MAX_PER_Z8, GV_WAVES, 2, 2, true); else PEQA_GEMV_GO(4, GV_MAX_PER_Z8, GV_WAVES, 2, 1, true); }
+        else { if (nx2) PEQA_GEMV_GO(3, GV_MAX_PER_Z8, GV_WAVES, 2, 2, true); else PEQA_GEMV_GO(3, GV_MAX_PER_Z8, GV_WAVES, NB_G31, 1, true); }
     } else {
-        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, GV_MAX_PER, GV_WAVES, 2, false); else PEQA_GEMV_GO(4, GV_MAX_PER, GV_WAVES, 1, false); }
-        else { if (nx2) PEQA_GEMV_GO(3, GV_MAX_PER, GV_WAVES, 2, false); else PEQA_GEMV_GO(3, GV_MAX_PER, GV_WAVES, 1, false); }
+        if (bits == 4) { if (nx2) PEQA_GEMV_GO(4, GV_MAX_PER, GV_WAVES, 2, 2, false); else PEQA_GEMV_GO(4, GV_MAX_PER, GV_WAVES, 2, 1, false); }
+        else { if (nx2) PEQA_GEMV_GO(3, GV_MAX_PER, GV_WAVES, 2, 2, false); else PEQA_GEMV_GO(3, GV_MAX_PER, GV_WAVES, 2, 1, false); }
     }
 #undef PEQA_GEMV_GO
     if (e != hipSuccess || !sliced) return e;

@@ -833,7 +833,7 @@ struct TraceState {
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
-    "gemv_finish", "group_table", "dds_kept", "dz_partial", "dz_finish", "transpose_pad", "gemm_dw", "gemm_bwd"};
+    "gemv_finish", "group_table", "dds_kept", "dz_partial", "dz_finish", "transpose_pad", "gemm_dw", "gemm_bwd", "gemm_multi_y", "gemm_multi_dds", "gemm_multi_dx"};
 
 }  // namespace
 namespace {

@@ -227,6 +227,25 @@ __device__ __forceinline__ void scale_dy_rows(const uint16_t *__restrict__ dY, c
     if (tid < rows) crow[t0 + tid] = (red[tid * 4] + red[tid * 4 + 1]) + (red[tid * 4 + 2] + red[tid * 4 + 3]);
 }
 
+// out[j] = partial[0][j] + partial[1][j] + ... in that order (deterministic).
+__device__ __forceinline__ void reduce_partials_at(const float *__restrict__ partial, int ntiles, size_t n, size_t j,
+                                                   float *__restrict__ out)
+{
+    if (j >= n) return;
+    // eight loads in flight, added in tile order
+    float s = 0.f;
+    int tt = 0;
+    for (; tt + 8 <= ntiles; tt += 8) {
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = partial[(size_t)(tt + u) * n + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += p[u];
+    }
+    for (; tt < ntiles; ++tt) s += partial[(size_t)tt * n + j];
+    out[j] = s;
+}
+
 // One 64 x 64 tile of the step-major transposed copy that the token contraction of group-wise layers reads:
 // dst[t / 32][cc][t % 32] = src[t, cc] for t < T, 0 for T <= t < Tp, tile (bt, bc) of 64 tokens x 64 columns,
 // by one workgroup of 256 threads through `tile`, 64 x 66 bf16 of LDS.  C % 64 == 0.

@@ -37,6 +37,8 @@
 //                     partial per (token tile, channel, group).  This is the older of two routes to
 //                     the grouped scale gradient (the default contracts over tokens, peqa_dw.hip)
 //                     and runs only on request (option grouped_dds = 1).
+#include <stddef.h>
+
 #include <type_traits>
 
 #include "peqa_device.h"
@@ -766,6 +768,67 @@ __global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmArgs a_dds, G
     else gemm_tile<BITS, MODE_DDS, false, 1>(a_dds, wg, lds);
 }
 
+// Bandwidth-bound side work inside a multi-contraction launch: auxiliary workgroup `w` of `m.aux_wgs` walks the
+// units w, w + aux_wgs, ... of one index space: first the SDY_ROWS-row blocks of the scale_dy jobs, then the
+// 256-element chunks of the reduce jobs.
+static_assert(SDY_ROWS == SDY_ROWS_HOST, "row blocks of scale_dy_rows");
+__device__ __forceinline__ void multi_aux(int n_sdy, int n_red, int aux_wgs, int w, uint8_t *lds)
+{
+    struct { int n_sdy, n_red, aux_wgs; } m{n_sdy, n_red, aux_wgs};
+    float *red = reinterpret_cast<float *>(lds);
+    constexpr uint32_t SDY0 = offsetof(MultiArgs, sdy), RED0 = offsetof(MultiArgs, red);
+    const int n_blk = m.n_sdy > 0 ? kernarg_load<int>(SDY0 + (uint32_t)((m.n_sdy - 1) * sizeof(ScaleDyJob) + offsetof(ScaleDyJob, blk_end))) : 0;
+    const int n_chunk = m.n_red > 0 ? kernarg_load<int>(RED0 + (uint32_t)((m.n_red - 1) * sizeof(ReduceJob) + offsetof(ReduceJob, chunk_end))) : 0;
+    for (int u = w; u < n_blk + n_chunk; u += m.aux_wgs) {
+        if (u < n_blk) {
+            int j = 0, b0 = 0;
+            for (int i = 0; i + 1 < m.n_sdy; ++i) {
+                const int e = kernarg_load<int>(SDY0 + (uint32_t)(i * sizeof(ScaleDyJob) + offsetof(ScaleDyJob, blk_end)));
+                if (u >= e) { j = i + 1; b0 = e; }
+            }
+            const ScaleDyJob J = kernarg_load<ScaleDyJob>(SDY0 + (uint32_t)(j * sizeof(ScaleDyJob)));
+            scale_dy_rows(J.dY, J.s0, J.ds, J.z0, nullptr, J.T, J.N, J.dYs, J.crow, u - b0, red);
+            __syncthreads();                                   // `red` is reused by the next block
+        } else {
+            const int c = u - n_blk;
+            int j = 0, c0 = 0;
+            for (int i = 0; i + 1 < m.n_red; ++i) {
+                const int e = kernarg_load<int>(RED0 + (uint32_t)(i * sizeof(ReduceJob) + offsetof(ReduceJob, chunk_end)));
+                if (c >= e) { j = i + 1; c0 = e; }
+            }
+            const ReduceJob J = kernarg_load<ReduceJob>(RED0 + (uint32_t)(j * sizeof(ReduceJob)));
+            reduce_partials_at(J.partial, J.ntiles, (size_t)J.n, (size_t)(c - c0) * 256 + threadIdx.x, J.out);
+        }
+    }
+}
+
+// Several per-channel contractions as four-wave tiles of one launch (see MultiArgs): workgroup -> (job, tile) by the
+// jobs' running totals; the job's arguments come out of the argument block with scalar loads.
+template <int BITS>
+__global__ __launch_bounds__(256, 2) void gemm_multi_kernel(MultiArgs m)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    int b = (int)blockIdx.x;
+    if (b >= m.aux_begin) {
+        if (b < m.aux_begin + m.aux_wgs) {
+            multi_aux(m.n_sdy, m.n_red, m.aux_wgs, b - m.aux_begin, lds);
+            return;
+        }
+        b -= m.aux_wgs;
+    }
+    int j = 0, wg0 = 0;
+#pragma unroll
+    for (int i = 0; i < MULTI_MAX_JOBS - 1; ++i) {
+        const int e = kernarg_load<int>((uint32_t)(i * sizeof(MultiJob) + offsetof(MultiJob, wg_end)));
+        if (b >= e) { j = i + 1; wg0 = e; }
+    }
+    const int mode = kernarg_load<int>((uint32_t)(j * sizeof(MultiJob) + offsetof(MultiJob, mode)));
+    const GemmArgs a = kernarg_load<GemmArgs>((uint32_t)(j * sizeof(MultiJob) + offsetof(MultiJob, a)));
+    if (mode == MODE_Y) gemm_tile<BITS, MODE_Y, false, 1>(a, b - wg0, lds);
+    else if (mode == MODE_DDS) gemm_tile<BITS, MODE_DDS, false, 1>(a, b - wg0, lds);
+    else gemm_tile<BITS, MODE_DX, false, 1>(a, b - wg0, lds);
+}
+
 }  // namespace
 
 // Contraction halves per workgroup.  Eight waves with two halves, one workgroup per compute unit, when a launch
@@ -878,6 +941,52 @@ static hipError_t launch_pair(const GemmArgs &a_dds, const GemmArgs &a_dx, hipSt
     const int n_first = grid_of(dx_first ? a_dx : a_dds), n_second = grid_of(dx_first ? a_dds : a_dx);
     hipLaunchKernelGGL((gemm_bwd_pair_kernel<BITS>), dim3(n_first + n_second), dim3(256), lds_bytes, stream, a_dds, a_dx,
                        n_first, dx_first);
+    return hipGetLastError();
+}
+
+int gemm_multi_wgs(int tiles_t, int tiles_c)
+{
+    const int pt = tiles_t >= 4 ? 4 : (tiles_t >= 2 ? 2 : 1), pc = 32 / pt;
+    const int patches = ((tiles_t + pt - 1) / pt) * ((tiles_c + pc - 1) / pc);
+    return ((patches + 7) / 8) * 8 * 32;
+}
+
+hipError_t launch_gemm_multi(int bits, MultiArgs &m, hipStream_t stream)
+{
+    if (m.n_jobs < 0 || m.n_jobs > MULTI_MAX_JOBS || m.n_sdy < 0 || m.n_sdy > MULTI_MAX_JOBS || m.n_red < 0 ||
+        m.n_red > MULTI_MAX_JOBS)
+        return hipErrorInvalidValue;
+    int total = 0;
+    for (int j = 0; j < MULTI_MAX_JOBS; ++j) {
+        if (j < m.n_jobs) {
+            GemmArgs &a = m.job[j].a;
+            if (a.gsz > 0 || a.tp_blocks) return hipErrorInvalidValue;
+            a.patch_t = a.tiles_t >= 4 ? 4 : (a.tiles_t >= 2 ? 2 : 1);
+            total += gemm_multi_wgs(a.tiles_t, a.tiles_c);
+        } else {
+            m.job[j] = m.job[m.n_jobs > 0 ? m.n_jobs - 1 : 0];
+        }
+        m.job[j].wg_end = total;
+    }
+    if ((m.aux_begin & 7) || (m.aux_wgs & 7) || m.aux_begin < 0 || m.aux_begin > total) return hipErrorInvalidValue;
+    if (total + m.aux_wgs == 0) return hipSuccess;
+    const int lds_bytes = ring_bytes(1);
+    static int attr_bytes[2][64] = {{0}};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    const void *f = bits == 4 ? reinterpret_cast<const void *>(&gemm_multi_kernel<4>)
+                              : reinterpret_cast<const void *>(&gemm_multi_kernel<3>);
+    if (attr_bytes[bits == 4][dev] < lds_bytes) {
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_bytes[bits == 4][dev] = lds_bytes;
+    }
+    const int mode0 = m.n_jobs > 0 ? m.job[0].mode : MODE_DX;
+    const int kid = mode0 == MODE_Y ? KID_GEMM_MULTI_Y : (mode0 == MODE_DDS ? KID_GEMM_MULTI_DDS : KID_GEMM_MULTI_DX);
+    trace_before(kid, stream);
+    if (bits == 4) hipLaunchKernelGGL((gemm_multi_kernel<4>), dim3(total + m.aux_wgs), dim3(256), lds_bytes, stream, m);
+    else hipLaunchKernelGGL((gemm_multi_kernel<3>), dim3(total + m.aux_wgs), dim3(256), lds_bytes, stream, m);
+    trace_after(kid, stream);
     return hipGetLastError();
 }
 

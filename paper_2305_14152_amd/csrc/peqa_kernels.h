@@ -59,6 +59,46 @@ bool gemm_four_waves(int tiles);
 // launch of four-wave workgroups (measured faster than two launches at every T).  The dX arguments' input (the scaled dY) must be complete before the launch.
 hipError_t launch_gemm_bwd_pair(int bits, const GemmArgs &a_dds, const GemmArgs &a_dx, hipStream_t stream);
 
+// Several contractions in ONE launch of four-wave workgroups (gemm_multi_kernel): the tiles of job 0 first, then
+// job 1's, ... (the caller orders them by contraction length, longest first, so that the last, partly filled round
+// of the launch is made of short tiles).  Per-channel layers only.  Workgroups numbered [aux_begin, aux_begin +
+// aux_wgs) do bandwidth-bound side work of the same backward instead of a tile: every one of them walks a share
+// of the row blocks of the scale_dy jobs, or of the 256-element chunks of the reduce jobs.  They sit in the middle
+// of the grid, where they start while most compute units still run tiles, so that their memory traffic hides
+// behind matrix work.  All job sizes, aux_begin and aux_wgs are multiples of 8 (workgroup id % 8 = XCD throughout).
+constexpr int MULTI_MAX_JOBS = 8;
+struct MultiJob {
+    GemmArgs a;
+    int mode;                 // MODE_Y, MODE_DDS or MODE_DX
+    int wg_end;               // tile workgroups of this job and all before it (unused entries: the total)
+};
+constexpr int SDY_ROWS_HOST = 4;      // token rows per row block of scale_dy_rows (checked against the device constant)
+struct ScaleDyJob {           // dYs = bf16(dY (s0 + ds)), crow[t] = sum_i dYs[t,i] (16 + z0[i])   (scale_dy_rows)
+    const uint16_t *dY;
+    const float *s0, *ds;
+    const uint8_t *z0;
+    uint16_t *dYs;
+    float *crow;
+    int T, N;
+    int blk_end;              // row blocks (of SDY_ROWS rows) of this job and all before it
+};
+struct ReduceJob {            // out[j] = sum over ntiles of partial[tile][j], fixed order
+    const float *partial;
+    float *out;
+    int ntiles, n;
+    int chunk_end;            // 256-element chunks of this job and all before it
+};
+struct MultiArgs {
+    MultiJob job[MULTI_MAX_JOBS];          // must stay the first member: indexed in the argument block
+    ScaleDyJob sdy[MULTI_MAX_JOBS];
+    ReduceJob red[MULTI_MAX_JOBS];
+    int n_jobs, n_sdy, n_red;
+    int aux_begin, aux_wgs;
+};
+hipError_t launch_gemm_multi(int bits, MultiArgs &m, hipStream_t stream);
+// workgroups a contraction's tiles take in such a launch (a multiple of 8: whole XCD patches)
+int gemm_multi_wgs(int tiles_t, int tiles_c);
+
 // Arguments of the token contraction dW = dY^T X with the codes applied in its epilogue (peqa_dw.hip):
 // the scale gradient of group-wise layers.
 struct DwArgs {
@@ -110,6 +150,15 @@ hipError_t launch_gemv(int bits, const GemvArgs &a, hipStream_t stream);
 
 // peqa_small.hip
 hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs, hipStream_t stream);
+// the same for up to ROWSUM_MAX inputs of T rows each in one launch
+constexpr int ROWSUM_MAX = 8;
+struct RowsumMulti {
+    const uint16_t *X[ROWSUM_MAX];
+    float *rs[ROWSUM_MAX];
+    int K[ROWSUM_MAX];
+    int n, T;
+};
+hipError_t launch_rowsum_multi(const RowsumMulti &a, hipStream_t stream);
 // dYs = bf16(dY (s0 + ds)) and crow; with n_red > 0 the same launch also sums `ntiles` partial vectors of n_red
 // floats into red_out (launch_reduce_partials' job), an independent piece of work of the same backward
 hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds, const uint8_t *z0, const float *dz,
@@ -161,7 +210,7 @@ void trace_after(int kernel_id, hipStream_t stream);
 
 enum {
     KID_QUANTIZE = 0, KID_ROWSUM, KID_GEMM_Y, KID_GEMM_DDS, KID_GEMM_DX, KID_SCALE_DY,
-    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_DZ_PARTIAL, KID_DZ_FINISH, KID_TRANSPOSE, KID_GEMM_DW, KID_GEMM_BWD, KID_COUNT
+    KID_REDUCE, KID_ADAMW, KID_GEMV, KID_GEMV_FINISH, KID_GROUP_TABLE, KID_DDS_KEPT, KID_DZ_PARTIAL, KID_DZ_FINISH, KID_TRANSPOSE, KID_GEMM_DW, KID_GEMM_BWD, KID_GEMM_MULTI_Y, KID_GEMM_MULTI_DDS, KID_GEMM_MULTI_DX, KID_COUNT
 };
 
 }  // namespace peqa

@@ -16,8 +16,7 @@ __device__ __forceinline__ float wave_sum(float v)
 
 // rs[t, h] = sum of X[t, k] over contraction half h (k < ksplit, k >= ksplit), fp32.
 // One wave per token row; 16-byte loads.
-__global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict__ X, int T, int K, int ksplit,
-                                                      float *__restrict__ rs)
+__device__ __forceinline__ void rowsum_rows(const uint16_t *__restrict__ X, int T, int K, int ksplit, float *__restrict__ rs)
 {
     const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
@@ -43,6 +42,25 @@ __global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict_
     s[0] = wave_sum(s[0]);
     s[1] = wave_sum(s[1]);
     if (lane == 0) { rs[2 * t] = s[0]; rs[2 * t + 1] = s[1]; }
+}
+
+__global__ __launch_bounds__(256) void rowsum_kernel(const uint16_t *__restrict__ X, int T, int K, int ksplit,
+                                                      float *__restrict__ rs)
+{
+    rowsum_rows(X, T, K, ksplit, rs);
+}
+
+// rowsum_kernel's work for several inputs of T rows each: blockIdx.y selects the input.
+__global__ __launch_bounds__(256) void rowsum_multi_kernel(RowsumMulti a)
+{
+    const int y = blockIdx.y;
+    const uint16_t *X = a.X[0];
+    float *rs = a.rs[0];
+    int K = a.K[0];
+#pragma unroll
+    for (int i = 1; i < ROWSUM_MAX; ++i)
+        if (y == i) { X = a.X[i]; rs = a.rs[i]; K = a.K[i]; }
+    rowsum_rows(X, a.T, K, K / 2, rs);
 }
 
 // rsg[t, g] = sum of X[t, k] over scale group g (gsz features, a multiple of 64), fp32.
@@ -91,25 +109,6 @@ __global__ __launch_bounds__(256) void group_table_kernel(const float *__restric
     float *o = sb + (g * N + n) * 2;
     o[0] = s;
     o[1] = -s * (kCodeOffset + (float)z0[j] + (dz ? dz[j] : 0.f));
-}
-
-// out[j] = partial[0][j] + partial[1][j] + ... in that order (deterministic).
-__device__ __forceinline__ void reduce_partials_at(const float *__restrict__ partial, int ntiles, size_t n, size_t j,
-                                                   float *__restrict__ out)
-{
-    if (j >= n) return;
-    // eight loads in flight, added in tile order
-    float s = 0.f;
-    int tt = 0;
-    for (; tt + 8 <= ntiles; tt += 8) {
-        float p[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = partial[(size_t)(tt + u) * n + j];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) s += p[u];
-    }
-    for (; tt < ntiles; ++tt) s += partial[(size_t)tt * n + j];
-    out[j] = s;
 }
 
 // scale_dy_rows (peqa_device.h) for every block of SDY_ROWS token rows.  Workgroups past the last row block do an
@@ -294,6 +293,14 @@ hipError_t launch_rowsum(const uint16_t *X, int T, int K, int ksplit, float *rs,
 {
     trace_before(KID_ROWSUM, stream);
     hipLaunchKernelGGL(rowsum_kernel, dim3((T + 3) / 4), dim3(256), 0, stream, X, T, K, ksplit, rs);
+    trace_after(KID_ROWSUM, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_rowsum_multi(const RowsumMulti &a, hipStream_t stream)
+{
+    trace_before(KID_ROWSUM, stream);
+    hipLaunchKernelGGL(rowsum_multi_kernel, dim3((a.T + 3) / 4, a.n), dim3(256), 0, stream, a);
     trace_after(KID_ROWSUM, stream);
     return hipGetLastError();
 }

@@ -203,3 +203,89 @@ def test_full_size_quantize_search(gpu, oracle):
         e_ref = ((Wb - oracle.dequant(codes[bad], rs0[bad], None, rz0[bad], group)) ** 2).sum(axis=1)
         e_gpu = ((Wb - oracle.dequant(got[bad], gs0, None, gz0, group)) ** 2).sum(axis=1)
         assert (np.abs(e_gpu - e_ref) <= 1e-12 * e_ref).all()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_full_size_block(gpu, oracle, cfg):
+    """The launch configuration bench.py times: the whole decoder block behind peqa_block_fwd / peqa_block_bwd, q, k, v
+    and gate, up stacked (4 items), at the workload's full size.  Y and dX on one token row of every 128-row tile
+    against all channels / features, d_ds on one channel of every 128; for the 13B workload also the T = 1 and
+    T = 16 block forward with the seven layers as separate items (slices of the stacked arrays), every channel."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    c = synth.CONFIGS[cfg]
+    bits, group, T = c["bits"], c["group"], c["T"]
+    (n_a, k_a, _), (n_m, k_m, _), (n_d, k_d, _) = c["layers"]
+    shapes = [(3 * n_a, k_a, 0, 0), (n_a, k_a, 0, 1), (2 * n_m, k_m, 1, 2), (n_d, k_d, 2, 3)]    # N, K, layer index, input
+    print("full size block cfg=%d T=%d bits=%d g=%d" % (cfg, T, bits, group), flush=True)
+    rng = np.random.default_rng(5000 + cfg)
+    members, dicts, inputs = [], [], {}
+    for (N, K, li, xi) in shapes:
+        W = synth.weights(cfg, li, N=N)
+        layer = gpu.GpuLayer(W, bits, group)
+        codes, s0, z0 = oracle.quantize(W, bits, group)
+        del W
+        layer.W0 = None
+        ds = synth.normal_f32(500 + cfg + xi, s0.shape, 1e-3 * float(np.mean(s0)))
+        if xi not in inputs:
+            X = synth.activations(cfg, li) if xi != 1 else synth.normal_bf16(900 + cfg, (T, K), 1.0)
+            inputs[xi] = (X, gpu.to_dev(X), torch.zeros((T, 2), dtype=torch.float32, device="cuda"))
+        X, Xd, rs = inputs[xi]
+        dY = synth.output_grads(cfg, li, N=N)
+        members.append(dict(N=N, K=K, codes=codes, s0=s0, z0=z0, ds=ds, X=X, dY=dY, layer=layer))
+        dicts.append(dict(L=layer.L, packed=layer.packed, s0=layer.s0, z0=layer.z0, ds=gpu.to_dev(ds), X=Xd,
+                          Y=torch.zeros((T, N), dtype=torch.int16, device="cuda"), dY=gpu.to_dev(dY),
+                          dX=torch.zeros((T, K), dtype=torch.int16, device="cuda"),
+                          d_ds=torch.zeros(s0.shape, dtype=torch.float32, device="cuda"),
+                          row_sums=rs if not group else None))
+    items = peqa.block_items(dicts)
+    nb = max(peqa.block_workspace_bytes(items, T, op) for op in (peqa.PEQA_OP_FWD, peqa.PEQA_OP_BWD))
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    peqa.block_fwd(items, T, ws, nb)
+    peqa.block_bwd(items, T, ws, nb)
+    torch.cuda.synchronize()
+    ts = _one_per_tile(T, 128, (128, T - 128), rng)
+    for m, d in zip(members, dicts):
+        N, K = m["N"], m["K"]
+        print("  item N=%d K=%d" % (N, K), flush=True)
+        Y = gpu.bf16_dev_to_f64(d["Y"])
+        Yref = oracle.fwd(m["codes"], m["s0"], m["ds"], m["z0"], m["X"][ts], group)
+        assert np.abs(Y[ts] - Yref).max() <= Y_TOL * np.abs(Yref).max()
+        assert (np.abs(Y).reshape(T // 128, 128, N // 128, 128).max(axis=(1, 3)) > 0).all()
+        del Y
+        dX = gpu.bf16_dev_to_f64(d["dX"])
+        dXref, _, _ = oracle.bwd(m["codes"], m["s0"], m["ds"], m["z0"], m["X"][ts], m["dY"][ts], group, want_P=False)
+        assert np.abs(dX[ts] - dXref).max() <= Y_TOL * np.abs(dXref).max()
+        assert (np.abs(dX).reshape(T // 128, 128, K // 128, 128).max(axis=(1, 3)) > 0).all()
+        del dX
+        ns = _one_per_tile(N, 128, (128, 256, N // 2), rng)
+        _, gref, _ = oracle.bwd(m["codes"][ns], m["s0"][ns], m["ds"][ns], m["z0"][ns], m["X"],
+                                np.ascontiguousarray(m["dY"][:, ns]), group, want_dX=False)
+        g = gpu.to_host(d["d_ds"]).astype(np.float64)
+        gpu.assert_scale_grad_close(g[ns], gref)
+        assert np.isfinite(g).all() and (np.abs(g).reshape(N // 128, -1).max(axis=1) > 0).all()
+    if cfg != 4:
+        return
+    # deployment forward of the block: seven items (q, k, v and gate, up as slices of the stacked arrays), one call
+    for Ts in (1, 16):
+        seven, refs = [], []
+        for m, d, (N, K, li, xi) in zip(members, dicts, shapes):
+            count = {0: 3, 1: 1, 2: 2, 3: 1}[xi]
+            n1 = N // count
+            L1 = peqa.layout(n1, K, bits, group)
+            w1 = peqa.packed_words(L1)
+            Xs = np.ascontiguousarray(m["X"][:Ts])
+            Xsd = gpu.to_dev(Xs)
+            for i in range(count):
+                sl = slice(i * n1, (i + 1) * n1)
+                seven.append(dict(L=L1, packed=d["packed"][i * w1:(i + 1) * w1], s0=d["s0"][sl], z0=d["z0"][sl], ds=d["ds"][sl],
+                                  X=Xsd, Y=torch.zeros((Ts, n1), dtype=torch.int16, device="cuda")))
+                refs.append((m["codes"][sl], m["s0"][sl], m["ds"][sl], m["z0"][sl], Xs))
+        it7 = peqa.block_items(seven)
+        nb7 = peqa.block_workspace_bytes(it7, Ts, peqa.PEQA_OP_FWD)
+        ws7 = torch.empty(nb7, dtype=torch.uint8, device="cuda")
+        peqa.block_fwd(it7, Ts, ws7, nb7)
+        torch.cuda.synchronize()
+        for d7, (codes, s0, ds, z0, Xs) in zip(seven, refs):
+            Yref = oracle.fwd(codes, s0, ds, z0, Xs, group)
+            assert np.abs(gpu.bf16_dev_to_f64(d7["Y"]) - Yref).max() <= Y_TOL * np.abs(Yref).max()

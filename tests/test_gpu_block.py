@@ -145,3 +145,65 @@ def test_block_skips_and_errors(gpu, oracle):
     assert peqa.block_workspace_bytes(mixed, T, peqa.PEQA_OP_BWD) == 0
     assert lib.peqa_block_bwd(2, ctypes.addressof(mixed), T, ws.data_ptr(), nb, None) == peqa.PEQA_ERR_PARAM
     assert lib.peqa_block_fwd(9, ctypes.addressof(items), T, ws.data_ptr(), nb, None) == peqa.PEQA_ERR_PARAM
+
+
+def test_block_graph_capture_replays_match_eager(gpu, oracle):
+    """The block calls captured in a HIP graph (multi-contraction launches with their auxiliary workgroups, the
+    row sums, the T <= 16 launch with its slice sums): replays, with eager work between them, equal the eager
+    results bit for bit."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    T = 200
+    members = [Member(gpu, oracle, 37000 + 100 * j, 4, N, K, 0, T) for j, (N, K) in enumerate(((384, 512), (256, 1152), (128, 256)))]
+    dicts = []
+    for m in members:
+        dicts.append(dict(L=m.layer.L, packed=m.layer.packed, s0=m.layer.s0, z0=m.layer.z0, ds=m.dsd, X=gpu.to_dev(m.X),
+                          Y=torch.zeros((T, m.N), dtype=torch.int16, device="cuda"), dY=gpu.to_dev(m.dY),
+                          dX=torch.zeros((T, m.K), dtype=torch.int16, device="cuda"),
+                          d_ds=torch.zeros(m.s0.shape, dtype=torch.float32, device="cuda"),
+                          row_sums=torch.zeros((T, 2), dtype=torch.float32, device="cuda")))
+    items = peqa.block_items(dicts)
+    nb = max(peqa.block_workspace_bytes(items, T, op) for op in (peqa.PEQA_OP_FWD, peqa.PEQA_OP_BWD))
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    small = [dict(d, X=d["X"][:5].contiguous(), Y=torch.zeros((5, d["Y"].shape[1]), dtype=torch.int16, device="cuda")) for d in dicts]
+    items5 = peqa.block_items(small)
+    nb5 = peqa.block_workspace_bytes(items5, 5, peqa.PEQA_OP_FWD)
+    ws5 = torch.empty(nb5, dtype=torch.uint8, device="cuda")
+
+    def run(stream):
+        peqa.block_fwd(items, T, ws, nb, stream)
+        peqa.block_bwd(items, T, ws, nb, stream)
+        peqa.block_fwd(items5, 5, ws5, nb5, stream)
+
+    outs = [d[k] for d in dicts for k in ("Y", "dX", "d_ds")] + [d["Y"] for d in small]
+    run(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        run(torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        for t in outs:
+            t.fill_(7)                                # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for t, w in zip(outs, want):
+            assert (t == w).all(), rep
+    # and the eager results are right
+    for m, d in zip(members, dicts):
+        Yref = oracle.fwd(m.codes, m.s0, m.ds, m.z0, m.X, 0)
+        assert np.abs(gpu.bf16_dev_to_f64(d["Y"]) - Yref).max() <= Y_TOL * np.abs(Yref).max()
+
+
+def test_block_is_deterministic(gpu, oracle):
+    """Two block backward calls give the same bits (fixed reduction order, no atomics)."""
+    import torch
+    T = 300
+    members = [Member(gpu, oracle, 38000 + 100 * j, 3, N, K, 0, T) for j, (N, K) in enumerate(((640, 384), (256, 896)))]
+    a = _run_block(gpu, members, T, backward=True)
+    b = _run_block(gpu, members, T, backward=True)
+    for da, db in zip(a, b):
+        assert (gpu.to_host(da["d_ds"]).view(np.uint32) == gpu.to_host(db["d_ds"]).view(np.uint32)).all()
+        assert (gpu.to_host(da["dX"]) == gpu.to_host(db["dX"])).all()
+        assert (gpu.to_host(da["Y"]) == gpu.to_host(db["Y"])).all()

@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-small-batch", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
+    ap.add_argument("--only-small-batch", action="store_true",
+                    help="run only the T = 1 / 16 block forward of --config through peqa_block_fwd and print its "
+                         "figures (for profiling that kernel alone)")
     ap.add_argument("--no-kept-product", action="store_true",
                     help="skip the secondary timing of the variant that keeps the forward's product")
     ap.add_argument("--separate", action="store_true",
@@ -120,8 +123,9 @@ class Block:
 
 
 def time_steps(torch, peqa, blk, steps, warmup, use_graph=False):
-    """Times `steps` training steps of the block; returns (seconds per step, per-kernel trace of the same steps
-    run once more with every launch bracketed by HIP events)."""
+    """Times `steps` training steps of the block.  Returns seconds per step; the per-kernel trace of a few extra
+    steps with every launch bracketed by HIP events, and their number; the trace of the dominant contraction
+    kernel's launches inside the timed region, and that kernel's name."""
     stream = torch.cuda.current_stream().cuda_stream
     upd = [(d["ds"].numel(), d["ds"], d["d_ds"], d["m"], d["v"], d["s0"]) for d in blk.layers]
     T = blk.T
@@ -151,16 +155,41 @@ def time_steps(torch, peqa, blk, steps, warmup, use_graph=False):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    # every launch bracketed by HIP events: the per-kernel table, and which contraction kernel dominates.  (Events
+    # between all launches leave gaps in which the chip cools: kernels measure a few per cent shorter here than in
+    # the timed region, where launches are back to back.)
+    n_all = max(2, min(steps, 5))
+    peqa.trace_begin(64 * n_all + 16)
+    for _ in range(n_all):
+        step(replay=False)
+    torch.cuda.synchronize()
+    trace_all = peqa.trace_end()
+    dom = dominant_kernel(trace_all)
+    # the timed region; only the dominant kernel's launches are bracketed by events (one pair per launch, every
+    # other launch back to back as without tracing), which is where the roofline figure comes from
+    if graph[0] is None:
+        peqa.trace_begin(8 * steps + 16, prefix=dom)
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / steps
-    peqa.trace_begin(64 * steps + 16)
-    for _ in range(steps):
-        step(replay=False)
-    torch.cuda.synchronize()
-    return dt, peqa.trace_end()
+    trace_dom = peqa.trace_end() if graph[0] is None else {}
+    return dt, trace_all, n_all, trace_dom, dom
+
+
+def dominant_kernel(trace):
+    """Name prefix of the contraction kernel with the most time; the three kinds of multi-contraction launch are one
+    kernel (gemm_multi_kernel) and count together."""
+    groups = {}
+    for k, (n, ms) in trace.items():
+        if k in CONTRACTIONS:
+            key = "gemm_multi" if k.startswith("gemm_multi") else k
+            groups[key] = groups.get(key, 0.0) + ms
+    return max(groups, key=groups.get)
 
 
 def kernel_table(blk, trace, steps):
@@ -177,22 +206,27 @@ def kernel_table(blk, trace, steps):
     return out
 
 
-def roofline_of(blk, trace, steps):
-    """The contraction kernel with the most time: algorithmic flops of its launches / their HIP-event duration."""
-    cands = [k for k in trace if k in CONTRACTIONS]
-    dom = max(cands, key=lambda k: trace[k][1])
-    n, ms = trace[dom]
-    flops = blk.flops / 3.0 * (2.0 if dom == "gemm_bwd" else 1.0) * steps
+def roofline_of(blk, trace_dom, dom, timed_steps):
+    """The dominant contraction kernel: algorithmic flops of its launches / their HIP-event duration, both over
+    the timed region (the two warm-up steps before it included)."""
+    n = sum(v[0] for k, v in trace_dom.items() if k.startswith(dom))
+    ms = sum(v[1] for k, v in trace_dom.items() if k.startswith(dom))
+    kinds = [k for k in trace_dom if k.startswith(dom)]
+    steps = timed_steps + 2
+    # per step the launches of one kind do one contraction per item (gemm_bwd: two)
+    flops = blk.flops / 3.0 * (2.0 if dom == "gemm_bwd" else 1.0) * len(kinds) * steps
     achieved = flops / (ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+    return {"bound": "mfma", "kernel": dom + ("_kernel: the forward, scale-gradient and dX launches of a step" if dom == "gemm_multi" else ""),
+            "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
             "traffic_note": "not measured in this run; rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries of this "
                             "command are under profiles/ (see profiles/README.md)",
             "flops_per_launch": flops / n, "avg_launch_us": round(ms * 1e3 / n, 2),
-            "launches_per_step": round(n / steps, 2), "timing": "HIP events on the launching stream"}
+            "launches_per_step": round(n / steps, 2),
+            "timing": "HIP events on the launching stream around this kernel's launches only, inside the timed region"}
 
 
-def small_batch(torch, peqa, synth, config, reps=20):
+def small_batch(torch, peqa, synth, config, reps=20, per_layer=True):
     """Forward of one block at T = 1 and T = 16 through the matrix-vector path: all seven layers in one
     peqa_block_fwd call (one launch plus the sum of the sliced layers), and, for comparison, seven
     peqa_linear_fwd calls.  Algorithmic bytes per layer: packed codes + s0, ds (fp32) and z0 (uint8) per scale +
@@ -232,7 +266,7 @@ def small_batch(torch, peqa, synth, config, reps=20):
                     peqa.linear_fwd(d["L"], p, d["s0"], d["ds"], d["z0"], d["X"], T, d["Y"], ws1, nb1, stream)
 
         res = {}
-        for name, fn in (("block_call", run_block), ("per_layer_calls", run_layers)):
+        for name, fn in (("block_call", run_block), ("per_layer_calls", run_layers))[:2 if per_layer else 1]:
             for _ in range(3):
                 fn()
             torch.cuda.synchronize()
@@ -348,6 +382,9 @@ def main():
     peqa.lib()                                   # fails loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = synth.CONFIGS[args.config]
+    if args.only_small_batch:
+        print(json.dumps({"small_batch": small_batch(torch, peqa, synth, args.config, per_layer=False)}))
+        return
 
     if args.pmc_calibration:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
@@ -358,7 +395,7 @@ def main():
         del src, dst
 
     blk = Block(torch, peqa, synth, args.config, args.separate)
-    dt, trace = time_steps(torch, peqa, blk, args.steps, args.warmup, args.graph)
+    dt, trace, n_all, trace_dom, dom = time_steps(torch, peqa, blk, args.steps, args.warmup, args.graph)
     tflops = blk.flops / dt / 1e12
     assert abs(blk.flops - synth.block_flops(args.config)) < 1e-6 * blk.flops
 
@@ -379,8 +416,9 @@ def main():
         "launch": ("hip graph of: " if args.graph else "direct calls: ") +
                   "peqa_block_fwd, peqa_block_bwd (row sums of the inputs kept from the forward), then "
                   "peqa_scale_update_multi (one direct launch)",
-        "kernels": kernel_table(blk, trace, args.steps),
-        "roofline": roofline_of(blk, trace, args.steps),
+        "kernels": kernel_table(blk, trace, n_all),
+        "kernels_note": "from %d extra steps with every launch bracketed by HIP events (not part of the timed region)" % n_all,
+        "roofline": roofline_of(blk, trace_dom, dom, args.steps) if trace_dom else None,
         "device": device_info(torch, peqa),
     }
     if not args.no_kept_product and not cfg["group"]:
@@ -399,14 +437,14 @@ def main():
         for c in (2, 3, 4):
             b = Block(torch, peqa, synth, c, args.separate)
             steps = max(3, min(args.steps, 10))
-            d, tr = time_steps(torch, peqa, b, steps, 2)
-            r = roofline_of(b, tr, steps)
+            d, tr, n_all_c, tr_dom, dom_c = time_steps(torch, peqa, b, steps, 2)
+            r = roofline_of(b, tr_dom, dom_c, steps)
             others["cfg%d" % c] = {"workload": workload_name(synth.CONFIGS[c], b.T), "ms_per_step": round(d * 1e3, 4),
                                    "tflops": round(b.flops / d / 1e12, 1),
                                    "frac_of_bf16_mfma_peak": round(b.flops / d / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                                    "tokens_per_s": round(b.T / d, 1), "steps": steps,
                                    "dominant_kernel": {k: r[k] for k in ("kernel", "achieved", "frac", "avg_launch_us")},
-                                   "kernels": kernel_table(b, tr, steps)}
+                                   "kernels": kernel_table(b, tr, n_all_c)}
             del b
             torch.cuda.empty_cache()
         out["other_configs"] = others

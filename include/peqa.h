@@ -372,6 +372,10 @@ peqa_status peqa_device_info(int32_t *compute_units, int32_t *clock_khz);
  * it returns the number of distinct kernels seen.  Not thread-safe.
  */
 peqa_status peqa_trace_begin(int32_t max_launches);
+/* Restricts tracing to the kernels whose reported name starts with `prefix` (NULL or "": all kernels, the
+ * default).  Bracketing only the kernel of interest leaves the other launches of a timed region back to back,
+ * as they are without tracing.  Names are at most 31 characters (PEQA_ERR_PARAM otherwise). */
+peqa_status peqa_trace_select(const char *prefix);
 int32_t peqa_trace_end(int32_t max_kernels, const char **names, int32_t *launches, float *total_ms);
 
 #ifdef __cplusplus

@@ -5,6 +5,7 @@
 
 #include <limits.h>
 #include <math.h>
+#include <string.h>
 
 #include "peqa_host.h"
 
@@ -830,6 +831,7 @@ struct TraceState {
     hipEvent_t *ev = nullptr;     // 2 per launch
     int *kid = nullptr;
 } g_trace;
+char g_trace_prefix[32] = "";     // only kernels whose name starts with this are bracketed ("" = all)
 
 const char *const kKernelNames[peqa::KID_COUNT] = {
     "quantize", "rowsum", "gemm_y", "gemm_dds", "gemm_dx", "scale_dy", "reduce_partials", "adamw", "gemv",
@@ -850,17 +852,21 @@ void trace_release()
 
 namespace peqa {
 
+static bool trace_selected(int kernel_id)
+{
+    return g_trace_prefix[0] == 0 || strncmp(kKernelNames[kernel_id], g_trace_prefix, strlen(g_trace_prefix)) == 0;
+}
+
 void trace_before(int kernel_id, hipStream_t stream)
 {
-    if (!g_trace.on || g_trace.used >= g_trace.cap) return;
+    if (!g_trace.on || g_trace.used >= g_trace.cap || !trace_selected(kernel_id)) return;
     g_trace.kid[g_trace.used] = kernel_id;
     (void)hipEventRecord(g_trace.ev[2 * g_trace.used], stream);
 }
 
 void trace_after(int kernel_id, hipStream_t stream)
 {
-    (void)kernel_id;
-    if (!g_trace.on || g_trace.used >= g_trace.cap) return;
+    if (!g_trace.on || g_trace.used >= g_trace.cap || !trace_selected(kernel_id)) return;
     (void)hipEventRecord(g_trace.ev[2 * g_trace.used + 1], stream);
     ++g_trace.used;
 }
@@ -868,6 +874,14 @@ void trace_after(int kernel_id, hipStream_t stream)
 }  // namespace peqa
 
 extern "C" {
+
+peqa_status peqa_trace_select(const char *prefix)
+{
+    if (prefix && strlen(prefix) >= sizeof(g_trace_prefix)) return PEQA_ERR_PARAM;
+    strncpy(g_trace_prefix, prefix ? prefix : "", sizeof(g_trace_prefix) - 1);
+    g_trace_prefix[sizeof(g_trace_prefix) - 1] = 0;
+    return PEQA_OK;
+}
 
 peqa_status peqa_trace_begin(int32_t max_launches)
 {

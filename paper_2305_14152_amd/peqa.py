@@ -21,7 +21,7 @@ EXPORTS = ["peqa_check_layout", "peqa_packed_words", "peqa_num_scales", "peqa_wo
            "peqa_scale_update_multi", "peqa_device_info",
            "peqa_row_sums", "peqa_linear_fwd_fused_rs", "peqa_linear_bwd_rs",
            "peqa_set_option", "peqa_get_option", "peqa_linear_fwd_static",
-           "peqa_block_workspace_bytes", "peqa_block_fwd", "peqa_block_bwd"]
+           "peqa_block_workspace_bytes", "peqa_block_fwd", "peqa_block_bwd", "peqa_trace_select"]
 
 
 class Layout(ctypes.Structure):
@@ -111,6 +111,8 @@ def lib():
         L.peqa_block_fwd.restype = i32
         L.peqa_block_bwd.argtypes = [i32, vp, i32, vp, sz, vp]
         L.peqa_block_bwd.restype = i32
+        L.peqa_trace_select.argtypes = [ctypes.c_char_p]
+        L.peqa_trace_select.restype = i32
         L.peqa_trace_begin.argtypes = [i32]
         L.peqa_trace_begin.restype = i32
         L.peqa_trace_end.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(i32),
@@ -337,7 +339,10 @@ def get_option(option):
     return int(lib().peqa_get_option(int(option)))
 
 
-def trace_begin(max_launches):
+def trace_begin(max_launches, prefix=None):
+    """Brackets the library's launches with HIP events until trace_end(); `prefix` restricts it to kernels whose
+    name starts with it."""
+    _check(lib().peqa_trace_select(prefix.encode() if prefix else None), "peqa_trace_select")
     _check(lib().peqa_trace_begin(int(max_launches)), "peqa_trace_begin")
 
 

@@ -19,13 +19,12 @@ peqa_status check_items(int32_t n, const peqa_block_item *items, int32_t T)
     return PEQA_OK;
 }
 
-// Distinct inputs of the per-channel items, in order of first appearance: xi[j] = index of item j's input.
+// Distinct inputs of the items, in order of first appearance: xi[j] = index of item j's input.
 int distinct_inputs(int32_t n, const peqa_block_item *items, int *xi, const uint16_t **xs, int *ks)
 {
     int nx = 0;
     for (int j = 0; j < n; ++j) {
         xi[j] = -1;
-        if (grouped(&items[j].layout)) continue;
         for (int i = 0; i < nx; ++i)
             if (xs[i] == items[j].X && ks[i] == items[j].layout.k_in) xi[j] = i;
         if (xi[j] < 0) {
@@ -37,40 +36,45 @@ int distinct_inputs(int32_t n, const peqa_block_item *items, int *xi, const uint
     return nx;
 }
 
+// Regions of the workspace.  Sized per item, so that the size does not depend on which items share an input; a call
+// uses the region of the first item that reads an input for all that share it.
 struct BlockSpace {
-    size_t rs[PEQA_MAX_BLOCK];       // row sums of distinct input i (per-channel items, T > 16)
+    size_t rs[PEQA_MAX_BLOCK];       // per-channel item, T > 16: row sums of its input
     size_t dys[PEQA_MAX_BLOCK];      // backward, per-channel item j: bf16(dY (s0 + ds)) [T, N]
     size_t crow[PEQA_MAX_BLOCK];     //   its row factors [T]
     size_t partial[PEQA_MAX_BLOCK];  //   per-token-tile partials of its scale gradient [tiles_t, N]
-    size_t item;                     // scratch of one group-wise item at a time (the largest single need)
+    size_t table[PEQA_MAX_BLOCK];    // group-wise item j: its (s, b) table [G, N, 2]
+    size_t xt[PEQA_MAX_BLOCK];       // backward, group-wise item j: step-major transposed copy of its input [K, T']
+    size_t dyt[PEQA_MAX_BLOCK];      //   the same of its dY [N, T']
+    size_t pc[PEQA_MAX_BLOCK];       //   scale gradient per 64-feature chunk [N, K / 64]
     size_t total;
 };
 
 BlockSpace carve_block(int32_t n, const peqa_block_item *items, int32_t T, int32_t op)
 {
     BlockSpace w{};
-    int xi[PEQA_MAX_BLOCK], ks[PEQA_MAX_BLOCK];
-    const uint16_t *xs[PEQA_MAX_BLOCK];
-    const int nx = distinct_inputs(n, items, xi, xs, ks);
-    const size_t tiles_t = ((size_t)T + 127) / 128;
+    const size_t tiles_t = ((size_t)T + 127) / 128, Tp = ((size_t)T + 63) / 64 * 64;
     size_t off = 0;
-    for (int i = 0; i < nx; ++i) { w.rs[i] = off; off += round256((size_t)T * 2 * sizeof(float)); }
-    size_t need = 0;
     for (int j = 0; j < n; ++j) {
         const peqa_layout *L = &items[j].layout;
+        const size_t N = (size_t)L->n_out, K = (size_t)L->k_in;
         if (grouped(L)) {
-            const size_t b = peqa_workspace_bytes(L, T, op);
-            need = b > need ? b : need;
-        } else if (op == PEQA_OP_BWD) {
-            const size_t N = (size_t)L->n_out;
+            w.table[j] = off; off += round256(N * (size_t)groups(L) * 2 * sizeof(float));
+            if (op == PEQA_OP_BWD) {
+                w.xt[j] = off;  off += round256(K * Tp * sizeof(uint16_t));
+                w.dyt[j] = off; off += round256(N * Tp * sizeof(uint16_t));
+                w.pc[j] = off;  off += round256(N * (K / 64) * sizeof(float));
+            }
+            continue;
+        }
+        w.rs[j] = off; off += round256((size_t)T * 2 * sizeof(float));
+        if (op == PEQA_OP_BWD) {
             w.dys[j] = off;     off += round256((size_t)T * N * sizeof(uint16_t));
             w.crow[j] = off;    off += round256((size_t)T * sizeof(float));
             w.partial[j] = off; off += round256(tiles_t * N * sizeof(float));
         }
     }
-    w.item = off;
-    w.total = off + round256(need);
-    if (w.total == 0) w.total = 256;
+    w.total = off ? off : 256;
     return w;
 }
 
@@ -86,7 +90,7 @@ void sort_jobs(peqa::MultiArgs &m)
 }
 
 // Auxiliary workgroups of a multi-contraction launch: after the first round of tiles (two per compute unit), a
-// multiple of 8.
+// multiple of 8.  A launch without tiles is made of auxiliary workgroups alone: four per compute unit.
 void place_aux(peqa::MultiArgs &m, int aux_wgs)
 {
     int total = 0;
@@ -95,7 +99,28 @@ void place_aux(peqa::MultiArgs &m, int aux_wgs)
     if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const int first_round = 2 * cus / 8 * 8;
     m.aux_begin = total < first_round ? total : first_round;
-    m.aux_wgs = (m.n_sdy > 0 || m.n_red > 0) ? aux_wgs : 0;
+    if (total == 0) aux_wgs = 4 * cus / 8 * 8;
+    m.aux_wgs = (m.n_sdy > 0 || m.n_red > 0 || m.n_tp > 0) ? aux_wgs : 0;
+}
+
+// (s, b) tables of every group-wise item: one launch.
+peqa_status group_tables(int32_t n, const peqa_block_item *items, uint8_t *ws, const BlockSpace &w, bool only_dx,
+                         hipStream_t s)
+{
+    peqa::GroupTableMulti gt{};
+    for (int j = 0; j < n; ++j) {
+        const peqa_block_item &it = items[j];
+        if (!grouped(&it.layout) || (only_dx && !it.dX)) continue;
+        const int i = gt.n++;
+        gt.s0[i] = it.s0; gt.ds[i] = it.ds; gt.z0[i] = it.z0;
+        gt.sb[i] = reinterpret_cast<float *>(ws + w.table[j]);
+        gt.N[i] = it.layout.n_out; gt.G[i] = groups(&it.layout);
+    }
+    if (gt.n == 0) return PEQA_OK;
+    for (int i = gt.n; i < peqa::GT_MAX; ++i) {
+        gt.s0[i] = gt.s0[0]; gt.ds[i] = gt.ds[0]; gt.z0[i] = gt.z0[0]; gt.sb[i] = gt.sb[0]; gt.N[i] = gt.N[0]; gt.G[i] = gt.G[0];
+    }
+    return dev_status(peqa::launch_group_table_multi(gt, s));
 }
 
 }  // namespace
@@ -145,45 +170,61 @@ peqa_status peqa_block_fwd(int32_t n, const peqa_block_item *items, int32_t T, v
     int xi[PEQA_MAX_BLOCK], ks[PEQA_MAX_BLOCK];
     const uint16_t *xs[PEQA_MAX_BLOCK];
     const int nx = distinct_inputs(n, items, xi, xs, ks);
+    const int bits = items[0].layout.bits;
     // row sums of every distinct input of the per-channel items: one launch
-    const float *rs[PEQA_MAX_BLOCK];
-    if (nx > 0) {
+    const float *rs[PEQA_MAX_BLOCK] = {nullptr};
+    {
         peqa::RowsumMulti r{};
-        for (int i = 0; i < peqa::ROWSUM_MAX; ++i) {
-            const int k = i < nx ? i : nx - 1;
-            float *dst = reinterpret_cast<float *>(ws + w.rs[k]);
-            for (int j = 0; j < n; ++j)
-                if (xi[j] == k && items[j].row_sums) { dst = items[j].row_sums; break; }
-            r.X[i] = xs[k]; r.K[i] = ks[k]; r.rs[i] = dst;
-            if (i < nx) rs[i] = dst;
+        int nr = 0;
+        for (int i = 0; i < nx; ++i) {
+            float *dst = nullptr;
+            for (int j = 0; j < n; ++j) {
+                if (xi[j] != i || grouped(&items[j].layout)) continue;
+                if (!dst) dst = reinterpret_cast<float *>(ws + w.rs[j]);
+                if (items[j].row_sums) { dst = items[j].row_sums; break; }
+            }
+            if (!dst) continue;
+            r.X[nr] = xs[i]; r.K[nr] = ks[i]; r.rs[nr] = dst;
+            ++nr;
+            rs[i] = dst;
         }
-        r.n = nx; r.T = T;
-        if (peqa::launch_rowsum_multi(r, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (nr > 0) {
+            for (int i = nr; i < peqa::ROWSUM_MAX; ++i) { r.X[i] = r.X[nr - 1]; r.K[i] = r.K[nr - 1]; r.rs[i] = r.rs[nr - 1]; }
+            r.n = nr; r.T = T;
+            if (peqa::launch_rowsum_multi(r, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        }
     }
-    // all per-channel contractions: one launch
-    peqa::MultiArgs m{};
+    st = group_tables(n, items, ws, w, false, s);
+    if (st != PEQA_OK) return st;
+    // all per-channel contractions in one launch, all group-wise ones in another
+    peqa::MultiArgs m{}, mg{};
     for (int j = 0; j < n; ++j) {
         const peqa_block_item &it = items[j];
-        if (grouped(&it.layout)) continue;
         const int N = it.layout.n_out, K = it.layout.k_in;
-        peqa::MultiJob &job = m.job[m.n_jobs++];
+        const bool gw = grouped(&it.layout);
+        peqa::MultiArgs &dst = gw ? mg : m;
+        peqa::MultiJob &job = dst.job[dst.n_jobs++];
         job.mode = peqa::MODE_Y;
         peqa::GemmArgs &a = job.a;
         a.packed = it.packed; a.A = it.X; a.T = T; a.KC = K; a.C = N; a.K = K;
         a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
-        a.s0 = it.s0; a.ds = it.ds; a.z0 = it.z0; a.rs = rs[xi[j]]; a.out = it.Y;
+        a.out = it.Y;
+        if (gw) {
+            a.N = N; a.gsz = it.layout.group_size; a.G = groups(&it.layout);
+            a.sb = reinterpret_cast<const float *>(ws + w.table[j]);
+        } else {
+            a.s0 = it.s0; a.ds = it.ds; a.z0 = it.z0; a.rs = rs[xi[j]];
+        }
     }
     if (m.n_jobs > 0) {
         sort_jobs(m);
         place_aux(m, 0);
-        if (peqa::launch_gemm_multi(items[0].layout.bits, m, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_gemm_multi(bits, false, m, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
-    for (int j = 0; j < n; ++j) {
-        const peqa_block_item &it = items[j];
-        if (!grouped(&it.layout)) continue;
-        st = peqa_linear_fwd(&it.layout, it.packed, it.s0, it.ds, it.z0, it.X, T, it.Y, ws + w.item,
-                             workspace_bytes - w.item, stream);
-        if (st != PEQA_OK) return st;
+    if (mg.n_jobs > 0) {
+        sort_jobs(mg);
+        place_aux(mg, 0);
+        if (peqa::launch_gemm_multi(bits, true, mg, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
     return PEQA_OK;
 }
@@ -211,7 +252,7 @@ peqa_status peqa_block_bwd(int32_t n, const peqa_block_item *items, int32_t T, v
     int xi[PEQA_MAX_BLOCK], ks[PEQA_MAX_BLOCK];
     const uint16_t *xs[PEQA_MAX_BLOCK];
     const int nx = distinct_inputs(n, items, xi, xs, ks);
-    const int tiles_t = (T + 127) / 128;
+    const int tiles_t = (T + 127) / 128, Tp = (T + 63) / 64 * 64;
     const int bits = items[0].layout.bits;
 
     // ---- per-channel items.  Row sums of the inputs whose scale gradient is wanted: the caller's (kept from the
@@ -223,13 +264,14 @@ peqa_status peqa_block_bwd(int32_t n, const peqa_block_item *items, int32_t T, v
         for (int i = 0; i < nx; ++i) {
             bool wanted = false;
             const float *have = nullptr;
+            float *dst = nullptr;
             for (int j = 0; j < n; ++j)
-                if (xi[j] == i) {
+                if (xi[j] == i && !grouped(&items[j].layout)) {
                     wanted = wanted || items[j].d_ds != nullptr;
                     if (items[j].row_sums) have = items[j].row_sums;
+                    if (!dst) dst = reinterpret_cast<float *>(ws + w.rs[j]);
                 }
             if (have || !wanted) { rs[i] = have; continue; }
-            float *dst = reinterpret_cast<float *>(ws + w.rs[i]);
             r.X[nr] = xs[i]; r.K[nr] = ks[i]; r.rs[nr] = dst;
             ++nr;
             rs[i] = dst;
@@ -279,21 +321,66 @@ peqa_status peqa_block_bwd(int32_t n, const peqa_block_item *items, int32_t T, v
     if (ma.n_jobs > 0 || ma.n_sdy > 0) {
         sort_jobs(ma);
         place_aux(ma, 128);
-        if (peqa::launch_gemm_multi(bits, ma, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_gemm_multi(bits, false, ma, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
     if (mb.n_jobs > 0 || mb.n_red > 0) {
         sort_jobs(mb);
         place_aux(mb, 64);
-        if (peqa::launch_gemm_multi(bits, mb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_gemm_multi(bits, false, mb, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
 
-    // ---- group-wise items, one by one
+    // ---- group-wise items.  Their (s, b) tables in one launch; every dX contraction in one launch, whose auxiliary
+    // workgroups write the transposed copies of X (once per distinct input) and dY that the scale gradients read;
+    // the token contractions of all scale gradients in one launch; the sums of their chunks in one launch.
+    st = group_tables(n, items, ws, w, true, s);
+    if (st != PEQA_OK) return st;
+    peqa::MultiArgs mg{};
+    peqa::DwMultiArgs dw{};
+    const uint16_t *xt_of[PEQA_MAX_BLOCK] = {nullptr};
+    int tp_tiles = 0;
     for (int j = 0; j < n; ++j) {
         const peqa_block_item &it = items[j];
         if (!grouped(&it.layout)) continue;
-        st = peqa_linear_bwd(&it.layout, it.packed, it.s0, it.ds, it.z0, it.X, it.dY, T, it.dX, it.d_ds, ws + w.item,
-                             workspace_bytes - w.item, stream);
-        if (st != PEQA_OK) return st;
+        const int N = it.layout.n_out, K = it.layout.k_in, G = groups(&it.layout);
+        if (it.dX) {
+            peqa::MultiJob &job = mg.job[mg.n_jobs++];
+            job.mode = peqa::MODE_DX;
+            peqa::GemmArgs &a = job.a;
+            a.packed = it.packed; a.A = it.dY; a.T = T; a.KC = N; a.C = K; a.K = K;
+            a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
+            a.N = N; a.gsz = it.layout.group_size; a.G = G;
+            a.sb = reinterpret_cast<const float *>(ws + w.table[j]); a.out = it.dX;
+        }
+        if (it.d_ds) {
+            if (!xt_of[xi[j]]) {
+                uint16_t *xt = reinterpret_cast<uint16_t *>(ws + w.xt[j]);
+                peqa::TransposeJob &t = mg.tp[mg.n_tp++];
+                t.src = it.X; t.dst = xt; t.T = T; t.C = K; t.Tp = Tp;
+                tp_tiles += (Tp / 64) * (K / 64);
+                t.tile_end = tp_tiles;
+                xt_of[xi[j]] = xt;
+            }
+            uint16_t *dyt = reinterpret_cast<uint16_t *>(ws + w.dyt[j]);
+            peqa::TransposeJob &t = mg.tp[mg.n_tp++];
+            t.src = it.dY; t.dst = dyt; t.T = T; t.C = N; t.Tp = Tp;
+            tp_tiles += (Tp / 64) * (N / 64);
+            t.tile_end = tp_tiles;
+            peqa::DwArgs &a = dw.job[dw.n_jobs];
+            a.Xt = xt_of[xi[j]]; a.dYt = dyt; a.packed = it.packed; a.z0 = it.z0;
+            a.pc = reinterpret_cast<float *>(ws + w.pc[j]);
+            a.N = N; a.K = K; a.Tp = Tp; a.gsz = it.layout.group_size; a.G = G;
+            a.tiles_f = (K + 255) / 256; a.tiles_c = (N + 255) / 256;
+            dw.d_ds[dw.n_jobs++] = it.d_ds;
+        }
+    }
+    if (mg.n_jobs > 0 || mg.n_tp > 0) {
+        sort_jobs(mg);
+        place_aux(mg, 128);
+        if (peqa::launch_gemm_multi(bits, true, mg, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    }
+    if (dw.n_jobs > 0) {
+        if (peqa::launch_dw_multi(bits, dw, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_chunk_reduce_multi(dw, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
     return PEQA_OK;
 }

@@ -27,6 +27,8 @@
 // chunk_reduce_kernel adds the chunks of every group in order.  The loop runs at about 1.0 us per step
 // against 0.5 us for its matrix instructions and fragment reads alone in a test loop; the 32 KB of DMA per
 // step and compute unit are what is left to suspect, unconfirmed.
+#include <stddef.h>
+
 #include "peqa_device.h"
 #include "peqa_kernels.h"
 
@@ -59,9 +61,8 @@ __device__ __forceinline__ uint32_t code_at(const uint32_t *blk, int r, int cc)
 
 // WM = waves along the features (2: 128 x 128 wave tiles, one wave per SIMD; 4: 64 x 128, two per SIMD)
 template <int BITS, int WM>
-__global__ __launch_bounds__(128 * WM, 1) void dw_kernel(DwArgs a)
+__device__ __forceinline__ void dw_tile(const DwArgs &a, const int wg, uint8_t *lds)
 {
-    extern __shared__ __align__(16) uint8_t lds[];
     constexpr int WPB = 2 * BITS;
     constexpr int NRT = 16 / WM;                           // accumulator row tiles per wave
     constexpr int DW_DMA = 16 / WM;                        // DMA instructions per wave per step (32 of 1 KB per stage)
@@ -74,7 +75,6 @@ __global__ __launch_bounds__(128 * WM, 1) void dw_kernel(DwArgs a)
     // x 8 channel tiles, so that operand rows are shared through that XCD's L2
     int tile_f, tile_c;
     {
-        const int wg = blockIdx.x;
         const int xcd = wg & 7, local = wg >> 3;
         const int g = (local >> 5) * 8 + xcd, r = local & 31;
         const int patches_f = (a.tiles_f + 3) / 4;
@@ -223,6 +223,31 @@ __global__ __launch_bounds__(128 * WM, 1) void dw_kernel(DwArgs a)
     });
 }
 
+template <int BITS, int WM>
+__global__ __launch_bounds__(128 * WM, 1) void dw_kernel(DwArgs a)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    dw_tile<BITS, WM>(a, (int)blockIdx.x, lds);
+}
+
+// The token contractions of several layers in one launch: the tiles of job 0 first, then job 1's, ...  One layer's
+// tiles alone often fill the machine a fraction over a whole number of times (400 tiles of 256 x 256 on 256 compute
+// units for a 5120 x 5120 layer); together only the last round of the launch is partly filled.
+template <int BITS, int WM>
+__global__ __launch_bounds__(128 * WM, 1) void dw_multi_kernel(DwMultiArgs m)
+{
+    extern __shared__ __align__(16) uint8_t lds[];
+    const int b = (int)blockIdx.x;
+    int j = 0, wg0 = 0;
+#pragma unroll
+    for (int i = 0; i < DW_MAX_JOBS - 1; ++i) {
+        const int e = m.wg_end[i];
+        if (b >= e) { j = i + 1; wg0 = e; }
+    }
+    const DwArgs a = kernarg_load<DwArgs>((uint32_t)(j * sizeof(DwArgs)));
+    dw_tile<BITS, WM>(a, b - wg0, lds);
+}
+
 // transpose_pad_tile (peqa_device.h) for every 64 x 64 tile of src [T, C] (Tp / 64 x C / 64 workgroups).
 __global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t *__restrict__ src, int T, int C, int Tp,
                                                              uint16_t *__restrict__ dst)
@@ -242,10 +267,30 @@ __global__ __launch_bounds__(256) void chunk_reduce_kernel(const float *__restri
     d_ds[j] = s;
 }
 
+// chunk_reduce_kernel for the jobs of a dw_multi launch: blockIdx.y = job.
+__global__ __launch_bounds__(256) void chunk_reduce_multi_kernel(DwMultiArgs m)
+{
+    const DwArgs a = kernarg_load<DwArgs>((uint32_t)(blockIdx.y * sizeof(DwArgs)));
+    float *d_ds = m.d_ds[0];
+#pragma unroll
+    for (int i = 1; i < DW_MAX_JOBS; ++i)
+        if ((int)blockIdx.y == i) d_ds = m.d_ds[i];
+    const size_t n = (size_t)a.N * a.G;
+    const int per = a.gsz >> 6;
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    float s = 0.f;
+    for (int e = 0; e < per; ++e) s += a.pc[j * per + e];
+    d_ds[j] = s;
+}
+
 constexpr int kMaxDev = 64;
 bool g_attr_done[2][kMaxDev];
+bool g_attr_done_multi[2][kMaxDev];
 
 }  // namespace
+
+static bool dw_args_ok(const DwArgs &a);
 
 hipError_t launch_transpose_pad(const uint16_t *src, int T, int C, int Tp, uint16_t *dst, hipStream_t stream)
 {
@@ -258,9 +303,7 @@ hipError_t launch_transpose_pad(const uint16_t *src, int T, int C, int Tp, uint1
 hipError_t launch_dw(int bits, const DwArgs &a, hipStream_t stream)
 {
     // what the kernel's indexing assumes
-    if (a.K % 64 != 0 || a.N % 128 != 0 || a.Tp % 64 != 0 || a.Tp < 64 || a.gsz % 64 != 0 || a.K % a.gsz != 0)
-        return hipErrorInvalidValue;
-    if ((uint64_t)(a.K > a.N ? a.K : a.N) * 64u >= ((uint64_t)1 << 32)) return hipErrorInvalidValue;   // 32-bit DMA offsets
+    if (!dw_args_ok(a)) return hipErrorInvalidValue;
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -279,6 +322,58 @@ hipError_t launch_dw(int bits, const DwArgs &a, hipStream_t stream)
     trace_before(KID_GEMM_DW, stream);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(128 * DW_WM), DW_LDS, stream, a);
     trace_after(KID_GEMM_DW, stream);
+    return hipGetLastError();
+}
+
+static bool dw_args_ok(const DwArgs &a)
+{
+    if (a.K % 64 != 0 || a.N % 128 != 0 || a.Tp % 64 != 0 || a.Tp < 64 || a.gsz % 64 != 0 || a.K % a.gsz != 0) return false;
+    return (uint64_t)(a.K > a.N ? a.K : a.N) * 64u < ((uint64_t)1 << 32);   // 32-bit DMA offsets
+}
+
+hipError_t launch_dw_multi(int bits, DwMultiArgs &m, hipStream_t stream)
+{
+    if (m.n_jobs < 1 || m.n_jobs > DW_MAX_JOBS) return hipErrorInvalidValue;
+    int total = 0;
+    for (int j = 0; j < DW_MAX_JOBS; ++j) {
+        if (j < m.n_jobs) {
+            const DwArgs &a = m.job[j];
+            if (!dw_args_ok(a)) return hipErrorInvalidValue;
+            const int patches_f = (a.tiles_f + 3) / 4, patches_c = (a.tiles_c + 7) / 8;
+            total += ((patches_f * patches_c + 7) / 8) * 8 * 32;
+        } else {
+            m.job[j] = m.job[m.n_jobs - 1];
+            m.d_ds[j] = m.d_ds[m.n_jobs - 1];
+        }
+        m.wg_end[j] = total;
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+    auto kern = bits == 4 ? dw_multi_kernel<4, DW_WM> : dw_multi_kernel<3, DW_WM>;
+    bool &done = g_attr_done_multi[bits == 4][dev];
+    if (!done) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, DW_LDS);
+        if (e != hipSuccess) return e;
+        done = true;
+    }
+    trace_before(KID_GEMM_DW, stream);
+    hipLaunchKernelGGL(kern, dim3(total), dim3(128 * DW_WM), DW_LDS, stream, m);
+    trace_after(KID_GEMM_DW, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_chunk_reduce_multi(const DwMultiArgs &m, hipStream_t stream)
+{
+    size_t nmax = 0;
+    for (int j = 0; j < m.n_jobs; ++j) {
+        const size_t n = (size_t)m.job[j].N * m.job[j].G;
+        nmax = n > nmax ? n : nmax;
+    }
+    trace_before(KID_REDUCE, stream);
+    hipLaunchKernelGGL(chunk_reduce_multi_kernel, dim3((unsigned)((nmax + 255) / 256), m.n_jobs), dim3(256), 0, stream, m);
+    trace_after(KID_REDUCE, stream);
     return hipGetLastError();
 }
 

@@ -243,6 +243,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
         dma16(lane * 16, src, lds_base + tbl_off + (B & 1) * tbuf + ((ALONG_CH && fine) ? wt * 1024 : 0));
     };
     const bool table_wave = wt == 0 || (ALONG_CH && fine);
+    // The next block is fetched at the step m with (m & tbl_mask) == tbl_phase: its second step when a block has four,
+    // its first when it has two; never by the other waves.  Both wave-uniform, and said so, which makes the test one
+    // scalar compare that keeps no vector register.
+    // (Along channels the same form costs registers instead: the plain test stays there.)
+    const int tbl_mask = (1 << bshift) - 1;
+    const int tbl_phase = ALONG_CH ? 0 : __builtin_amdgcn_readfirstlane(table_wave ? (bshift == 2 ? 1 : 0) : -1);
+    auto next_table_at = [&](int m) __attribute__((always_inline)) -> bool {
+        if constexpr (ALONG_CH) return (m & tbl_mask) == (bshift == 2 ? 1 : 0) && table_wave;
+        else return (m & tbl_mask) == tbl_phase;
+    };
     // Entries of contraction step m for this lane's 8 block channels: along features 8 c .. 8 c + 7 of
     // block m / 4, along channels 32 (m % 4) + 8 q .. + 7.  Along channels every fragment needs all
     // eight (element e of a fragment is channel e): they are read into registers once per step.
@@ -404,7 +414,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
             // after m's into it.  With blocks of four steps this is done at the block's second step
             // (three steps of lead); with blocks of two, at its first (two steps: the DMA is complete
             // after the next step's wait and visible after its barrier, just in time).
-            if ((m & ((1 << bshift) - 1)) == (bshift == 2 ? 1 : 0) && table_wave) issue_table((m >> bshift) + 1);
+            if (next_table_at(m)) issue_table((m >> bshift) + 1);
         }
         BlockUnpacker<BITS, ALONG_CH> up;
         up.prepare(bw[CUR]);
@@ -469,7 +479,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
             // after m's into it.  With blocks of four steps this is done at the block's second step
             // (three steps of lead); with blocks of two, at its first (two steps: the DMA is complete
             // after the next step's wait and visible after its barrier, just in time).
-            if ((m & ((1 << bshift) - 1)) == (bshift == 2 ? 1 : 0) && table_wave) issue_table((m >> bshift) + 1);
+            if (next_table_at(m)) issue_table((m >> bshift) + 1);
         }
         BlockUnpacker<BITS, ALONG_CH> up;
         up.prepare(bw[CUR]);
@@ -772,14 +782,28 @@ __global__ __launch_bounds__(256, 2) void gemm_bwd_pair_kernel(GemmArgs a_dds, G
 // units w, w + aux_wgs, ... of one index space: first the SDY_ROWS-row blocks of the scale_dy jobs, then the
 // 256-element chunks of the reduce jobs.
 static_assert(SDY_ROWS == SDY_ROWS_HOST, "row blocks of scale_dy_rows");
-__device__ __forceinline__ void multi_aux(int n_sdy, int n_red, int aux_wgs, int w, uint8_t *lds)
+__device__ __forceinline__ void multi_aux(int n_sdy, int n_red, int n_tp, int aux_wgs, int w, uint8_t *lds)
 {
-    struct { int n_sdy, n_red, aux_wgs; } m{n_sdy, n_red, aux_wgs};
+    struct { int n_sdy, n_red, n_tp, aux_wgs; } m{n_sdy, n_red, n_tp, aux_wgs};
     float *red = reinterpret_cast<float *>(lds);
-    constexpr uint32_t SDY0 = offsetof(MultiArgs, sdy), RED0 = offsetof(MultiArgs, red);
+    constexpr uint32_t SDY0 = offsetof(MultiArgs, sdy), RED0 = offsetof(MultiArgs, red), TP0 = offsetof(MultiArgs, tp);
     const int n_blk = m.n_sdy > 0 ? kernarg_load<int>(SDY0 + (uint32_t)((m.n_sdy - 1) * sizeof(ScaleDyJob) + offsetof(ScaleDyJob, blk_end))) : 0;
     const int n_chunk = m.n_red > 0 ? kernarg_load<int>(RED0 + (uint32_t)((m.n_red - 1) * sizeof(ReduceJob) + offsetof(ReduceJob, chunk_end))) : 0;
-    for (int u = w; u < n_blk + n_chunk; u += m.aux_wgs) {
+    const int n_tile = m.n_tp > 0 ? kernarg_load<int>(TP0 + (uint32_t)((m.n_tp - 1) * sizeof(TransposeJob) + offsetof(TransposeJob, tile_end))) : 0;
+    for (int u = w; u < n_blk + n_chunk + n_tile; u += m.aux_wgs) {
+        if (u >= n_blk + n_chunk) {
+            const int x = u - n_blk - n_chunk;
+            int j = 0, x0 = 0;
+            for (int i = 0; i + 1 < m.n_tp; ++i) {
+                const int e = kernarg_load<int>(TP0 + (uint32_t)(i * sizeof(TransposeJob) + offsetof(TransposeJob, tile_end)));
+                if (x >= e) { j = i + 1; x0 = e; }
+            }
+            const TransposeJob J = kernarg_load<TransposeJob>(TP0 + (uint32_t)(j * sizeof(TransposeJob)));
+            const int bts = J.Tp >> 6;
+            transpose_pad_tile(J.src, J.T, J.C, J.dst, (x - x0) % bts, (x - x0) / bts, reinterpret_cast<uint16_t(*)[64 + 2]>(lds));
+            __syncthreads();                                   // the LDS tile is reused by the next one
+            continue;
+        }
         if (u < n_blk) {
             int j = 0, b0 = 0;
             for (int i = 0; i + 1 < m.n_sdy; ++i) {
@@ -804,17 +828,21 @@ __device__ __forceinline__ void multi_aux(int n_sdy, int n_red, int aux_wgs, int
 
 // Several per-channel contractions as four-wave tiles of one launch (see MultiArgs): workgroup -> (job, tile) by the
 // jobs' running totals; the job's arguments come out of the argument block with scalar loads.
-template <int BITS>
+// GMODE < 0: per-channel jobs of any mode; GMODE = MODE_Y or MODE_DX: group-wise jobs, all of that mode (their
+// scale gradient is the token contraction of peqa_dw.hip).
+template <int BITS, int GMODE>
 __global__ __launch_bounds__(256, 2) void gemm_multi_kernel(MultiArgs m)
 {
     extern __shared__ __align__(16) uint8_t lds[];
     int b = (int)blockIdx.x;
-    if (b >= m.aux_begin) {
-        if (b < m.aux_begin + m.aux_wgs) {
-            multi_aux(m.n_sdy, m.n_red, m.aux_wgs, b - m.aux_begin, lds);
-            return;
+    if constexpr (GMODE != MODE_Y) {                           // a group-wise forward has no side work
+        if (b >= m.aux_begin) {
+            if (b < m.aux_begin + m.aux_wgs) {
+                multi_aux(m.n_sdy, m.n_red, m.n_tp, m.aux_wgs, b - m.aux_begin, lds);
+                return;
+            }
+            b -= m.aux_wgs;
         }
-        b -= m.aux_wgs;
     }
     int j = 0, wg0 = 0;
 #pragma unroll
@@ -822,11 +850,15 @@ __global__ __launch_bounds__(256, 2) void gemm_multi_kernel(MultiArgs m)
         const int e = kernarg_load<int>((uint32_t)(i * sizeof(MultiJob) + offsetof(MultiJob, wg_end)));
         if (b >= e) { j = i + 1; wg0 = e; }
     }
-    const int mode = kernarg_load<int>((uint32_t)(j * sizeof(MultiJob) + offsetof(MultiJob, mode)));
     const GemmArgs a = kernarg_load<GemmArgs>((uint32_t)(j * sizeof(MultiJob) + offsetof(MultiJob, a)));
-    if (mode == MODE_Y) gemm_tile<BITS, MODE_Y, false, 1>(a, b - wg0, lds);
-    else if (mode == MODE_DDS) gemm_tile<BITS, MODE_DDS, false, 1>(a, b - wg0, lds);
-    else gemm_tile<BITS, MODE_DX, false, 1>(a, b - wg0, lds);
+    if constexpr (GMODE >= 0) {
+        gemm_tile<BITS, GMODE, true, 1>(a, b - wg0, lds);
+    } else {
+        const int mode = kernarg_load<int>((uint32_t)(j * sizeof(MultiJob) + offsetof(MultiJob, mode)));
+        if (mode == MODE_Y) gemm_tile<BITS, MODE_Y, false, 1>(a, b - wg0, lds);
+        else if (mode == MODE_DDS) gemm_tile<BITS, MODE_DDS, false, 1>(a, b - wg0, lds);
+        else gemm_tile<BITS, MODE_DX, false, 1>(a, b - wg0, lds);
+    }
 }
 
 }  // namespace
@@ -951,18 +983,40 @@ int gemm_multi_wgs(int tiles_t, int tiles_c)
     return ((patches + 7) / 8) * 8 * 32;
 }
 
-hipError_t launch_gemm_multi(int bits, MultiArgs &m, hipStream_t stream)
+template <int BITS, int GMODE>
+static hipError_t launch_multi(dim3 grid, int lds_bytes, const MultiArgs &m, hipStream_t stream)
+{
+    static int attr_bytes[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (attr_bytes[dev] < lds_bytes) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_multi_kernel<BITS, GMODE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_bytes[dev] = lds_bytes;
+    }
+    hipLaunchKernelGGL((gemm_multi_kernel<BITS, GMODE>), grid, dim3(256), lds_bytes, stream, m);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_multi(int bits, bool grouped, MultiArgs &m, hipStream_t stream)
 {
     if (m.n_jobs < 0 || m.n_jobs > MULTI_MAX_JOBS || m.n_sdy < 0 || m.n_sdy > MULTI_MAX_JOBS || m.n_red < 0 ||
-        m.n_red > MULTI_MAX_JOBS)
+        m.n_red > MULTI_MAX_JOBS || m.n_tp < 0 || m.n_tp > 2 * MULTI_MAX_JOBS)
         return hipErrorInvalidValue;
-    int total = 0;
+    int total = 0, lds_bytes = ring_bytes(1);
     for (int j = 0; j < MULTI_MAX_JOBS; ++j) {
         if (j < m.n_jobs) {
             GemmArgs &a = m.job[j].a;
-            if (a.gsz > 0 || a.tp_blocks) return hipErrorInvalidValue;
+            if ((a.gsz > 0) != grouped || a.tp_blocks) return hipErrorInvalidValue;
+            if (grouped && m.job[j].mode == MODE_DDS) return hipErrorInvalidValue;
             a.patch_t = a.tiles_t >= 4 ? 4 : (a.tiles_t >= 2 ? 2 : 1);
             total += gemm_multi_wgs(a.tiles_t, a.tiles_c);
+            // group-wise: the scale tables behind the ring (twice as large for dX when groups end inside a 128-feature run)
+            if (grouped) {
+                const int need = ring_bytes(1) + (m.job[j].mode == MODE_DX && (a.gsz & 127) ? 2 : 1) * tbl_bytes(1);
+                lds_bytes = need > lds_bytes ? need : lds_bytes;
+            }
         } else {
             m.job[j] = m.job[m.n_jobs > 0 ? m.n_jobs - 1 : 0];
         }
@@ -970,24 +1024,21 @@ hipError_t launch_gemm_multi(int bits, MultiArgs &m, hipStream_t stream)
     }
     if ((m.aux_begin & 7) || (m.aux_wgs & 7) || m.aux_begin < 0 || m.aux_begin > total) return hipErrorInvalidValue;
     if (total + m.aux_wgs == 0) return hipSuccess;
-    const int lds_bytes = ring_bytes(1);
-    static int attr_bytes[2][64] = {{0}};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-    const void *f = bits == 4 ? reinterpret_cast<const void *>(&gemm_multi_kernel<4>)
-                              : reinterpret_cast<const void *>(&gemm_multi_kernel<3>);
-    if (attr_bytes[bits == 4][dev] < lds_bytes) {
-        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_bytes[bits == 4][dev] = lds_bytes;
-    }
     const int mode0 = m.n_jobs > 0 ? m.job[0].mode : MODE_DX;
+    if (grouped) {
+        for (int j = 0; j < m.n_jobs; ++j)
+            if (m.job[j].mode != mode0) return hipErrorInvalidValue;
+        if (mode0 == MODE_Y && m.aux_wgs != 0) return hipErrorInvalidValue;
+    }
     const int kid = mode0 == MODE_Y ? KID_GEMM_MULTI_Y : (mode0 == MODE_DDS ? KID_GEMM_MULTI_DDS : KID_GEMM_MULTI_DX);
     trace_before(kid, stream);
-    if (bits == 4) hipLaunchKernelGGL((gemm_multi_kernel<4>), dim3(total + m.aux_wgs), dim3(256), lds_bytes, stream, m);
-    else hipLaunchKernelGGL((gemm_multi_kernel<3>), dim3(total + m.aux_wgs), dim3(256), lds_bytes, stream, m);
+    const dim3 grid(total + m.aux_wgs);
+    hipError_t e;
+    if (!grouped) e = bits == 4 ? launch_multi<4, -1>(grid, lds_bytes, m, stream) : launch_multi<3, -1>(grid, lds_bytes, m, stream);
+    else if (mode0 == MODE_Y) e = bits == 4 ? launch_multi<4, MODE_Y>(grid, lds_bytes, m, stream) : launch_multi<3, MODE_Y>(grid, lds_bytes, m, stream);
+    else e = bits == 4 ? launch_multi<4, MODE_DX>(grid, lds_bytes, m, stream) : launch_multi<3, MODE_DX>(grid, lds_bytes, m, stream);
     trace_after(kid, stream);
-    return hipGetLastError();
+    return e;
 }
 
 hipError_t launch_gemm_bwd_pair(int bits, const GemmArgs &dds_in, const GemmArgs &dx_in, hipStream_t stream)

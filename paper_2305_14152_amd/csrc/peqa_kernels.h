@@ -63,7 +63,8 @@ hipError_t launch_gemm_bwd_pair(int bits, const GemmArgs &a_dds, const GemmArgs 
 // job 1's, ... (the caller orders them by contraction length, longest first, so that the last, partly filled round
 // of the launch is made of short tiles).  Per-channel layers only.  Workgroups numbered [aux_begin, aux_begin +
 // aux_wgs) do bandwidth-bound side work of the same backward instead of a tile: every one of them walks a share
-// of the row blocks of the scale_dy jobs, or of the 256-element chunks of the reduce jobs.  They sit in the middle
+// of the row blocks of the scale_dy jobs, of the 256-element chunks of the reduce jobs, or of the 64 x 64 tiles of
+// the transpose jobs (the operands of the token contraction of group-wise layers).  They sit in the middle
 // of the grid, where they start while most compute units still run tiles, so that their memory traffic hides
 // behind matrix work.  All job sizes, aux_begin and aux_wgs are multiples of 8 (workgroup id % 8 = XCD throughout).
 constexpr int MULTI_MAX_JOBS = 8;
@@ -88,14 +89,23 @@ struct ReduceJob {            // out[j] = sum over ntiles of partial[tile][j], f
     int ntiles, n;
     int chunk_end;            // 256-element chunks of this job and all before it
 };
+struct TransposeJob {         // dst[t / 32][c][t % 32] = src[t, c], zero-padded to Tp tokens      (transpose_pad_tile)
+    const uint16_t *src;
+    uint16_t *dst;
+    int T, C, Tp;
+    int tile_end;             // 64 x 64 tiles of this job and all before it
+};
 struct MultiArgs {
     MultiJob job[MULTI_MAX_JOBS];          // must stay the first member: indexed in the argument block
     ScaleDyJob sdy[MULTI_MAX_JOBS];
     ReduceJob red[MULTI_MAX_JOBS];
-    int n_jobs, n_sdy, n_red;
+    TransposeJob tp[2 * MULTI_MAX_JOBS];
+    int n_jobs, n_sdy, n_red, n_tp;
     int aux_begin, aux_wgs;
 };
-hipError_t launch_gemm_multi(int bits, MultiArgs &m, hipStream_t stream);
+// Per-channel jobs (any mode), or, with `grouped`, group-wise MODE_Y / MODE_DX jobs (their tables in a.sb).
+static_assert(sizeof(MultiArgs) <= 4096, "kernel argument block");
+hipError_t launch_gemm_multi(int bits, bool grouped, MultiArgs &m, hipStream_t stream);
 // workgroups a contraction's tiles take in such a launch (a multiple of 8: whole XCD patches)
 int gemm_multi_wgs(int tiles_t, int tiles_c);
 
@@ -115,6 +125,26 @@ struct DwArgs {
 hipError_t launch_transpose_pad(const uint16_t *src, int T, int C, int Tp, uint16_t *dst, hipStream_t stream);
 hipError_t launch_dw(int bits, const DwArgs &a, hipStream_t stream);
 hipError_t launch_chunk_reduce(const float *pc, size_t n, int per, float *d_ds, hipStream_t stream);
+// The token contractions of up to DW_MAX_JOBS layers in one launch, and the sums of their chunks in another.
+constexpr int DW_MAX_JOBS = 8;
+struct DwMultiArgs {
+    DwArgs job[DW_MAX_JOBS];               // must stay the first member: indexed in the argument block
+    int wg_end[DW_MAX_JOBS];               // workgroups of job j and all before it (unused entries: the total)
+    float *d_ds[DW_MAX_JOBS];              // [N, G] out of the chunk sums
+    int n_jobs;
+};
+hipError_t launch_dw_multi(int bits, DwMultiArgs &m, hipStream_t stream);
+hipError_t launch_chunk_reduce_multi(const DwMultiArgs &m, hipStream_t stream);
+// The (s, b) tables of up to GT_MAX layers in one launch.
+constexpr int GT_MAX = 8;
+struct GroupTableMulti {
+    const float *s0[GT_MAX], *ds[GT_MAX];
+    const uint8_t *z0[GT_MAX];
+    float *sb[GT_MAX];
+    int N[GT_MAX], G[GT_MAX];
+    int n;
+};
+hipError_t launch_group_table_multi(const GroupTableMulti &a, hipStream_t stream);
 
 // Arguments of the T <= 16 forward (peqa_gemv.hip): up to GEMV_MAX_LAYERS layers in one launch, laid side by
 // side along the workgroup index.  Every layer has its own shape, input and slicing, so that the linears of a

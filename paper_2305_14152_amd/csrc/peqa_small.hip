@@ -111,6 +111,26 @@ __global__ __launch_bounds__(256) void group_table_kernel(const float *__restric
     o[1] = -s * (kCodeOffset + (float)z0[j] + (dz ? dz[j] : 0.f));
 }
 
+// group_table_kernel for several layers: blockIdx.y = layer.
+__global__ __launch_bounds__(256) void group_table_multi_kernel(GroupTableMulti a)
+{
+    const int y = blockIdx.y;
+    const float *s0 = a.s0[0], *ds = a.ds[0];
+    const uint8_t *z0 = a.z0[0];
+    float *sb = a.sb[0];
+    int N = a.N[0], G = a.G[0];
+#pragma unroll
+    for (int i = 1; i < GT_MAX; ++i)
+        if (y == i) { s0 = a.s0[i]; ds = a.ds[i]; z0 = a.z0[i]; sb = a.sb[i]; N = a.N[i]; G = a.G[i]; }
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;   // = n * G + g
+    if (j >= (size_t)N * G) return;
+    const size_t n = j / G, g = j - n * G;
+    const float s = ds ? s0[j] + ds[j] : s0[j];
+    float *o = sb + (g * N + n) * 2;
+    o[0] = s;
+    o[1] = -s * (kCodeOffset + (float)z0[j]);
+}
+
 // scale_dy_rows (peqa_device.h) for every block of SDY_ROWS token rows.  Workgroups past the last row block do an
 // independent job in the same launch: the fixed-order sum of the scale-gradient partials (n_red = 0: none),
 // which the backward needs between its two contractions too.
@@ -321,6 +341,19 @@ hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z
     const size_t n = (size_t)N * G;
     hipLaunchKernelGGL(group_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, ds, z0, dz, N, G,
                        sb);
+    trace_after(KID_GROUP_TABLE, stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_group_table_multi(const GroupTableMulti &a, hipStream_t stream)
+{
+    size_t nmax = 0;
+    for (int i = 0; i < a.n; ++i) {
+        const size_t n = (size_t)a.N[i] * a.G[i];
+        nmax = n > nmax ? n : nmax;
+    }
+    trace_before(KID_GROUP_TABLE, stream);
+    hipLaunchKernelGGL(group_table_multi_kernel, dim3((unsigned)((nmax + 255) / 256), a.n), dim3(256), 0, stream, a);
     trace_after(KID_GROUP_TABLE, stream);
     return hipGetLastError();
 }

@@ -167,6 +167,8 @@ struct GemvArgs {
     GemvLayer layer[GEMV_MAX_LAYERS];   // must stay the first member: the kernels index it in the argument block
     int n_layers;
     int T;
+    int second_from;                    // workgroups from this index on are taken to be the second on their compute
+                                        // unit (set by launch_gemv: the number of compute units)
 };
 // zbyte: no layer of the launch has a trained zero-point offset, so zero-points stay bytes in LDS and a slice may
 // span more scale groups

@@ -207,3 +207,86 @@ def test_block_is_deterministic(gpu, oracle):
         assert (gpu.to_host(da["d_ds"]).view(np.uint32) == gpu.to_host(db["d_ds"]).view(np.uint32)).all()
         assert (gpu.to_host(da["dX"]) == gpu.to_host(db["dX"])).all()
         assert (gpu.to_host(da["Y"]) == gpu.to_host(db["Y"])).all()
+
+
+@pytest.mark.parametrize("bits,group", [(3, 128), (4, 192), (4, 64)])
+def test_block_groupwise_skips_and_shared_inputs(gpu, oracle, bits, group):
+    """Group-wise members of one backward call: some want only dX, some only the scale gradient (among them members
+    that read one X, whose transposed copy is made once), and a call in which nobody wants dX (its launch then has
+    no tiles, only the workgroups that write the transposed copies).  Twice, for the same bits."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    T = 170
+    K = 3 * group * 2 if group != 64 else 512
+    print("block group-wise skips bits=%d g=%d K=%d" % (bits, group, K), flush=True)
+    X = synth.normal_bf16(39000 + group, (T, K), 1.0)
+    members = [Member(gpu, oracle, 39100 + 100 * j + group, bits, N, K, group, T, X=(X if shared else None), with_ds=(j != 1))
+               for j, (N, shared) in enumerate(((256, True), (384, True), (128, False), (256, True)))]
+    wants = ((True, False), (False, True), (True, True), (False, True))        # (dX, d_ds) per member
+    for only_grad in (False, True):
+        results = []
+        for rep in range(2):
+            Xd = gpu.to_dev(X)
+            dicts = []
+            for m, (want_dx, want_g) in zip(members, wants):
+                want_dx = want_dx and not only_grad
+                dicts.append(dict(L=m.layer.L, packed=m.layer.packed, s0=m.layer.s0, z0=m.layer.z0, ds=m.dsd,
+                                  X=Xd if m.X is X else gpu.to_dev(m.X), dY=gpu.to_dev(m.dY), Y=None,
+                                  dX=torch.full((T, m.K), 7, dtype=torch.int16, device="cuda") if want_dx else None,
+                                  d_ds=torch.full(m.s0.shape, 7.0, dtype=torch.float32, device="cuda") if want_g else None))
+            items = peqa.block_items(dicts)
+            nb = peqa.block_workspace_bytes(items, T, peqa.PEQA_OP_BWD)
+            ws = torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda")
+            peqa.block_bwd(items, T, ws, nb)
+            torch.cuda.synchronize()
+            results.append(dicts)
+        for m, d, d2 in zip(members, results[0], results[1]):
+            dXref, gref, _ = oracle.bwd(m.codes, m.s0, m.ds, m.z0, m.X, m.dY, group)
+            if d["dX"] is not None:
+                assert np.abs(gpu.bf16_dev_to_f64(d["dX"]) - dXref).max() <= Y_TOL * np.abs(dXref).max(), (m.N, only_grad)
+                assert (gpu.to_host(d["dX"]) == gpu.to_host(d2["dX"])).all()
+            if d["d_ds"] is not None:
+                gpu.assert_scale_grad_close(gpu.to_host(d["d_ds"]), gref)
+                assert (gpu.to_host(d["d_ds"]).view(np.uint32) == gpu.to_host(d2["d_ds"]).view(np.uint32)).all()
+
+
+def test_block_groupwise_graph_capture(gpu, oracle):
+    """The block calls on group-wise layers captured in a HIP graph: replays equal the eager results bit for bit."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    T = 200
+    members = [Member(gpu, oracle, 39500 + 100 * j, 3, N, K, 128, T) for j, (N, K) in enumerate(((384, 512), (256, 1152), (128, 256)))]
+    dicts = []
+    for m in members:
+        dicts.append(dict(L=m.layer.L, packed=m.layer.packed, s0=m.layer.s0, z0=m.layer.z0, ds=m.dsd, X=gpu.to_dev(m.X),
+                          Y=torch.zeros((T, m.N), dtype=torch.int16, device="cuda"), dY=gpu.to_dev(m.dY),
+                          dX=torch.zeros((T, m.K), dtype=torch.int16, device="cuda"),
+                          d_ds=torch.zeros(m.s0.shape, dtype=torch.float32, device="cuda")))
+    items = peqa.block_items(dicts)
+    nb = max(peqa.block_workspace_bytes(items, T, op) for op in (peqa.PEQA_OP_FWD, peqa.PEQA_OP_BWD))
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+
+    def run(stream):
+        peqa.block_fwd(items, T, ws, nb, stream)
+        peqa.block_bwd(items, T, ws, nb, stream)
+
+    outs = [d[k] for d in dicts for k in ("Y", "dX", "d_ds")]
+    run(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=torch.cuda.Stream()):
+        run(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        for t in outs:
+            t.fill_(7)
+        ws.fill_(rep)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for t, w in zip(outs, want):
+            assert (t == w).all(), rep
+    for m, d in zip(members, dicts):
+        dXref, gref, _ = oracle.bwd(m.codes, m.s0, m.ds, m.z0, m.X, m.dY, 128)
+        assert np.abs(gpu.bf16_dev_to_f64(d["dX"]) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+        gpu.assert_scale_grad_close(gpu.to_host(d["d_ds"]), gref)

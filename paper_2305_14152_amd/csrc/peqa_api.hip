@@ -238,7 +238,7 @@ static peqa_status fwd_impl(const peqa_layout *L, const uint32_t *packed, const 
     }
     if (grouped(L)) {
         float *sb = reinterpret_cast<float *>(ws + w.table);
-        if (peqa::launch_group_table(s0, ds, z0, dz, N, groups(L), sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+        if (peqa::launch_group_table(s0, ds, z0, dz, N, groups(L), false, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
         peqa::GemmArgs a{};
         a.packed = packed; a.A = X; a.T = T; a.KC = K; a.C = N; a.K = K;
         a.tiles_c = (N + 255) / 256; a.tiles_t = (T + 127) / 128;
@@ -500,11 +500,14 @@ static peqa_status bwd_impl(const peqa_layout *L, const uint32_t *packed, const 
         const bool tp_in_dx = d_ds && by_tokens && dX && peqa::gemm_four_waves(tiles_t * ((K + 255) / 256));
         auto run_dx = [&](bool with_transposes) -> peqa_status {
             float *sb = reinterpret_cast<float *>(ws + w.table);
-            if (peqa::launch_group_table(s0, ds, z0, dz, N, G, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
+            // four-wave tiles of a group size that is a multiple of 128, integer zero-points: the scale goes on the
+            // activation side
+            const bool a_side = L->group_size % 128 == 0 && !dz && peqa::gemm_four_waves(tiles_t * ((K + 255) / 256));
+            if (peqa::launch_group_table(s0, ds, z0, dz, N, G, a_side, sb, s) != hipSuccess) return PEQA_ERR_DEVICE;
             peqa::GemmArgs a{};
             a.packed = packed; a.A = dY; a.T = T; a.KC = N; a.C = K; a.K = K;
             a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
-            a.N = N; a.gsz = L->group_size; a.G = G; a.sb = sb; a.out = dX;
+            a.N = N; a.gsz = L->group_size; a.G = G; a.sb = sb; a.out = dX; a.a_side = a_side;
             if (with_transposes) {
                 a.tp_blocks = (Tp / 64) * (K / 64 + N / 64); a.tp_Tp = Tp; a.tp_X = X; a.tp_Xt = xt; a.tp_dYt = dyt;
             }

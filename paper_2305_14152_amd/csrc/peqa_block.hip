@@ -103,7 +103,11 @@ void place_aux(peqa::MultiArgs &m, int aux_wgs)
     m.aux_wgs = (m.n_sdy > 0 || m.n_red > 0 || m.n_tp > 0) ? aux_wgs : 0;
 }
 
-// (s, b) tables of every group-wise item: one launch.
+// The dX tiles of a group-wise layer whose group size is a multiple of 128 scale their activation fragments (the tiles
+// of the multi-contraction launches are all of the four-wave form, and block items have integer zero-points).
+bool a_side(const peqa_layout *L) { return L->group_size > 0 && L->group_size % 128 == 0; }
+
+// Tables of every group-wise item (of those whose dX is wanted, in the form their dX tiles read, if only_dx): one launch.
 peqa_status group_tables(int32_t n, const peqa_block_item *items, uint8_t *ws, const BlockSpace &w, bool only_dx,
                          hipStream_t s)
 {
@@ -115,10 +119,12 @@ peqa_status group_tables(int32_t n, const peqa_block_item *items, uint8_t *ws, c
         gt.s0[i] = it.s0; gt.ds[i] = it.ds; gt.z0[i] = it.z0;
         gt.sb[i] = reinterpret_cast<float *>(ws + w.table[j]);
         gt.N[i] = it.layout.n_out; gt.G[i] = groups(&it.layout);
+        gt.a_side[i] = only_dx && a_side(&it.layout);
     }
     if (gt.n == 0) return PEQA_OK;
     for (int i = gt.n; i < peqa::GT_MAX; ++i) {
         gt.s0[i] = gt.s0[0]; gt.ds[i] = gt.ds[0]; gt.z0[i] = gt.z0[0]; gt.sb[i] = gt.sb[0]; gt.N[i] = gt.N[0]; gt.G[i] = gt.G[0];
+        gt.a_side[i] = gt.a_side[0];
     }
     return dev_status(peqa::launch_group_table_multi(gt, s));
 }
@@ -334,7 +340,7 @@ peqa_status peqa_block_bwd(int32_t n, const peqa_block_item *items, int32_t T, v
     // the token contractions of all scale gradients in one launch; the sums of their chunks in one launch.
     st = group_tables(n, items, ws, w, true, s);
     if (st != PEQA_OK) return st;
-    peqa::MultiArgs mg{};
+    peqa::MultiArgs mg{}, mg2{};                          // dX jobs that scale their activation fragments; the others
     peqa::DwMultiArgs dw{};
     const uint16_t *xt_of[PEQA_MAX_BLOCK] = {nullptr};
     int tp_tiles = 0;
@@ -343,12 +349,13 @@ peqa_status peqa_block_bwd(int32_t n, const peqa_block_item *items, int32_t T, v
         if (!grouped(&it.layout)) continue;
         const int N = it.layout.n_out, K = it.layout.k_in, G = groups(&it.layout);
         if (it.dX) {
-            peqa::MultiJob &job = mg.job[mg.n_jobs++];
+            peqa::MultiArgs &dst = a_side(&it.layout) ? mg : mg2;
+            peqa::MultiJob &job = dst.job[dst.n_jobs++];
             job.mode = peqa::MODE_DX;
             peqa::GemmArgs &a = job.a;
             a.packed = it.packed; a.A = it.dY; a.T = T; a.KC = N; a.C = K; a.K = K;
             a.tiles_c = (K + 255) / 256; a.tiles_t = tiles_t;
-            a.N = N; a.gsz = it.layout.group_size; a.G = G;
+            a.N = N; a.gsz = it.layout.group_size; a.G = G; a.a_side = a_side(&it.layout);
             a.sb = reinterpret_cast<const float *>(ws + w.table[j]); a.out = it.dX;
         }
         if (it.d_ds) {
@@ -377,6 +384,11 @@ peqa_status peqa_block_bwd(int32_t n, const peqa_block_item *items, int32_t T, v
         sort_jobs(mg);
         place_aux(mg, 128);
         if (peqa::launch_gemm_multi(bits, true, mg, s) != hipSuccess) return PEQA_ERR_DEVICE;
+    }
+    if (mg2.n_jobs > 0) {
+        sort_jobs(mg2);
+        place_aux(mg2, 0);
+        if (peqa::launch_gemm_multi(bits, true, mg2, s) != hipSuccess) return PEQA_ERR_DEVICE;
     }
     if (dw.n_jobs > 0) {
         if (peqa::launch_dw_multi(bits, dw, s) != hipSuccess) return PEQA_ERR_DEVICE;

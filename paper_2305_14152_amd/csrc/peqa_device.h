@@ -52,6 +52,30 @@ __device__ __forceinline__ uint32_t scale_pair(uint32_t pair, float s_lo, float 
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// A pair of bf16 times a pair of fp32 factors, rounded once (to nearest even) back to a bf16 pair.
+__device__ __forceinline__ uint32_t mul_pair(uint32_t pair, float s_lo, float s_hi)
+{
+    f32x2 v;
+    v[0] = __uint_as_float(pair << 16) * s_lo;
+    v[1] = __uint_as_float(pair & 0xFFFF0000u) * s_hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Two fp32 rounded (to nearest even) to a bf16 pair: one conversion instruction.
+__device__ __forceinline__ uint32_t cvt_pair(float lo, float hi)
+{
+    f32x2 v;
+    v[0] = lo;
+    v[1] = hi;
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// c + a.lo * b.lo + a.hi * b.hi of two bf16 pairs, in fp32 (v_dot2c_f32_bf16).
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
+
 // ((x shifted) & mask) | magic in two VALU ops (one when no shift is needed).  mask rides the
 // constant bus (SGPR), magic a VGPR.  Volatile assembly, shift included, so that the unpacking
 // stays exactly where the caller interleaves it with matrix instructions.

@@ -63,14 +63,22 @@ constexpr int tbl_bytes(int kw) { return 2 * kw * 2 * 1024; }           // group
                                                                         // twice that for MODE_DX when groups end inside a 128-feature run
 
 // One tile of one contraction: the work of workgroup number `wg` of a launch of this contraction alone.
-template <int BITS, int MODE, bool GROUPED, int KW>
+// ASCALE (group-wise dX in the four-wave form, group size a multiple of 128, integer zero-points): every wave's 128
+// feature columns lie in one scale group g, so the scale s[i, g] varies along the contraction only and is applied to the
+// activation fragments in registers, A_g[t,i] = bf16(dY[t,i] s[i,g]): 16 registers per step instead of the 32 of the
+// weight fragments.  The codes are contracted as the exact integers 16 + Q, as in the per-channel kernels, and the
+// zero-point term crow[t] = sum_i A_g[t,i] (16 + z[i,g]) is added up beside the matrix instructions from the same
+// rounded fragments (one dot2 per register against the exact bf16 of 16 + z), so that it cancels the code offset.
+template <int BITS, int MODE, bool GROUPED, int KW, bool ASCALE = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8_t *lds)
 {
     constexpr int STAGE_BYTES = stage_bytes(KW);
     constexpr int WPB = 2 * BITS;                          // words per 8x8 block
     constexpr bool ALONG_CH = (MODE == MODE_DX);           // contraction over output channels
-    constexpr bool SCALED = GROUPED && MODE != MODE_DDS;   // weights enter the MFMA already scaled
+    constexpr bool SCALED = GROUPED && MODE != MODE_DDS;   // the scale is applied inside the loop
+    constexpr bool WSCALED = SCALED && !ASCALE;            // ... to the weights: they enter the MFMA already scaled
     constexpr bool PAIRED = GROUPED && MODE == MODE_DDS;   // one scale group per contraction half
+    static_assert(!ASCALE || (GROUPED && MODE == MODE_DX && KW == 1), "activation-side scaling is a form of the four-wave group-wise dX");
     static_assert(KW == 2 || (KW == 1 && !PAIRED), "the paired scale gradient needs both contraction halves");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -239,7 +247,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
         B = B < last ? B : last;
         const size_t g = ALONG_CH ? (size_t)((col0 + (fine ? 64 * wt : 0)) / a.gsz) : (size_t)((B << (5 + bshift)) / a.gsz);
         const size_t ch = ALONG_CH ? (size_t)B << 7 : (size_t)col0;
-        const uint8_t *src = reinterpret_cast<const uint8_t *>(a.sb) + (wave_on ? (g * a.N + ch) * 8 : 0);
+        // (s, b) pairs of 128 channels, 1 KB; with activation-side scaling the 1 KB of block B: its 128 scales, then its
+        // 128 offsets 16 + z as bf16 (exact), then padding
+        const uint8_t *src = reinterpret_cast<const uint8_t *>(a.sb) +
+                             (wave_on ? (ASCALE ? (g * (size_t)(a.N >> 7) + (size_t)B) * 1024 : (g * a.N + ch) * 8) : 0);
         dma16(lane * 16, src, lds_base + tbl_off + (B & 1) * tbuf + ((ALONG_CH && fine) ? wt * 1024 : 0));
     };
     const bool table_wave = wt == 0 || (ALONG_CH && fine);
@@ -259,8 +270,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
     // Along features fragment I needs only entry I: it is read when the fragment's first register is
     // built, which keeps 14 registers free.
     float sc[8], bo[8];
+    uint32_t zf[4];                                        // ASCALE: 16 + z of the same channels as exact bf16 pairs
+    float crow_acc[4] = {0.f, 0.f, 0.f, 0.f};              // ASCALE: this lane's part of crow of token rows 16 rt + c
     const uint8_t *tbl_row = nullptr;
     auto read_table = [&](int m) __attribute__((always_inline)) {
+        if constexpr (ASCALE) {
+            // scales and offsets of channels 32 (m % 4) + 8 q .. + 7 of the block.  (The step after the last one reads the
+            // last one's: a buffer that has been written, whatever the number of blocks.)
+            m = m < m0 + nit ? m : m0 + nit - 1;
+            tbl_row = lds + tbl_off + ((m >> 2) & 1) * tbuf + (m & 3) * 128 + q * 32;
+            const f32x4 lo = *reinterpret_cast<const f32x4 *>(tbl_row), hi = *reinterpret_cast<const f32x4 *>(tbl_row + 16);
+            const u32x4 zv = *reinterpret_cast<const u32x4 *>(lds + tbl_off + ((m >> 2) & 1) * tbuf + 512 + (m & 3) * 64 + q * 16);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { sc[e] = lo[e]; sc[4 + e] = hi[e]; zf[e] = zv[e]; }
+            return;
+        }
         tbl_row = lds + tbl_off + ((m >> bshift) & 1) * tbuf +
                   (ALONG_CH ? (fine ? (c >> 3) * 1024 : 0) + (m & 3) * 256 + q * 64 : c * 64);
         if constexpr (ALONG_CH) {
@@ -275,7 +299,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
     auto next_frag_reg = [&](const BlockUnpacker<BITS, ALONG_CH> &up, auto i_c, auto j_c) __attribute__((always_inline)) -> uint32_t {
         constexpr int I = decltype(i_c)::value, J = decltype(j_c)::value;
         const uint32_t pr = up.template frag_reg<I, J>(magic);
-        if constexpr (!SCALED) {
+        if constexpr (!WSCALED) {
             return pr;
         } else if constexpr (!ALONG_CH) {
             if constexpr (J == 0) {
@@ -286,6 +310,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
             return scale_pair(pr, sc[0], bo[0], sc[0], bo[0]);
         } else {
             return scale_pair(pr, sc[2 * J], bo[2 * J], sc[2 * J + 1], bo[2 * J + 1]);
+        }
+    };
+
+    // ASCALE: the activation fragment of row tile rt (8 contraction elements 8 q .. 8 q + 7 of a step) times the
+    // step's scales, and its part of the zero-point term
+    auto scale_a = [&](u32x4 &f, int rt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int J = 0; J < 4; ++J) {
+            f[J] = mul_pair(f[J], sc[2 * J], sc[2 * J + 1]);
+            crow_acc[rt] = dot2_bf16(f[J], zf[J], crow_acc[rt]);
         }
     };
 
@@ -337,6 +371,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
 #pragma unroll
         for (int rt = 0; rt < 4; ++rt) read_a(0, afrag, rt);
         if constexpr (SCALED) read_table(m0);
+        if constexpr (ASCALE) {
+#pragma unroll
+            for (int rt = 0; rt < 3; ++rt) scale_a(afrag[rt], rt);   // the fourth: in step 0 (see scale_next)
+        }
         BlockUnpacker<BITS, ALONG_CH> up;
         up.prepare(bw[1]);
         static_for<8>([&](auto i) {
@@ -398,6 +436,27 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
     const uint32_t a_voff_2 = KW == 2 ? a_voff + (uint32_t)(kh1 - kh0) * 2u : a_voff_hi;   // second activation DMA, same source pointer
     const uint32_t dst_a = lds_base + wave * 1024;
     const uint32_t dst_b = lds_base + KW * A_HALF_BYTES + slot * B_WAVE_BYTES + wt * 1024;
+    // ASCALE: a fragment is scaled one row tile after its read was issued, when its data has arrived (scaling the one
+    // just read would stall the wave for the LDS latency four times a step): after the matrix instructions of row
+    // tile rt >= 1 of step `it`, the fragment of row tile rt - 1 of step it + 1.  Row tile 3's fragment, read at the end
+    // of the step before, is scaled at the top of its own step, before that step fetches the scales of the next.
+    // The last step does the same with the fragments it reads for the step after it (a tile of real data, re-fetched
+    // by the tail of the ring: finite values), which are never contracted: what they added to crow is taken out
+    // again after the loop (take_out_phantom), which keeps branches and a second copy of the step out of the loop.
+    constexpr bool RING_UNROLL_C = !SCALED || (WSCALED && KW == 1 && !(ALONG_CH && BITS == 4));   // see below
+    auto scale_next = [&](auto rt_c) __attribute__((always_inline)) {
+        constexpr int rt = decltype(rt_c)::value;
+        if constexpr (rt >= 1) scale_a(afrag[rt - 1], rt - 1);
+    };
+    auto take_out_phantom = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int rt = 0; rt < 3; ++rt) {
+            float p = 0.f;
+#pragma unroll
+            for (int J = 0; J < 4; ++J) p = dot2_bf16(afrag[rt][J], zf[J], p);
+            crow_acc[rt] -= p;
+        }
+    };
     // (inlined by force: ten copies are more than the inliner takes by itself, and a call would pass the
     // captured scalars through memory)
     auto step = [&](int it, auto stage_c) __attribute__((always_inline)) {
@@ -406,6 +465,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
         constexpr int NS = (S + 1) % NSTAGE;                    // stage of step it + 1
         constexpr int NNS = (S + 2) % NSTAGE;                   // stage of step it + 2
         constexpr int PS = (S + NSTAGE - 1) % NSTAGE;           // stage of step it - 1 = of step it + NSTAGE - 1
+        if constexpr (ASCALE) {
+            scale_a(afrag[3], 3);
+            __builtin_amdgcn_sched_barrier(0);             // the old scales die before the new ones are read
+        }
         if constexpr (SCALED) {
             // the fragments built in this step belong to contraction step m = m0 + it + 1
             const int m = m0 + it + 1;
@@ -436,6 +499,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
                 }
             });
             read_a_st(std::integral_constant<int, NS>{}, afrag, rt);
+            static_assert(!ASCALE || !RING_UNROLL_C, "activation-side scaling runs the two-step loop");
         });
         // Own DMA for step it + 3 has landed; the barrier makes every wave's part visible.
         // No wait on LDS reads is needed here: what this step read is overwritten two steps later.
@@ -448,7 +512,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
     // register buffers alternate).  For the eight-wave per-channel kernels the unrolled loop measures the same
     // as the other (within 0.3 %): their loss against the four-wave form is ring fill, exchange and epilogue,
     // which nothing overlaps with one workgroup per compute unit.
-    constexpr bool RING_UNROLL = !SCALED || (KW == 1 && !(ALONG_CH && BITS == 4));
+    constexpr bool RING_UNROLL = RING_UNROLL_C;
     if constexpr (RING_UNROLL) {
         int it = 0;
         for (; it + NSTAGE <= nit; it += NSTAGE)
@@ -471,6 +535,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
         const int nstage = cur + 1 == NSTAGE ? 0 : cur + 1;       // stage of step it + 1
         const int nnstage = nstage + 1 == NSTAGE ? 0 : nstage + 1; // stage of step it + 2
         const int pstage = cur == 0 ? NSTAGE - 1 : cur - 1;       // stage of step it - 1 = of step it + NSTAGE - 1
+        if constexpr (ASCALE) {
+            scale_a(afrag[3], 3);
+            __builtin_amdgcn_sched_barrier(0);             // the old scales die before the new ones are read
+        }
         if constexpr (SCALED) {
             // the fragments built in this step belong to contraction step m = m0 + it + 1
             const int m = m0 + it + 1;
@@ -496,6 +564,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
                 if constexpr (m == 21) issue_one(2, pre_b, cur);
             });
             read_a(nstage, afrag, rt);
+            if constexpr (ASCALE) scale_next(rt_c);
         });
         // Own DMA for step it + 3 has landed; the barrier makes every wave's part visible.
         // No wait on LDS reads is needed here: what this step read is overwritten two steps later.
@@ -508,12 +577,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
         step2(it + 1, std::integral_constant<int, 1>{});
     }
     }
+    if constexpr (ASCALE) take_out_phantom();
     // The loop's exits meet here; this keeps the accumulators in their AGPRs past that point (the compiler would
     // otherwise copy all 128 of them into VGPRs at once, more than there are)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 8; ++j) asm volatile("" : "+a"(acc[i][j]));
+    // ASCALE: the lanes (c, 0..3) hold the four feature-block parts of crow of token row 16 rt + c: add them (fixed
+    // order); every lane of the four then has the row's total
+    if constexpr (ASCALE) {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt) {
+            crow_acc[rt] += __shfl_xor(crow_acc[rt], 16);
+            crow_acc[rt] += __shfl_xor(crow_acc[rt], 32);
+        }
+    }
     // The epilogue works out its lane indices afresh (from a copy of the thread index that the compiler cannot
     // connect to the first one), so that none of them has to be held in a register through the loop.
     {
@@ -530,13 +609,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
             const u32x2 r2 = *reinterpret_cast<const u32x2 *>(a.rs + 2 * t);
             return __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
         } else if constexpr (MODE == MODE_DX) {
-            return a.crow[t];
+            if constexpr (ASCALE) return __shfl(crow_acc[rt], 4 * q + j);   // row 16 rt + 4 q + j: from lane c = 4 q + j
+            else return a.crow[t];
         } else {
             return 0.f;
         }
     };
     float ep_sc[8], ep_zoff[8], ep_row[8];
-    if (wave_on && !SCALED) {
+    if (wave_on && !WSCALED) {
         if constexpr (PAIRED) {
             const int g = half_on ? grp : a.G - 1;
 #pragma unroll
@@ -668,7 +748,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
                 if (t < T) {
                     float v[8];
                     const float r = r_[j];
-                    if constexpr (SCALED) {
+                    if constexpr (WSCALED) {
 #pragma unroll
                         for (int ct = 0; ct < 8; ++ct) v[ct] = sum[ct][j];
                     } else if constexpr (MODE == MODE_Y) {
@@ -697,7 +777,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
             // the correction terms of the last two are fetched while the first two are stored
             if (wave_on) {
                 float ep_row_hi[8];
-                if constexpr (!SCALED) {
+                if constexpr (!WSCALED) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) ep_row_hi[i] = row_term(2 + (i >> 2), i & 3);
                 }
@@ -740,7 +820,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs &a, const int wg, uint8
     }
 }
 
-template <int BITS, int MODE, bool GROUPED, int KW>
+template <int BITS, int MODE, bool GROUPED, int KW, bool ASCALE = false>
 __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
 {
     extern __shared__ __align__(16) uint8_t lds[];
@@ -758,7 +838,7 @@ __global__ __launch_bounds__(256 * KW, 3 - KW) void gemm_kernel(GemmArgs a)
             return;
         }
     }
-    gemm_tile<BITS, MODE, GROUPED, KW>(a, (int)blockIdx.x, lds);
+    gemm_tile<BITS, MODE, GROUPED, KW, ASCALE>(a, (int)blockIdx.x, lds);
 }
 
 // Both contractions of a per-channel backward in one launch of four-wave workgroups: the first n_first
@@ -829,7 +909,10 @@ __device__ __forceinline__ void multi_aux(int n_sdy, int n_red, int n_tp, int au
 // Several per-channel contractions as four-wave tiles of one launch (see MultiArgs): workgroup -> (job, tile) by the
 // jobs' running totals; the job's arguments come out of the argument block with scalar loads.
 // GMODE < 0: per-channel jobs of any mode; GMODE = MODE_Y or MODE_DX: group-wise jobs, all of that mode (their
-// scale gradient is the token contraction of peqa_dw.hip).
+// scale gradient is the token contraction of peqa_dw.hip); GMODE_DX_ASIDE: group-wise dX jobs that all scale their
+// activation fragments.
+constexpr int GMODE_DX_ASIDE = 3;
+static_assert(MODE_Y != 3 && MODE_DDS != 3 && MODE_DX != 3, "a value of its own");
 template <int BITS, int GMODE>
 __global__ __launch_bounds__(256, 2) void gemm_multi_kernel(MultiArgs m)
 {
@@ -851,7 +934,9 @@ __global__ __launch_bounds__(256, 2) void gemm_multi_kernel(MultiArgs m)
         if (b >= e) { j = i + 1; wg0 = e; }
     }
     const GemmArgs a = kernarg_load<GemmArgs>((uint32_t)(j * sizeof(MultiJob) + offsetof(MultiJob, a)));
-    if constexpr (GMODE >= 0) {
+    if constexpr (GMODE == GMODE_DX_ASIDE) {
+        gemm_tile<BITS, MODE_DX, true, 1, true>(a, b - wg0, lds);
+    } else if constexpr (GMODE >= 0) {
         gemm_tile<BITS, GMODE, true, 1>(a, b - wg0, lds);
     } else {
         const int mode = kernarg_load<int>((uint32_t)(j * sizeof(MultiJob) + offsetof(MultiJob, mode)));
@@ -881,7 +966,7 @@ static int halves_per_workgroup(int tiles, bool paired)
 
 bool gemm_four_waves(int tiles) { return halves_per_workgroup(tiles, false) == 1; }
 
-template <int BITS, int MODE, bool GROUPED, int KW>
+template <int BITS, int MODE, bool GROUPED, int KW, bool ASCALE = false>
 static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
 {
     // dynamic LDS: the ring, plus the scale tables of the grouped forward / dX (twice as large for dX
@@ -892,7 +977,7 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     if (attr_bytes[dev] < lds_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MODE, GROUPED, KW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_kernel<BITS, MODE, GROUPED, KW, ASCALE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
         attr_bytes[dev] = lds_bytes;
@@ -906,7 +991,7 @@ static hipError_t launch_one(const GemmArgs &a, hipStream_t stream)
     constexpr bool SPARE_TP = MODE == MODE_DX && GROUPED && KW == 1;
     if (!SPARE_TP && a.tp_blocks != 0) return hipErrorInvalidValue;
     const int spare_blocks = SPARE_TP ? a.tp_blocks : 0;
-    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW>), dim3(grid + spare_blocks, gy), dim3(256 * KW), lds_bytes,
+    hipLaunchKernelGGL((gemm_kernel<BITS, MODE, GROUPED, KW, ASCALE>), dim3(grid + spare_blocks, gy), dim3(256 * KW), lds_bytes,
                        stream, a);
     return hipGetLastError();
 }
@@ -915,6 +1000,13 @@ template <int BITS, int MODE, bool GROUPED>
 static hipError_t launch_halves(const GemmArgs &a, hipStream_t stream)
 {
     constexpr bool PAIRED = GROUPED && MODE == MODE_DDS;
+    if constexpr (GROUPED && MODE == MODE_DX) {
+        // scales on the activation side: the table is in that form, and only the four-wave tile reads it
+        if (a.a_side) {
+            if (a.gsz % 128 != 0 || halves_per_workgroup(a.tiles_t * a.tiles_c, false) != 1) return hipErrorInvalidValue;
+            return launch_one<BITS, MODE, GROUPED, 1, true>(a, stream);
+        }
+    }
     if constexpr (!PAIRED) {
         if (halves_per_workgroup(a.tiles_t * a.tiles_c, false) == 1) return launch_one<BITS, MODE, GROUPED, 1>(a, stream);
     }
@@ -1025,9 +1117,12 @@ hipError_t launch_gemm_multi(int bits, bool grouped, MultiArgs &m, hipStream_t s
     if ((m.aux_begin & 7) || (m.aux_wgs & 7) || m.aux_begin < 0 || m.aux_begin > total) return hipErrorInvalidValue;
     if (total + m.aux_wgs == 0) return hipSuccess;
     const int mode0 = m.n_jobs > 0 ? m.job[0].mode : MODE_DX;
+    const bool a_side = grouped && m.n_jobs > 0 && m.job[0].a.a_side != 0;
     if (grouped) {
-        for (int j = 0; j < m.n_jobs; ++j)
-            if (m.job[j].mode != mode0) return hipErrorInvalidValue;
+        for (int j = 0; j < m.n_jobs; ++j) {
+            if (m.job[j].mode != mode0 || (m.job[j].a.a_side != 0) != a_side) return hipErrorInvalidValue;
+            if (a_side && (mode0 != MODE_DX || m.job[j].a.gsz % 128 != 0)) return hipErrorInvalidValue;
+        }
         if (mode0 == MODE_Y && m.aux_wgs != 0) return hipErrorInvalidValue;
     }
     const int kid = mode0 == MODE_Y ? KID_GEMM_MULTI_Y : (mode0 == MODE_DDS ? KID_GEMM_MULTI_DDS : KID_GEMM_MULTI_DX);
@@ -1036,6 +1131,7 @@ hipError_t launch_gemm_multi(int bits, bool grouped, MultiArgs &m, hipStream_t s
     hipError_t e;
     if (!grouped) e = bits == 4 ? launch_multi<4, -1>(grid, lds_bytes, m, stream) : launch_multi<3, -1>(grid, lds_bytes, m, stream);
     else if (mode0 == MODE_Y) e = bits == 4 ? launch_multi<4, MODE_Y>(grid, lds_bytes, m, stream) : launch_multi<3, MODE_Y>(grid, lds_bytes, m, stream);
+    else if (a_side) e = bits == 4 ? launch_multi<4, GMODE_DX_ASIDE>(grid, lds_bytes, m, stream) : launch_multi<3, GMODE_DX_ASIDE>(grid, lds_bytes, m, stream);
     else e = bits == 4 ? launch_multi<4, MODE_DX>(grid, lds_bytes, m, stream) : launch_multi<3, MODE_DX>(grid, lds_bytes, m, stream);
     trace_after(kid, stream);
     return e;

@@ -47,6 +47,8 @@ struct GemmArgs {
     int N;                    // output channels of the layer
     int gsz, G;               // group size and groups per channel
     const float *sb;          // [G, N, 2] (s0 + ds, -(s0 + ds)(16 + z0))  (MODE_Y, MODE_DX)
+    int a_side;               // MODE_DX, four-wave form, gsz % 128 == 0: the scales go on the activation fragments
+                              // and sb is the table launch_group_table makes with a_side
                               // rs is then [T, G]: sums of X over every scale group (MODE_DDS),
                               // partial is [tiles_t, N, G] and z0 is [N, G]
 };
@@ -141,7 +143,7 @@ struct GroupTableMulti {
     const float *s0[GT_MAX], *ds[GT_MAX];
     const uint8_t *z0[GT_MAX];
     float *sb[GT_MAX];
-    int N[GT_MAX], G[GT_MAX];
+    int N[GT_MAX], G[GT_MAX], a_side[GT_MAX];
     int n;
 };
 hipError_t launch_group_table_multi(const GroupTableMulti &a, hipStream_t stream);
@@ -197,8 +199,10 @@ hipError_t launch_scale_dy(const uint16_t *dY, const float *s0, const float *ds,
                            int T, int N, uint16_t *dYs, float *crow, const float *partial, int ntiles, size_t n_red,
                            float *red_out, hipStream_t stream);
 hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float *rsg, hipStream_t stream);
+// sb [G, N, 2] = (s, -s (16 + z)); with a_side [G, N / 128] blocks of 1 KB: the 128 scales s of a block of channels,
+// then their offsets 16 + z as bf16 (same size in all: 8 N G bytes)
 hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, const float *dz, int N, int G,
-                              float *sb, hipStream_t stream);
+                              bool a_side, float *sb, hipStream_t stream);
 // zero-point gradient: partial [ceil(T / KEPT_ROWS), N, G] from dY and the group sums rsg [T, G] of X, then
 // d_dz[j] = -(s0 + ds)[j] * (sum of the partials)
 hipError_t launch_dz_partial(const uint16_t *dY, const float *rsg, int T, int N, int G, float *partial,

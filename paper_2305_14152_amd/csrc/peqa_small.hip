@@ -96,19 +96,37 @@ __global__ __launch_bounds__(256) void rowsum_groups_kernel(const uint16_t *__re
     }
 }
 
-// sb[g, n] = (s, -s (16 + z)) with s = (s0 + ds)[n, g], z = (z0 + dz)[n, g]: the per-group table from which
-// the grouped contractions scale their weights.
-__global__ __launch_bounds__(256) void group_table_kernel(const float *__restrict__ s0, const float *__restrict__ ds,
-                                                           const uint8_t *__restrict__ z0, const float *__restrict__ dz,
-                                                           int N, int G, float *__restrict__ sb)
+// Entry j = n * G + g of the per-group table from which the grouped contractions take their scales, with
+// s = (s0 + ds)[n, g] and z = (z0 + dz)[n, g].
+//   a_side = 0:  sb[g][n] = (s, -s (16 + z)): the weights are scaled in the loop (forward, dX)
+//   a_side = 1:  sb[g][n / 128] = 1 KB: the 128 scales s of channels 128 (n / 128) .. + 127, then their 128 offsets
+//                16 + z as bf16 (exact: integer zero-points only), then 256 bytes never read: what a dX tile that scales
+//                its activation fragments fetches per block of channels
+__device__ __forceinline__ void group_table_entry(const float *__restrict__ s0, const float *__restrict__ ds,
+                                                  const uint8_t *__restrict__ z0, const float *__restrict__ dz, int N,
+                                                  int G, int a_side, float *__restrict__ sb, size_t j)
 {
-    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;   // = n * G + g
-    if (j >= (size_t)N * G) return;
     const size_t n = j / G, g = j - n * G;
     const float s = ds ? s0[j] + ds[j] : s0[j];
-    float *o = sb + (g * N + n) * 2;
-    o[0] = s;
-    o[1] = -s * (kCodeOffset + (float)z0[j] + (dz ? dz[j] : 0.f));
+    const float zoff = kCodeOffset + (float)z0[j] + (dz ? dz[j] : 0.f);
+    if (a_side) {
+        float *blk = sb + (g * (size_t)(N >> 7) + (n >> 7)) * 256;
+        blk[n & 127] = s;
+        reinterpret_cast<uint16_t *>(blk + 128)[n & 127] = (uint16_t)float_to_bf16_bits(zoff);
+    } else {
+        float *o = sb + (g * N + n) * 2;
+        o[0] = s;
+        o[1] = -s * zoff;
+    }
+}
+
+__global__ __launch_bounds__(256) void group_table_kernel(const float *__restrict__ s0, const float *__restrict__ ds,
+                                                           const uint8_t *__restrict__ z0, const float *__restrict__ dz,
+                                                           int N, int G, int a_side, float *__restrict__ sb)
+{
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= (size_t)N * G) return;
+    group_table_entry(s0, ds, z0, dz, N, G, a_side, sb, j);
 }
 
 // group_table_kernel for several layers: blockIdx.y = layer.
@@ -118,17 +136,13 @@ __global__ __launch_bounds__(256) void group_table_multi_kernel(GroupTableMulti 
     const float *s0 = a.s0[0], *ds = a.ds[0];
     const uint8_t *z0 = a.z0[0];
     float *sb = a.sb[0];
-    int N = a.N[0], G = a.G[0];
+    int N = a.N[0], G = a.G[0], a_side = a.a_side[0];
 #pragma unroll
     for (int i = 1; i < GT_MAX; ++i)
-        if (y == i) { s0 = a.s0[i]; ds = a.ds[i]; z0 = a.z0[i]; sb = a.sb[i]; N = a.N[i]; G = a.G[i]; }
-    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;   // = n * G + g
+        if (y == i) { s0 = a.s0[i]; ds = a.ds[i]; z0 = a.z0[i]; sb = a.sb[i]; N = a.N[i]; G = a.G[i]; a_side = a.a_side[i]; }
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= (size_t)N * G) return;
-    const size_t n = j / G, g = j - n * G;
-    const float s = ds ? s0[j] + ds[j] : s0[j];
-    float *o = sb + (g * N + n) * 2;
-    o[0] = s;
-    o[1] = -s * (kCodeOffset + (float)z0[j]);
+    group_table_entry(s0, ds, z0, nullptr, N, G, a_side, sb, j);
 }
 
 // scale_dy_rows (peqa_device.h) for every block of SDY_ROWS token rows.  Workgroups past the last row block do an
@@ -335,12 +349,12 @@ hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float 
 }
 
 hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, const float *dz, int N, int G,
-                              float *sb, hipStream_t stream)
+                              bool a_side, float *sb, hipStream_t stream)
 {
     trace_before(KID_GROUP_TABLE, stream);
     const size_t n = (size_t)N * G;
     hipLaunchKernelGGL(group_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, ds, z0, dz, N, G,
-                       sb);
+                       a_side ? 1 : 0, sb);
     trace_after(KID_GROUP_TABLE, stream);
     return hipGetLastError();
 }

@@ -219,7 +219,11 @@ peqa_status peqa_linear_fwd_fused(int32_t n, const peqa_fwd_item *items, const u
  *     items' contractions in one launch of four-wave tiles, longest contraction first.  Backward = all scale-gradient
  *     contractions in one launch whose grid also carries the scaling of dY for every item, then all dX
  *     contractions in one launch whose grid also carries the fixed-order sums of the scale-gradient partials.
- *     Group-wise layers run item by item as peqa_linear_fwd / peqa_linear_bwd do.
+ *     Group-wise layers: forward = the scale tables of all items in one launch, then all contractions in one
+ *     launch.  Backward = the tables, then all dX contractions in one launch whose grid also writes the
+ *     transposed copies of X (once per distinct X) and dY, then the token contractions of all scale
+ *     gradients in one launch and the sums of their chunks in another.  (Always the token-contraction
+ *     route: PEQA_OPT_GROUPED_DDS is not consulted.)
  *   row_sums (optional, [T, 2] fp32 per distinct X, caller-owned): when not NULL, peqa_block_fwd stores the row
  *     sums of the item's X there (see peqa_row_sums) and peqa_block_bwd reads them instead of taking them again;
  *     items that share X may share the array.  Ignored by T <= 16 and by group-wise layers.

@@ -22,11 +22,15 @@
 // A wave's features are 64-feature chunks, the unit in which the epilogue reports (every group is a whole
 // number of chunks).  Operands go global -> LDS by DMA into a ring of 4 stages of 32 KB (one 32-token step:
 // 256 + 256 rows of 64 B, XOR-swizzled as in the other contraction kernel); fragments for step it + 1 are read
-// from LDS while step it's matrix instructions run.  The epilogue reads each lane's codes straight from the
-// packed array, forms sum dW Q - z sum dW over each chunk with two shuffles, and writes pc[i, chunk];
-// chunk_reduce_kernel adds the chunks of every group in order.  The loop runs at about 1.0 us per step
-// against 0.5 us for its matrix instructions and fragment reads alone in a test loop; the 32 KB of DMA per
-// step and compute unit are what is left to suspect, unconfirmed.
+// from LDS while step it's matrix instructions run.  The epilogue takes each lane's codes from a copy of the tile's
+// packed words that one of the ring's spare stages brought into LDS (see issue_one), at word positions and shifts
+// worked out once per lane, forms sum dW Q - z sum dW over each chunk with two shuffles, and writes pc[i, chunk];
+// chunk_reduce_kernel adds the chunks of every group in order.
+// Where the time of a tile goes at T = 2048 (64 steps; timestamps per workgroup on the 13B shapes): 2.6 us from its
+// start to its first fragments, 47-53 us in the loop (0.75-0.85 us per step against 0.49 us of matrix instructions:
+// timing builds without the loop's DMAs, without its fragment reads, and without both ran the launch in 0.80, 0.92
+// and 0.78 of its time, so with one workgroup per compute unit and a barrier per step about three quarters of the
+// loop is the floor of this form), 6 us in the epilogue, 2 us until the next tile starts on the unit.
 #include <stddef.h>
 
 #include "peqa_device.h"
@@ -43,21 +47,6 @@ constexpr int DW_A_BYTES = DW_TF * 64;           // 16 KB: 256 feature rows x 32
 constexpr int DW_STAGE = (DW_TF + DW_TC) * 64;   // 32 KB
 constexpr int DW_LDS = DW_NST * DW_STAGE;        // 128 KB
 constexpr int DW_WM = 4;                         // waves along the features: see dw_kernel
-
-// Code of (channel row r, feature column cc) of one packed 8x8 block (the layout of peqa.h).
-template <int BITS>
-__device__ __forceinline__ uint32_t code_at(const uint32_t *blk, int r, int cc)
-{
-    if constexpr (BITS == 4) {
-        return (blk[r] >> (4 * ((cc >> 1) + 4 * (cc & 1)))) & 15u;
-    } else {
-        const int u = 4 * (r >> 1) + (cc >> 1), h = 16 * (cc & 1), par = r & 1;
-        if (u < 15) return (blk[2 * (u / 5) + par] >> (h + 3 * (u % 5))) & 7u;
-        const uint32_t b0 = (blk[par] >> (15 + h)) & 1u, b1 = (blk[2 + par] >> (15 + h)) & 1u,
-                       b2 = (blk[4 + par] >> (15 + h)) & 1u;
-        return b0 | (b1 << 1) | (b2 << 2);
-    }
-}
 
 // WM = waves along the features (2: 128 x 128 wave tiles, one wave per SIMD; 4: 64 x 128, two per SIMD)
 template <int BITS, int WM>
@@ -105,9 +94,35 @@ __device__ __forceinline__ void dw_tile(const DwArgs &a, const int wg, uint8_t *
             voff[j] = (uint32_t)row * 64u + chunk * 16u;
         }
     }
+    // The queue runs four stages past the last step, so that the DMA count per step is constant.  Of those, the
+    // stage numbered `nsteps` carries the packed codes of the tile's 256 x 256 weights for the epilogue: the two runs of
+    // 8 step tiles (RUN bytes each: contiguous in the tile-major layout) of its two 128-channel tile rows, copied
+    // linearly, KB number d by DMA d = DW_DMA wave + j; the others re-fetch the last step.  Runs past the matrix
+    // (second tile row beyond N, step tiles beyond K, the KBs after the two runs at 3 bits) are read from valid
+    // memory somewhere else and never looked at.
+    constexpr uint32_t CODE_TILE = 64 * WPB * 4, CODE_RUN = 8 * CODE_TILE;   // one 128 x 32 tile; 8 of them (12 or 16 KB)
+    const uint8_t *code_src[DW_DMA];
+    {
+        const size_t total = (size_t)a.N * a.K / 8 * BITS, row_bytes = (size_t)(a.K >> 5) * CODE_TILE;
+#pragma unroll
+        for (int j = 0; j < DW_DMA; ++j) {
+            const uint32_t byte = (uint32_t)(DW_DMA * wave + j) * 1024u;
+            uint32_t run = byte / CODE_RUN;
+            const uint32_t off = byte - run * CODE_RUN;
+            if (run > 1 || (2 * tile_c + (int)run) * 128 >= a.N) run = 0;
+            size_t g = (size_t)(2 * tile_c + run) * row_bytes + (size_t)tile_f * CODE_RUN + off;
+            g = g + 1024 <= total ? g : total - 1024;
+            code_src[j] = reinterpret_cast<const uint8_t *>(a.packed) + g;
+        }
+    }
     auto issue_one = [&](int j, int it, int stage) {
-        const int s = it < nsteps ? it : nsteps - 1;       // the tail re-fetches the last step: constant DMA count
-        dma16(voff[j], src + (size_t)s * step_bytes, lds_base + stage * DW_STAGE + (DW_DMA * wave + j) * 1024);
+        const uint32_t dst = lds_base + stage * DW_STAGE + (DW_DMA * wave + j) * 1024;
+        if (it == nsteps) {
+            dma16((uint32_t)lane * 16u, code_src[j], dst);
+        } else {
+            const int s = it < nsteps ? it : nsteps - 1;
+            dma16(voff[j], src + (size_t)s * step_bytes, dst);
+        }
     };
     auto issue = [&](int it, int stage) {
 #pragma unroll
@@ -189,36 +204,83 @@ __device__ __forceinline__ void dw_tile(const DwArgs &a, const int wg, uint8_t *
     const int fb = k0 + 16 * NRT * wm, cb = n0 + 128 * wn;
     if (cb >= a.N) return;                                 // wave-uniform (N % 128 == 0)
     const int nchunks = a.K >> 6;
-    const size_t tile_row_words = (size_t)(a.K >> 5) * 64 * WPB;   // words per row of 128-channel tiles
+    // the tile's codes, in the ring slot of stage `nsteps`: run wn = this wave's 128 channels
+    const uint8_t *code_lds = lds + (nsteps & (DW_NST - 1)) * DW_STAGE + wn * CODE_RUN;
+    // The lane's four features of an accumulator tile are half a row of one 8 x 8 code block: row r = c % 8 (cb is a
+    // multiple of 128), columns 4 hq .. 4 hq + 3 with hq = q % 2 (fb + 16 rt is a multiple of 16).  Where those four
+    // codes sit inside the block's words depends on (r, hq) only: worked out once per lane, so that a tile costs a few
+    // loads at fixed offsets and shifts by lane constants (taken code by code with run-time row and column, the
+    // epilogue took a third of the kernel's time at T = 2048).
+    //   4 bits: word r, code of column cc at bits [4 p, 4 p + 4), p = cc / 2 + 4 (cc % 2): after a shift by 8 hq the four
+    //           codes are at bits 0, 16, 4, 20.
+    //   3 bits: cell u = 4 (r / 2) + cc / 2 holds columns cc = 2 (u % 4), 2 (u % 4) + 1 in its low and high half-word:
+    //           the lane has cells u0 = 4 (r / 2) + 2 hq and u0 + 1; cell u < 15 is field u % 5 of word 2 (u / 5) + r % 2,
+    //           cell 15 is spread over the top bits of the half-words of words r % 2, 2 + r % 2, 4 + r % 2.
+    const int r = c & 7, par = r & 1, hq = q & 1;
+    const int u0 = 4 * (r >> 1) + 2 * hq, u1 = u0 + 1;
+    const bool spare = u1 == 15;
+    // word (within the block) and shift of the lane's two cells; the spare cell is put together in the same form
+    // (low code at bit 0, high code at bit 16) from the top bits of the three words
+    const int wi0 = 2 * (u0 / 5) + par, sh0 = 3 * (u0 % 5);
+    const int wi1 = spare ? par : 2 * (u1 / 5) + par, sh1 = spare ? 0 : 3 * (u1 % 5);
+    // one byte of a register to fp32 in one instruction (v_cvt_f32_ubyte0 / 2)
+    auto byte0 = [](uint32_t v) { return (float)(v & 0xFFu); };
+    auto byte2 = [](uint32_t v) { return (float)((v >> 16) & 0xFFu); };
+    auto lane_codes = [&](const uint32_t *blk, float *code) {
+        if constexpr (BITS == 4) {
+            const uint32_t w = blk[r] >> (8 * hq);
+            const uint32_t t0 = w & 0x000F000Fu, t1 = (w >> 4) & 0x000F000Fu;
+            code[0] = byte0(t0);
+            code[1] = byte2(t0);
+            code[2] = byte0(t1);
+            code[3] = byte2(t1);
+        } else {
+            const uint32_t A = blk[par], B = blk[2 + par], C = blk[4 + par];
+            const uint32_t S = ((A >> 15) & 0x00010001u) | ((B >> 14) & 0x00020002u) | ((C >> 13) & 0x00040004u);
+            const uint32_t t0 = (blk[wi0] >> sh0) & 0x00070007u;
+            const uint32_t t1 = ((spare ? S : blk[wi1]) >> sh1) & 0x00070007u;
+            code[0] = byte0(t0);
+            code[1] = byte2(t0);
+            code[2] = byte0(t1);
+            code[3] = byte2(t1);
+        }
+    };
     static_for<NRT / 4>([&](auto h_c) {
         constexpr int h = h_c.value;
         const int fh = fb + 64 * h;
         if (fh >= a.K) return;                             // wave-uniform (K % 64 == 0)
         const int chunk = fh >> 6, grp = fh / a.gsz;
+        // zero-points of the lane's eight channels, fetched together and by every lane: inside the q == 0 branch below
+        // each would be a load of its own with a full memory latency in front of the store
+        float zv[8];
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) {
+            const size_t sg = (size_t)(cb + 16 * ct + c) * a.G + grp;
+            zv[ct] = (float)a.z0[sg] + (a.dz ? a.dz[sg] : 0.f);
+        }
         static_for<8>([&](auto ct_c) {
             constexpr int ct = ct_c.value;
             const int i = cb + 16 * ct + c;
-            const uint32_t *ch_tile = a.packed + (size_t)(i >> 7) * tile_row_words + (size_t)(((i >> 3) & 15) * 4) * WPB;
+            // blocks of channel block (i / 8) % 16 = 2 ct + c / 8 within the tiles of the run
+            const uint32_t *ch_tile = reinterpret_cast<const uint32_t *>(code_lds) + (2 * ct + (c >> 3)) * 4 * WPB;
             float s1 = 0.f, s0 = 0.f;
             static_for<4>([&](auto r_c) {
                 constexpr int rt = 4 * h + r_c.value;
                 const f32x4 v = read_acc(acc[rt][ct]);
-                const int f = fb + 16 * rt + 4 * q;        // first of the lane's 4 features: one code block
-                const uint32_t *blk = ch_tile + (size_t)(f >> 5) * 64 * WPB + ((f >> 3) & 3) * WPB;
+                // the lane's features fb + 16 rt + 4 q + j: step tile (fb - k0 + 16 rt) / 32 of the run, block column
+                // 2 (rt % 2) + q / 2
+                const uint32_t *blk = ch_tile + (((fb - k0) >> 5) + (rt >> 1)) * 64 * WPB + (2 * (rt & 1) + (q >> 1)) * WPB;
+                float code[4];
+                lane_codes(blk, code);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float code = (float)code_at<BITS>(blk, i & 7, (f & 7) + j);
-                    s1 += v[j] * code;
+                    s1 += v[j] * code[j];
                     s0 += v[j];
                 }
             });
             s1 += __shfl_xor(s1, 16); s0 += __shfl_xor(s0, 16);
             s1 += __shfl_xor(s1, 32); s0 += __shfl_xor(s0, 32);
-            if (q == 0) {
-                const size_t sg = (size_t)i * a.G + grp;
-                const float z = (float)a.z0[sg] + (a.dz ? a.dz[sg] : 0.f);
-                a.pc[(size_t)i * nchunks + chunk] = s1 - z * s0;
-            }
+            if (q == 0) a.pc[(size_t)i * nchunks + chunk] = s1 - zv[ct] * s0;
         });
     });
 }

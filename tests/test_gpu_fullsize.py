@@ -209,8 +209,8 @@ def test_full_size_quantize_search(gpu, oracle):
 def test_full_size_block(gpu, oracle, cfg):
     """The launch configuration bench.py times: the whole decoder block behind peqa_block_fwd / peqa_block_bwd, q, k, v
     and gate, up stacked (4 items), at the workload's full size.  Y and dX on one token row of every 128-row tile
-    against all channels / features, d_ds on one channel of every 128; for the 13B workload also the T = 1 and
-    T = 16 block forward with the seven layers as separate items (slices of the stacked arrays), every channel."""
+    against all channels / features, d_ds on one channel of every 128; for the 7B and the 13B workload also the
+    T <= 16 block forward with the seven layers as separate items (slices of the stacked arrays), every channel."""
     import torch
     from paper_2305_14152_amd import peqa
     c = synth.CONFIGS[cfg]
@@ -264,10 +264,11 @@ def test_full_size_block(gpu, oracle, cfg):
         g = gpu.to_host(d["d_ds"]).astype(np.float64)
         gpu.assert_scale_grad_close(g[ns], gref)
         assert np.isfinite(g).all() and (np.abs(g).reshape(N // 128, -1).max(axis=1) > 0).all()
-    if cfg != 4:
+    if cfg not in (1, 4):
         return
-    # deployment forward of the block: seven items (q, k, v and gate, up as slices of the stacked arrays), one call
-    for Ts in (1, 16):
+    # deployment forward of the block: seven items (q, k, v and gate, up as slices of the stacked arrays), one call.
+    # (T = 1 and 4 take the three-workgroups-per-unit slicing on the per-channel 7B block, T = 16 the other.)
+    for Ts in ((1, 16) if cfg == 4 else (1, 4, 16)):
         seven, refs = [], []
         for m, d, (N, K, li, xi) in zip(members, dicts, shapes):
             count = {0: 3, 1: 1, 2: 2, 3: 1}[xi]

@@ -77,3 +77,74 @@ def _random_shape(gpu, oracle, case, bits, N, K, group, T):
     assert np.abs(gpu.bf16_dev_to_f64(dXz) - dXzref).max() <= Y_TOL * np.abs(dXzref).max()
     gpu.assert_scale_grad_close(gpu.to_host(ddsz), gsref, "d_ds")
     gpu.assert_scale_grad_close(gpu.to_host(ddz), gzref, "d_dz")
+
+
+def _block_cases(n, seed):
+    """Random blocks for the block calls: bit width, group size, T, and 1 to 6 members of random shapes, some of which
+    share the input of the member before them; every member randomly with or without its offset ds, its dX, its d_ds."""
+    import math
+    rng = np.random.default_rng(seed)
+    out = []
+    for case in range(n):
+        bits = int(rng.choice([3, 4]))
+        group = int(rng.choice([0, 0, 64, 128, 128, 192, 256, 384]))
+        kunit = 128 if group == 0 else (group * 128) // math.gcd(group, 128)
+        T = int(rng.choice([1, 5, 16, 17, 33, 64, 65, 100, 128, 129, 200, 257, 384]))
+        members = []
+        for j in range(int(rng.integers(1, 7))):
+            N = 128 * int(rng.integers(1, 6))
+            if j > 0 and rng.random() < 0.4:
+                K, xi = members[-1][1], members[-1][2]
+            else:
+                K, xi = kunit * int(rng.integers(1, max(2, 1536 // kunit))), j
+            members.append((N, K, xi, bool(rng.random() < 0.6), bool(rng.random() < 0.85), bool(rng.random() < 0.85)))
+        out.append((case, bits, group, T, tuple(members)))
+    return out
+
+
+@pytest.mark.parametrize("case,bits,group,T,members", _block_cases(20, 20240611))
+def test_random_block(gpu, oracle, case, bits, group, T, members):
+    """peqa_block_fwd / peqa_block_bwd on a random block against the oracle, member by member, and the forward against
+    the single-layer call (the same products, possibly added in another order)."""
+    import torch
+    from paper_2305_14152_amd import peqa
+    print("random block %d: bits=%d g=%d T=%d members=%s" % (case, bits, group, T, members), flush=True)
+    inputs, host, dicts = {}, [], []
+    for j, (N, K, xi, with_ds, want_dx, want_g) in enumerate(members):
+        seed = 400000 + 1000 * case + 10 * j
+        W = synth.normal_f32(seed, (N, K), 0.02)
+        layer = gpu.GpuLayer(W, bits, group)
+        codes, s0, z0 = oracle.quantize(W, bits, group)
+        ds = synth.normal_f32(seed + 1, s0.shape, 1e-3) if with_ds else None
+        if xi not in inputs:
+            X = synth.normal_bf16(seed + 2, (T, K), 1.0)
+            inputs[xi] = (X, gpu.to_dev(X))
+        X, Xd = inputs[xi]
+        dY = synth.normal_bf16(seed + 3, (T, N), 1.0)
+        host.append((layer, codes, s0, z0, ds, X, dY))
+        dicts.append(dict(L=layer.L, packed=layer.packed, s0=layer.s0, z0=layer.z0, ds=gpu.to_dev(ds) if with_ds else None, X=Xd,
+                          Y=torch.zeros((T, N), dtype=torch.int16, device="cuda"), dY=gpu.to_dev(dY),
+                          dX=torch.full((T, K), 7, dtype=torch.int16, device="cuda") if want_dx else None,
+                          d_ds=torch.full(s0.shape, 7.0, dtype=torch.float32, device="cuda") if want_g else None))
+    items = peqa.block_items(dicts)
+    nb = peqa.block_workspace_bytes(items, T, peqa.PEQA_OP_FWD)
+    ws = torch.full((nb,), 0xA5, dtype=torch.uint8, device="cuda")
+    peqa.block_fwd(items, T, ws, nb)
+    if T > 16:
+        nbb = peqa.block_workspace_bytes(items, T, peqa.PEQA_OP_BWD)
+        wsb = torch.full((nbb,), 0xA5, dtype=torch.uint8, device="cuda")
+        peqa.block_bwd(items, T, wsb, nbb)
+    torch.cuda.synchronize()
+    for (layer, codes, s0, z0, ds, X, dY), d in zip(host, dicts):
+        Yref = oracle.fwd(codes, s0, ds, z0, X, group)
+        Y = gpu.bf16_dev_to_f64(d["Y"])
+        assert np.abs(Y - Yref).max() <= Y_TOL * np.abs(Yref).max()
+        Y1 = gpu.bf16_dev_to_f64(layer.fwd(d["X"], d["ds"]))
+        assert np.abs(Y - Y1).max() <= 2.0 ** -7 * np.abs(Yref).max()
+        if T <= 16:
+            continue
+        dXref, gref, _ = oracle.bwd(codes, s0, ds, z0, X, dY, group)
+        if d["dX"] is not None:
+            assert np.abs(gpu.bf16_dev_to_f64(d["dX"]) - dXref).max() <= Y_TOL * np.abs(dXref).max()
+        if d["d_ds"] is not None:
+            gpu.assert_scale_grad_close(gpu.to_host(d["d_ds"]), gref)

@@ -4,6 +4,11 @@
 
 using namespace peqa::host;
 
+// every table of a launch holds an entry per item of a call
+static_assert(peqa::MULTI_MAX_JOBS >= PEQA_MAX_BLOCK && peqa::DW_MAX_JOBS >= PEQA_MAX_BLOCK && peqa::GT_MAX >= PEQA_MAX_BLOCK &&
+                  peqa::ROWSUM_MAX >= PEQA_MAX_BLOCK && peqa::GEMV_MAX_LAYERS >= PEQA_MAX_BLOCK,
+              "launch tables against PEQA_MAX_BLOCK");
+
 namespace {
 
 peqa_status check_items(int32_t n, const peqa_block_item *items, int32_t T)

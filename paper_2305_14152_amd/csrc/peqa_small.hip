@@ -129,8 +129,66 @@ __global__ __launch_bounds__(256) void group_table_kernel(const float *__restric
     group_table_entry(s0, ds, z0, dz, N, G, a_side, sb, j);
 }
 
-// group_table_kernel for several layers: blockIdx.y = layer.
+// The same table by workgroups of GT_CH channels x all groups, through LDS: memory has a channel's groups next to each
+// other and the table a group's channels, so entry by entry every 8-byte write is a transaction of its own (25 us for
+// the four tables of a 13B block); here the reads run along the groups and the writes along the channels, 128 bytes
+// per group.  `lds`: 2 x GT_CH x G floats.
+constexpr int GT_CH = 16;
+__device__ __forceinline__ void group_table_tile(const float *__restrict__ s0, const float *__restrict__ ds,
+                                                 const uint8_t *__restrict__ z0, const float *__restrict__ dz, int N, int G,
+                                                 int a_side, float *__restrict__ sb, int n0, float *lds)
+{
+    float *s_l = lds, *z_l = lds + GT_CH * G;
+    const size_t base = (size_t)n0 * G;
+    for (int e = threadIdx.x; e < GT_CH * G; e += 256) {
+        const size_t j = base + e;
+        s_l[e] = ds ? s0[j] + ds[j] : s0[j];
+        z_l[e] = kCodeOffset + (float)z0[j] + (dz ? dz[j] : 0.f);
+    }
+    __syncthreads();
+    const int nl = threadIdx.x % GT_CH, n = n0 + nl;
+    for (int g = threadIdx.x / GT_CH; g < G; g += 256 / GT_CH) {
+        const float s = s_l[nl * G + g], zoff = z_l[nl * G + g];
+        if (a_side) {
+            float *blk = sb + ((size_t)g * (size_t)(N >> 7) + (n >> 7)) * 256;
+            blk[n & 127] = s;
+            reinterpret_cast<uint16_t *>(blk + 128)[n & 127] = (uint16_t)float_to_bf16_bits(zoff);
+        } else {
+            f32x2 o;
+            o[0] = s;
+            o[1] = -s * zoff;
+            *reinterpret_cast<f32x2 *>(sb + ((size_t)g * N + n) * 2) = o;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void group_table_tile_kernel(const float *__restrict__ s0, const float *__restrict__ ds,
+                                                                const uint8_t *__restrict__ z0, const float *__restrict__ dz,
+                                                                int N, int G, int a_side, float *__restrict__ sb)
+{
+    extern __shared__ __align__(16) float gt_lds[];
+    group_table_tile(s0, ds, z0, dz, N, G, a_side, sb, (int)blockIdx.x * GT_CH, gt_lds);
+}
+
+// group_table_tile_kernel for several layers: blockIdx.y = layer.
 __global__ __launch_bounds__(256) void group_table_multi_kernel(GroupTableMulti a)
+{
+    extern __shared__ __align__(16) float gt_lds[];
+    const int y = blockIdx.y;
+    const float *s0 = a.s0[0], *ds = a.ds[0];
+    const uint8_t *z0 = a.z0[0];
+    float *sb = a.sb[0];
+    int N = a.N[0], G = a.G[0], a_side = a.a_side[0];
+#pragma unroll
+    for (int i = 1; i < GT_MAX; ++i)
+        if (y == i) { s0 = a.s0[i]; ds = a.ds[i]; z0 = a.z0[i]; sb = a.sb[i]; N = a.N[i]; G = a.G[i]; a_side = a.a_side[i]; }
+    const int n0 = (int)blockIdx.x * GT_CH;
+    if (n0 >= N) return;                                   // uniform per workgroup
+    group_table_tile(s0, ds, z0, nullptr, N, G, a_side, sb, n0, gt_lds);
+}
+
+// the same entry by entry, for rows of more groups than the tile form's LDS holds
+__global__ __launch_bounds__(256) void group_table_multi_entry_kernel(GroupTableMulti a)
 {
     const int y = blockIdx.y;
     const float *s0 = a.s0[0], *ds = a.ds[0];
@@ -348,13 +406,21 @@ hipError_t launch_rowsum_groups(const uint16_t *X, int T, int K, int gsz, float 
     return hipGetLastError();
 }
 
+// most groups per channel the tile form takes (48 KB of LDS)
+constexpr int GT_TILE_MAX_G = 48 * 1024 / (2 * GT_CH * (int)sizeof(float));
+
 hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z0, const float *dz, int N, int G,
                               bool a_side, float *sb, hipStream_t stream)
 {
     trace_before(KID_GROUP_TABLE, stream);
-    const size_t n = (size_t)N * G;
-    hipLaunchKernelGGL(group_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, ds, z0, dz, N, G,
-                       a_side ? 1 : 0, sb);
+    if (G <= GT_TILE_MAX_G) {
+        hipLaunchKernelGGL(group_table_tile_kernel, dim3(N / GT_CH), dim3(256), 2 * GT_CH * G * sizeof(float), stream, s0, ds, z0,
+                           dz, N, G, a_side ? 1 : 0, sb);
+    } else {
+        const size_t n = (size_t)N * G;
+        hipLaunchKernelGGL(group_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, s0, ds, z0, dz, N, G,
+                           a_side ? 1 : 0, sb);
+    }
     trace_after(KID_GROUP_TABLE, stream);
     return hipGetLastError();
 }
@@ -362,12 +428,18 @@ hipError_t launch_group_table(const float *s0, const float *ds, const uint8_t *z
 hipError_t launch_group_table_multi(const GroupTableMulti &a, hipStream_t stream)
 {
     size_t nmax = 0;
+    int Nmax = 0, Gmax = 0;
     for (int i = 0; i < a.n; ++i) {
         const size_t n = (size_t)a.N[i] * a.G[i];
         nmax = n > nmax ? n : nmax;
+        Nmax = a.N[i] > Nmax ? a.N[i] : Nmax;
+        Gmax = a.G[i] > Gmax ? a.G[i] : Gmax;
     }
     trace_before(KID_GROUP_TABLE, stream);
-    hipLaunchKernelGGL(group_table_multi_kernel, dim3((unsigned)((nmax + 255) / 256), a.n), dim3(256), 0, stream, a);
+    if (Gmax <= GT_TILE_MAX_G)
+        hipLaunchKernelGGL(group_table_multi_kernel, dim3(Nmax / GT_CH, a.n), dim3(256), 2 * GT_CH * Gmax * sizeof(float), stream, a);
+    else
+        hipLaunchKernelGGL(group_table_multi_entry_kernel, dim3((unsigned)((nmax + 255) / 256), a.n), dim3(256), 0, stream, a);
     trace_after(KID_GROUP_TABLE, stream);
     return hipGetLastError();
 }
